@@ -1,0 +1,209 @@
+#!/usr/bin/env python3
+"""Benchmark of the convolution hot path on one MI355X.
+
+A "step" is one pass of the whole hot path -- forward, backward data, backward filter and backward
+bias -- over every layer of the workload, with all inputs already resident in HBM.  The default
+workload is the large grouped-conv configuration (layers 5.a, 5.b, 5.c: the GEMM-bound shapes the
+metric is about).  The metric is fwd+bwd GFLOP/s = 3 * (multiply-add FLOPs of one pass) / time,
+counting only algorithmic FLOPs (no credit for tile padding; bias adds and the bias-gradient
+reduction add time but no FLOPs).
+
+Prints ONE JSON line (rank 0 is the only rank: this benchmark is single-GPU).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+PEAK_FP32_MFMA_TFLOPS = 157.3  # MI355X published dense fp32 matrix peak
+PEAK_HBM_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="config4", help="config0..config4 or a comma list of layer names")
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
+    ap.add_argument("--cpu-sample-images", type=int, default=32)
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only: every box of this build has a single MI355X and the "
+              "path has no multi-GPU part; run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_1810_02272_amd as conv
+    from paper_1810_02272_amd import workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU (there is no CPU path)", file=sys.stderr)
+        sys.exit(2)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    if args.workload.startswith("config"):
+        cfg = int(args.workload[len("config"):])
+        layers = [l for l in workloads.LAYERS if l.config == cfg]
+    else:
+        layers = [workloads.BY_NAME[n] for n in args.workload.split(",")]
+
+    # ---- set-up (untimed): descriptors, inputs resident in HBM, one shared workspace ----
+    state = []
+    ws_bytes = 0
+    for l in layers:
+        d = conv.conv_desc_create(conv.ConvParams(**l.params_dict()))
+        ws_bytes = max(ws_bytes, conv.conv_desc_workspace_bytes(d))
+        x, w, b, dy = workloads.layer_inputs(l, bias="zero")
+        t = dict(layer=l, desc=d, x=x.to(dev), w=w.to(dev), b=b.to(dev), dy=dy.to(dev),
+                 y=torch.empty(l.y_shape, device=dev), dx=torch.empty(l.x_shape, device=dev),
+                 dw=torch.empty(l.w_shape, device=dev), db=torch.empty(l.k, device=dev))
+        state.append(t)
+    ws = torch.empty(max(ws_bytes // 4, 1), device=dev)
+    stream = torch.cuda.current_stream()
+
+    passes = ("fwd", "bwd_data", "bwd_filter", "bwd_bias")
+
+    def run_pass(t, name):
+        d = t["desc"]
+        if name == "fwd":
+            conv.conv_forward(d, t["x"], t["w"], t["b"], t["y"], ws, stream)
+        elif name == "bwd_data":
+            conv.conv_backward_data(d, t["w"], t["dy"], t["dx"], ws, stream)
+        elif name == "bwd_filter":
+            conv.conv_backward_filter(d, t["x"], t["dy"], t["dw"], 0.0, ws, stream)
+        else:
+            conv.conv_backward_bias(d, t["dy"], t["db"], 0.0, ws, stream)
+
+    def step(events=None):
+        for t in state:
+            for name in passes:
+                if events is not None:
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record(stream)
+                    run_pass(t, name)
+                    e1.record(stream)
+                    events.append((t["layer"].name, name, e0, e1))
+                else:
+                    run_pass(t, name)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly --steps steps, HIP events around every pass on the launch stream ----
+    events = []
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(events)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+
+    wall = t1 - t0
+    flop_step = 3 * sum(l.flop_per_pass for l in layers)
+    value = flop_step * args.steps / wall / 1e9
+    ms_per_step = wall / args.steps * 1e3
+
+    # per (layer, pass) average duration from the events
+    acc = {}
+    for lname, pname, e0, e1 in events:
+        acc.setdefault((lname, pname), []).append(e0.elapsed_time(e1))
+    per_layer = []
+    for t in state:
+        l = t["layer"]
+        row = {"layer": l.name, "gflop_per_pass": l.flop_per_pass / 1e9,
+               "kernels": conv.conv_desc_kernel_names(t["desc"])}
+        tot = 0.0
+        for name in passes:
+            ms = sum(acc[(l.name, name)]) / len(acc[(l.name, name)])
+            row[name + "_ms"] = round(ms, 5)
+            tot += ms
+            if name != "bwd_bias":
+                row[name + "_tflops"] = round(l.flop_per_pass / ms / 1e9, 2)
+        row["fwd_bwd_tflops"] = round(3 * l.flop_per_pass / tot / 1e9, 2)
+        row["fwd_bwd_frac_of_fp32_mfma_peak"] = round(3 * l.flop_per_pass / tot / 1e9 / PEAK_FP32_MFMA_TFLOPS, 4)
+        per_layer.append(row)
+
+    # dominant launch: the (layer, pass) with the largest average duration
+    (dl, dp), dms = max(((k, sum(v) / len(v)) for k, v in acc.items()), key=lambda kv: kv[1])
+    dlayer = workloads.BY_NAME[dl]
+    dstate = next(t for t in state if t["layer"].name == dl)
+    kernel_names = dict(kv.split("=") for kv in conv.conv_desc_kernel_names(dstate["desc"]).split(";"))
+    if dp == "bwd_bias":
+        bytes_launch = 4 * dlayer.n * dlayer.k * dlayer.out_hw * dlayer.out_hw
+        achieved = bytes_launch / (dms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                    "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": None}
+    else:
+        achieved = dlayer.flop_per_pass / (dms * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_FP32_MFMA_TFLOPS,
+                    "unit": "TFLOP/s", "frac": round(achieved / PEAK_FP32_MFMA_TFLOPS, 4), "traffic": None}
+    roofline.update({"kernel": kernel_names.get(dp, dp), "layer": dl, "pass": dp, "avg_ms": round(dms, 5),
+                     "algorithmic_gflop_per_launch": dlayer.flop_per_pass / 1e9})
+    traffic_file = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "hbm_traffic.json")
+    if os.path.exists(traffic_file):  # measured separately with rocprofv3 --pmc (see profiles/)
+        try:
+            tr = json.load(open(traffic_file))
+            roofline["traffic"] = tr.get(f"{dl}:{dp}")
+        except Exception:
+            pass
+
+    out = {
+        "metric": "conv fwd+bwd GFLOP/s (forward + backward data + backward filter + backward bias), fp32",
+        "value": round(value, 1), "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: layers " + ",".join(l.name for l in layers)
+                               + " (N=%d each), fwd+bwd_data+bwd_filter+bwd_bias, beta=0, bias=0" % layers[0].n,
+                   "frac_of_fp32_mfma_peak": round(value / 1e3 / PEAK_FP32_MFMA_TFLOPS, 4)},
+        "roofline": roofline,
+        "per_layer": per_layer,
+    }
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(layers, args.cpu_sample_images)
+    print(json.dumps(out))
+
+
+def cpu_baseline(layers, n_sample):
+    """The CPU oracle, as it stands, on the first n_sample images of each layer of the workload."""
+    import numpy as np
+
+    import oracle
+    from oracle import OracleParams
+    from paper_1810_02272_amd import workloads
+
+    flop = 0.0
+    secs = 0.0
+    for l in layers:
+        n = min(n_sample, l.n)
+        pd = l.params_dict()
+        pd["n"] = n
+        op = OracleParams(**pd)
+        x, w, b, dy = workloads.layer_inputs(l, bias="zero")
+        x, dy = x[:n].numpy().astype(np.float64), dy[:n].numpy().astype(np.float64)
+        w, b = w.numpy().astype(np.float64), b.numpy().astype(np.float64)
+        t0 = time.perf_counter()
+        oracle.forward(op, x, w, b)
+        oracle.backward_data(op, w, dy)
+        oracle.backward_filter(op, x, dy)
+        oracle.backward_bias(op, dy)
+        secs += time.perf_counter() - t0
+        flop += 3.0 * l.flop_per_pass * n / l.n
+    return {"value": round(flop / secs / 1e9, 3), "unit": "GFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"first {n_sample} images of each layer, fwd+bwd_data+bwd_filter+bwd_bias, "
+                      f"double-precision nested loops, {secs:.1f} s"}
+
+
+if __name__ == "__main__":
+    main()

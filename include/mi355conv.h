@@ -1,0 +1,111 @@
+/*
+ * mi355conv -- Caffe-semantics 2-D ConvolutionLayer for AMD MI355X (gfx950), fp32.
+ *
+ * The paper lists the convolution layer among the "vision layers" of its Table 1 and
+ * states in its Abstract that the stack follows C++ Caffe; its "General Architecture"
+ * section describes a low-level native library that owns the device work, is called
+ * with plain values and opaque handles, and never moves data off the GPU.  This header
+ * is that boundary for the convolution layer: plain C, opaque descriptor, device
+ * pointers in, device pointers out, no host<->device copies, no device allocation.
+ *
+ * Semantics (Cg = c/group, Kg = num_output/group, xz = x extended by zero):
+ *   OH = floor((h + 2 pad_h - dilation_h (kernel_h - 1) - 1) / stride_h) + 1, same for OW
+ *   forward         y[n,k,oh,ow] = bias[k] + sum_{c',i,j} w[k,c',i,j] *
+ *                     xz[n, (k / Kg) Cg + c', oh stride_h - pad_h + i dilation_h,
+ *                                             ow stride_w - pad_w + j dilation_w]
+ *                   (a cross-correlation: the kernel is not flipped)
+ *   backward data   dx = the transpose of the linear map x -> y applied to dy (overwrites dx)
+ *   backward filter dw[k,c',i,j] = beta dw[k,c',i,j] + sum_{n,oh,ow} dy[n,k,oh,ow] * xz[... same tap ...]
+ *   backward bias   db[k] = beta db[k] + sum_{n,oh,ow} dy[n,k,oh,ow]
+ * beta = 1 is Caffe's "parameter diffs accumulate until the solver applies them" rule
+ * (the paper's Appendix A/B training loops rely on it); beta = 0 overwrites and never
+ * reads the old contents (NaN-safe).
+ *
+ * Layouts: dense, last index fastest, fp32, DEVICE memory, 16-byte aligned bases:
+ *   x, dx : [n][c][h][w]          y, dy : [n][num_output][OH][OW]
+ *   w, dw : [num_output][c/group][kernel_h][kernel_w]        bias, db : [num_output]
+ * An output buffer must not overlap any input buffer or the workspace.
+ *
+ * Ownership: the caller owns every device buffer including the workspace; the library
+ * keeps no pointer after a call returns and allocates no device memory.  A conv_desc_t
+ * is host memory owned by the library from conv_desc_create to conv_desc_destroy; it is
+ * immutable and may be shared between threads.
+ *
+ * Execution: every pass is enqueued on the caller's HIP stream (`hip_stream` is a
+ * hipStream_t passed as void*; NULL = the default stream) and returns without
+ * synchronising.  Passes that use the workspace must not run concurrently on different
+ * streams with the same workspace.
+ *
+ * Errors: every function returns a conv_status_t (0 = success, negative = error); no
+ * exception, abort or printing crosses this boundary.  On error nothing is enqueued.
+ */
+#ifndef MI355CONV_H
+#define MI355CONV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  CONV_OK = 0,
+  CONV_EINVAL = -1,     /* null pointer, non-positive size, divisibility, bias/bias_term mismatch, beta not 0/1 */
+  CONV_ESHAPE = -2,     /* computed OH or OW < 1, or a tensor (or the workspace) of 2^30 or more elements:
+                           the kernels address every buffer with unsigned 32-bit byte offsets */
+  CONV_EWORKSPACE = -3, /* workspace null or smaller than conv_desc_workspace_bytes */
+  CONV_EHIP = -4        /* the HIP runtime refused a launch; see conv_last_hip_error */
+} conv_status_t;
+
+/* Caffe's convolution parameters plus the bottom blob shape (2-D spatial, channel axis 1). */
+typedef struct {
+  int32_t n, c, h, w;             /* bottom blob shape; n may be 0 (every pass is then a no-op) */
+  int32_t num_output;             /* K >= 1 */
+  int32_t kernel_h, kernel_w;     /* >= 1 */
+  int32_t stride_h, stride_w;     /* >= 1 */
+  int32_t pad_h, pad_w;           /* >= 0 */
+  int32_t dilation_h, dilation_w; /* >= 1 */
+  int32_t group;                  /* >= 1; c % group == 0 and num_output % group == 0 */
+  int32_t bias_term;              /* 0 or 1 */
+} conv_params_t;
+
+typedef struct conv_desc conv_desc_t;
+
+/*
+ * Validates `p`, computes OH/OW, picks the kernel variants and sizes the workspace.
+ * Host-only: touches no device.  *out is set only on success.
+ */
+int conv_desc_create(conv_desc_t** out, const conv_params_t* p);
+int conv_desc_destroy(conv_desc_t* d);
+/* Any of n, k, oh, ow may be NULL. */
+int conv_desc_output_shape(const conv_desc_t* d, int32_t* n, int32_t* k, int32_t* oh, int32_t* ow);
+/* Bytes of device workspace sufficient for any of the four passes (may be 0). */
+int conv_desc_workspace_bytes(const conv_desc_t* d, size_t* bytes);
+
+/* y = bias + w (*) x.  `bias` must be NULL iff bias_term == 0.  The bias add is fused. */
+int conv_forward(const conv_desc_t* d, const float* x, const float* w, const float* bias, float* y,
+                 void* ws, size_t ws_bytes, void* hip_stream);
+
+/* dx = transpose-of-forward applied to dy; every element of dx is written. */
+int conv_backward_data(const conv_desc_t* d, const float* w, const float* dy, float* dx,
+                       void* ws, size_t ws_bytes, void* hip_stream);
+
+/* dw = beta*dw + filter gradient; beta must be exactly 0 or 1.  Deterministic (no float atomics). */
+int conv_backward_filter(const conv_desc_t* d, const float* x, const float* dy, float* dw, float beta,
+                         void* ws, size_t ws_bytes, void* hip_stream);
+
+/* db = beta*db + sum of dy over n, oh, ow; CONV_EINVAL on a bias_term == 0 descriptor. */
+int conv_backward_bias(const conv_desc_t* d, const float* dy, float* db, float beta,
+                       void* ws, size_t ws_bytes, void* hip_stream);
+
+const char* conv_status_string(int status);
+/* hipError_t value of the most recent CONV_EHIP on the calling thread (0 if none). */
+int conv_last_hip_error(void);
+/* Names of the kernel variants the descriptor selected, for logs and profiles ("fwd=...;bwd_data=...;..."). */
+const char* conv_desc_kernel_names(const conv_desc_t* d);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MI355CONV_H */

@@ -1,0 +1,22 @@
+"""MI355X-native Caffe-semantics convolution layer (fp32): thin Python binding over libmi355conv.so.
+
+The package holds the HIP sources (``csrc/``), the build step (``build.py``), the ctypes binding
+(``binding.py``: same names as the C entry points, argument marshalling only) and the seeded
+synthetic workloads (``workloads.py``).  There is no CPU fallback: without the built library, or
+without a GPU for the compute calls, the binding raises.
+"""
+from .binding import (  # noqa: F401
+    ConvError,
+    ConvParams,
+    conv_backward_bias,
+    conv_backward_data,
+    conv_backward_filter,
+    conv_desc_create,
+    conv_desc_destroy,
+    conv_desc_kernel_names,
+    conv_desc_output_shape,
+    conv_desc_workspace_bytes,
+    conv_forward,
+    conv_status_string,
+    library_path,
+)

@@ -1,0 +1,442 @@
+// Host side of the C boundary: parameter validation, shape arithmetic, kernel-variant choice,
+// workspace sizing and the five entry points.  No device memory is allocated anywhere here, and
+// conv_desc_create touches no device at all (it also runs on machines without a GPU).
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+
+#include "internal.h"
+
+using namespace mi355conv;
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+constexpr int64_t kMaxElems = (int64_t)1 << 30;  // 32-bit byte offsets in the kernels
+
+int64_t floor_div(int64_t a, int64_t b) {
+  int64_t q = a / b;
+  if ((a % b) != 0 && ((a < 0) != (b < 0))) --q;
+  return q;
+}
+
+int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+int64_t round_up(int64_t a, int64_t b) { return ceil_div(a, b) * b; }
+
+// Smallest padded row count wins; ties go to the larger tile.
+int32_t pick_corr_tile(int32_t rows) {
+  int32_t best = -1;
+  int64_t best_pad = 0, best_bm = 0;
+  for (int32_t t = 0; t < CORR_TILE_COUNT; ++t) {
+    int32_t bm, bn, bk;
+    corr_tile_shape(t, &bm, &bn, &bk);
+    const int64_t pad = round_up(rows, bm);
+    if (best < 0 || pad < best_pad || (pad == best_pad && bm > best_bm)) {
+      best = t;
+      best_pad = pad;
+      best_bm = bm;
+    }
+  }
+  return best;
+}
+
+int32_t pick_wgrad_tile(int32_t rows, int32_t kred) {
+  int32_t best = -1;
+  int64_t best_work = 0, best_area = 0;
+  for (int32_t t = 0; t < WGRAD_TILE_COUNT; ++t) {
+    int32_t bm, bn, bk;
+    wgrad_tile_shape(t, &bm, &bn, &bk);
+    int64_t work = round_up(rows, bm) * round_up(kred, bn);
+    const int64_t area = (int64_t)bm * bn;
+    // a narrower tile must save at least 3 % of the padded work to be worth its extra LDS traffic
+    if (best < 0 || work * 100 < best_work * 97 || (work <= best_work && area > best_area)) {
+      best = t;
+      best_work = work;
+      best_area = area;
+    }
+  }
+  return best;
+}
+
+int hip_fail(int e) {
+  g_last_hip_error = e;
+  return CONV_EHIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
+  if (!out || !pp) return CONV_EINVAL;
+  const conv_params_t p = *pp;
+  if (p.n < 0 || p.c < 1 || p.h < 1 || p.w < 1 || p.num_output < 1) return CONV_EINVAL;
+  if (p.kernel_h < 1 || p.kernel_w < 1 || p.stride_h < 1 || p.stride_w < 1) return CONV_EINVAL;
+  if (p.pad_h < 0 || p.pad_w < 0 || p.dilation_h < 1 || p.dilation_w < 1) return CONV_EINVAL;
+  if (p.group < 1 || p.c % p.group != 0 || p.num_output % p.group != 0) return CONV_EINVAL;
+  if (p.bias_term != 0 && p.bias_term != 1) return CONV_EINVAL;
+
+  const int64_t ext_h = (int64_t)p.dilation_h * (p.kernel_h - 1) + 1;
+  const int64_t ext_w = (int64_t)p.dilation_w * (p.kernel_w - 1) + 1;
+  const int64_t OH = floor_div((int64_t)p.h + 2 * (int64_t)p.pad_h - ext_h, p.stride_h) + 1;
+  const int64_t OW = floor_div((int64_t)p.w + 2 * (int64_t)p.pad_w - ext_w, p.stride_w) + 1;
+  if (OH < 1 || OW < 1) return CONV_ESHAPE;
+  // tap offsets are packed into 16 bits, coordinates into 28
+  if (ext_h > 32768 || ext_w > 32768 || p.pad_h > (1 << 20) || p.pad_w > (1 << 20)) return CONV_ESHAPE;
+  if (p.h > (1 << 24) || p.w > (1 << 24) || p.stride_h > (1 << 20) || p.stride_w > (1 << 20)) return CONV_ESHAPE;
+
+  const int64_t N = p.n, C = p.c, H = p.h, W = p.w, K = p.num_output, G = p.group;
+  const int64_t Cg = C / G, Kg = K / G;
+  const int64_t kred = Cg * p.kernel_h * p.kernel_w;
+  const int64_t x_elems = N * C * H * W, y_elems = N * K * OH * OW, w_elems = K * kred;
+  if (C * H * W >= kMaxElems || K * OH * OW >= kMaxElems) return CONV_ESHAPE;
+  if (x_elems >= kMaxElems || y_elems >= kMaxElems || w_elems >= kMaxElems) return CONV_ESHAPE;
+
+  conv_desc* d = new (std::nothrow) conv_desc;
+  if (!d) return CONV_EINVAL;
+  memset(d, 0, sizeof(*d));
+  d->p = p;
+  d->OH = (int32_t)OH;
+  d->OW = (int32_t)OW;
+  d->Cg = (int32_t)Cg;
+  d->Kg = (int32_t)Kg;
+
+  int32_t bm, bn, bk;
+
+  // ---- forward: rows = output channels of a group, k = (c, i, j), columns = (n, oh, ow) ----
+  {
+    d->fwd_tile = pick_corr_tile((int32_t)Kg);
+    corr_tile_shape(d->fwd_tile, &bm, &bn, &bk);
+    CorrArgs& a = d->fwd;
+    a.ncols = (int32_t)(N * OH * OW);
+    a.P = (int32_t)(OH * OW);
+    a.PW = (int32_t)OW;
+    a.mP = make_magic(a.P);
+    a.mPW = make_magic(a.PW);
+    a.IH = p.h;
+    a.IW = p.w;
+    a.IHW = p.h * p.w;
+    a.in_img_stride = (int32_t)(C * H * W);
+    a.in_grp_stride = (int32_t)(Cg * H * W);
+    a.TW = p.kernel_w;
+    a.THW = p.kernel_h * p.kernel_w;
+    a.mTW = make_magic(a.TW);
+    a.mTHW = make_magic(a.THW);
+    a.sh = p.stride_h;
+    a.sw = p.stride_w;
+    a.dh = p.dilation_h;
+    a.dw = p.dilation_w;
+    a.ph = p.pad_h;
+    a.pw = p.pad_w;
+    a.Kred = (int32_t)kred;
+    a.KP = (int32_t)round_up(kred, bk);
+    a.Mrows = (int32_t)Kg;
+    a.MP = (int32_t)round_up(Kg, bm);
+    a.RSh = a.RSw = a.RShw = 1;
+    a.mRSw = make_magic(1);
+    a.mRShw = make_magic(1);
+    a.opad_h = a.opad_w = 0;
+    a.OHd = (int32_t)OH;
+    a.OWd = (int32_t)OW;
+    a.out_img_stride = (int32_t)(K * OH * OW);
+    a.chan_per_grp = (int32_t)Kg;
+    a.G = (int32_t)G;
+    a.m_tiles = a.MP / bm;
+    a.col_tiles = (int32_t)ceil_div(a.ncols, bn);
+    PackArgs& k = d->fwd_pack;
+    k.mode = 0;
+    k.G = (int32_t)G;
+    k.Kg = (int32_t)Kg;
+    k.Cg = (int32_t)Cg;
+    k.kh = p.kernel_h;
+    k.kw = p.kernel_w;
+    k.sh = k.sw = k.dh = k.dw = 1;
+    k.Qh = k.Qw = 1;
+    k.Kred = a.Kred;
+    k.KP = a.KP;
+    k.Mrows = a.Mrows;
+    k.MP = a.MP;
+    const int64_t pack_elems = G * (int64_t)a.KP * a.MP;
+    if (pack_elems >= kMaxElems || (int64_t)G * a.m_tiles * a.col_tiles >= ((int64_t)1 << 31)) {
+      delete d;
+      return CONV_ESHAPE;
+    }
+    d->fwd_ws = (size_t)pack_elems * 4;
+  }
+
+  // ---- backward data: a stride-1 correlation over dy whose rows are (c, row phase, column
+  // phase) of dx -- input position h + pad = stride*a + rh collects the taps i with
+  // i*dilation = stride*q + rh from dy row a - q, q = 0 .. Q-1 ----
+  {
+    const int64_t Qh = ((int64_t)p.kernel_h - 1) * p.dilation_h / p.stride_h + 1;
+    const int64_t Qw = ((int64_t)p.kernel_w - 1) * p.dilation_w / p.stride_w + 1;
+    const int64_t Ah = (H - 1 + p.pad_h) / p.stride_h + 1;
+    const int64_t Aw = (W - 1 + p.pad_w) / p.stride_w + 1;
+    const int64_t rows = Cg * p.stride_h * p.stride_w;
+    const int64_t kred_b = Kg * Qh * Qw;
+    if (rows >= ((int64_t)1 << 24) || N * Ah * Aw >= ((int64_t)1 << 31) || kred_b >= kMaxElems) {
+      delete d;
+      return CONV_ESHAPE;
+    }
+    d->bwd_tile = pick_corr_tile((int32_t)rows);
+    corr_tile_shape(d->bwd_tile, &bm, &bn, &bk);
+    CorrArgs& a = d->bwd;
+    a.ncols = (int32_t)(N * Ah * Aw);
+    a.P = (int32_t)(Ah * Aw);
+    a.PW = (int32_t)Aw;
+    a.mP = make_magic(a.P);
+    a.mPW = make_magic(a.PW);
+    a.IH = (int32_t)OH;
+    a.IW = (int32_t)OW;
+    a.IHW = (int32_t)(OH * OW);
+    a.in_img_stride = (int32_t)(K * OH * OW);
+    a.in_grp_stride = (int32_t)(Kg * OH * OW);
+    a.TW = (int32_t)Qw;
+    a.THW = (int32_t)(Qh * Qw);
+    a.mTW = make_magic(a.TW);
+    a.mTHW = make_magic(a.THW);
+    a.sh = a.sw = a.dh = a.dw = 1;
+    a.ph = (int32_t)(Qh - 1);
+    a.pw = (int32_t)(Qw - 1);
+    a.Kred = (int32_t)kred_b;
+    a.KP = (int32_t)round_up(kred_b, bk);
+    a.Mrows = (int32_t)rows;
+    a.MP = (int32_t)round_up(rows, bm);
+    a.RSh = p.stride_h;
+    a.RSw = p.stride_w;
+    a.RShw = p.stride_h * p.stride_w;
+    a.mRSw = make_magic(a.RSw);
+    a.mRShw = make_magic(a.RShw);
+    a.opad_h = p.pad_h;
+    a.opad_w = p.pad_w;
+    a.OHd = p.h;
+    a.OWd = p.w;
+    a.out_img_stride = (int32_t)(C * H * W);
+    a.chan_per_grp = (int32_t)Cg;
+    a.G = (int32_t)G;
+    a.m_tiles = a.MP / bm;
+    a.col_tiles = (int32_t)ceil_div(a.ncols, bn);
+    PackArgs& k = d->bwd_pack;
+    k.mode = 1;
+    k.G = (int32_t)G;
+    k.Kg = (int32_t)Kg;
+    k.Cg = (int32_t)Cg;
+    k.kh = p.kernel_h;
+    k.kw = p.kernel_w;
+    k.sh = p.stride_h;
+    k.sw = p.stride_w;
+    k.dh = p.dilation_h;
+    k.dw = p.dilation_w;
+    k.Qh = (int32_t)Qh;
+    k.Qw = (int32_t)Qw;
+    k.Kred = a.Kred;
+    k.KP = a.KP;
+    k.Mrows = a.Mrows;
+    k.MP = a.MP;
+    const int64_t pack_elems = G * (int64_t)a.KP * a.MP;
+    if (pack_elems >= kMaxElems || (int64_t)G * a.m_tiles * a.col_tiles >= ((int64_t)1 << 31)) {
+      delete d;
+      return CONV_ESHAPE;
+    }
+    d->bwd_ws = (size_t)pack_elems * 4;
+  }
+
+  // ---- backward filter: rows = output channels, columns = (c, i, j), reduction over (n, oh, ow)
+  {
+    d->wg_tile = pick_wgrad_tile((int32_t)Kg, (int32_t)kred);
+    wgrad_tile_shape(d->wg_tile, &bm, &bn, &bk);
+    WgradArgs& a = d->wg;
+    a.ncols = (int32_t)(N * OH * OW);
+    a.P = (int32_t)(OH * OW);
+    a.PW = (int32_t)OW;
+    a.mP = make_magic(a.P);
+    a.mPW = make_magic(a.PW);
+    a.Kg = (int32_t)Kg;
+    a.Ktot = (int32_t)K;
+    a.Cg = (int32_t)Cg;
+    a.C = p.c;
+    a.H = p.h;
+    a.W = p.w;
+    a.HW = p.h * p.w;
+    a.kw = p.kernel_w;
+    a.khw = p.kernel_h * p.kernel_w;
+    a.mKW = make_magic(a.kw);
+    a.mKHW = make_magic(a.khw);
+    a.sh = p.stride_h;
+    a.sw = p.stride_w;
+    a.dh = p.dilation_h;
+    a.dw = p.dilation_w;
+    a.ph = p.pad_h;
+    a.pw = p.pad_w;
+    a.Kred = (int32_t)kred;
+    a.G = (int32_t)G;
+    a.m_tiles = (int32_t)ceil_div(Kg, bm);
+    a.n_tiles = (int32_t)ceil_div(kred, bn);
+    // split the reduction so that the grid has about four workgroups per compute unit, each split
+    // at least four k tiles long, and the partials stay below 256 MiB
+    const int64_t tiles = G * a.m_tiles * a.n_tiles;
+    int64_t S = ceil_div(1024, tiles);
+    const int64_t max_by_len = ceil_div((int64_t)a.ncols, 4 * bk);
+    const int64_t max_by_ws = ((int64_t)64 << 20) / (w_elems > 0 ? w_elems : 1);
+    if (S > max_by_len) S = max_by_len;
+    if (S > max_by_ws) S = max_by_ws;
+    if (S < 1) S = 1;
+    a.cols_per_split = (int32_t)round_up(ceil_div((int64_t)a.ncols > 0 ? a.ncols : 1, S), bk);
+    a.S = (int32_t)ceil_div((int64_t)a.ncols > 0 ? a.ncols : 1, a.cols_per_split);
+    if (a.S * w_elems >= kMaxElems || tiles * a.S >= ((int64_t)1 << 31)) {
+      delete d;
+      return CONV_ESHAPE;
+    }
+    d->wg_ws = (size_t)a.S * (size_t)w_elems * 4;
+  }
+
+  // ---- backward bias ----
+  {
+    BiasGradArgs& a = d->bg;
+    a.N = p.n;
+    a.K = p.num_output;
+    a.P = (int32_t)(OH * OW);
+    int64_t S = ceil_div(2048, K);
+    if (S > N) S = N;
+    if (S < 1) S = 1;
+    a.n_per_split = (int32_t)ceil_div(N > 0 ? N : 1, S);
+    a.S = (int32_t)ceil_div(N > 0 ? N : 1, a.n_per_split);
+    d->bg_ws = p.bias_term ? (size_t)a.S * K * 4 : 0;
+  }
+
+  d->ws_bytes = d->fwd_ws;
+  if (d->bwd_ws > d->ws_bytes) d->ws_bytes = d->bwd_ws;
+  if (d->wg_ws > d->ws_bytes) d->ws_bytes = d->wg_ws;
+  if (d->bg_ws > d->ws_bytes) d->ws_bytes = d->bg_ws;
+  snprintf(d->names, sizeof(d->names), "fwd=%s;bwd_data=%s;bwd_filter=%s(S=%d);bwd_bias=bias_grad(S=%d)",
+           corr_tile_name(d->fwd_tile), corr_tile_name(d->bwd_tile), wgrad_tile_name(d->wg_tile), d->wg.S, d->bg.S);
+  *out = d;
+  return CONV_OK;
+}
+
+int conv_desc_destroy(conv_desc_t* d) {
+  if (!d) return CONV_EINVAL;
+  delete d;
+  return CONV_OK;
+}
+
+int conv_desc_output_shape(const conv_desc_t* d, int32_t* n, int32_t* k, int32_t* oh, int32_t* ow) {
+  if (!d) return CONV_EINVAL;
+  if (n) *n = d->p.n;
+  if (k) *k = d->p.num_output;
+  if (oh) *oh = d->OH;
+  if (ow) *ow = d->OW;
+  return CONV_OK;
+}
+
+int conv_desc_workspace_bytes(const conv_desc_t* d, size_t* bytes) {
+  if (!d || !bytes) return CONV_EINVAL;
+  *bytes = d->ws_bytes;
+  return CONV_OK;
+}
+
+const char* conv_desc_kernel_names(const conv_desc_t* d) { return d ? d->names : ""; }
+
+int conv_forward(const conv_desc_t* d, const float* x, const float* w, const float* bias, float* y, void* ws,
+                 size_t ws_bytes, void* hip_stream) {
+  if (!d || !w) return CONV_EINVAL;
+  if ((d->p.bias_term != 0) != (bias != nullptr)) return CONV_EINVAL;
+  if (d->p.n == 0) return CONV_OK;  // empty blobs: nothing to read or write
+  if (!x || !y) return CONV_EINVAL;
+  if (d->fwd_ws > 0 && (!ws || ws_bytes < d->fwd_ws)) return CONV_EWORKSPACE;
+  PackArgs k = d->fwd_pack;
+  k.w = w;
+  k.A = static_cast<float*>(ws);
+  int e = launch_pack(k, hip_stream);
+  if (e) return hip_fail(e);
+  CorrArgs a = d->fwd;
+  a.A = k.A;
+  a.in = x;
+  a.bias = bias;
+  a.out = y;
+  e = launch_corr(d->fwd_tile, a, hip_stream);
+  return e ? hip_fail(e) : CONV_OK;
+}
+
+int conv_backward_data(const conv_desc_t* d, const float* w, const float* dy, float* dx, void* ws, size_t ws_bytes,
+                       void* hip_stream) {
+  if (!d || !w) return CONV_EINVAL;
+  if (d->p.n == 0) return CONV_OK;
+  if (!dy || !dx) return CONV_EINVAL;
+  if (d->bwd_ws > 0 && (!ws || ws_bytes < d->bwd_ws)) return CONV_EWORKSPACE;
+  PackArgs k = d->bwd_pack;
+  k.w = w;
+  k.A = static_cast<float*>(ws);
+  int e = launch_pack(k, hip_stream);
+  if (e) return hip_fail(e);
+  CorrArgs a = d->bwd;
+  a.A = k.A;
+  a.in = dy;
+  a.bias = nullptr;
+  a.out = dx;
+  e = launch_corr(d->bwd_tile, a, hip_stream);
+  return e ? hip_fail(e) : CONV_OK;
+}
+
+int conv_backward_filter(const conv_desc_t* d, const float* x, const float* dy, float* dw, float beta, void* ws,
+                         size_t ws_bytes, void* hip_stream) {
+  if (!d || !dw) return CONV_EINVAL;
+  if (!(beta == 0.f || beta == 1.f)) return CONV_EINVAL;
+  const bool empty = d->p.n == 0;  // the gradient sum is empty: dw = beta*dw
+  if (!empty && (!x || !dy)) return CONV_EINVAL;
+  if (!empty && d->wg_ws > 0 && (!ws || ws_bytes < d->wg_ws)) return CONV_EWORKSPACE;
+  WgradArgs a = d->wg;
+  a.dy = dy;
+  a.x = x;
+  a.part = static_cast<float*>(ws);
+  int e = empty ? 0 : launch_wgrad(d->wg_tile, a, hip_stream);
+  if (e) return hip_fail(e);
+  ReduceArgs r;
+  r.part = a.part;
+  r.dst = dw;
+  r.count = (int32_t)((int64_t)d->p.num_output * d->wg.Kred);
+  r.S = empty ? 0 : a.S;
+  r.beta = beta;
+  e = launch_reduce(r, hip_stream);
+  return e ? hip_fail(e) : CONV_OK;
+}
+
+int conv_backward_bias(const conv_desc_t* d, const float* dy, float* db, float beta, void* ws, size_t ws_bytes,
+                       void* hip_stream) {
+  if (!d || !db) return CONV_EINVAL;
+  if (!d->p.bias_term) return CONV_EINVAL;
+  if (!(beta == 0.f || beta == 1.f)) return CONV_EINVAL;
+  const bool empty = d->p.n == 0;
+  if (!empty && !dy) return CONV_EINVAL;
+  if (!empty && (!ws || ws_bytes < d->bg_ws)) return CONV_EWORKSPACE;
+  BiasGradArgs a = d->bg;
+  a.dy = dy;
+  a.part = static_cast<float*>(ws);
+  int e = empty ? 0 : launch_bias_grad(a, hip_stream);
+  if (e) return hip_fail(e);
+  ReduceArgs r;
+  r.part = a.part;
+  r.dst = db;
+  r.count = d->p.num_output;
+  r.S = empty ? 0 : a.S;
+  r.beta = beta;
+  e = launch_reduce(r, hip_stream);
+  return e ? hip_fail(e) : CONV_OK;
+}
+
+const char* conv_status_string(int status) {
+  switch (status) {
+    case CONV_OK: return "success";
+    case CONV_EINVAL: return "invalid argument";
+    case CONV_ESHAPE: return "unsupported shape (empty output or a tensor too large for 32-bit offsets)";
+    case CONV_EWORKSPACE: return "workspace missing or too small";
+    case CONV_EHIP: return "HIP launch failed";
+    default: return "unknown status";
+  }
+}
+
+int conv_last_hip_error(void) { return g_last_hip_error; }
+
+}  // extern "C"

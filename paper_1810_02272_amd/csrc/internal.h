@@ -1,0 +1,166 @@
+// Internal declarations shared by the host-side descriptor code and the gfx950 kernels.
+// Nothing here is part of the public boundary (that is include/mi355conv.h).
+#pragma once
+
+#include <stddef.h>
+#include <stdint.h>
+
+#include "mi355conv.h"
+
+namespace mi355conv {
+
+// Unsigned division by a run-time constant with one multiply-high, one add and one shift
+// (Granlund-Montgomery round-up method).  Exact for dividends below 2^31.
+struct Magic {
+  uint32_t mul;
+  uint32_t shift;
+};
+
+inline Magic make_magic(uint32_t d) {
+  Magic m;
+  uint32_t s = 0;
+  while ((1ull << s) < d) ++s;
+  m.shift = s;
+  m.mul = (uint32_t)(((1ull << 32) * ((1ull << s) - d)) / d + 1);
+  return m;
+}
+
+// ---------------------------------------------------------------------------------------------
+// "Correlation" kernels: forward and backward-data share one implicit-GEMM kernel
+//   D[m][col] = sum_kk A[kk][m] * gather(in)[kk][col]
+// with kk = (channel, tap_h, tap_w), col = (image, a, b), and a table-driven epilogue that
+// scatters row m / column col to its place in the output blob.
+struct CorrArgs {
+  const float* A;     // packed operand, [G][KP][MP] floats, zero padded
+  const float* in;    // blob that is gathered, [N][in_chan_total][IH][IW]
+  const float* bias;  // per output channel, or null
+  float* out;
+  // column space
+  int32_t ncols, P, PW;  // ncols = N*P, P = PH*PW
+  Magic mP, mPW;
+  // gather geometry: row = a*sh - ph + i*dh, column = b*sw - pw + j*dw
+  int32_t IH, IW, IHW;
+  int32_t in_img_stride;  // elements between images of `in`
+  int32_t in_grp_stride;  // elements between the channel blocks of two groups
+  int32_t TW, THW;        // taps per row, taps per channel
+  Magic mTW, mTHW;
+  int32_t sh, sw, dh, dw, ph, pw;
+  int32_t Kred, KP;   // reduction length and its padded size (multiple of the k tile)
+  int32_t Mrows, MP;  // rows per group and padded rows (multiple of the m tile)
+  // epilogue: row m = (c*RSh + rh)*RSw + rw lands at channel g*chan_per_grp + c,
+  // spatial (a*RSh + rh - opad_h, b*RSw + rw - opad_w) of an [N][*][OHd][OWd] blob
+  int32_t RSw, RShw;
+  Magic mRSw, mRShw;
+  int32_t RSh;
+  int32_t opad_h, opad_w;
+  int32_t OHd, OWd;
+  int32_t out_img_stride;
+  int32_t chan_per_grp;
+  // grid
+  int32_t G, m_tiles, col_tiles;
+};
+
+// Packs the weights into the A operand of the correlation kernel.
+//   mode 0 (forward): A[g][kk][m] = w[g*Kg + m][kk]
+//   mode 1 (backward data): rows m = (c, rh, rw), kk = (k, qh', qw'); the entry is
+//     w[g*Kg + k][c][i][j] with i*dil_h = stride_h*(Qh-1-qh') + rh (and likewise j), else 0.
+struct PackArgs {
+  const float* w;
+  float* A;
+  int32_t mode;
+  int32_t G, Kg, Cg, kh, kw;
+  int32_t sh, sw, dh, dw;
+  int32_t Qh, Qw;
+  int32_t Kred, KP, Mrows, MP;
+};
+
+// Backward filter: part[s][g][k][nn] = sum over the split's columns of dy * gathered x.
+struct WgradArgs {
+  const float* dy;
+  const float* x;
+  float* part;
+  int32_t ncols, P, PW;
+  Magic mP, mPW;
+  int32_t Kg, Ktot;
+  int32_t Cg, C, H, W, HW;
+  int32_t kw, khw;
+  Magic mKW, mKHW;
+  int32_t sh, sw, dh, dw, ph, pw;
+  int32_t Kred;
+  int32_t cols_per_split, S;
+  int32_t G, m_tiles, n_tiles;
+};
+
+struct ReduceArgs {
+  const float* part;  // [S][count]
+  float* dst;         // [count]
+  int32_t count, S;
+  float beta;
+};
+
+struct BiasGradArgs {
+  const float* dy;  // [N][K][P]
+  float* part;      // [K][S]
+  int32_t N, K, P;
+  int32_t S;        // splits over the images
+  int32_t n_per_split;
+};
+
+// Tile variants, chosen once per descriptor.
+enum CorrTile : int32_t {
+  CORR_128x128 = 0,  // 32x32x2 MFMA, 2x2 waves of 64x64
+  CORR_96x128,       // 32x32x2, 1x4 waves of 96x32
+  CORR_64x128,       // 32x32x2, 1x4 waves of 64x32
+  CORR_32x256,       // 32x32x2, 1x4 waves of 32x64
+  CORR_48x256,       // 16x16x4, 1x4 waves of 48x64
+  CORR_16x256,       // 16x16x4, 1x4 waves of 16x64
+  CORR_TILE_COUNT
+};
+enum WgradTile : int32_t {
+  WGRAD_128x128 = 0,  // 2x2 waves of 64x64
+  WGRAD_96x128,       // 1x4 waves of 96x32
+  WGRAD_64x128,       // 1x4 waves of 64x32
+  WGRAD_32x128,       // 1x4 waves of 32x32
+  WGRAD_128x64,       // 2x2 waves of 64x32
+  WGRAD_TILE_COUNT
+};
+
+void corr_tile_shape(int32_t tile, int32_t* bm, int32_t* bn, int32_t* bk);
+void wgrad_tile_shape(int32_t tile, int32_t* bm, int32_t* bn, int32_t* bk);
+const char* corr_tile_name(int32_t tile);
+const char* wgrad_tile_name(int32_t tile);
+
+// Launchers (defined next to the kernels).  Each returns the hipError_t of the launch as int.
+int launch_pack(const PackArgs& a, void* stream);
+int launch_corr(int32_t tile, const CorrArgs& a, void* stream);
+int launch_wgrad(int32_t tile, const WgradArgs& a, void* stream);
+int launch_reduce(const ReduceArgs& a, void* stream);
+int launch_bias_grad(const BiasGradArgs& a, void* stream);
+
+}  // namespace mi355conv
+
+// The descriptor: everything that can be decided from the parameters alone.
+struct conv_desc {
+  conv_params_t p;
+  int32_t OH, OW;
+  int32_t Cg, Kg;
+  // forward
+  int32_t fwd_tile;
+  mi355conv::CorrArgs fwd;  // pointers left null
+  mi355conv::PackArgs fwd_pack;
+  size_t fwd_ws;
+  // backward data
+  int32_t bwd_tile;
+  mi355conv::CorrArgs bwd;
+  mi355conv::PackArgs bwd_pack;
+  size_t bwd_ws;
+  // backward filter
+  int32_t wg_tile;
+  mi355conv::WgradArgs wg;
+  size_t wg_ws;
+  // backward bias
+  mi355conv::BiasGradArgs bg;
+  size_t bg_ws;
+  size_t ws_bytes;
+  char names[256];
+};

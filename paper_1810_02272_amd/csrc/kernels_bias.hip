@@ -1,0 +1,62 @@
+// Bias gradient of the Caffe-semantics convolution layer (paper Table 1):
+//   db[k] = beta*db[k] + sum over n, oh, ow of dy[n,k,oh,ow]
+// One read of dy, so HBM-bound.  Stage 1: grid (K, S) -- each workgroup sums channel k over a
+// slice of the batch with a wave-level DPP reduction and writes part[s][k]; stage 2 (the shared
+// reduce kernel) adds the S partials in order and applies beta.
+#include <hip/hip_runtime.h>
+
+#include "device_utils.h"
+#include "internal.h"
+
+namespace mi355conv {
+
+namespace {
+
+// Sum over the 64 lanes of a wave; every lane of row 0 returns the total.
+__device__ __forceinline__ float wave_sum(float v) {
+  // within quads: xor 1, xor 2; within rows of 16: half mirror, mirror
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, false));
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, false));
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xF, 0xF, false));
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x140, 0xF, 0xF, false));
+  // the four row sums
+  const int iv = __builtin_bit_cast(int, v);
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 0)) +
+         __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 16)) +
+         __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 32)) +
+         __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 48));
+}
+
+__global__ __launch_bounds__(256) void bias_grad_kernel(const BiasGradArgs a) {
+  __shared__ float wsum[4];
+  const int k = blockIdx.x, s = blockIdx.y;
+  const int n0 = s * a.n_per_split;
+  int n1 = n0 + a.n_per_split;
+  if (n1 > a.N) n1 = a.N;
+  // four independent accumulators per thread keep several loads in flight
+  float acc0 = 0.f, acc1 = 0.f, acc2 = 0.f, acc3 = 0.f;
+  for (int n = n0; n < n1; ++n) {
+    const float* src = a.dy + ((size_t)n * a.K + k) * a.P;
+    int p = threadIdx.x;
+    for (; p + 768 < a.P; p += 1024) {
+      acc0 += src[p];
+      acc1 += src[p + 256];
+      acc2 += src[p + 512];
+      acc3 += src[p + 768];
+    }
+    for (; p < a.P; p += 256) acc0 += src[p];
+  }
+  const float w = wave_sum((acc0 + acc1) + (acc2 + acc3));
+  if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = w;
+  __syncthreads();
+  if (threadIdx.x == 0) a.part[(size_t)s * a.K + k] = (wsum[0] + wsum[1]) + (wsum[2] + wsum[3]);
+}
+
+}  // namespace
+
+int launch_bias_grad(const BiasGradArgs& a, void* stream) {
+  hipLaunchKernelGGL(bias_grad_kernel, dim3(a.K, a.S), dim3(256), 0, (hipStream_t)stream, a);
+  return (int)hipGetLastError();
+}
+
+}  // namespace mi355conv

@@ -1,0 +1,349 @@
+// Implicit-GEMM correlation kernel for gfx950, used by the forward pass and (through the
+// sub-pixel rewriting of the transposed map) by the backward-data pass of the Caffe-semantics
+// convolution layer (paper Table 1, "vision layers"; lowering + GEMM + bias are the steps the
+// low-level math library of the paper's "General Architecture" section performs).
+//
+//   D[m][col] = sum_kk A[kk][m] * B[kk][col]
+//   B[kk][col] = in[n, g*Cg + c, a*sh - ph + i*dh, b*sw - pw + j*dw]  (0 outside the image)
+//   kk = (c, i, j), col = (n, a, b)
+//
+// B is never materialised: each workgroup gathers BK x BN elements of it straight from the NCHW
+// blob into LDS, double buffered, while the fp32 MFMA pipe works on the previous chunk.  A is the
+// weight matrix, packed beforehand into k-major zero-padded form so that its tiles are plain
+// 16-byte row copies.  The epilogue adds the bias and scatters each accumulator through two
+// small LDS tables (row -> channel/sub-pixel offset, column -> image/pixel offset), which is
+// what lets one kernel serve both passes.
+#include <hip/hip_runtime.h>
+
+#include "device_utils.h"
+#include "internal.h"
+
+namespace mi355conv {
+
+namespace {
+
+constexpr int kThreads = 256;
+
+template <int MT, int MB, int NB, int WM, int WN, int BK>
+struct CorrCfg {
+  static constexpr int BM = WM * MB * MT;
+  static constexpr int BN = WN * NB * MT;
+  // Leading dimensions congruent to 16 mod 32 floats: the 16-wide MFMA operand read touches two
+  // k rows per half wave, and this keeps the two rows on disjoint banks.
+  static constexpr int LDA = BM + ((BM % 32 == 16) ? 0 : 16);
+  static constexpr int LDB = BN + ((BN % 32 == 16) ? 0 : 16);
+  static constexpr int RPW = BK / 4;   // gathered k rows per wave and chunk
+  static constexpr int CPL = BN / 64;  // gathered columns per lane
+  static constexpr int A_F4 = BK * BM / 4;
+  static constexpr int A_PER = (A_F4 + kThreads - 1) / kThreads;
+  static constexpr int STAGE = BK * (LDA + LDB);  // floats per pipeline stage
+  static constexpr int SMEM = 2 * STAGE;
+  static_assert(WM * WN == 4, "four waves per workgroup");
+  static_assert(BN % 64 == 0 && BK % 4 == 0 && BM % 4 == 0, "tile shape");
+  static_assert(RPW * CPL <= 32, "validity bits are kept in one register");
+  static_assert(4 * BM + 3 * BN <= SMEM, "epilogue tables reuse the pipeline buffers");
+};
+
+template <int MT, int MB, int NB, int WM, int WN, int BK>
+__global__ __launch_bounds__(kThreads) void corr_kernel(const CorrArgs a) {
+  using C = CorrCfg<MT, MB, NB, WM, WN, BK>;
+  using M = Mfma<MT>;
+  constexpr int BM = C::BM, BN = C::BN, LDA = C::LDA, LDB = C::LDB, RPW = C::RPW, CPL = C::CPL;
+
+  __shared__ __align__(16) float smem[C::SMEM];
+
+  const int t = threadIdx.x;
+  const int lane = t & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(t >> 6);
+  const int wm = wv / WN, wn = wv % WN;
+
+  // tile coordinates: m tile fastest, then column tile, then group
+  uint32_t lin = xcd_contiguous_block_id();
+  const uint32_t m_tile = lin % (uint32_t)a.m_tiles;
+  lin /= (uint32_t)a.m_tiles;
+  const uint32_t col_tile = lin % (uint32_t)a.col_tiles;
+  const uint32_t g = lin / (uint32_t)a.col_tiles;
+
+  // per-lane column state of the gather (fixed for the whole reduction)
+  uint32_t cbase[CPL];
+  int cih0[CPL], ciw0[CPL];
+#pragma unroll
+  for (int q = 0; q < CPL; ++q) {
+    const uint32_t col = col_tile * BN + q * 64 + lane;
+    if (col < (uint32_t)a.ncols) {
+      const uint32_t n = mdiv(col, a.mP);
+      const uint32_t pix = col - n * a.P;
+      const uint32_t pa = mdiv(pix, a.mPW);
+      const uint32_t pb = pix - pa * a.PW;
+      const int ih0 = (int)pa * a.sh - a.ph;
+      const int iw0 = (int)pb * a.sw - a.pw;
+      cih0[q] = ih0;
+      ciw0[q] = iw0;
+      cbase[q] = 4u * (uint32_t)((int)(n * a.in_img_stride + g * a.in_grp_stride) + ih0 * a.IW + iw0);
+    } else {
+      cih0[q] = -(1 << 28);  // every bounds test fails
+      ciw0[q] = 0;
+      cbase[q] = 0;
+    }
+  }
+
+  const float* Ag = a.A + ((size_t)g * a.KP) * a.MP + (size_t)m_tile * BM;
+  const int TH = a.THW / a.TW;
+
+  typename M::Acc acc[MB][NB];
+#pragma unroll
+  for (int i = 0; i < MB; ++i)
+#pragma unroll
+    for (int j = 0; j < NB; ++j)
+#pragma unroll
+      for (int r = 0; r < M::NR; ++r) acc[i][j][r] = 0.f;
+
+  f32x4 ra[C::A_PER];
+  float rb[RPW][CPL];
+  uint32_t okbits = 0;
+
+  auto load_chunk = [&](int k0) {
+#pragma unroll
+    for (int p = 0; p < C::A_PER; ++p) {
+      const int idx = t + p * kThreads;
+      if (C::A_F4 % kThreads == 0 || idx < C::A_F4) {
+        const int row = idx / (BM / 4), c4 = idx % (BM / 4);
+        ra[p] = *reinterpret_cast<const f32x4*>(Ag + (size_t)(k0 + row) * a.MP + c4 * 4);
+      }
+    }
+    // (channel, tap row, tap column) of this wave's first k row: uniform, so scalar work
+    const uint32_t kk0 = (uint32_t)(k0 + wv * RPW);
+    uint32_t c = mdiv(kk0, a.mTHW);
+    const uint32_t rem = kk0 - c * a.THW;
+    uint32_t i = mdiv(rem, a.mTW);
+    uint32_t j = rem - i * a.TW;
+    okbits = 0;
+#pragma unroll
+    for (int e = 0; e < RPW; ++e) {
+      const bool kvalid = (kk0 + e) < (uint32_t)a.Kred;
+      const uint32_t koff = 4u * (c * a.IHW + i * a.dh * a.IW + j * a.dw);
+      const int idh = (int)i * a.dh, jdw = (int)j * a.dw;
+#pragma unroll
+      for (int q = 0; q < CPL; ++q) {
+        const int ih = cih0[q] + idh, iw = ciw0[q] + jdw;
+        const bool ok = kvalid && (uint32_t)ih < (uint32_t)a.IH && (uint32_t)iw < (uint32_t)a.IW;
+        rb[e][q] = ld_f32(a.in, ok ? cbase[q] + koff : 0u);
+        okbits |= (ok ? 1u : 0u) << (e * CPL + q);
+      }
+      if (++j == (uint32_t)a.TW) {
+        j = 0;
+        if (++i == (uint32_t)TH) {
+          i = 0;
+          ++c;
+        }
+      }
+    }
+  };
+
+  auto store_chunk = [&](int buf) {
+    float* sA = smem + buf * C::STAGE;
+    float* sB = sA + BK * LDA;
+#pragma unroll
+    for (int p = 0; p < C::A_PER; ++p) {
+      const int idx = t + p * kThreads;
+      if (C::A_F4 % kThreads == 0 || idx < C::A_F4) {
+        const int row = idx / (BM / 4), c4 = idx % (BM / 4);
+        *reinterpret_cast<f32x4*>(sA + row * LDA + c4 * 4) = ra[p];
+      }
+    }
+#pragma unroll
+    for (int e = 0; e < RPW; ++e)
+#pragma unroll
+      for (int q = 0; q < CPL; ++q)
+        sB[(wv * RPW + e) * LDB + q * 64 + lane] = ((okbits >> (e * CPL + q)) & 1u) ? rb[e][q] : 0.f;
+  };
+
+  auto compute_chunk = [&](int buf) {
+    const float* sA = smem + buf * C::STAGE;
+    const float* sB = sA + BK * LDA;
+    const int krow = lane / MT, mi = lane % MT;
+#pragma unroll
+    for (int ks = 0; ks < BK / M::KS; ++ks) {
+      float av[MB], bv[NB];
+#pragma unroll
+      for (int i = 0; i < MB; ++i) av[i] = sA[(ks * M::KS + krow) * LDA + (wm * MB + i) * MT + mi];
+#pragma unroll
+      for (int j = 0; j < NB; ++j) bv[j] = sB[(ks * M::KS + krow) * LDB + (wn * NB + j) * MT + mi];
+#pragma unroll
+      for (int i = 0; i < MB; ++i)
+#pragma unroll
+        for (int j = 0; j < NB; ++j) M::run(av[i], bv[j], acc[i][j]);
+    }
+  };
+
+  const int nchunks = a.KP / BK;
+  load_chunk(0);
+  store_chunk(0);
+  __syncthreads();
+  for (int kc = 0; kc < nchunks; ++kc) {
+    const bool more = kc + 1 < nchunks;
+    if (more) load_chunk((kc + 1) * BK);
+    compute_chunk(kc & 1);
+    if (more) store_chunk((kc + 1) & 1);
+    __syncthreads();
+  }
+
+  // ---- epilogue: tables, then scatter -------------------------------------------------------
+  int* rowoff = reinterpret_cast<int*>(smem);
+  int* rowH = rowoff + BM;
+  int* rowW = rowH + BM;
+  float* rowB = reinterpret_cast<float*>(rowW + BM);
+  int* coloff = reinterpret_cast<int*>(rowB + BM);
+  int* colH = coloff + BN;
+  int* colW = colH + BN;
+  for (int m = t; m < BM; m += kThreads) {
+    const uint32_t gm = m_tile * BM + m;
+    int off = 0, hh = -(1 << 28), ww = 0;
+    float bb = 0.f;
+    if (gm < (uint32_t)a.Mrows) {
+      const uint32_t c = mdiv(gm, a.mRShw);
+      const uint32_t rem = gm - c * a.RShw;
+      const uint32_t rh = mdiv(rem, a.mRSw);
+      const uint32_t rw = rem - rh * a.RSw;
+      const uint32_t chan = g * a.chan_per_grp + c;
+      hh = (int)rh - a.opad_h;
+      ww = (int)rw - a.opad_w;
+      off = (int)(chan * (uint32_t)(a.OHd * a.OWd)) + hh * a.OWd + ww;
+      if (a.bias) bb = a.bias[chan];
+    }
+    rowoff[m] = off;
+    rowH[m] = hh;
+    rowW[m] = ww;
+    rowB[m] = bb;
+  }
+  for (int cl = t; cl < BN; cl += kThreads) {
+    const uint32_t col = col_tile * BN + cl;
+    int off = 0, hh = -(1 << 28), ww = 0;
+    if (col < (uint32_t)a.ncols) {
+      const uint32_t n = mdiv(col, a.mP);
+      const uint32_t pix = col - n * a.P;
+      const uint32_t pa = mdiv(pix, a.mPW);
+      const uint32_t pb = pix - pa * a.PW;
+      hh = (int)pa * a.RSh;
+      ww = (int)pb * a.RSw;
+      off = (int)(n * (uint32_t)a.out_img_stride) + hh * a.OWd + ww;
+    }
+    coloff[cl] = off;
+    colH[cl] = hh;
+    colW[cl] = ww;
+  }
+  __syncthreads();
+
+#pragma unroll
+  for (int j = 0; j < NB; ++j) {
+    const int cl = (wn * NB + j) * MT + lane % MT;
+    const int co = coloff[cl], cH = colH[cl], cW = colW[cl];
+#pragma unroll
+    for (int i = 0; i < MB; ++i)
+#pragma unroll
+      for (int r = 0; r < M::NR; ++r) {
+        const int ml = (wm * MB + i) * MT + M::row(r, lane);
+        const int hh = rowH[ml] + cH, ww = rowW[ml] + cW;
+        if ((uint32_t)hh < (uint32_t)a.OHd && (uint32_t)ww < (uint32_t)a.OWd)
+          a.out[rowoff[ml] + co] = acc[i][j][r] + rowB[ml];
+      }
+  }
+}
+
+// A[g][kk][m] = w[g*Kg + m][kk]: a tiled transpose through LDS, both sides coalesced.
+__global__ __launch_bounds__(256) void pack_fwd_kernel(const PackArgs a) {
+  __shared__ float tile[32][33];
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
+  const int m0 = blockIdx.x * 32, k0 = blockIdx.y * 32, g = blockIdx.z;
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int m = m0 + ty + 8 * r, kk = k0 + tx;
+    float v = 0.f;
+    if (m < a.Mrows && kk < a.Kred) v = a.w[((size_t)g * a.Kg + m) * a.Kred + kk];
+    tile[ty + 8 * r][tx] = v;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int kk = k0 + ty + 8 * r, m = m0 + tx;
+    if (kk < a.KP && m < a.MP) a.A[((size_t)g * a.KP + kk) * a.MP + m] = tile[tx][ty + 8 * r];
+  }
+}
+
+// Backward data: rows are (input channel, row phase, column phase), k is (output channel,
+// flipped reduced tap).  Phase (rh, rw) of input position h + pad = stride*a + rh is reached by
+// tap i exactly when i*dilation = stride*q + rh for an integer q >= 0; the gather then reads
+// dy at a - q.  Entries with no such tap are zero.
+__global__ __launch_bounds__(256) void pack_bwd_kernel(const PackArgs a) {
+  const size_t total = (size_t)a.G * a.KP * a.MP;
+  const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= total) return;
+  const int m = (int)(idx % a.MP);
+  const int kk = (int)((idx / a.MP) % a.KP);
+  const int g = (int)(idx / ((size_t)a.MP * a.KP));
+  float v = 0.f;
+  if (m < a.Mrows && kk < a.Kred) {
+    const int QQ = a.Qh * a.Qw;
+    const int k = kk / QQ, qr = kk % QQ;
+    const int qh = a.Qh - 1 - qr / a.Qw, qw = a.Qw - 1 - qr % a.Qw;
+    const int ss = a.sh * a.sw;
+    const int c = m / ss, mr = m % ss;
+    const int rh = mr / a.sw, rw = mr % a.sw;
+    const int th = a.sh * qh + rh, tw = a.sw * qw + rw;
+    if (th % a.dh == 0 && tw % a.dw == 0) {
+      const int i = th / a.dh, j = tw / a.dw;
+      if (i < a.kh && j < a.kw) v = a.w[((((size_t)g * a.Kg + k) * a.Cg + c) * a.kh + i) * a.kw + j];
+    }
+  }
+  a.A[idx] = v;
+}
+
+template <int MT, int MB, int NB, int WM, int WN, int BK>
+int launch_corr_t(const CorrArgs& a, hipStream_t s) {
+  const uint32_t blocks = (uint32_t)a.G * a.m_tiles * a.col_tiles;
+  hipLaunchKernelGGL((corr_kernel<MT, MB, NB, WM, WN, BK>), dim3(blocks), dim3(kThreads), 0, s, a);
+  return (int)hipGetLastError();
+}
+
+}  // namespace
+
+void corr_tile_shape(int32_t tile, int32_t* bm, int32_t* bn, int32_t* bk) {
+  static const int32_t shapes[CORR_TILE_COUNT][3] = {{128, 128, 16}, {96, 128, 16}, {64, 128, 16},
+                                                    {32, 256, 16},  {48, 256, 16}, {16, 256, 16}};
+  *bm = shapes[tile][0];
+  *bn = shapes[tile][1];
+  *bk = shapes[tile][2];
+}
+
+const char* corr_tile_name(int32_t tile) {
+  static const char* names[CORR_TILE_COUNT] = {"corr_m32_128x128x16", "corr_m32_96x128x16", "corr_m32_64x128x16",
+                                               "corr_m32_32x256x16",  "corr_m16_48x256x16", "corr_m16_16x256x16"};
+  return names[tile];
+}
+
+int launch_corr(int32_t tile, const CorrArgs& a, void* stream) {
+  hipStream_t s = (hipStream_t)stream;
+  switch (tile) {
+    case CORR_128x128: return launch_corr_t<32, 2, 2, 2, 2, 16>(a, s);
+    case CORR_96x128:  return launch_corr_t<32, 3, 1, 1, 4, 16>(a, s);
+    case CORR_64x128:  return launch_corr_t<32, 2, 1, 1, 4, 16>(a, s);
+    case CORR_32x256:  return launch_corr_t<32, 1, 2, 1, 4, 16>(a, s);
+    case CORR_48x256:  return launch_corr_t<16, 3, 4, 1, 4, 16>(a, s);
+    case CORR_16x256:  return launch_corr_t<16, 1, 4, 1, 4, 16>(a, s);
+    default: return (int)hipErrorInvalidValue;
+  }
+}
+
+int launch_pack(const PackArgs& a, void* stream) {
+  hipStream_t s = (hipStream_t)stream;
+  if (a.mode == 0) {
+    dim3 grid((a.MP + 31) / 32, (a.KP + 31) / 32, a.G);
+    hipLaunchKernelGGL(pack_fwd_kernel, grid, dim3(256), 0, s, a);
+  } else {
+    const size_t total = (size_t)a.G * a.KP * a.MP;
+    hipLaunchKernelGGL(pack_bwd_kernel, dim3((uint32_t)((total + 255) / 256)), dim3(256), 0, s, a);
+  }
+  return (int)hipGetLastError();
+}
+
+}  // namespace mi355conv

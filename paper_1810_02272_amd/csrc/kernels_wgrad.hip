@@ -1,0 +1,240 @@
+// Backward-filter kernel for gfx950 (Caffe-semantics convolution layer, paper Table 1):
+//   dW_g[k][(c,i,j)] = sum over columns (n,oh,ow) of dy[n, g*Kg + k, oh, ow] *
+//                      x[n, g*Cg + c, oh*sh - ph + i*dh, ow*sw - pw + j*dw]   (0 outside the image)
+// an implicit GEMM whose reduction runs over the N*OH*OW output positions.  The output is tiny and
+// the reduction huge, so the reduction is split over workgroups (split-K); every split writes its
+// partial tile to the workspace and a second kernel adds the partials in a fixed order, which
+// keeps the result deterministic (no float atomics) and applies beta.
+//
+// Both operands are read with lanes along the reduction index (contiguous in dy, contiguous for
+// stride-1 x), written to LDS as [row][k] with an odd leading dimension and read back by the
+// 32x32x2 fp32 MFMA operand pattern (lane l: row l%32, k l/32) without bank conflicts.
+#include <hip/hip_runtime.h>
+
+#include "device_utils.h"
+#include "internal.h"
+
+namespace mi355conv {
+
+namespace {
+
+constexpr int kThreads = 256;
+
+template <int MB, int NB, int WM, int WN>
+struct WgCfg {
+  static constexpr int MT = 32;
+  static constexpr int BK = 32;
+  static constexpr int BM = WM * MB * MT;
+  static constexpr int BN = WN * NB * MT;
+  static constexpr int LDK = BK + 1;
+  static constexpr int A_PER = BM / 8;  // rows per thread: 32 lanes along k, 8 row slots
+  static constexpr int B_PER = BN / 8;
+  static constexpr int STAGE = (BM + BN) * LDK;
+  static constexpr int SMEM_BYTES = 2 * STAGE * 4;
+  static_assert(WM * WN == 4, "four waves per workgroup");
+  static_assert(B_PER <= 32, "validity bits are kept in one register");
+};
+
+template <int MB, int NB, int WM, int WN>
+__global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradArgs a) {
+  using C = WgCfg<MB, NB, WM, WN>;
+  using M = Mfma<32>;
+  constexpr int BM = C::BM, BN = C::BN, BK = C::BK, LDK = C::LDK, A_PER = C::A_PER, B_PER = C::B_PER;
+
+  extern __shared__ __align__(16) float smem[];
+
+  const int t = threadIdx.x;
+  const int lane = t & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(t >> 6);
+  const int wm = wv / WN, wn = wv % WN;
+  const int kc = t & 31, rslot = t >> 5;
+
+  // tile coordinates: (m tile, n tile) fastest so that neighbours share the same columns
+  uint32_t lin = xcd_contiguous_block_id();
+  const uint32_t m_tile = lin % (uint32_t)a.m_tiles;
+  lin /= (uint32_t)a.m_tiles;
+  const uint32_t n_tile = lin % (uint32_t)a.n_tiles;
+  lin /= (uint32_t)a.n_tiles;
+  const uint32_t split = lin % (uint32_t)a.S;
+  const uint32_t g = lin / (uint32_t)a.S;
+
+  // Rows this thread loads, fixed for the whole kernel.  Rows past the matrix edge are clamped to
+  // the last real row: they only feed accumulators that are never stored.
+  uint32_t aoff[A_PER];
+#pragma unroll
+  for (int e = 0; e < A_PER; ++e) {
+    uint32_t m = m_tile * BM + rslot + 8 * e;
+    if (m > (uint32_t)a.Kg - 1) m = (uint32_t)a.Kg - 1;
+    aoff[e] = 4u * m * (uint32_t)a.P;
+  }
+  uint32_t boff[B_PER], bij[B_PER];
+#pragma unroll
+  for (int e = 0; e < B_PER; ++e) {
+    uint32_t nn = n_tile * BN + rslot + 8 * e;
+    if (nn > (uint32_t)a.Kred - 1) nn = (uint32_t)a.Kred - 1;
+    const uint32_t c = mdiv(nn, a.mKHW);
+    const uint32_t rem = nn - c * a.khw;
+    const uint32_t i = mdiv(rem, a.mKW);
+    const uint32_t j = rem - i * a.kw;
+    boff[e] = 4u * ((g * a.Cg + c) * (uint32_t)a.HW + i * a.dh * a.W + j * a.dw);
+    bij[e] = ((i * a.dh) << 16) | (j * a.dw);
+  }
+
+  const uint32_t c_begin = split * (uint32_t)a.cols_per_split;
+  uint32_t c_end = c_begin + (uint32_t)a.cols_per_split;
+  if (c_end > (uint32_t)a.ncols) c_end = (uint32_t)a.ncols;
+  const int nchunks = c_begin < c_end ? (int)((c_end - c_begin + BK - 1) / BK) : 0;
+
+  M::Acc acc[MB][NB];
+#pragma unroll
+  for (int i = 0; i < MB; ++i)
+#pragma unroll
+    for (int j = 0; j < NB; ++j)
+#pragma unroll
+      for (int r = 0; r < M::NR; ++r) acc[i][j][r] = 0.f;
+
+  float ra[A_PER], rb[B_PER];
+  uint32_t okbits = 0;
+  bool colok = false;
+
+  auto load_chunk = [&](int chunk) {
+    const uint32_t col = c_begin + chunk * BK + kc;
+    colok = col < c_end;
+    uint32_t n = 0, pix = 0;
+    int ih0 = -(1 << 28), iw0 = 0;
+    if (colok) {
+      n = mdiv(col, a.mP);
+      pix = col - n * a.P;
+      const uint32_t oh = mdiv(pix, a.mPW);
+      const uint32_t ow = pix - oh * a.PW;
+      ih0 = (int)oh * a.sh - a.ph;
+      iw0 = (int)ow * a.sw - a.pw;
+    }
+    const uint32_t dybase = 4u * ((n * a.Ktot + g * a.Kg) * (uint32_t)a.P + pix);
+    const uint32_t xbase = 4u * (uint32_t)((int)(n * (uint32_t)(a.C * a.HW)) + ih0 * a.W + iw0);
+#pragma unroll
+    for (int e = 0; e < A_PER; ++e) ra[e] = ld_f32(a.dy, colok ? dybase + aoff[e] : 0u);
+    okbits = 0;
+#pragma unroll
+    for (int e = 0; e < B_PER; ++e) {
+      const int ih = ih0 + (int)(bij[e] >> 16), iw = iw0 + (int)(bij[e] & 0xffffu);
+      const bool ok = (uint32_t)ih < (uint32_t)a.H && (uint32_t)iw < (uint32_t)a.W;
+      rb[e] = ld_f32(a.x, ok ? xbase + boff[e] : 0u);
+      okbits |= (ok ? 1u : 0u) << e;
+    }
+  };
+
+  auto store_chunk = [&](int buf) {
+    float* sA = smem + buf * C::STAGE;
+    float* sB = sA + BM * LDK;
+#pragma unroll
+    for (int e = 0; e < A_PER; ++e) sA[(rslot + 8 * e) * LDK + kc] = colok ? ra[e] : 0.f;
+#pragma unroll
+    for (int e = 0; e < B_PER; ++e) sB[(rslot + 8 * e) * LDK + kc] = ((okbits >> e) & 1u) ? rb[e] : 0.f;
+  };
+
+  auto compute_chunk = [&](int buf) {
+    const float* sA = smem + buf * C::STAGE;
+    const float* sB = sA + BM * LDK;
+    const int krow = lane >> 5, mi = lane & 31;
+#pragma unroll
+    for (int ks = 0; ks < BK / 2; ++ks) {
+      float av[MB], bv[NB];
+#pragma unroll
+      for (int i = 0; i < MB; ++i) av[i] = sA[((wm * MB + i) * 32 + mi) * LDK + ks * 2 + krow];
+#pragma unroll
+      for (int j = 0; j < NB; ++j) bv[j] = sB[((wn * NB + j) * 32 + mi) * LDK + ks * 2 + krow];
+#pragma unroll
+      for (int i = 0; i < MB; ++i)
+#pragma unroll
+        for (int j = 0; j < NB; ++j) M::run(av[i], bv[j], acc[i][j]);
+    }
+  };
+
+  if (nchunks > 0) {
+    load_chunk(0);
+    store_chunk(0);
+  }
+  __syncthreads();
+  for (int ch = 0; ch < nchunks; ++ch) {
+    const bool more = ch + 1 < nchunks;
+    if (more) load_chunk(ch + 1);
+    compute_chunk(ch & 1);
+    if (more) store_chunk((ch + 1) & 1);
+    __syncthreads();
+  }
+
+  // partial tile -> workspace [split][g][k][nn]
+  float* dst = a.part + ((size_t)split * a.G + g) * ((size_t)a.Kg * a.Kred);
+#pragma unroll
+  for (int j = 0; j < NB; ++j) {
+    const uint32_t nn = n_tile * BN + (wn * NB + j) * 32 + (lane & 31);
+#pragma unroll
+    for (int i = 0; i < MB; ++i)
+#pragma unroll
+      for (int r = 0; r < M::NR; ++r) {
+        const uint32_t k = m_tile * BM + (wm * MB + i) * 32 + M::row(r, lane);
+        if (k < (uint32_t)a.Kg && nn < (uint32_t)a.Kred) dst[(size_t)k * a.Kred + nn] = acc[i][j][r];
+      }
+  }
+}
+
+template <int MB, int NB, int WM, int WN>
+int launch_wgrad_t(const WgradArgs& a, hipStream_t s) {
+  using C = WgCfg<MB, NB, WM, WN>;
+  static bool configured = false;
+  if (!configured) {  // more than 64 KB of LDS needs an explicit opt-in, once per process
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&wgrad_kernel<MB, NB, WM, WN>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM_BYTES);
+    if (e != hipSuccess) return (int)e;
+    configured = true;
+  }
+  const uint32_t blocks = (uint32_t)a.G * a.S * a.m_tiles * a.n_tiles;
+  hipLaunchKernelGGL((wgrad_kernel<MB, NB, WM, WN>), dim3(blocks), dim3(kThreads), C::SMEM_BYTES, s, a);
+  return (int)hipGetLastError();
+}
+
+// dst = beta*dst + sum_s part[s]; the partials are added in split order, so the result does not
+// depend on scheduling.
+__global__ __launch_bounds__(256) void reduce_kernel(const ReduceArgs a) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= a.count) return;
+  float s = 0.f;
+  for (int k = 0; k < a.S; ++k) s += a.part[(size_t)k * a.count + i];
+  a.dst[i] = (a.beta == 0.f) ? s : a.beta * a.dst[i] + s;
+}
+
+}  // namespace
+
+void wgrad_tile_shape(int32_t tile, int32_t* bm, int32_t* bn, int32_t* bk) {
+  static const int32_t shapes[WGRAD_TILE_COUNT][3] = {
+      {128, 128, 32}, {96, 128, 32}, {64, 128, 32}, {32, 128, 32}, {128, 64, 32}};
+  *bm = shapes[tile][0];
+  *bn = shapes[tile][1];
+  *bk = shapes[tile][2];
+}
+
+const char* wgrad_tile_name(int32_t tile) {
+  static const char* names[WGRAD_TILE_COUNT] = {"wgrad_m32_128x128x32", "wgrad_m32_96x128x32", "wgrad_m32_64x128x32",
+                                                "wgrad_m32_32x128x32", "wgrad_m32_128x64x32"};
+  return names[tile];
+}
+
+int launch_wgrad(int32_t tile, const WgradArgs& a, void* stream) {
+  hipStream_t s = (hipStream_t)stream;
+  switch (tile) {
+    case WGRAD_128x128: return launch_wgrad_t<2, 2, 2, 2>(a, s);
+    case WGRAD_96x128:  return launch_wgrad_t<3, 1, 1, 4>(a, s);
+    case WGRAD_64x128:  return launch_wgrad_t<2, 1, 1, 4>(a, s);
+    case WGRAD_32x128:  return launch_wgrad_t<1, 1, 1, 4>(a, s);
+    case WGRAD_128x64:  return launch_wgrad_t<2, 1, 2, 2>(a, s);
+    default: return (int)hipErrorInvalidValue;
+  }
+}
+
+int launch_reduce(const ReduceArgs& a, void* stream) {
+  hipLaunchKernelGGL(reduce_kernel, dim3((a.count + 255) / 256), dim3(256), 0, (hipStream_t)stream, a);
+  return (int)hipGetLastError();
+}
+
+}  // namespace mi355conv

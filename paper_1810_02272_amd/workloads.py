@@ -1,0 +1,124 @@
+"""Seeded synthetic inputs for the eleven benchmark layer shapes (and ad-hoc shapes for tests).
+
+This module holds data and random-number recipes only -- none of the layer's arithmetic -- so the
+GPU tests, the benchmark and the CPU checker can all draw identical bits from it.  The output
+sizes below are written out as data (they are the sizes the benchmark configurations chain
+through: 28->24, 12->8, 84->20->9->7, 227->55, ...), not computed here.
+
+Stand-ins: the shapes are those of digit-like 28x28x1, small-image 32x32x3, large-image
+227x227x3 and stacked-frame 84x84x4 workloads; the values are the distributions the benchmark
+configurations prescribe (no dataset is used).
+"""
+from __future__ import annotations
+
+import math
+from dataclasses import dataclass
+
+import torch
+
+BASE_SEED = 1810_02272 * 10
+
+
+@dataclass(frozen=True)
+class Layer:
+    name: str
+    config: int          # index into the benchmark configuration list
+    n: int
+    c: int
+    hw: int              # square input
+    k: int               # num_output
+    kernel: int
+    stride: int
+    pad: int
+    group: int
+    out_hw: int          # square output (data, see module docstring)
+    x_dist: str          # "uniform01" or "normal"
+    w_dist: str          # "xavier" or "gauss0.01"
+    dy_std: float
+
+    @property
+    def x_shape(self):
+        return (self.n, self.c, self.hw, self.hw)
+
+    @property
+    def w_shape(self):
+        return (self.k, self.c // self.group, self.kernel, self.kernel)
+
+    @property
+    def y_shape(self):
+        return (self.n, self.k, self.out_hw, self.out_hw)
+
+    @property
+    def flop_per_pass(self) -> int:
+        """Multiply-adds x2 of one pass (forward; each backward pass has the same count)."""
+        return 2 * self.n * self.k * (self.c // self.group) * self.kernel * self.kernel * self.out_hw * self.out_hw
+
+    def params_dict(self) -> dict:
+        return dict(n=self.n, c=self.c, h=self.hw, w=self.hw, num_output=self.k, kernel_h=self.kernel,
+                    kernel_w=self.kernel, stride_h=self.stride, stride_w=self.stride, pad_h=self.pad, pad_w=self.pad,
+                    dilation_h=1, dilation_w=1, group=self.group, bias_term=1)
+
+
+# dy ~ N(0, 1e-2) is read as variance 1e-2, i.e. standard deviation 0.1.
+LAYERS = [
+    Layer("1.a", 0, 64, 1, 28, 20, 5, 1, 0, 1, 24, "uniform01", "xavier", 1.0),
+    Layer("2.a", 1, 64, 20, 12, 50, 5, 1, 0, 1, 8, "uniform01", "xavier", 1.0),
+    Layer("3.a", 2, 32, 4, 84, 32, 8, 4, 0, 1, 20, "uniform01", "gauss0.01", 0.1),
+    Layer("3.b", 2, 32, 32, 20, 64, 4, 2, 0, 1, 9, "uniform01", "gauss0.01", 0.1),
+    Layer("3.c", 2, 32, 64, 9, 64, 3, 1, 0, 1, 7, "uniform01", "gauss0.01", 0.1),
+    Layer("4.a", 3, 100, 3, 32, 32, 5, 1, 2, 1, 32, "normal", "gauss0.01", 1.0),
+    Layer("4.b", 3, 100, 32, 16, 32, 5, 1, 2, 1, 16, "normal", "gauss0.01", 1.0),
+    Layer("4.c", 3, 100, 32, 8, 64, 5, 1, 2, 1, 8, "normal", "gauss0.01", 1.0),
+    Layer("5.a", 4, 128, 3, 227, 96, 11, 4, 0, 1, 55, "normal", "gauss0.01", 0.1),
+    Layer("5.b", 4, 128, 96, 27, 256, 5, 1, 2, 2, 27, "normal", "gauss0.01", 0.1),
+    Layer("5.c", 4, 128, 256, 13, 384, 3, 1, 1, 1, 13, "normal", "gauss0.01", 0.1),
+]
+BY_NAME = {l.name: l for l in LAYERS}
+
+
+def _gen(seed: int) -> torch.Generator:
+    g = torch.Generator(device="cpu")
+    g.manual_seed(seed)
+    return g
+
+
+def draw(shape, dist: str, seed: int, scale: float = 1.0) -> torch.Tensor:
+    """fp32 CPU tensor from a named distribution with its own seed."""
+    g = _gen(seed)
+    if dist == "uniform01":
+        return torch.rand(shape, generator=g, dtype=torch.float32)
+    if dist == "normal":
+        return torch.randn(shape, generator=g, dtype=torch.float32) * scale
+    if dist == "uniform_pm":  # U[-scale, scale)
+        return (torch.rand(shape, generator=g, dtype=torch.float32) * 2.0 - 1.0) * scale
+    raise ValueError(dist)
+
+
+def layer_inputs(layer: Layer, bias: str = "zero", n: int | None = None):
+    """(x, w, b, dy) as fp32 CPU tensors.  bias: "zero" (benchmark) or "random" (parity, U[-0.1,0.1)).
+
+    ``n`` draws only the first n images (x and dy are generated image-major, so a prefix of the
+    full batch is bit-identical to the same images of the full draw).
+    """
+    idx = LAYERS.index(layer)
+    seed = BASE_SEED + 1000 * idx
+    nn = layer.n if n is None else n
+    xs, ys = (nn,) + layer.x_shape[1:], (nn,) + layer.y_shape[1:]
+    x = draw(xs, layer.x_dist, seed + 0)
+    fan_in = (layer.c // layer.group) * layer.kernel * layer.kernel
+    if layer.w_dist == "xavier":  # U[-a, a], a = sqrt(3 / fan_in)
+        w = draw(layer.w_shape, "uniform_pm", seed + 1, math.sqrt(3.0 / fan_in))
+    else:
+        w = draw(layer.w_shape, "normal", seed + 1, 0.01)
+    b = torch.zeros(layer.k, dtype=torch.float32) if bias == "zero" else draw((layer.k,), "uniform_pm", seed + 2, 0.1)
+    dy = draw(ys, "normal", seed + 3, layer.dy_std)
+    return x, w, b, dy
+
+
+def random_inputs(x_shape, w_shape, y_shape, seed: int, bias: bool = True):
+    """Inputs for an arbitrary shape (property tests): x, dy ~ N(0,1), w ~ N(0, 0.1), b ~ U[-1,1)."""
+    x = draw(x_shape, "normal", seed)
+    w = draw(w_shape, "normal", seed + 1, 0.1)
+    b = draw((w_shape[0],), "uniform_pm", seed + 2, 1.0) if bias else None
+    dy = draw(y_shape, "normal", seed + 3)
+    return x, w, b, dy

@@ -1,0 +1,94 @@
+"""Host-only checks of the C boundary (no GPU): the library loads, exports every symbol the header
+declares, validates parameters, computes output shapes and sizes its workspace."""
+import ctypes
+import json
+import os
+import re
+
+import pytest
+
+import paper_1810_02272_amd as conv
+from paper_1810_02272_amd import binding, workloads
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+GOLDEN = os.path.join(ROOT, "tests", "golden")
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "mi355conv.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(conv_[a-z_]+)\s*\(", header))
+    assert {"conv_desc_create", "conv_forward", "conv_backward_data", "conv_backward_filter",
+            "conv_backward_bias"} <= declared
+    lib = ctypes.CDLL(conv.library_path())
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_output_shape_matches_size_table():
+    table = json.load(open(os.path.join(GOLDEN, "output_sizes.json")))
+    for i, k, s, pad, d, out in table["rows"]:
+        p = conv.ConvParams(1, 1, i, i, 1, k, k, s, s, pad, pad, d, d)
+        if out < 1:
+            with pytest.raises(conv.ConvError) as e:
+                conv.conv_desc_create(p)
+            assert e.value.status == binding.CONV_ESHAPE
+        else:
+            assert conv.conv_desc_output_shape(conv.conv_desc_create(p)) == (1, 1, out, out)
+
+
+def test_benchmark_layers_shapes_and_workspace():
+    for l in workloads.LAYERS:
+        d = conv.conv_desc_create(conv.ConvParams(**l.params_dict()))
+        assert conv.conv_desc_output_shape(d) == l.y_shape
+        assert 0 < conv.conv_desc_workspace_bytes(d) < (1 << 30)
+        names = conv.conv_desc_kernel_names(d)
+        assert "fwd=" in names and "bwd_data=" in names and "bwd_filter=" in names
+
+
+@pytest.mark.parametrize("bad", [
+    dict(c=0), dict(h=0), dict(num_output=0), dict(kernel_h=0), dict(stride_w=0), dict(pad_h=-1),
+    dict(dilation_w=0), dict(group=0), dict(group=2, c=3), dict(group=2, c=4, num_output=3), dict(bias_term=2),
+    dict(n=-1),
+])
+def test_invalid_parameters_are_rejected(bad):
+    base = dict(n=2, c=4, h=8, w=8, num_output=4, kernel_h=3, kernel_w=3)
+    base.update(bad)
+    with pytest.raises(conv.ConvError) as e:
+        conv.conv_desc_create(conv.ConvParams(**base))
+    assert e.value.status == binding.CONV_EINVAL
+
+
+def test_too_large_tensors_are_rejected():
+    with pytest.raises(conv.ConvError) as e:
+        conv.conv_desc_create(conv.ConvParams(4096, 64, 128, 128, 64, 3, 3))
+    assert e.value.status == binding.CONV_ESHAPE
+
+
+def test_null_arguments_and_status_strings():
+    lib = binding._load()
+    assert lib.conv_desc_create(None, None) == binding.CONV_EINVAL
+    assert lib.conv_desc_destroy(None) == binding.CONV_EINVAL
+    assert lib.conv_desc_workspace_bytes(None, None) == binding.CONV_EINVAL
+    d = conv.conv_desc_create(conv.ConvParams(1, 1, 4, 4, 1, 3, 3, bias_term=0))
+    # null tensors, bias given for bias_term = 0, bias gradient on a bias-free layer, beta not 0/1
+    assert lib.conv_forward(d.handle, None, None, None, None, None, 0, None) == binding.CONV_EINVAL
+    assert lib.conv_forward(d.handle, 16, 16, 16, 16, None, 0, None) == binding.CONV_EINVAL
+    assert lib.conv_backward_bias(d.handle, 16, 16, 0.0, 16, 1 << 20, None) == binding.CONV_EINVAL
+    assert lib.conv_backward_filter(d.handle, 16, 16, 16, 0.5, 16, 1 << 20, None) == binding.CONV_EINVAL
+    # workspace missing / too small is detected before anything is enqueued
+    assert lib.conv_forward(d.handle, 16, 16, None, 16, None, 0, None) == binding.CONV_EWORKSPACE
+    assert lib.conv_backward_data(d.handle, 16, 16, 16, 16, 4, None) == binding.CONV_EWORKSPACE
+    assert lib.conv_backward_filter(d.handle, 16, 16, 16, 1.0, None, 0, None) == binding.CONV_EWORKSPACE
+    for s in (0, -1, -2, -3, -4, -99):
+        assert conv.conv_status_string(s)
+    assert conv.conv_status_string(0) == "success"
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    p = conv.ConvParams(1, 1, 4, 4, 1, 3, 3)
+    d = conv.conv_desc_create(p)
+    x = torch.zeros(1, 1, 4, 4)
+    with pytest.raises(TypeError):
+        conv.conv_forward(d, x, torch.zeros(1, 1, 3, 3), torch.zeros(1), torch.zeros(1, 1, 2, 2))

@@ -1,0 +1,226 @@
+"""GPU parity: the HIP path behind the C boundary against the CPU oracle, same seeded inputs.
+
+Tolerance.  The kernels multiply in fp32 and accumulate in fp32 (MFMA); the oracle is the exact
+double-precision result for the same fp32 inputs.  The gate is the normalised maximum error
+max|gpu - ref| / max|ref| <= 1e-4 per output tensor (the bar the benchmark definition states).
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_1810_02272_amd as conv
+from oracle import OracleParams
+from paper_1810_02272_amd import workloads
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-4
+DEV = "cuda:0"
+
+
+def nerr(gpu: torch.Tensor, ref: np.ndarray) -> float:
+    g = gpu.detach().cpu().double().numpy().reshape(ref.shape)
+    denom = max(float(np.max(np.abs(ref))), 1e-30) if ref.size else 1.0
+    return float(np.max(np.abs(g - ref))) / denom if ref.size else 0.0
+
+
+def run_all(pd: dict, x, w, b, dy, beta_check=True, poison=True):
+    """Run the four passes on the GPU; returns (y, dx, dw, db) device tensors."""
+    p = conv.ConvParams(**pd)
+    d = conv.conv_desc_create(p)
+    ws_bytes = conv.conv_desc_workspace_bytes(d)
+    fill = float("nan") if poison else 0.0
+    ws = torch.full((max(ws_bytes // 4, 1),), fill, device=DEV)
+    xd, wd, dyd = x.to(DEV), w.to(DEV), dy.to(DEV)
+    bd = b.to(DEV) if b is not None else None
+    y = torch.full(tuple(dy.shape), fill, device=DEV)
+    dx = torch.full(tuple(x.shape), fill, device=DEV)
+    dw = torch.full(tuple(w.shape), fill, device=DEV)
+    conv.conv_forward(d, xd, wd, bd, y, ws)
+    ws.fill_(fill)
+    conv.conv_backward_data(d, wd, dyd, dx, ws)
+    ws.fill_(fill)
+    conv.conv_backward_filter(d, xd, dyd, dw, 0.0, ws)
+    db = None
+    if b is not None:
+        db = torch.full((p.num_output,), fill, device=DEV)
+        ws.fill_(fill)
+        conv.conv_backward_bias(d, dyd, db, 0.0, ws)
+    torch.cuda.synchronize()
+    return d, ws, (xd, wd, bd, dyd), (y, dx, dw, db)
+
+
+def check_full(pd: dict, seed: int, bias=True):
+    op = OracleParams(**pd)
+    xs, wsh, ys = oracle.x_shape(op), oracle.w_shape(op), oracle.output_shape(op)
+    x, w, b, dy = workloads.random_inputs(xs, wsh, ys, seed, bias=bias)
+    d, ws, dev_in, (y, dx, dw, db) = run_all(pd, x, w, b, dy)
+    assert conv.conv_desc_output_shape(d) == ys
+    xn, wn, dyn = x.numpy(), w.numpy(), dy.numpy()
+    bn = b.numpy() if b is not None else None
+    errs = {
+        "y": nerr(y, oracle.forward(op, xn, wn, bn)),
+        "dx": nerr(dx, oracle.backward_data(op, wn, dyn)),
+        "dw": nerr(dw, oracle.backward_filter(op, xn, dyn)),
+    }
+    if b is not None:
+        errs["db"] = nerr(db, oracle.backward_bias(op, dyn))
+    for k, v in errs.items():
+        assert np.isfinite(v) and v <= TOL, (pd, k, v, conv.conv_desc_kernel_names(d))
+    return errs
+
+
+def P(n, c, h, w, k, kh, kw, sh=1, sw=1, ph=0, pw=0, dh=1, dw=1, g=1, bias=1):
+    return dict(n=n, c=c, h=h, w=w, num_output=k, kernel_h=kh, kernel_w=kw, stride_h=sh, stride_w=sw, pad_h=ph,
+                pad_w=pw, dilation_h=dh, dilation_w=dw, group=g, bias_term=bias)
+
+
+# Shapes chosen to span several tiles in every dimension with ragged tails, and to hit every
+# parameter: stride (incl. non-divisible), pad (incl. >= kernel extent), dilation, group,
+# non-square everything, 1x1, full-size kernel, single channel, every tile variant.
+SWEEP = [
+    P(3, 5, 17, 19, 7, 3, 3),
+    P(2, 3, 9, 11, 4, 1, 1),
+    P(4, 6, 13, 13, 9, 13, 13),                            # kernel = input: inner product
+    P(3, 4, 23, 17, 10, 3, 5, 2, 3, 1, 2),                  # non-square stride/pad/kernel
+    P(2, 8, 15, 15, 12, 3, 3, 1, 1, 1, 1, 2, 2),            # dilation 2
+    P(2, 4, 21, 18, 6, 3, 2, 2, 1, 2, 0, 3, 2),             # stride + dilation mix
+    P(3, 6, 12, 14, 9, 3, 3, 2, 2, 1, 1, 2, 2, 3),          # groups + stride + dilation (gcd != 1)
+    P(2, 2, 6, 6, 3, 3, 3, 1, 1, 3, 4),                     # pad >= kernel extent
+    P(5, 1, 28, 28, 20, 5, 5),                              # layer 1.a at a small batch
+    P(2, 3, 51, 51, 96, 11, 11, 4, 4),                      # 5.a-like: 96 rows, stride 4
+    P(3, 16, 14, 14, 130, 5, 5, 1, 1, 2, 2, 1, 1, 2),       # 5.b-like: grouped, 65 rows per group
+    P(2, 40, 13, 13, 384, 3, 3, 1, 1, 1, 1),                # 5.c-like: three 128-row tiles
+    P(2, 96, 9, 9, 8, 3, 3, 1, 1, 1, 1, 1, 1, 2),           # 48 backward rows per group (16-wide MFMA tile)
+    P(7, 3, 32, 32, 32, 5, 5, 1, 1, 2, 2),                  # layer 4.a at a small batch
+    P(2, 4, 40, 36, 32, 8, 8, 4, 4),                        # layer 3.a-like
+    P(3, 32, 20, 20, 64, 4, 4, 2, 2),                       # layer 3.b-like
+    P(1, 1, 5, 7, 1, 2, 3, 3, 2, 0, 1),                     # tiny, stride > kernel
+    P(2, 3, 10, 10, 5, 3, 3, 3, 3, 0, 0, 1, 1, 1, 0),       # no bias, stride leaves unread rows
+    P(1, 200, 7, 7, 50, 3, 3, 1, 1, 1, 1),                  # long reduction, 50 rows
+]
+
+
+@pytest.mark.parametrize("i", range(len(SWEEP)))
+def test_sweep_full_compare(i):
+    pd = SWEEP[i]
+    print("case", i, pd, flush=True)
+    check_full(pd, seed=7000 + 10 * i, bias=bool(pd["bias_term"]))
+
+
+@pytest.mark.parametrize("name", [l.name for l in workloads.LAYERS if l.config <= 3])
+def test_benchmark_layers_configs_0_to_3_full(name):
+    """Configurations 0-3 at full size, every output element against the oracle."""
+    l = workloads.BY_NAME[name]
+    print("layer", name, flush=True)
+    pd = l.params_dict()
+    op = OracleParams(**pd)
+    x, w, b, dy = workloads.layer_inputs(l, bias="random")
+    d, ws, _, (y, dx, dw, db) = run_all(pd, x, w, b, dy)
+    xn, wn, bn, dyn = x.numpy(), w.numpy(), b.numpy(), dy.numpy()
+    assert nerr(y, oracle.forward(op, xn, wn, bn)) <= TOL
+    assert nerr(dx, oracle.backward_data(op, wn, dyn)) <= TOL
+    assert nerr(dw, oracle.backward_filter(op, xn, dyn)) <= TOL
+    assert nerr(db, oracle.backward_bias(op, dyn)) <= TOL
+
+
+@pytest.mark.parametrize("name", ["5.a", "5.b", "5.c"])
+def test_benchmark_layers_config_4_sampled(name):
+    """The large grouped-conv configuration at full size, in the launch configuration the benchmark
+    times: outputs the oracle computes one by one (random samples plus corners), the bias gradient
+    in full, and exact invariants that hold at any size."""
+    l = workloads.BY_NAME[name]
+    print("layer", name, flush=True)
+    pd = l.params_dict()
+    op = OracleParams(**pd)
+    x, w, b, dy = workloads.layer_inputs(l, bias="random")
+    d, ws, (xd, wd, bd, dyd), (y, dx, dw, db) = run_all(pd, x, w, b, dy)
+    xn, wn, bn, dyn = x.numpy(), w.numpy(), b.numpy(), dy.numpy()
+    rng = np.random.default_rng(123)
+
+    def samples(total, count):
+        edge = np.array([0, 1, total - 2, total - 1])
+        return np.unique(np.concatenate([edge, rng.integers(0, total, size=count)]))
+
+    yi, xi, wi = samples(y.numel(), 6000), samples(dx.numel(), 6000), samples(dw.numel(), 300)
+    ref_y = oracle.forward_at(op, xn, wn, bn, yi)
+    ref_dx = oracle.backward_data_at(op, wn, dyn, xi)
+    ref_dw = oracle.backward_filter_at(op, xn, dyn, wi)
+    ref_db = oracle.backward_bias(op, dyn)
+    yc, dxc, dwc = y.cpu().double().numpy().ravel(), dx.cpu().double().numpy().ravel(), dw.cpu().double().numpy().ravel()
+    # normalise by the largest magnitude of the whole GPU tensor's sampled reference
+    assert np.max(np.abs(yc[yi] - ref_y)) / np.max(np.abs(ref_y)) <= TOL
+    assert np.max(np.abs(dxc[xi] - ref_dx)) / np.max(np.abs(ref_dx)) <= TOL
+    assert np.max(np.abs(dwc[wi] - ref_dw)) / np.max(np.abs(ref_dw)) <= TOL
+    assert nerr(db, ref_db) <= TOL
+    assert np.all(np.isfinite(yc)) and np.all(np.isfinite(dxc)) and np.all(np.isfinite(dwc))
+    # invariants over the whole tensors: <y - b, dy> = <x, dx> = <w, dw> (double sums of fp32 results)
+    lin = float(np.sum((yc.reshape(y.shape) - bn[None, :, None, None]) * dyn.astype(np.float64)))
+    via_dx = float(np.sum(dxc * xn.astype(np.float64).ravel()))
+    via_dw = float(np.sum(dwc * wn.astype(np.float64).ravel()))
+    scale = float(np.sqrt(y.numel())) * float(np.max(np.abs(ref_y))) * l.dy_std
+    assert abs(lin - via_dx) <= 1e-3 * scale and abs(lin - via_dw) <= 1e-3 * scale, (lin, via_dx, via_dw, scale)
+
+
+def test_beta_accumulates_and_overwrites():
+    pd = P(3, 6, 11, 12, 10, 3, 3, 2, 1, 1, 1, 1, 1, 2)
+    op = OracleParams(**pd)
+    x, w, b, dy = workloads.random_inputs(oracle.x_shape(op), oracle.w_shape(op), oracle.output_shape(op), 4242)
+    d, ws, (xd, wd, bd, dyd), (y, dx, dw, db) = run_all(pd, x, w, b, dy)
+    dw0, db0 = dw.clone(), db.clone()
+    conv.conv_backward_filter(d, xd, dyd, dw, 1.0, ws)
+    conv.conv_backward_bias(d, dyd, db, 1.0, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(dw, dw0 + dw0) and torch.equal(db, db0 + db0)   # x + x is exact in fp32
+    ref = oracle.backward_filter(op, x.numpy(), dy.numpy(), dw=dw0.cpu().numpy(), beta=1.0)
+    assert nerr(dw, ref) <= TOL
+
+
+def test_runs_are_bitwise_repeatable():
+    pd = P(4, 8, 19, 19, 24, 5, 5, 2, 2, 2, 2, 1, 1, 2)
+    op = OracleParams(**pd)
+    x, w, b, dy = workloads.random_inputs(oracle.x_shape(op), oracle.w_shape(op), oracle.output_shape(op), 99)
+    _, _, _, first = run_all(pd, x, w, b, dy)
+    _, _, _, second = run_all(pd, x, w, b, dy, poison=False)
+    for a, c in zip(first, second):
+        assert torch.equal(a, c)
+
+
+def test_empty_batch_is_a_noop():
+    pd = P(0, 3, 8, 8, 4, 3, 3)
+    p = conv.ConvParams(**pd)
+    d = conv.conv_desc_create(p)
+    ws = torch.zeros(max(conv.conv_desc_workspace_bytes(d) // 4, 1), device=DEV)
+    x = torch.zeros(0, 3, 8, 8, device=DEV)
+    w = torch.ones(4, 3, 3, 3, device=DEV)
+    b = torch.ones(4, device=DEV)
+    y = torch.zeros(0, 4, 6, 6, device=DEV)
+    dw = torch.full((4, 3, 3, 3), 5.0, device=DEV)
+    db = torch.full((4,), 5.0, device=DEV)
+    conv.conv_forward(d, x, w, b, y, ws)
+    conv.conv_backward_data(d, w, y, x, ws)
+    conv.conv_backward_filter(d, x, y, dw, 1.0, ws)
+    conv.conv_backward_bias(d, y, db, 1.0, ws)
+    torch.cuda.synchronize()
+    assert torch.all(dw == 5.0) and torch.all(db == 5.0)
+    conv.conv_backward_filter(d, x, y, dw, 0.0, ws)
+    conv.conv_backward_bias(d, y, db, 0.0, ws)
+    torch.cuda.synchronize()
+    assert torch.all(dw == 0.0) and torch.all(db == 0.0)
+
+
+def test_runs_on_a_side_stream():
+    pd = P(2, 4, 10, 10, 6, 3, 3, 1, 1, 1, 1)
+    op = OracleParams(**pd)
+    x, w, b, dy = workloads.random_inputs(oracle.x_shape(op), oracle.w_shape(op), oracle.output_shape(op), 5)
+    p = conv.ConvParams(**pd)
+    d = conv.conv_desc_create(p)
+    ws = torch.zeros(max(conv.conv_desc_workspace_bytes(d) // 4, 1), device=DEV)
+    xd, wd, bd = x.to(DEV), w.to(DEV), b.to(DEV)
+    y = torch.zeros(tuple(dy.shape), device=DEV)
+    torch.cuda.synchronize()
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        conv.conv_forward(d, xd, wd, bd, y, ws)
+    s.synchronize()
+    assert nerr(y, oracle.forward(op, x.numpy(), w.numpy(), b.numpy())) <= TOL

@@ -138,7 +138,7 @@ def main():
     (dl, dp), dms = max(((k, sum(v) / len(v)) for k, v in acc.items()), key=lambda kv: kv[1])
     dlayer = workloads.BY_NAME[dl]
     dstate = next(t for t in state if t["layer"].name == dl)
-    kernel_names = dict(kv.split("=") for kv in conv.conv_desc_kernel_names(dstate["desc"]).split(";"))
+    kernel_names = dict(kv.split("=", 1) for kv in conv.conv_desc_kernel_names(dstate["desc"]).split(";"))
     if dp == "bwd_bias":
         bytes_launch = 4 * dlayer.n * dlayer.k * dlayer.out_hw * dlayer.out_hw
         achieved = bytes_launch / (dms * 1e-3) / 1e9

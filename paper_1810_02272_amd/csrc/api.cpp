@@ -120,6 +120,7 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
     a.IHW = p.h * p.w;
     a.in_img_stride = (int32_t)(C * H * W);
     a.in_grp_stride = (int32_t)(Cg * H * W);
+    a.in_bytes = (uint32_t)(4 * x_elems);
     a.TW = p.kernel_w;
     a.THW = p.kernel_h * p.kernel_w;
     a.mTW = make_magic(a.TW);
@@ -193,6 +194,7 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
     a.IHW = (int32_t)(OH * OW);
     a.in_img_stride = (int32_t)(K * OH * OW);
     a.in_grp_stride = (int32_t)(Kg * OH * OW);
+    a.in_bytes = (uint32_t)(4 * y_elems);
     a.TW = (int32_t)Qw;
     a.THW = (int32_t)(Qh * Qw);
     a.mTW = make_magic(a.TW);

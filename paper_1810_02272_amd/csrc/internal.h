@@ -35,6 +35,7 @@ struct CorrArgs {
   const float* in;    // blob that is gathered, [N][in_chan_total][IH][IW]
   const float* bias;  // per output channel, or null
   float* out;
+  uint32_t in_bytes;  // size of `in`, the range of the gather's hardware bounds check
   // column space
   int32_t ncols, P, PW;  // ncols = N*P, P = PH*PW
   Magic mP, mPW;

@@ -40,7 +40,6 @@ struct CorrCfg {
   static constexpr int SMEM = 2 * STAGE;
   static_assert(WM * WN == 4, "four waves per workgroup");
   static_assert(BN % 64 == 0 && BK % 4 == 0 && BM % 4 == 0, "tile shape");
-  static_assert(RPW * CPL <= 32, "validity bits are kept in one register");
   static_assert(4 * BM + 3 * BN <= SMEM, "epilogue tables reuse the pipeline buffers");
 };
 
@@ -81,14 +80,30 @@ __global__ __launch_bounds__(kThreads) void corr_kernel(const CorrArgs a) {
       ciw0[q] = iw0;
       cbase[q] = 4u * (uint32_t)((int)(n * a.in_img_stride + g * a.in_grp_stride) + ih0 * a.IW + iw0);
     } else {
-      cih0[q] = -(1 << 28);  // every bounds test fails
+      cih0[q] = -(1 << 29);  // every bounds test fails, also with the 2^28 of an invalid k row
       ciw0[q] = 0;
       cbase[q] = 0;
     }
   }
 
+  // A tile: 16-byte pieces, one 32-bit byte offset per piece, advanced by a scalar per chunk
   const float* Ag = a.A + ((size_t)g * a.KP) * a.MP + (size_t)m_tile * BM;
+  uint32_t aoff[C::A_PER];
+#pragma unroll
+  for (int p = 0; p < C::A_PER; ++p) {
+    const int idx = t + p * kThreads;
+    const int row = idx / (BM / 4), c4 = idx % (BM / 4);
+    aoff[p] = 4u * (uint32_t)(row * a.MP + c4 * 4);
+  }
+  const uint32_t a_chunk_bytes = 4u * (uint32_t)(BK * a.MP);
   const int TH = a.THW / a.TW;
+
+  // The gathered blob as a raw buffer resource: a lane whose tap falls outside the image (or
+  // whose k row or column is past the edge) presents an offset past the end, and the hardware
+  // range check returns 0 for it -- no branch, no mask to keep.  (The offset used is the buffer
+  // size itself: the first byte past the end, with no 32-bit wrap when the access size is added.)
+  const __amdgpu_buffer_rsrc_t in_rsrc =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(a.in), 0, (int)a.in_bytes, 0x00020000);
 
   typename M::Acc acc[MB][NB];
 #pragma unroll
@@ -100,35 +115,33 @@ __global__ __launch_bounds__(kThreads) void corr_kernel(const CorrArgs a) {
 
   f32x4 ra[C::A_PER];
   float rb[RPW][CPL];
-  uint32_t okbits = 0;
 
-  auto load_chunk = [&](int k0) {
+  auto load_chunk = [&](int kc) {
 #pragma unroll
     for (int p = 0; p < C::A_PER; ++p) {
       const int idx = t + p * kThreads;
-      if (C::A_F4 % kThreads == 0 || idx < C::A_F4) {
-        const int row = idx / (BM / 4), c4 = idx % (BM / 4);
-        ra[p] = *reinterpret_cast<const f32x4*>(Ag + (size_t)(k0 + row) * a.MP + c4 * 4);
-      }
+      if (C::A_F4 % kThreads == 0 || idx < C::A_F4)
+        ra[p] = *reinterpret_cast<const f32x4*>(reinterpret_cast<const char*>(Ag) +
+                                                (aoff[p] + (uint32_t)kc * a_chunk_bytes));
     }
     // (channel, tap row, tap column) of this wave's first k row: uniform, so scalar work
-    const uint32_t kk0 = (uint32_t)(k0 + wv * RPW);
+    const uint32_t kk0 = (uint32_t)(kc * BK + wv * RPW);
     uint32_t c = mdiv(kk0, a.mTHW);
     const uint32_t rem = kk0 - c * a.THW;
     uint32_t i = mdiv(rem, a.mTW);
     uint32_t j = rem - i * a.TW;
-    okbits = 0;
 #pragma unroll
     for (int e = 0; e < RPW; ++e) {
-      const bool kvalid = (kk0 + e) < (uint32_t)a.Kred;
       const uint32_t koff = 4u * (c * a.IHW + i * a.dh * a.IW + j * a.dw);
-      const int idh = (int)i * a.dh, jdw = (int)j * a.dw;
+      // k rows past the reduction length fail the row test (2^28 is beyond any image)
+      const int idh = (kk0 + e) < (uint32_t)a.Kred ? (int)i * a.dh : (1 << 28);
+      const int jdw = (int)j * a.dw;
 #pragma unroll
       for (int q = 0; q < CPL; ++q) {
         const int ih = cih0[q] + idh, iw = ciw0[q] + jdw;
-        const bool ok = kvalid && (uint32_t)ih < (uint32_t)a.IH && (uint32_t)iw < (uint32_t)a.IW;
-        rb[e][q] = ld_f32(a.in, ok ? cbase[q] + koff : 0u);
-        okbits |= (ok ? 1u : 0u) << (e * CPL + q);
+        const bool ok = ((uint32_t)ih < (uint32_t)a.IH) & ((uint32_t)iw < (uint32_t)a.IW);
+        rb[e][q] = __builtin_bit_cast(
+            float, __builtin_amdgcn_raw_buffer_load_b32(in_rsrc, ok ? cbase[q] + koff : a.in_bytes, 0, 0));
       }
       if (++j == (uint32_t)a.TW) {
         j = 0;
@@ -154,25 +167,28 @@ __global__ __launch_bounds__(kThreads) void corr_kernel(const CorrArgs a) {
 #pragma unroll
     for (int e = 0; e < RPW; ++e)
 #pragma unroll
-      for (int q = 0; q < CPL; ++q)
-        sB[(wv * RPW + e) * LDB + q * 64 + lane] = ((okbits >> (e * CPL + q)) & 1u) ? rb[e][q] : 0.f;
+      for (int q = 0; q < CPL; ++q) sB[(wv * RPW + e) * LDB + q * 64 + lane] = rb[e][q];
   };
 
   auto compute_chunk = [&](int buf) {
-    const float* sA = smem + buf * C::STAGE;
-    const float* sB = sA + BK * LDA;
-    const int krow = lane / MT, mi = lane % MT;
+    const float* sA = smem + buf * C::STAGE + (lane / MT) * LDA + wm * MB * MT + lane % MT;
+    const float* sB = smem + buf * C::STAGE + BK * LDA + (lane / MT) * LDB + wn * NB * MT + lane % MT;
+    constexpr int NKS = BK / M::KS;
+    float av[2][MB], bv[2][NB];
+    auto fetch = [&](int ks, int slot) {
 #pragma unroll
-    for (int ks = 0; ks < BK / M::KS; ++ks) {
-      float av[MB], bv[NB];
+      for (int i = 0; i < MB; ++i) av[slot][i] = sA[ks * M::KS * LDA + i * MT];
 #pragma unroll
-      for (int i = 0; i < MB; ++i) av[i] = sA[(ks * M::KS + krow) * LDA + (wm * MB + i) * MT + mi];
+      for (int j = 0; j < NB; ++j) bv[slot][j] = sB[ks * M::KS * LDB + j * MT];
+    };
+    fetch(0, 0);
 #pragma unroll
-      for (int j = 0; j < NB; ++j) bv[j] = sB[(ks * M::KS + krow) * LDB + (wn * NB + j) * MT + mi];
+    for (int ks = 0; ks < NKS; ++ks) {
+      if (ks + 1 < NKS) fetch(ks + 1, (ks + 1) & 1);  // operands of the next step, ahead of this step's MFMAs
 #pragma unroll
       for (int i = 0; i < MB; ++i)
 #pragma unroll
-        for (int j = 0; j < NB; ++j) M::run(av[i], bv[j], acc[i][j]);
+        for (int j = 0; j < NB; ++j) M::run(av[ks & 1][i], bv[ks & 1][j], acc[i][j]);
     }
   };
 
@@ -182,7 +198,7 @@ __global__ __launch_bounds__(kThreads) void corr_kernel(const CorrArgs a) {
   __syncthreads();
   for (int kc = 0; kc < nchunks; ++kc) {
     const bool more = kc + 1 < nchunks;
-    if (more) load_chunk((kc + 1) * BK);
+    if (more) load_chunk(kc + 1);
     compute_chunk(kc & 1);
     if (more) store_chunk((kc + 1) & 1);
     __syncthreads();

@@ -25,18 +25,33 @@ int64_t floor_div(int64_t a, int64_t b) {
 int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 int64_t round_up(int64_t a, int64_t b) { return ceil_div(a, b) * b; }
 
-// Smallest padded row count wins; ties go to the larger tile.
-int32_t pick_corr_tile(int32_t rows) {
-  int32_t best = -1;
+// Row tile: the smallest padded row count wins, ties go to the taller tile.  Column tile, among
+// the variants of that height: the one with the smallest estimated makespan on 256 compute
+// units -- rounds of workgroups times tile width -- with a 6 % handicap per halving of the
+// width (narrow tiles re-read the packed weights more often per FLOP).
+int32_t pick_corr_tile(int32_t rows, int64_t groups, int64_t ncols) {
   int64_t best_pad = 0, best_bm = 0;
   for (int32_t t = 0; t < CORR_TILE_COUNT; ++t) {
     int32_t bm, bn, bk;
     corr_tile_shape(t, &bm, &bn, &bk);
     const int64_t pad = round_up(rows, bm);
-    if (best < 0 || pad < best_pad || (pad == best_pad && bm > best_bm)) {
-      best = t;
+    if (best_bm == 0 || pad < best_pad || (pad == best_pad && bm > best_bm)) {
       best_pad = pad;
       best_bm = bm;
+    }
+  }
+  int32_t best = -1;
+  double best_cost = 0;
+  for (int32_t t = 0; t < CORR_TILE_COUNT; ++t) {
+    int32_t bm, bn, bk;
+    corr_tile_shape(t, &bm, &bn, &bk);
+    if (bm != best_bm) continue;
+    const int64_t units = groups * (best_pad / bm) * ceil_div(ncols > 0 ? ncols : 1, bn);
+    double cost = (double)ceil_div(units, 256) * bn;
+    for (int32_t w = bn; w < 256; w *= 2) cost *= 1.06;
+    if (best < 0 || cost < best_cost) {
+      best = t;
+      best_cost = cost;
     }
   }
   return best;
@@ -107,7 +122,7 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
 
   // ---- forward: rows = output channels of a group, k = (c, i, j), columns = (n, oh, ow) ----
   {
-    d->fwd_tile = pick_corr_tile((int32_t)Kg);
+    d->fwd_tile = pick_corr_tile((int32_t)Kg, G, N * OH * OW);
     corr_tile_shape(d->fwd_tile, &bm, &bn, &bk);
     CorrArgs& a = d->fwd;
     a.ncols = (int32_t)(N * OH * OW);
@@ -169,19 +184,21 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
 
   // ---- backward data: a stride-1 correlation over dy whose rows are (c, row phase, column
   // phase) of dx -- input position h + pad = stride*a + rh collects the taps i with
-  // i*dilation = stride*q + rh from dy row a - q, q = 0 .. Q-1 ----
+  // i*dilation = stride*q + rh from dy row a - q, q = 0 .. Q-1.  Positions with a < a0 =
+  // pad / stride lie wholly in the padding, so the column space starts at a0. ----
   {
     const int64_t Qh = ((int64_t)p.kernel_h - 1) * p.dilation_h / p.stride_h + 1;
     const int64_t Qw = ((int64_t)p.kernel_w - 1) * p.dilation_w / p.stride_w + 1;
-    const int64_t Ah = (H - 1 + p.pad_h) / p.stride_h + 1;
-    const int64_t Aw = (W - 1 + p.pad_w) / p.stride_w + 1;
+    const int64_t a0h = p.pad_h / p.stride_h, a0w = p.pad_w / p.stride_w;
+    const int64_t Ah = (H - 1 + p.pad_h) / p.stride_h + 1 - a0h;
+    const int64_t Aw = (W - 1 + p.pad_w) / p.stride_w + 1 - a0w;
     const int64_t rows = Cg * p.stride_h * p.stride_w;
     const int64_t kred_b = Kg * Qh * Qw;
     if (rows >= ((int64_t)1 << 24) || N * Ah * Aw >= ((int64_t)1 << 31) || kred_b >= kMaxElems) {
       delete d;
       return CONV_ESHAPE;
     }
-    d->bwd_tile = pick_corr_tile((int32_t)rows);
+    d->bwd_tile = pick_corr_tile((int32_t)rows, G, N * Ah * Aw);
     corr_tile_shape(d->bwd_tile, &bm, &bn, &bk);
     CorrArgs& a = d->bwd;
     a.ncols = (int32_t)(N * Ah * Aw);
@@ -200,8 +217,8 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
     a.mTW = make_magic(a.TW);
     a.mTHW = make_magic(a.THW);
     a.sh = a.sw = a.dh = a.dw = 1;
-    a.ph = (int32_t)(Qh - 1);
-    a.pw = (int32_t)(Qw - 1);
+    a.ph = (int32_t)(Qh - 1 - a0h);
+    a.pw = (int32_t)(Qw - 1 - a0w);
     a.Kred = (int32_t)kred_b;
     a.KP = (int32_t)round_up(kred_b, bk);
     a.Mrows = (int32_t)rows;
@@ -211,8 +228,8 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
     a.RShw = p.stride_h * p.stride_w;
     a.mRSw = make_magic(a.RSw);
     a.mRShw = make_magic(a.RShw);
-    a.opad_h = p.pad_h;
-    a.opad_w = p.pad_w;
+    a.opad_h = (int32_t)(p.pad_h - a0h * p.stride_h);
+    a.opad_w = (int32_t)(p.pad_w - a0w * p.stride_w);
     a.OHd = p.h;
     a.OWd = p.w;
     a.out_img_stride = (int32_t)(C * H * W);
@@ -255,6 +272,8 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
     a.PW = (int32_t)OW;
     a.mP = make_magic(a.P);
     a.mPW = make_magic(a.PW);
+    a.dy_bytes = (uint32_t)(4 * y_elems);
+    a.x_bytes = (uint32_t)(4 * x_elems);
     a.Kg = (int32_t)Kg;
     a.Ktot = (int32_t)K;
     a.Cg = (int32_t)Cg;
@@ -276,15 +295,18 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
     a.G = (int32_t)G;
     a.m_tiles = (int32_t)ceil_div(Kg, bm);
     a.n_tiles = (int32_t)ceil_div(kred, bn);
-    // split the reduction so that the grid has about four workgroups per compute unit, each split
-    // at least four k tiles long, and the partials stay below 256 MiB
+    // Split the reduction so that the grid has up to four workgroups per compute unit, each split
+    // at least four k tiles long and the partials at most 32 MiB; a grid slightly above a
+    // multiple of the 256 compute units is trimmed back to it (its last few workgroups would
+    // otherwise run alone).
     const int64_t tiles = G * a.m_tiles * a.n_tiles;
-    int64_t S = ceil_div(1024, tiles);
+    int64_t S = 1024 / tiles;
     const int64_t max_by_len = ceil_div((int64_t)a.ncols, 4 * bk);
-    const int64_t max_by_ws = ((int64_t)64 << 20) / (w_elems > 0 ? w_elems : 1);
+    const int64_t max_by_ws = ((int64_t)8 << 20) / (w_elems > 0 ? w_elems : 1);
     if (S > max_by_len) S = max_by_len;
     if (S > max_by_ws) S = max_by_ws;
     if (S < 1) S = 1;
+    while (S > 1 && tiles * S > 256 && (tiles * S) % 256 != 0 && (tiles * S) % 256 < 64) --S;
     a.cols_per_split = (int32_t)round_up(ceil_div((int64_t)a.ncols > 0 ? a.ncols : 1, S), bk);
     a.S = (int32_t)ceil_div((int64_t)a.ncols > 0 ? a.ncols : 1, a.cols_per_split);
     if (a.S * w_elems >= kMaxElems || tiles * a.S >= ((int64_t)1 << 31)) {

@@ -80,6 +80,7 @@ struct WgradArgs {
   const float* dy;
   const float* x;
   float* part;
+  uint32_t dy_bytes, x_bytes;  // sizes of the two blobs: the ranges of the hardware bounds checks
   int32_t ncols, P, PW;
   Magic mP, mPW;
   int32_t Kg, Ktot;
@@ -110,11 +111,17 @@ struct BiasGradArgs {
 // Tile variants, chosen once per descriptor.
 enum CorrTile : int32_t {
   CORR_128x128 = 0,  // 32x32x2 MFMA, 2x2 waves of 64x64
+  CORR_128x64,       // 32x32x2, 2x2 waves of 64x32
   CORR_96x128,       // 32x32x2, 1x4 waves of 96x32
+  CORR_96x256,       // 32x32x2, 1x4 waves of 96x64
   CORR_64x128,       // 32x32x2, 1x4 waves of 64x32
+  CORR_64x64,        // 32x32x2, 2x2 waves of 32x32
   CORR_32x256,       // 32x32x2, 1x4 waves of 32x64
+  CORR_32x128,       // 32x32x2, 1x4 waves of 32x32
   CORR_48x256,       // 16x16x4, 1x4 waves of 48x64
+  CORR_48x128,       // 16x16x4, 1x4 waves of 48x32
   CORR_16x256,       // 16x16x4, 1x4 waves of 16x64
+  CORR_16x64,        // 16x16x4, 1x4 waves of 16x16
   CORR_TILE_COUNT
 };
 enum WgradTile : int32_t {

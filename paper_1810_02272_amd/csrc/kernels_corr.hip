@@ -324,28 +324,37 @@ int launch_corr_t(const CorrArgs& a, hipStream_t s) {
 }  // namespace
 
 void corr_tile_shape(int32_t tile, int32_t* bm, int32_t* bn, int32_t* bk) {
-  static const int32_t shapes[CORR_TILE_COUNT][3] = {{128, 128, 16}, {96, 128, 16}, {64, 128, 16},
-                                                    {32, 256, 16},  {48, 256, 16}, {16, 256, 16}};
+  static const int32_t shapes[CORR_TILE_COUNT][3] = {
+      {128, 128, 16}, {128, 64, 16}, {96, 128, 16}, {96, 256, 16}, {64, 128, 16}, {64, 64, 16},
+      {32, 256, 16},  {32, 128, 16}, {48, 256, 16}, {48, 128, 16}, {16, 256, 16}, {16, 64, 16}};
   *bm = shapes[tile][0];
   *bn = shapes[tile][1];
   *bk = shapes[tile][2];
 }
 
 const char* corr_tile_name(int32_t tile) {
-  static const char* names[CORR_TILE_COUNT] = {"corr_m32_128x128x16", "corr_m32_96x128x16", "corr_m32_64x128x16",
-                                               "corr_m32_32x256x16",  "corr_m16_48x256x16", "corr_m16_16x256x16"};
+  static const char* names[CORR_TILE_COUNT] = {
+      "corr_m32_128x128x16", "corr_m32_128x64x16", "corr_m32_96x128x16", "corr_m32_96x256x16",
+      "corr_m32_64x128x16",  "corr_m32_64x64x16",  "corr_m32_32x256x16", "corr_m32_32x128x16",
+      "corr_m16_48x256x16",  "corr_m16_48x128x16", "corr_m16_16x256x16", "corr_m16_16x64x16"};
   return names[tile];
 }
 
 int launch_corr(int32_t tile, const CorrArgs& a, void* stream) {
   hipStream_t s = (hipStream_t)stream;
-  switch (tile) {
+  switch (tile) {  //                      MT MB NB WM WN BK
     case CORR_128x128: return launch_corr_t<32, 2, 2, 2, 2, 16>(a, s);
+    case CORR_128x64:  return launch_corr_t<32, 2, 1, 2, 2, 16>(a, s);
     case CORR_96x128:  return launch_corr_t<32, 3, 1, 1, 4, 16>(a, s);
+    case CORR_96x256:  return launch_corr_t<32, 3, 2, 1, 4, 16>(a, s);
     case CORR_64x128:  return launch_corr_t<32, 2, 1, 1, 4, 16>(a, s);
+    case CORR_64x64:   return launch_corr_t<32, 1, 1, 2, 2, 16>(a, s);
     case CORR_32x256:  return launch_corr_t<32, 1, 2, 1, 4, 16>(a, s);
+    case CORR_32x128:  return launch_corr_t<32, 1, 1, 1, 4, 16>(a, s);
     case CORR_48x256:  return launch_corr_t<16, 3, 4, 1, 4, 16>(a, s);
+    case CORR_48x128:  return launch_corr_t<16, 3, 2, 1, 4, 16>(a, s);
     case CORR_16x256:  return launch_corr_t<16, 1, 4, 1, 4, 16>(a, s);
+    case CORR_16x64:   return launch_corr_t<16, 1, 1, 1, 4, 16>(a, s);
     default: return (int)hipErrorInvalidValue;
   }
 }

@@ -32,7 +32,6 @@ struct WgCfg {
   static constexpr int STAGE = (BM + BN) * LDK;
   static constexpr int SMEM_BYTES = 2 * STAGE * 4;
   static_assert(WM * WN == 4, "four waves per workgroup");
-  static_assert(B_PER <= 32, "validity bits are kept in one register");
 };
 
 template <int MB, int NB, int WM, int WN>
@@ -93,13 +92,19 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradArgs a) {
 #pragma unroll
       for (int r = 0; r < M::NR; ++r) acc[i][j][r] = 0.f;
 
+  // Both blobs as raw buffer resources: a lane whose column is past the split, or whose tap falls
+  // outside the image, presents the buffer size as its offset and the hardware range check
+  // returns 0 for it (no branch, no mask to keep).
+  const __amdgpu_buffer_rsrc_t dy_rsrc =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(a.dy), 0, (int)a.dy_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t x_rsrc =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(a.x), 0, (int)a.x_bytes, 0x00020000);
+
   float ra[A_PER], rb[B_PER];
-  uint32_t okbits = 0;
-  bool colok = false;
 
   auto load_chunk = [&](int chunk) {
     const uint32_t col = c_begin + chunk * BK + kc;
-    colok = col < c_end;
+    const bool colok = col < c_end;
     uint32_t n = 0, pix = 0;
     int ih0 = -(1 << 28), iw0 = 0;
     if (colok) {
@@ -113,14 +118,15 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradArgs a) {
     const uint32_t dybase = 4u * ((n * a.Ktot + g * a.Kg) * (uint32_t)a.P + pix);
     const uint32_t xbase = 4u * (uint32_t)((int)(n * (uint32_t)(a.C * a.HW)) + ih0 * a.W + iw0);
 #pragma unroll
-    for (int e = 0; e < A_PER; ++e) ra[e] = ld_f32(a.dy, colok ? dybase + aoff[e] : 0u);
-    okbits = 0;
+    for (int e = 0; e < A_PER; ++e)
+      ra[e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+                                            dy_rsrc, colok ? dybase + aoff[e] : a.dy_bytes, 0, 0));
 #pragma unroll
     for (int e = 0; e < B_PER; ++e) {
       const int ih = ih0 + (int)(bij[e] >> 16), iw = iw0 + (int)(bij[e] & 0xffffu);
-      const bool ok = (uint32_t)ih < (uint32_t)a.H && (uint32_t)iw < (uint32_t)a.W;
-      rb[e] = ld_f32(a.x, ok ? xbase + boff[e] : 0u);
-      okbits |= (ok ? 1u : 0u) << e;
+      const bool ok = ((uint32_t)ih < (uint32_t)a.H) & ((uint32_t)iw < (uint32_t)a.W);
+      rb[e] = __builtin_bit_cast(
+          float, __builtin_amdgcn_raw_buffer_load_b32(x_rsrc, ok ? xbase + boff[e] : a.x_bytes, 0, 0));
     }
   };
 
@@ -128,22 +134,21 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradArgs a) {
     float* sA = smem + buf * C::STAGE;
     float* sB = sA + BM * LDK;
 #pragma unroll
-    for (int e = 0; e < A_PER; ++e) sA[(rslot + 8 * e) * LDK + kc] = colok ? ra[e] : 0.f;
+    for (int e = 0; e < A_PER; ++e) sA[(rslot + 8 * e) * LDK + kc] = ra[e];
 #pragma unroll
-    for (int e = 0; e < B_PER; ++e) sB[(rslot + 8 * e) * LDK + kc] = ((okbits >> e) & 1u) ? rb[e] : 0.f;
+    for (int e = 0; e < B_PER; ++e) sB[(rslot + 8 * e) * LDK + kc] = rb[e];
   };
 
   auto compute_chunk = [&](int buf) {
-    const float* sA = smem + buf * C::STAGE;
-    const float* sB = sA + BM * LDK;
-    const int krow = lane >> 5, mi = lane & 31;
+    const float* sA = smem + buf * C::STAGE + (wm * MB * 32 + (lane & 31)) * LDK + (lane >> 5);
+    const float* sB = smem + buf * C::STAGE + BM * LDK + (wn * NB * 32 + (lane & 31)) * LDK + (lane >> 5);
 #pragma unroll
     for (int ks = 0; ks < BK / 2; ++ks) {
       float av[MB], bv[NB];
 #pragma unroll
-      for (int i = 0; i < MB; ++i) av[i] = sA[((wm * MB + i) * 32 + mi) * LDK + ks * 2 + krow];
+      for (int i = 0; i < MB; ++i) av[i] = sA[i * 32 * LDK + ks * 2];
 #pragma unroll
-      for (int j = 0; j < NB; ++j) bv[j] = sB[((wn * NB + j) * 32 + mi) * LDK + ks * 2 + krow];
+      for (int j = 0; j < NB; ++j) bv[j] = sB[j * 32 * LDK + ks * 2];
 #pragma unroll
       for (int i = 0; i < MB; ++i)
 #pragma unroll
@@ -194,14 +199,35 @@ int launch_wgrad_t(const WgradArgs& a, hipStream_t s) {
   return (int)hipGetLastError();
 }
 
-// dst = beta*dst + sum_s part[s]; the partials are added in split order, so the result does not
-// depend on scheduling.
+// dst = beta*dst + sum_s part[s].  A block owns 64 consecutive elements; its four waves each add
+// a contiguous quarter of the splits (four independent chains per lane), and the four quarter
+// sums are combined in a fixed order, so the result does not depend on scheduling.
 __global__ __launch_bounds__(256) void reduce_kernel(const ReduceArgs a) {
-  const int i = blockIdx.x * 256 + threadIdx.x;
-  if (i >= a.count) return;
-  float s = 0.f;
-  for (int k = 0; k < a.S; ++k) s += a.part[(size_t)k * a.count + i];
-  a.dst[i] = (a.beta == 0.f) ? s : a.beta * a.dst[i] + s;
+  __shared__ float quarter[4][64];
+  const int lane = threadIdx.x & 63, q = threadIdx.x >> 6;
+  const int i = blockIdx.x * 64 + lane;
+  const int per = (a.S + 3) / 4;
+  const int s0 = q * per;
+  int s1 = s0 + per;
+  if (s1 > a.S) s1 = a.S;
+  float acc0 = 0.f, acc1 = 0.f, acc2 = 0.f, acc3 = 0.f;
+  if (i < a.count) {
+    const float* src = a.part + i;
+    int k = s0;
+    for (; k + 3 < s1; k += 4) {
+      acc0 += src[(size_t)k * a.count];
+      acc1 += src[(size_t)(k + 1) * a.count];
+      acc2 += src[(size_t)(k + 2) * a.count];
+      acc3 += src[(size_t)(k + 3) * a.count];
+    }
+    for (; k < s1; ++k) acc0 += src[(size_t)k * a.count];
+  }
+  quarter[q][lane] = (acc0 + acc1) + (acc2 + acc3);
+  __syncthreads();
+  if (q == 0 && i < a.count) {
+    const float s = (quarter[0][lane] + quarter[1][lane]) + (quarter[2][lane] + quarter[3][lane]);
+    a.dst[i] = (a.beta == 0.f) ? s : a.beta * a.dst[i] + s;
+  }
 }
 
 }  // namespace
@@ -233,7 +259,7 @@ int launch_wgrad(int32_t tile, const WgradArgs& a, void* stream) {
 }
 
 int launch_reduce(const ReduceArgs& a, void* stream) {
-  hipLaunchKernelGGL(reduce_kernel, dim3((a.count + 255) / 256), dim3(256), 0, (hipStream_t)stream, a);
+  hipLaunchKernelGGL(reduce_kernel, dim3((a.count + 63) / 64), dim3(256), 0, (hipStream_t)stream, a);
   return (int)hipGetLastError();
 }
 

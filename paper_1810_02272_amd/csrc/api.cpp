@@ -174,12 +174,18 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
     k.KP = a.KP;
     k.Mrows = a.Mrows;
     k.MP = a.MP;
+    k.tTW = a.TW;
+    k.tTHW = a.THW;
+    k.tIW = a.IW;
+    k.tIHW = a.IHW;
+    k.tdh = a.dh;
+    k.tdw = a.dw;
     const int64_t pack_elems = G * (int64_t)a.KP * a.MP;
     if (pack_elems >= kMaxElems || (int64_t)G * a.m_tiles * a.col_tiles >= ((int64_t)1 << 31)) {
       delete d;
       return CONV_ESHAPE;
     }
-    d->fwd_ws = (size_t)pack_elems * 4;
+    d->fwd_ws = (size_t)pack_elems * 4 + (size_t)a.KP * sizeof(KTabEntry);
   }
 
   // ---- backward data: a stride-1 correlation over dy whose rows are (c, row phase, column
@@ -254,12 +260,18 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
     k.KP = a.KP;
     k.Mrows = a.Mrows;
     k.MP = a.MP;
+    k.tTW = a.TW;
+    k.tTHW = a.THW;
+    k.tIW = a.IW;
+    k.tIHW = a.IHW;
+    k.tdh = a.dh;
+    k.tdw = a.dw;
     const int64_t pack_elems = G * (int64_t)a.KP * a.MP;
     if (pack_elems >= kMaxElems || (int64_t)G * a.m_tiles * a.col_tiles >= ((int64_t)1 << 31)) {
       delete d;
       return CONV_ESHAPE;
     }
-    d->bwd_ws = (size_t)pack_elems * 4;
+    d->bwd_ws = (size_t)pack_elems * 4 + (size_t)a.KP * sizeof(KTabEntry);
   }
 
   // ---- backward filter: rows = output channels, columns = (c, i, j), reduction over (n, oh, ow)
@@ -373,10 +385,12 @@ int conv_forward(const conv_desc_t* d, const float* x, const float* w, const flo
   PackArgs k = d->fwd_pack;
   k.w = w;
   k.A = static_cast<float*>(ws);
+  k.ktab = reinterpret_cast<KTabEntry*>(k.A + (size_t)k.G * k.KP * k.MP);
   int e = launch_pack(k, hip_stream);
   if (e) return hip_fail(e);
   CorrArgs a = d->fwd;
   a.A = k.A;
+  a.ktab = k.ktab;
   a.in = x;
   a.bias = bias;
   a.out = y;
@@ -393,10 +407,12 @@ int conv_backward_data(const conv_desc_t* d, const float* w, const float* dy, fl
   PackArgs k = d->bwd_pack;
   k.w = w;
   k.A = static_cast<float*>(ws);
+  k.ktab = reinterpret_cast<KTabEntry*>(k.A + (size_t)k.G * k.KP * k.MP);
   int e = launch_pack(k, hip_stream);
   if (e) return hip_fail(e);
   CorrArgs a = d->bwd;
   a.A = k.A;
+  a.ktab = k.ktab;
   a.in = dy;
   a.bias = nullptr;
   a.out = dx;

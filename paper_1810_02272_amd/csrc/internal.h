@@ -30,8 +30,17 @@ inline Magic make_magic(uint32_t d) {
 //   D[m][col] = sum_kk A[kk][m] * gather(in)[kk][col]
 // with kk = (channel, tap_h, tap_w), col = (image, a, b), and a table-driven epilogue that
 // scatters row m / column col to its place in the output blob.
+// Per reduction index kk = (c, i, j): byte offset c*IH*IW + i*dh*IW + j*dw of the tap and its
+// row / column displacement (for the bounds test).  Entries past the reduction length carry a
+// row displacement that fails every bounds test.
+struct KTabEntry {
+  uint32_t koff;
+  int32_t idh, jdw, pad;
+};
+
 struct CorrArgs {
   const float* A;     // packed operand, [G][KP][MP] floats, zero padded
+  const KTabEntry* ktab;  // [KP], written by the pack kernel
   const float* in;    // blob that is gathered, [N][in_chan_total][IH][IW]
   const float* bias;  // per output channel, or null
   float* out;
@@ -68,6 +77,8 @@ struct CorrArgs {
 struct PackArgs {
   const float* w;
   float* A;
+  KTabEntry* ktab;
+  int32_t tTW, tTHW, tIW, tIHW, tdh, tdw;  // gather geometry for the k table
   int32_t mode;
   int32_t G, Kg, Cg, kh, kw;
   int32_t sh, sw, dh, dw;
@@ -113,7 +124,6 @@ enum CorrTile : int32_t {
   CORR_128x128 = 0,  // 32x32x2 MFMA, 2x2 waves of 64x64
   CORR_128x64,       // 32x32x2, 2x2 waves of 64x32
   CORR_96x128,       // 32x32x2, 1x4 waves of 96x32
-  CORR_96x256,       // 32x32x2, 1x4 waves of 96x64
   CORR_64x128,       // 32x32x2, 1x4 waves of 64x32
   CORR_64x64,        // 32x32x2, 2x2 waves of 32x32
   CORR_32x256,       // 32x32x2, 1x4 waves of 32x64

@@ -96,7 +96,6 @@ __global__ __launch_bounds__(kThreads) void corr_kernel(const CorrArgs a) {
     aoff[p] = 4u * (uint32_t)(row * a.MP + c4 * 4);
   }
   const uint32_t a_chunk_bytes = 4u * (uint32_t)(BK * a.MP);
-  const int TH = a.THW / a.TW;
 
   // The gathered blob as a raw buffer resource: a lane whose tap falls outside the image (or
   // whose k row or column is past the edge) presents an offset past the end, and the hardware
@@ -116,91 +115,112 @@ __global__ __launch_bounds__(kThreads) void corr_kernel(const CorrArgs a) {
   f32x4 ra[C::A_PER];
   float rb[RPW][CPL];
 
-  auto load_chunk = [&](int kc) {
-#pragma unroll
-    for (int p = 0; p < C::A_PER; ++p) {
-      const int idx = t + p * kThreads;
-      if (C::A_F4 % kThreads == 0 || idx < C::A_F4)
-        ra[p] = *reinterpret_cast<const f32x4*>(reinterpret_cast<const char*>(Ag) +
-                                                (aoff[p] + (uint32_t)kc * a_chunk_bytes));
-    }
-    // (channel, tap row, tap column) of this wave's first k row: uniform, so scalar work
-    const uint32_t kk0 = (uint32_t)(kc * BK + wv * RPW);
-    uint32_t c = mdiv(kk0, a.mTHW);
-    const uint32_t rem = kk0 - c * a.THW;
-    uint32_t i = mdiv(rem, a.mTW);
-    uint32_t j = rem - i * a.TW;
-#pragma unroll
-    for (int e = 0; e < RPW; ++e) {
-      const uint32_t koff = 4u * (c * a.IHW + i * a.dh * a.IW + j * a.dw);
-      // k rows past the reduction length fail the row test (2^28 is beyond any image)
-      const int idh = (kk0 + e) < (uint32_t)a.Kred ? (int)i * a.dh : (1 << 28);
-      const int jdw = (int)j * a.dw;
-#pragma unroll
-      for (int q = 0; q < CPL; ++q) {
-        const int ih = cih0[q] + idh, iw = ciw0[q] + jdw;
-        const bool ok = ((uint32_t)ih < (uint32_t)a.IH) & ((uint32_t)iw < (uint32_t)a.IW);
-        rb[e][q] = __builtin_bit_cast(
-            float, __builtin_amdgcn_raw_buffer_load_b32(in_rsrc, ok ? cbase[q] + koff : a.in_bytes, 0, 0));
-      }
-      if (++j == (uint32_t)a.TW) {
-        j = 0;
-        if (++i == (uint32_t)TH) {
-          i = 0;
-          ++c;
-        }
-      }
+  auto load_a = [&](int kc, int p) {
+    const int idx = t + p * kThreads;
+    if (C::A_F4 % kThreads == 0 || idx < C::A_F4)
+      ra[p] = *reinterpret_cast<const f32x4*>(reinterpret_cast<const char*>(Ag) +
+                                              (aoff[p] + (uint32_t)kc * a_chunk_bytes));
+  };
+  auto store_a = [&](int buf, int p) {
+    const int idx = t + p * kThreads;
+    if (C::A_F4 % kThreads == 0 || idx < C::A_F4) {
+      const int row = idx / (BM / 4), c4 = idx % (BM / 4);
+      *reinterpret_cast<f32x4*>(smem + buf * C::STAGE + row * LDA + c4 * 4) = ra[p];
     }
   };
-
-  auto store_chunk = [&](int buf) {
-    float* sA = smem + buf * C::STAGE;
-    float* sB = sA + BK * LDA;
+  // Rows of this wave in a chunk: each tap's byte offset and (row, column) displacement come from
+  // the k table with scalar loads (the index is uniform over the wave), fetched one iteration
+  // ahead of their use so that their latency never sits in front of an MFMA.
+  KTabEntry te[RPW];
+  auto load_tab = [&](int kc) {
 #pragma unroll
-    for (int p = 0; p < C::A_PER; ++p) {
-      const int idx = t + p * kThreads;
-      if (C::A_F4 % kThreads == 0 || idx < C::A_F4) {
-        const int row = idx / (BM / 4), c4 = idx % (BM / 4);
-        *reinterpret_cast<f32x4*>(sA + row * LDA + c4 * 4) = ra[p];
-      }
+    for (int e = 0; e < RPW; ++e) te[e] = a.ktab[kc * BK + wv * RPW + e];
+  };
+  auto load_b = [&](int e) {
+#pragma unroll
+    for (int q = 0; q < CPL; ++q) {
+      const int ih = cih0[q] + te[e].idh, iw = ciw0[q] + te[e].jdw;
+      const bool ok = ((uint32_t)ih < (uint32_t)a.IH) & ((uint32_t)iw < (uint32_t)a.IW);
+      rb[e][q] = __builtin_bit_cast(
+          float, __builtin_amdgcn_raw_buffer_load_b32(in_rsrc, ok ? cbase[q] + te[e].koff : a.in_bytes, 0, 0));
     }
+  };
+  auto store_b = [&](int buf, int e) {
+    float* sB = smem + buf * C::STAGE + BK * LDA;
 #pragma unroll
-    for (int e = 0; e < RPW; ++e)
-#pragma unroll
-      for (int q = 0; q < CPL; ++q) sB[(wv * RPW + e) * LDB + q * 64 + lane] = rb[e][q];
+    for (int q = 0; q < CPL; ++q) sB[(wv * RPW + e) * LDB + q * 64 + lane] = rb[e][q];
   };
 
-  auto compute_chunk = [&](int buf) {
-    const float* sA = smem + buf * C::STAGE + (lane / MT) * LDA + wm * MB * MT + lane % MT;
-    const float* sB = smem + buf * C::STAGE + BK * LDA + (lane / MT) * LDB + wn * NB * MT + lane % MT;
-    constexpr int NKS = BK / M::KS;
+  // Software pipeline, three chunks deep: while the MFMA pipe works on chunk k out of one LDS
+  // buffer, the registers holding chunk k+1 (loaded during the previous iteration, so long since
+  // arrived) are written to the other buffer and immediately reloaded with chunk k+2.  The
+  // stores and loads are spread over the k steps of the chunk so that their address arithmetic
+  // issues in the shadow of the MFMAs of the same wave.  Chunk indices past the end are clamped:
+  // the last iterations re-load and re-store the final chunk into a buffer nobody reads.
+  const int nchunks = a.KP / BK;
+  constexpr int NKS = BK / M::KS;
+  const float* opA = smem + (lane / MT) * LDA + wm * MB * MT + lane % MT;
+  const float* opB = smem + BK * LDA + (lane / MT) * LDB + wn * NB * MT + lane % MT;
+
+  load_tab(0);
+#pragma unroll
+  for (int p = 0; p < C::A_PER; ++p) load_a(0, p);
+#pragma unroll
+  for (int e = 0; e < RPW; ++e) load_b(e);
+#pragma unroll
+  for (int p = 0; p < C::A_PER; ++p) store_a(0, p);
+#pragma unroll
+  for (int e = 0; e < RPW; ++e) store_b(0, e);
+  {
+    const int k1 = nchunks > 1 ? 1 : 0;
+    load_tab(k1);
+#pragma unroll
+    for (int p = 0; p < C::A_PER; ++p) load_a(k1, p);
+#pragma unroll
+    for (int e = 0; e < RPW; ++e) load_b(e);
+  }
+  load_tab(nchunks > 2 ? 2 : nchunks - 1);
+  __syncthreads();
+
+  for (int kc = 0; kc < nchunks; ++kc) {
+    const int cur = kc & 1, nxt = cur ^ 1;
+    const int kld = kc + 2 < nchunks ? kc + 2 : nchunks - 1;
+    const float* sA = opA + cur * C::STAGE;
+    const float* sB = opB + cur * C::STAGE;
     float av[2][MB], bv[2][NB];
-    auto fetch = [&](int ks, int slot) {
 #pragma unroll
-      for (int i = 0; i < MB; ++i) av[slot][i] = sA[ks * M::KS * LDA + i * MT];
+    for (int i = 0; i < MB; ++i) av[0][i] = sA[i * MT];
 #pragma unroll
-      for (int j = 0; j < NB; ++j) bv[slot][j] = sB[ks * M::KS * LDB + j * MT];
-    };
-    fetch(0, 0);
+    for (int j = 0; j < NB; ++j) bv[0][j] = sB[j * MT];
 #pragma unroll
     for (int ks = 0; ks < NKS; ++ks) {
-      if (ks + 1 < NKS) fetch(ks + 1, (ks + 1) & 1);  // operands of the next step, ahead of this step's MFMAs
+      if (ks + 1 < NKS) {  // operands of the next step, ahead of this step's MFMAs
+#pragma unroll
+        for (int i = 0; i < MB; ++i) av[(ks + 1) & 1][i] = sA[(ks + 1) * M::KS * LDA + i * MT];
+#pragma unroll
+        for (int j = 0; j < NB; ++j) bv[(ks + 1) & 1][j] = sB[(ks + 1) * M::KS * LDB + j * MT];
+      }
 #pragma unroll
       for (int i = 0; i < MB; ++i)
 #pragma unroll
         for (int j = 0; j < NB; ++j) M::run(av[ks & 1][i], bv[ks & 1][j], acc[i][j]);
+      // this step's share of the staging work
+#pragma unroll
+      for (int e = 0; e < RPW; ++e)
+        if (e * NKS / RPW == ks) {
+          store_b(nxt, e);
+          load_b(e);
+        }
+#pragma unroll
+      for (int p = 0; p < C::A_PER; ++p)
+        if ((p * NKS + NKS / 2) / C::A_PER % NKS == ks) {
+          store_a(nxt, p);
+          load_a(kld, p);
+        }
+      __builtin_amdgcn_sched_barrier(0);
     }
-  };
-
-  const int nchunks = a.KP / BK;
-  load_chunk(0);
-  store_chunk(0);
-  __syncthreads();
-  for (int kc = 0; kc < nchunks; ++kc) {
-    const bool more = kc + 1 < nchunks;
-    if (more) load_chunk(kc + 1);
-    compute_chunk(kc & 1);
-    if (more) store_chunk((kc + 1) & 1);
+    load_tab(kc + 3 < nchunks ? kc + 3 : nchunks - 1);  // table entries of the next iteration's loads
+    __builtin_amdgcn_sched_barrier(0);
     __syncthreads();
   }
 
@@ -266,6 +286,18 @@ __global__ __launch_bounds__(kThreads) void corr_kernel(const CorrArgs a) {
   }
 }
 
+// One k-table entry: where tap kk = (c, i, j) of the gather sits relative to a column's base.
+__device__ __forceinline__ void fill_ktab(const PackArgs& a, int kk) {
+  const int c = kk / a.tTHW, rem = kk % a.tTHW;
+  const int i = rem / a.tTW, j = rem % a.tTW;
+  KTabEntry e;
+  e.koff = 4u * (uint32_t)(c * a.tIHW + i * a.tdh * a.tIW + j * a.tdw);
+  e.idh = kk < a.Kred ? i * a.tdh : (1 << 28);  // k rows past the reduction length fail the row test
+  e.jdw = j * a.tdw;
+  e.pad = 0;
+  a.ktab[kk] = e;
+}
+
 // A[g][kk][m] = w[g*Kg + m][kk]: a tiled transpose through LDS, both sides coalesced.
 __global__ __launch_bounds__(256) void pack_fwd_kernel(const PackArgs a) {
   __shared__ float tile[32][33];
@@ -284,6 +316,8 @@ __global__ __launch_bounds__(256) void pack_fwd_kernel(const PackArgs a) {
     const int kk = k0 + ty + 8 * r, m = m0 + tx;
     if (kk < a.KP && m < a.MP) a.A[((size_t)g * a.KP + kk) * a.MP + m] = tile[tx][ty + 8 * r];
   }
+  if (blockIdx.x == 0 && blockIdx.z == 0 && threadIdx.x < 32 && k0 + (int)threadIdx.x < a.KP)
+    fill_ktab(a, k0 + threadIdx.x);
 }
 
 // Backward data: rows are (input channel, row phase, column phase), k is (output channel,
@@ -312,6 +346,7 @@ __global__ __launch_bounds__(256) void pack_bwd_kernel(const PackArgs a) {
     }
   }
   a.A[idx] = v;
+  if (m == 0 && g == 0) fill_ktab(a, kk);
 }
 
 template <int MT, int MB, int NB, int WM, int WN, int BK>
@@ -325,7 +360,7 @@ int launch_corr_t(const CorrArgs& a, hipStream_t s) {
 
 void corr_tile_shape(int32_t tile, int32_t* bm, int32_t* bn, int32_t* bk) {
   static const int32_t shapes[CORR_TILE_COUNT][3] = {
-      {128, 128, 16}, {128, 64, 16}, {96, 128, 16}, {96, 256, 16}, {64, 128, 16}, {64, 64, 16},
+      {128, 128, 16}, {128, 64, 16}, {96, 128, 16}, {64, 128, 16}, {64, 64, 16},
       {32, 256, 16},  {32, 128, 16}, {48, 256, 16}, {48, 128, 16}, {16, 256, 16}, {16, 64, 16}};
   *bm = shapes[tile][0];
   *bn = shapes[tile][1];
@@ -334,7 +369,7 @@ void corr_tile_shape(int32_t tile, int32_t* bm, int32_t* bn, int32_t* bk) {
 
 const char* corr_tile_name(int32_t tile) {
   static const char* names[CORR_TILE_COUNT] = {
-      "corr_m32_128x128x16", "corr_m32_128x64x16", "corr_m32_96x128x16", "corr_m32_96x256x16",
+      "corr_m32_128x128x16", "corr_m32_128x64x16", "corr_m32_96x128x16",
       "corr_m32_64x128x16",  "corr_m32_64x64x16",  "corr_m32_32x256x16", "corr_m32_32x128x16",
       "corr_m16_48x256x16",  "corr_m16_48x128x16", "corr_m16_16x256x16", "corr_m16_16x64x16"};
   return names[tile];
@@ -346,7 +381,6 @@ int launch_corr(int32_t tile, const CorrArgs& a, void* stream) {
     case CORR_128x128: return launch_corr_t<32, 2, 2, 2, 2, 16>(a, s);
     case CORR_128x64:  return launch_corr_t<32, 2, 1, 2, 2, 16>(a, s);
     case CORR_96x128:  return launch_corr_t<32, 3, 1, 1, 4, 16>(a, s);
-    case CORR_96x256:  return launch_corr_t<32, 3, 2, 1, 4, 16>(a, s);
     case CORR_64x128:  return launch_corr_t<32, 2, 1, 1, 4, 16>(a, s);
     case CORR_64x64:   return launch_corr_t<32, 1, 1, 2, 2, 16>(a, s);
     case CORR_32x256:  return launch_corr_t<32, 1, 2, 1, 4, 16>(a, s);

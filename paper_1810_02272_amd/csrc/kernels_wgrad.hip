@@ -102,70 +102,96 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradArgs a) {
 
   float ra[A_PER], rb[B_PER];
 
-  auto load_chunk = [&](int chunk) {
+  // per-lane state of the column (n, oh, ow) this lane loads in the chunk being fetched
+  uint32_t dybase = 0, xbase = 0;
+  int ih0 = 0, iw0 = 0;
+  bool colok = false;
+  auto col_state = [&](int chunk) {
     const uint32_t col = c_begin + chunk * BK + kc;
-    const bool colok = col < c_end;
-    uint32_t n = 0, pix = 0;
-    int ih0 = -(1 << 28), iw0 = 0;
-    if (colok) {
-      n = mdiv(col, a.mP);
-      pix = col - n * a.P;
-      const uint32_t oh = mdiv(pix, a.mPW);
-      const uint32_t ow = pix - oh * a.PW;
-      ih0 = (int)oh * a.sh - a.ph;
-      iw0 = (int)ow * a.sw - a.pw;
-    }
-    const uint32_t dybase = 4u * ((n * a.Ktot + g * a.Kg) * (uint32_t)a.P + pix);
-    const uint32_t xbase = 4u * (uint32_t)((int)(n * (uint32_t)(a.C * a.HW)) + ih0 * a.W + iw0);
-#pragma unroll
-    for (int e = 0; e < A_PER; ++e)
-      ra[e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
-                                            dy_rsrc, colok ? dybase + aoff[e] : a.dy_bytes, 0, 0));
-#pragma unroll
-    for (int e = 0; e < B_PER; ++e) {
-      const int ih = ih0 + (int)(bij[e] >> 16), iw = iw0 + (int)(bij[e] & 0xffffu);
-      const bool ok = ((uint32_t)ih < (uint32_t)a.H) & ((uint32_t)iw < (uint32_t)a.W);
-      rb[e] = __builtin_bit_cast(
-          float, __builtin_amdgcn_raw_buffer_load_b32(x_rsrc, ok ? xbase + boff[e] : a.x_bytes, 0, 0));
-    }
+    colok = col < c_end;
+    const uint32_t n = mdiv(col, a.mP);
+    const uint32_t pix = col - n * a.P;
+    const uint32_t oh = mdiv(pix, a.mPW);
+    const uint32_t ow = pix - oh * a.PW;
+    ih0 = colok ? (int)oh * a.sh - a.ph : -(1 << 28);  // columns past the split fail every bounds test
+    iw0 = (int)ow * a.sw - a.pw;
+    dybase = 4u * ((n * a.Ktot + g * a.Kg) * (uint32_t)a.P + pix);
+    xbase = 4u * (uint32_t)((int)(n * (uint32_t)(a.C * a.HW)) + ih0 * a.W + iw0);
   };
-
-  auto store_chunk = [&](int buf) {
-    float* sA = smem + buf * C::STAGE;
-    float* sB = sA + BM * LDK;
-#pragma unroll
-    for (int e = 0; e < A_PER; ++e) sA[(rslot + 8 * e) * LDK + kc] = ra[e];
-#pragma unroll
-    for (int e = 0; e < B_PER; ++e) sB[(rslot + 8 * e) * LDK + kc] = rb[e];
+  auto load_a = [&](int e) {
+    ra[e] = __builtin_bit_cast(
+        float, __builtin_amdgcn_raw_buffer_load_b32(dy_rsrc, colok ? dybase + aoff[e] : a.dy_bytes, 0, 0));
   };
-
-  auto compute_chunk = [&](int buf) {
-    const float* sA = smem + buf * C::STAGE + (wm * MB * 32 + (lane & 31)) * LDK + (lane >> 5);
-    const float* sB = smem + buf * C::STAGE + BM * LDK + (wn * NB * 32 + (lane & 31)) * LDK + (lane >> 5);
-#pragma unroll
-    for (int ks = 0; ks < BK / 2; ++ks) {
-      float av[MB], bv[NB];
-#pragma unroll
-      for (int i = 0; i < MB; ++i) av[i] = sA[i * 32 * LDK + ks * 2];
-#pragma unroll
-      for (int j = 0; j < NB; ++j) bv[j] = sB[j * 32 * LDK + ks * 2];
-#pragma unroll
-      for (int i = 0; i < MB; ++i)
-#pragma unroll
-        for (int j = 0; j < NB; ++j) M::run(av[i], bv[j], acc[i][j]);
-    }
+  auto load_b = [&](int e) {
+    const int ih = ih0 + (int)(bij[e] >> 16), iw = iw0 + (int)(bij[e] & 0xffffu);
+    const bool ok = ((uint32_t)ih < (uint32_t)a.H) & ((uint32_t)iw < (uint32_t)a.W);
+    rb[e] = __builtin_bit_cast(
+        float, __builtin_amdgcn_raw_buffer_load_b32(x_rsrc, ok ? xbase + boff[e] : a.x_bytes, 0, 0));
   };
+  auto store_a = [&](int buf, int e) { smem[buf * C::STAGE + (rslot + 8 * e) * LDK + kc] = ra[e]; };
+  auto store_b = [&](int buf, int e) { smem[buf * C::STAGE + BM * LDK + (rslot + 8 * e) * LDK + kc] = rb[e]; };
 
+  // Software pipeline, three chunks deep (see the correlation kernel): chunk ch is multiplied out
+  // of one LDS buffer while the registers holding chunk ch+1 are written to the other buffer and
+  // reloaded with chunk ch+2, one or two elements per k step, in the shadow of the MFMAs.
+  constexpr int NKS = BK / 2;
+  const float* opA = smem + (wm * MB * 32 + (lane & 31)) * LDK + (lane >> 5);
+  const float* opB = smem + BM * LDK + (wn * NB * 32 + (lane & 31)) * LDK + (lane >> 5);
   if (nchunks > 0) {
-    load_chunk(0);
-    store_chunk(0);
+    col_state(0);
+#pragma unroll
+    for (int e = 0; e < A_PER; ++e) load_a(e);
+#pragma unroll
+    for (int e = 0; e < B_PER; ++e) load_b(e);
+#pragma unroll
+    for (int e = 0; e < A_PER; ++e) store_a(0, e);
+#pragma unroll
+    for (int e = 0; e < B_PER; ++e) store_b(0, e);
+    col_state(nchunks > 1 ? 1 : 0);
+#pragma unroll
+    for (int e = 0; e < A_PER; ++e) load_a(e);
+#pragma unroll
+    for (int e = 0; e < B_PER; ++e) load_b(e);
   }
   __syncthreads();
   for (int ch = 0; ch < nchunks; ++ch) {
-    const bool more = ch + 1 < nchunks;
-    if (more) load_chunk(ch + 1);
-    compute_chunk(ch & 1);
-    if (more) store_chunk((ch + 1) & 1);
+    const int cur = ch & 1, nxt = cur ^ 1;
+    const float* sA = opA + cur * C::STAGE;
+    const float* sB = opB + cur * C::STAGE;
+    float av[2][MB], bv[2][NB];
+#pragma unroll
+    for (int i = 0; i < MB; ++i) av[0][i] = sA[i * 32 * LDK];
+#pragma unroll
+    for (int j = 0; j < NB; ++j) bv[0][j] = sB[j * 32 * LDK];
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) {
+      if (ks + 1 < NKS) {
+#pragma unroll
+        for (int i = 0; i < MB; ++i) av[(ks + 1) & 1][i] = sA[i * 32 * LDK + (ks + 1) * 2];
+#pragma unroll
+        for (int j = 0; j < NB; ++j) bv[(ks + 1) & 1][j] = sB[j * 32 * LDK + (ks + 1) * 2];
+      }
+#pragma unroll
+      for (int i = 0; i < MB; ++i)
+#pragma unroll
+        for (int j = 0; j < NB; ++j) M::run(av[ks & 1][i], bv[ks & 1][j], acc[i][j]);
+      // this step's share of the staging work: registers of chunk ch+1 go to LDS first ...
+#pragma unroll
+      for (int e = 0; e < A_PER; ++e)
+        if (e * NKS / A_PER == ks) store_a(nxt, e);
+#pragma unroll
+      for (int e = 0; e < B_PER; ++e)
+        if (e * NKS / B_PER == ks) store_b(nxt, e);
+      // ... then are reloaded with chunk ch+2 (column state switches once all stores are queued)
+      if (ks == 0) col_state(ch + 2 < nchunks ? ch + 2 : nchunks - 1);
+#pragma unroll
+      for (int e = 0; e < A_PER; ++e)
+        if (e * NKS / A_PER == ks) load_a(e);
+#pragma unroll
+      for (int e = 0; e < B_PER; ++e)
+        if (e * NKS / B_PER == ks) load_b(e);
+      __builtin_amdgcn_sched_barrier(0);
+    }
     __syncthreads();
   }
 

@@ -136,6 +136,7 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
     a.in_img_stride = (int32_t)(C * H * W);
     a.in_grp_stride = (int32_t)(Cg * H * W);
     a.in_bytes = (uint32_t)(4 * x_elems);
+    a.nopad = (p.pad_h == 0 && p.pad_w == 0 && 4 * x_elems < ((int64_t)1 << 31) - 4) ? 1 : 0;
     a.TW = p.kernel_w;
     a.THW = p.kernel_h * p.kernel_w;
     a.mTW = make_magic(a.TW);

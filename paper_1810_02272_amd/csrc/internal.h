@@ -39,12 +39,13 @@ struct KTabEntry {
 };
 
 struct CorrArgs {
-  const float* A;     // packed operand, [G][KP][MP] floats, zero padded
+  const float* A;     // packed operand, [G][MP][KP] floats, zero padded
   const KTabEntry* ktab;  // [KP], written by the pack kernel
   const float* in;    // blob that is gathered, [N][in_chan_total][IH][IW]
   const float* bias;  // per output channel, or null
   float* out;
   uint32_t in_bytes;  // size of `in`, the range of the gather's hardware bounds check
+  int32_t nopad;      // 1: every tap of a real column is inside the image and in_bytes < 2^31
   // column space
   int32_t ncols, P, PW;  // ncols = N*P, P = PH*PW
   Magic mP, mPW;
@@ -71,7 +72,7 @@ struct CorrArgs {
 };
 
 // Packs the weights into the A operand of the correlation kernel.
-//   mode 0 (forward): A[g][kk][m] = w[g*Kg + m][kk]
+//   mode 0 (forward): A[g][m][kk] = w[g*Kg + m][kk]
 //   mode 1 (backward data): rows m = (c, rh, rw), kk = (k, qh', qw'); the entry is
 //     w[g*Kg + k][c][i][j] with i*dil_h = stride_h*(Qh-1-qh') + rh (and likewise j), else 0.
 struct PackArgs {

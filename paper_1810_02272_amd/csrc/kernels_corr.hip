@@ -9,8 +9,8 @@
 //
 // B is never materialised: each workgroup gathers BK x BN elements of it straight from the NCHW
 // blob into LDS, double buffered, while the fp32 MFMA pipe works on the previous chunk.  A is the
-// weight matrix, packed beforehand into k-major zero-padded form so that its tiles are plain
-// 16-byte row copies.  The epilogue adds the bias and scatters each accumulator through two
+// weight matrix, packed beforehand into zero-padded [row][k] form so that its tiles are plain
+// 16-byte copies.  The epilogue adds the bias and scatters each accumulator through two
 // small LDS tables (row -> channel/sub-pixel offset, column -> image/pixel offset), which is
 // what lets one kernel serve both passes.
 #include <hip/hip_runtime.h>
@@ -28,26 +28,30 @@ template <int MT, int MB, int NB, int WM, int WN, int BK>
 struct CorrCfg {
   static constexpr int BM = WM * MB * MT;
   static constexpr int BN = WN * NB * MT;
-  // Leading dimensions congruent to 16 mod 32 floats: the 16-wide MFMA operand read touches two
-  // k rows per half wave, and this keeps the two rows on disjoint banks.
-  static constexpr int LDA = BM + ((BM % 32 == 16) ? 0 : 16);
-  static constexpr int LDB = BN + ((BN % 32 == 16) ? 0 : 16);
-  static constexpr int RPW = BK / 4;   // gathered k rows per wave and chunk
+  // Both LDS tiles are [row][k] with rows of BK + 4 floats: 16-byte aligned, and any 8 consecutive
+  // rows start on 8 distinct quads of banks, so the 16-byte operand reads (lane -> row) and the
+  // 16-byte staging writes are conflict free.
+  static constexpr int LDK = BK + 4;
+  static constexpr int RPW = 4;        // gathered k rows per wave and chunk: one 16-byte LDS write
   static constexpr int CPL = BN / 64;  // gathered columns per lane
-  static constexpr int A_F4 = BK * BM / 4;
-  static constexpr int A_PER = (A_F4 + kThreads - 1) / kThreads;
-  static constexpr int STAGE = BK * (LDA + LDB);  // floats per pipeline stage
+  static constexpr int A_WI = BM / 16;  // wave-wide 16-byte loads per chunk of A (16 rows x 16 k each)
+  static constexpr int A_PER = (A_WI + 3) / 4;
+  static constexpr int STAGE = (BM + BN) * LDK;  // floats per pipeline stage
   static constexpr int SMEM = 2 * STAGE;
+  static constexpr int KSS = 4 * (64 / MT);  // k values covered by one 16-byte operand read of a wave
+  static constexpr int NSS = BK / KSS;
+  static constexpr int NKS = BK / Mfma<MT>::KS;  // MFMA k steps per chunk
   static_assert(WM * WN == 4, "four waves per workgroup");
-  static_assert(BN % 64 == 0 && BK % 4 == 0 && BM % 4 == 0, "tile shape");
-  static_assert(4 * BM + 3 * BN <= SMEM, "epilogue tables reuse the pipeline buffers");
+  static_assert(BK == 16, "each wave gathers one quad of k rows per chunk");
+  static_assert(BN % 64 == 0 && BM % 16 == 0, "tile shape");
+  static_assert(4 * (BM + BN) <= SMEM, "epilogue tables reuse the pipeline buffers");
 };
 
-template <int MT, int MB, int NB, int WM, int WN, int BK>
+template <int MT, int MB, int NB, int WM, int WN, int BK, bool PAD>
 __global__ __launch_bounds__(kThreads) void corr_kernel(const CorrArgs a) {
   using C = CorrCfg<MT, MB, NB, WM, WN, BK>;
   using M = Mfma<MT>;
-  constexpr int BM = C::BM, BN = C::BN, LDA = C::LDA, LDB = C::LDB, RPW = C::RPW, CPL = C::CPL;
+  constexpr int BM = C::BM, BN = C::BN, LDK = C::LDK, RPW = C::RPW, CPL = C::CPL;
 
   __shared__ __align__(16) float smem[C::SMEM];
 
@@ -63,7 +67,11 @@ __global__ __launch_bounds__(kThreads) void corr_kernel(const CorrArgs a) {
   const uint32_t col_tile = lin % (uint32_t)a.col_tiles;
   const uint32_t g = lin / (uint32_t)a.col_tiles;
 
-  // per-lane column state of the gather (fixed for the whole reduction)
+  // Per-lane column state of the gather (fixed for the whole reduction).  Without padding every
+  // tap of a real column is inside the image, so validity is folded into the offsets: a column
+  // past the edge gets base 2^31 and a k row past the reduction length gets offset 2^31 - 4 (from
+  // the k table); either pushes the sum beyond the buffer (which is then below 2^31 bytes) and
+  // the hardware range check returns 0.
   uint32_t cbase[CPL];
   int cih0[CPL], ciw0[CPL];
 #pragma unroll
@@ -82,25 +90,18 @@ __global__ __launch_bounds__(kThreads) void corr_kernel(const CorrArgs a) {
     } else {
       cih0[q] = -(1 << 29);  // every bounds test fails, also with the 2^28 of an invalid k row
       ciw0[q] = 0;
-      cbase[q] = 0;
+      cbase[q] = 0x80000000u;
     }
   }
 
-  // A tile: 16-byte pieces, one 32-bit byte offset per piece, advanced by a scalar per chunk
-  const float* Ag = a.A + ((size_t)g * a.KP) * a.MP + (size_t)m_tile * BM;
+  // A tile: [row][k], 16 bytes (four k) per lane; a wave-wide load covers 16 rows x 16 k with
+  // 8 consecutive lanes on 8 consecutive rows (conflict-free LDS write, 64-byte runs in memory).
+  const float* Ag = a.A + ((size_t)g * a.MP + (size_t)m_tile * BM) * a.KP;
+  const int arow = (lane & 7) + 8 * (lane >> 5), ac4 = (lane >> 3) & 3;
   uint32_t aoff[C::A_PER];
 #pragma unroll
-  for (int p = 0; p < C::A_PER; ++p) {
-    const int idx = t + p * kThreads;
-    const int row = idx / (BM / 4), c4 = idx % (BM / 4);
-    aoff[p] = 4u * (uint32_t)(row * a.MP + c4 * 4);
-  }
-  const uint32_t a_chunk_bytes = 4u * (uint32_t)(BK * a.MP);
+  for (int p = 0; p < C::A_PER; ++p) aoff[p] = 4u * (uint32_t)(((wv + 4 * p) * 16 + arow) * a.KP + ac4 * 4);
 
-  // The gathered blob as a raw buffer resource: a lane whose tap falls outside the image (or
-  // whose k row or column is past the edge) presents an offset past the end, and the hardware
-  // range check returns 0 for it -- no branch, no mask to keep.  (The offset used is the buffer
-  // size itself: the first byte past the end, with no 32-bit wrap when the access size is added.)
   const __amdgpu_buffer_rsrc_t in_rsrc =
       __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(a.in), 0, (int)a.in_bytes, 0x00020000);
 
@@ -113,20 +114,15 @@ __global__ __launch_bounds__(kThreads) void corr_kernel(const CorrArgs a) {
       for (int r = 0; r < M::NR; ++r) acc[i][j][r] = 0.f;
 
   f32x4 ra[C::A_PER];
-  float rb[RPW][CPL];
+  f32x4 rb[CPL];  // element e of rb[q]: k row 4*wv + e of column q*64 + lane
 
   auto load_a = [&](int kc, int p) {
-    const int idx = t + p * kThreads;
-    if (C::A_F4 % kThreads == 0 || idx < C::A_F4)
-      ra[p] = *reinterpret_cast<const f32x4*>(reinterpret_cast<const char*>(Ag) +
-                                              (aoff[p] + (uint32_t)kc * a_chunk_bytes));
+    if (C::A_WI % 4 == 0 || wv + 4 * p < C::A_WI)
+      ra[p] = *reinterpret_cast<const f32x4*>(reinterpret_cast<const char*>(Ag) + (aoff[p] + (uint32_t)kc * (BK * 4)));
   };
   auto store_a = [&](int buf, int p) {
-    const int idx = t + p * kThreads;
-    if (C::A_F4 % kThreads == 0 || idx < C::A_F4) {
-      const int row = idx / (BM / 4), c4 = idx % (BM / 4);
-      *reinterpret_cast<f32x4*>(smem + buf * C::STAGE + row * LDA + c4 * 4) = ra[p];
-    }
+    if (C::A_WI % 4 == 0 || wv + 4 * p < C::A_WI)
+      *reinterpret_cast<f32x4*>(smem + buf * C::STAGE + ((wv + 4 * p) * 16 + arow) * LDK + ac4 * 4) = ra[p];
   };
   // Rows of this wave in a chunk: each tap's byte offset and (row, column) displacement come from
   // the k table with scalar loads (the index is uniform over the wave), fetched one iteration
@@ -136,19 +132,17 @@ __global__ __launch_bounds__(kThreads) void corr_kernel(const CorrArgs a) {
 #pragma unroll
     for (int e = 0; e < RPW; ++e) te[e] = a.ktab[kc * BK + wv * RPW + e];
   };
-  auto load_b = [&](int e) {
-#pragma unroll
-    for (int q = 0; q < CPL; ++q) {
+  auto load_b = [&](int q, int e) {
+    uint32_t off = cbase[q] + te[e].koff;
+    if (PAD) {
       const int ih = cih0[q] + te[e].idh, iw = ciw0[q] + te[e].jdw;
       const bool ok = ((uint32_t)ih < (uint32_t)a.IH) & ((uint32_t)iw < (uint32_t)a.IW);
-      rb[e][q] = __builtin_bit_cast(
-          float, __builtin_amdgcn_raw_buffer_load_b32(in_rsrc, ok ? cbase[q] + te[e].koff : a.in_bytes, 0, 0));
+      off = ok ? off : a.in_bytes;  // the buffer size: first byte past the end, no 32-bit wrap
     }
+    rb[q][e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(in_rsrc, off, 0, 0));
   };
-  auto store_b = [&](int buf, int e) {
-    float* sB = smem + buf * C::STAGE + BK * LDA;
-#pragma unroll
-    for (int q = 0; q < CPL; ++q) sB[(wv * RPW + e) * LDB + q * 64 + lane] = rb[e][q];
+  auto store_b = [&](int buf, int q) {
+    *reinterpret_cast<f32x4*>(smem + buf * C::STAGE + BM * LDK + (q * 64 + lane) * LDK + wv * 4) = rb[q];
   };
 
   // Software pipeline, three chunks deep: while the MFMA pipe works on chunk k out of one LDS
@@ -157,27 +151,35 @@ __global__ __launch_bounds__(kThreads) void corr_kernel(const CorrArgs a) {
   // stores and loads are spread over the k steps of the chunk so that their address arithmetic
   // issues in the shadow of the MFMAs of the same wave.  Chunk indices past the end are clamped:
   // the last iterations re-load and re-store the final chunk into a buffer nobody reads.
+  //
+  // MFMA operands come from LDS as 16-byte reads: lane l takes row l%MT and the four k values
+  // KSS*s + 4*(l/MT) .. +3, which feed four consecutive MFMAs; the k order inside a group of KSS
+  // is thereby permuted, identically for both operands, which a sum does not notice.
   const int nchunks = a.KP / BK;
-  constexpr int NKS = BK / M::KS;
-  const float* opA = smem + (lane / MT) * LDA + wm * MB * MT + lane % MT;
-  const float* opB = smem + BK * LDA + (lane / MT) * LDB + wn * NB * MT + lane % MT;
+  constexpr int NKS = C::NKS, NSS = C::NSS;
+  const float* opA = smem + (wm * MB * MT + lane % MT) * LDK + (lane / MT) * 4;
+  const float* opB = smem + BM * LDK + (wn * NB * MT + lane % MT) * LDK + (lane / MT) * 4;
 
   load_tab(0);
 #pragma unroll
   for (int p = 0; p < C::A_PER; ++p) load_a(0, p);
 #pragma unroll
-  for (int e = 0; e < RPW; ++e) load_b(e);
+  for (int q = 0; q < CPL; ++q)
+#pragma unroll
+    for (int e = 0; e < RPW; ++e) load_b(q, e);
 #pragma unroll
   for (int p = 0; p < C::A_PER; ++p) store_a(0, p);
 #pragma unroll
-  for (int e = 0; e < RPW; ++e) store_b(0, e);
+  for (int q = 0; q < CPL; ++q) store_b(0, q);
   {
     const int k1 = nchunks > 1 ? 1 : 0;
     load_tab(k1);
 #pragma unroll
     for (int p = 0; p < C::A_PER; ++p) load_a(k1, p);
 #pragma unroll
-    for (int e = 0; e < RPW; ++e) load_b(e);
+    for (int q = 0; q < CPL; ++q)
+#pragma unroll
+      for (int e = 0; e < RPW; ++e) load_b(q, e);
   }
   load_tab(nchunks > 2 ? 2 : nchunks - 1);
   __syncthreads();
@@ -187,30 +189,35 @@ __global__ __launch_bounds__(kThreads) void corr_kernel(const CorrArgs a) {
     const int kld = kc + 2 < nchunks ? kc + 2 : nchunks - 1;
     const float* sA = opA + cur * C::STAGE;
     const float* sB = opB + cur * C::STAGE;
-    float av[2][MB], bv[2][NB];
+    f32x4 av[2][MB], bv[2][NB];
 #pragma unroll
-    for (int i = 0; i < MB; ++i) av[0][i] = sA[i * MT];
+    for (int i = 0; i < MB; ++i) av[0][i] = *reinterpret_cast<const f32x4*>(sA + i * MT * LDK);
 #pragma unroll
-    for (int j = 0; j < NB; ++j) bv[0][j] = sB[j * MT];
+    for (int j = 0; j < NB; ++j) bv[0][j] = *reinterpret_cast<const f32x4*>(sB + j * MT * LDK);
 #pragma unroll
     for (int ks = 0; ks < NKS; ++ks) {
-      if (ks + 1 < NKS) {  // operands of the next step, ahead of this step's MFMAs
+      const int ss = ks / 4, u = ks % 4;
+      if (u == 0 && ss + 1 < NSS) {  // operands of the next group of four steps
 #pragma unroll
-        for (int i = 0; i < MB; ++i) av[(ks + 1) & 1][i] = sA[(ks + 1) * M::KS * LDA + i * MT];
+        for (int i = 0; i < MB; ++i)
+          av[(ss + 1) & 1][i] = *reinterpret_cast<const f32x4*>(sA + i * MT * LDK + (ss + 1) * C::KSS);
 #pragma unroll
-        for (int j = 0; j < NB; ++j) bv[(ks + 1) & 1][j] = sB[(ks + 1) * M::KS * LDB + j * MT];
+        for (int j = 0; j < NB; ++j)
+          bv[(ss + 1) & 1][j] = *reinterpret_cast<const f32x4*>(sB + j * MT * LDK + (ss + 1) * C::KSS);
       }
 #pragma unroll
       for (int i = 0; i < MB; ++i)
 #pragma unroll
-        for (int j = 0; j < NB; ++j) M::run(av[ks & 1][i], bv[ks & 1][j], acc[i][j]);
+        for (int j = 0; j < NB; ++j) M::run(av[ss & 1][i][u], bv[ss & 1][j][u], acc[i][j]);
       // this step's share of the staging work
 #pragma unroll
-      for (int e = 0; e < RPW; ++e)
-        if (e * NKS / RPW == ks) {
-          store_b(nxt, e);
-          load_b(e);
-        }
+      for (int q = 0; q < CPL; ++q)
+#pragma unroll
+        for (int e = 0; e < RPW; ++e)
+          if ((q * RPW + e) * NKS / (CPL * RPW) == ks) {
+            if (e == 0) store_b(nxt, q);
+            load_b(q, e);
+          }
 #pragma unroll
       for (int p = 0; p < C::A_PER; ++p)
         if ((p * NKS + NKS / 2) / C::A_PER % NKS == ks) {
@@ -225,13 +232,9 @@ __global__ __launch_bounds__(kThreads) void corr_kernel(const CorrArgs a) {
   }
 
   // ---- epilogue: tables, then scatter -------------------------------------------------------
-  int* rowoff = reinterpret_cast<int*>(smem);
-  int* rowH = rowoff + BM;
-  int* rowW = rowH + BM;
-  float* rowB = reinterpret_cast<float*>(rowW + BM);
-  int* coloff = reinterpret_cast<int*>(rowB + BM);
-  int* colH = coloff + BN;
-  int* colW = colH + BN;
+  // rowtab[m] = {offset, row shift, column shift, bias}; coltab[col] = {offset, row, column, -}
+  int4* rowtab = reinterpret_cast<int4*>(smem);
+  int4* coltab = rowtab + BM;
   for (int m = t; m < BM; m += kThreads) {
     const uint32_t gm = m_tile * BM + m;
     int off = 0, hh = -(1 << 28), ww = 0;
@@ -247,10 +250,7 @@ __global__ __launch_bounds__(kThreads) void corr_kernel(const CorrArgs a) {
       off = (int)(chan * (uint32_t)(a.OHd * a.OWd)) + hh * a.OWd + ww;
       if (a.bias) bb = a.bias[chan];
     }
-    rowoff[m] = off;
-    rowH[m] = hh;
-    rowW[m] = ww;
-    rowB[m] = bb;
+    rowtab[m] = make_int4(off, hh, ww, __builtin_bit_cast(int, bb));
   }
   for (int cl = t; cl < BN; cl += kThreads) {
     const uint32_t col = col_tile * BN + cl;
@@ -264,26 +264,26 @@ __global__ __launch_bounds__(kThreads) void corr_kernel(const CorrArgs a) {
       ww = (int)pb * a.RSw;
       off = (int)(n * (uint32_t)a.out_img_stride) + hh * a.OWd + ww;
     }
-    coloff[cl] = off;
-    colH[cl] = hh;
-    colW[cl] = ww;
+    coltab[cl] = make_int4(off, hh, ww, 0);
   }
   __syncthreads();
 
+  int4 ct[NB];
 #pragma unroll
-  for (int j = 0; j < NB; ++j) {
-    const int cl = (wn * NB + j) * MT + lane % MT;
-    const int co = coloff[cl], cH = colH[cl], cW = colW[cl];
+  for (int j = 0; j < NB; ++j) ct[j] = coltab[(wn * NB + j) * MT + lane % MT];
 #pragma unroll
-    for (int i = 0; i < MB; ++i)
+  for (int i = 0; i < MB; ++i)
 #pragma unroll
-      for (int r = 0; r < M::NR; ++r) {
-        const int ml = (wm * MB + i) * MT + M::row(r, lane);
-        const int hh = rowH[ml] + cH, ww = rowW[ml] + cW;
+    for (int r = 0; r < M::NR; ++r) {
+      const int4 rt = rowtab[(wm * MB + i) * MT + M::row(r, lane)];
+      const float bb = __builtin_bit_cast(float, rt.w);
+#pragma unroll
+      for (int j = 0; j < NB; ++j) {
+        const int hh = rt.y + ct[j].y, ww = rt.z + ct[j].z;
         if ((uint32_t)hh < (uint32_t)a.OHd && (uint32_t)ww < (uint32_t)a.OWd)
-          a.out[rowoff[ml] + co] = acc[i][j][r] + rowB[ml];
+          a.out[rt.x + ct[j].x] = acc[i][j][r] + bb;
       }
-  }
+    }
 }
 
 // One k-table entry: where tap kk = (c, i, j) of the gather sits relative to a column's base.
@@ -291,33 +291,24 @@ __device__ __forceinline__ void fill_ktab(const PackArgs& a, int kk) {
   const int c = kk / a.tTHW, rem = kk % a.tTHW;
   const int i = rem / a.tTW, j = rem % a.tTW;
   KTabEntry e;
-  e.koff = 4u * (uint32_t)(c * a.tIHW + i * a.tdh * a.tIW + j * a.tdw);
-  e.idh = kk < a.Kred ? i * a.tdh : (1 << 28);  // k rows past the reduction length fail the row test
+  // k rows past the reduction length fail the row test and point beyond any buffer below 2^31 bytes
+  e.koff = kk < a.Kred ? 4u * (uint32_t)(c * a.tIHW + i * a.tdh * a.tIW + j * a.tdw) : 0x7FFFFFFCu;
+  e.idh = kk < a.Kred ? i * a.tdh : (1 << 28);
   e.jdw = j * a.tdw;
   e.pad = 0;
   a.ktab[kk] = e;
 }
 
-// A[g][kk][m] = w[g*Kg + m][kk]: a tiled transpose through LDS, both sides coalesced.
+// Forward: A[g][m][kk] = w[g*Kg + m][kk], zero padded to [MP][KP] (the weight blob's own order).
 __global__ __launch_bounds__(256) void pack_fwd_kernel(const PackArgs a) {
-  __shared__ float tile[32][33];
-  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
-  const int m0 = blockIdx.x * 32, k0 = blockIdx.y * 32, g = blockIdx.z;
-#pragma unroll
-  for (int r = 0; r < 4; ++r) {
-    const int m = m0 + ty + 8 * r, kk = k0 + tx;
-    float v = 0.f;
-    if (m < a.Mrows && kk < a.Kred) v = a.w[((size_t)g * a.Kg + m) * a.Kred + kk];
-    tile[ty + 8 * r][tx] = v;
-  }
-  __syncthreads();
-#pragma unroll
-  for (int r = 0; r < 4; ++r) {
-    const int kk = k0 + ty + 8 * r, m = m0 + tx;
-    if (kk < a.KP && m < a.MP) a.A[((size_t)g * a.KP + kk) * a.MP + m] = tile[tx][ty + 8 * r];
-  }
-  if (blockIdx.x == 0 && blockIdx.z == 0 && threadIdx.x < 32 && k0 + (int)threadIdx.x < a.KP)
-    fill_ktab(a, k0 + threadIdx.x);
+  const size_t total = (size_t)a.G * a.MP * a.KP;
+  const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= total) return;
+  const int kk = (int)(idx % a.KP);
+  const int m = (int)((idx / a.KP) % a.MP);
+  const int g = (int)(idx / ((size_t)a.MP * a.KP));
+  a.A[idx] = (m < a.Mrows && kk < a.Kred) ? a.w[((size_t)g * a.Kg + m) * a.Kred + kk] : 0.f;
+  if (m == 0 && g == 0) fill_ktab(a, kk);
 }
 
 // Backward data: rows are (input channel, row phase, column phase), k is (output channel,
@@ -325,11 +316,11 @@ __global__ __launch_bounds__(256) void pack_fwd_kernel(const PackArgs a) {
 // tap i exactly when i*dilation = stride*q + rh for an integer q >= 0; the gather then reads
 // dy at a - q.  Entries with no such tap are zero.
 __global__ __launch_bounds__(256) void pack_bwd_kernel(const PackArgs a) {
-  const size_t total = (size_t)a.G * a.KP * a.MP;
+  const size_t total = (size_t)a.G * a.MP * a.KP;
   const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= total) return;
-  const int m = (int)(idx % a.MP);
-  const int kk = (int)((idx / a.MP) % a.KP);
+  const int kk = (int)(idx % a.KP);
+  const int m = (int)((idx / a.KP) % a.MP);
   const int g = (int)(idx / ((size_t)a.MP * a.KP));
   float v = 0.f;
   if (m < a.Mrows && kk < a.Kred) {
@@ -352,7 +343,10 @@ __global__ __launch_bounds__(256) void pack_bwd_kernel(const PackArgs a) {
 template <int MT, int MB, int NB, int WM, int WN, int BK>
 int launch_corr_t(const CorrArgs& a, hipStream_t s) {
   const uint32_t blocks = (uint32_t)a.G * a.m_tiles * a.col_tiles;
-  hipLaunchKernelGGL((corr_kernel<MT, MB, NB, WM, WN, BK>), dim3(blocks), dim3(kThreads), 0, s, a);
+  if (a.nopad)
+    hipLaunchKernelGGL((corr_kernel<MT, MB, NB, WM, WN, BK, false>), dim3(blocks), dim3(kThreads), 0, s, a);
+  else
+    hipLaunchKernelGGL((corr_kernel<MT, MB, NB, WM, WN, BK, true>), dim3(blocks), dim3(kThreads), 0, s, a);
   return (int)hipGetLastError();
 }
 
@@ -395,13 +389,12 @@ int launch_corr(int32_t tile, const CorrArgs& a, void* stream) {
 
 int launch_pack(const PackArgs& a, void* stream) {
   hipStream_t s = (hipStream_t)stream;
-  if (a.mode == 0) {
-    dim3 grid((a.MP + 31) / 32, (a.KP + 31) / 32, a.G);
+  const size_t total = (size_t)a.G * a.KP * a.MP;
+  const dim3 grid((uint32_t)((total + 255) / 256));
+  if (a.mode == 0)
     hipLaunchKernelGGL(pack_fwd_kernel, grid, dim3(256), 0, s, a);
-  } else {
-    const size_t total = (size_t)a.G * a.KP * a.MP;
-    hipLaunchKernelGGL(pack_bwd_kernel, dim3((uint32_t)((total + 255) / 256)), dim3(256), 0, s, a);
-  }
+  else
+    hipLaunchKernelGGL(pack_bwd_kernel, grid, dim3(256), 0, s, a);
   return (int)hipGetLastError();
 }
 

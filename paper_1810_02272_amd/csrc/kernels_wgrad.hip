@@ -7,8 +7,10 @@
 // keeps the result deterministic (no float atomics) and applies beta.
 //
 // Both operands are read with lanes along the reduction index (contiguous in dy, contiguous for
-// stride-1 x), written to LDS as [row][k] with an odd leading dimension and read back by the
-// 32x32x2 fp32 MFMA operand pattern (lane l: row l%32, k l/32) without bank conflicts.
+// stride-1 x) and written to LDS as [row][k].  The MFMA operands come back as 16-byte reads:
+// lane l takes row l%32 and the four k values 8t + 4(l/32) .. +3, which feed four consecutive
+// 32x32x2 instructions -- the k order inside a group of eight is permuted, identically for both
+// operands, which a sum does not notice.
 #include <hip/hip_runtime.h>
 
 #include "device_utils.h"
@@ -26,7 +28,7 @@ struct WgCfg {
   static constexpr int BK = 32;
   static constexpr int BM = WM * MB * MT;
   static constexpr int BN = WN * NB * MT;
-  static constexpr int LDK = BK + 1;
+  static constexpr int LDK = BK + 4;  // 16-byte aligned rows; 8 consecutive rows start on 8 distinct bank quads
   static constexpr int A_PER = BM / 8;  // rows per thread: 32 lanes along k, 8 row slots
   static constexpr int B_PER = BN / 8;
   static constexpr int STAGE = (BM + BN) * LDK;
@@ -134,9 +136,10 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradArgs a) {
   // Software pipeline, three chunks deep (see the correlation kernel): chunk ch is multiplied out
   // of one LDS buffer while the registers holding chunk ch+1 are written to the other buffer and
   // reloaded with chunk ch+2, one or two elements per k step, in the shadow of the MFMAs.
-  constexpr int NKS = BK / 2;
-  const float* opA = smem + (wm * MB * 32 + (lane & 31)) * LDK + (lane >> 5);
-  const float* opB = smem + BM * LDK + (wn * NB * 32 + (lane & 31)) * LDK + (lane >> 5);
+  constexpr int NKS = BK / 2;  // MFMA k steps per chunk; four of them share one 16-byte operand read
+  constexpr int NSS = BK / 8;
+  const float* opA = smem + (wm * MB * 32 + (lane & 31)) * LDK + (lane >> 5) * 4;
+  const float* opB = smem + BM * LDK + (wn * NB * 32 + (lane & 31)) * LDK + (lane >> 5) * 4;
   if (nchunks > 0) {
     col_state(0);
 #pragma unroll
@@ -158,23 +161,26 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradArgs a) {
     const int cur = ch & 1, nxt = cur ^ 1;
     const float* sA = opA + cur * C::STAGE;
     const float* sB = opB + cur * C::STAGE;
-    float av[2][MB], bv[2][NB];
+    f32x4 av[2][MB], bv[2][NB];
 #pragma unroll
-    for (int i = 0; i < MB; ++i) av[0][i] = sA[i * 32 * LDK];
+    for (int i = 0; i < MB; ++i) av[0][i] = *reinterpret_cast<const f32x4*>(sA + i * 32 * LDK);
 #pragma unroll
-    for (int j = 0; j < NB; ++j) bv[0][j] = sB[j * 32 * LDK];
+    for (int j = 0; j < NB; ++j) bv[0][j] = *reinterpret_cast<const f32x4*>(sB + j * 32 * LDK);
 #pragma unroll
     for (int ks = 0; ks < NKS; ++ks) {
-      if (ks + 1 < NKS) {
+      const int ss = ks / 4, u = ks % 4;
+      if (u == 0 && ss + 1 < NSS) {  // operands of the next group of four steps
 #pragma unroll
-        for (int i = 0; i < MB; ++i) av[(ks + 1) & 1][i] = sA[i * 32 * LDK + (ks + 1) * 2];
+        for (int i = 0; i < MB; ++i)
+          av[(ss + 1) & 1][i] = *reinterpret_cast<const f32x4*>(sA + i * 32 * LDK + (ss + 1) * 8);
 #pragma unroll
-        for (int j = 0; j < NB; ++j) bv[(ks + 1) & 1][j] = sB[j * 32 * LDK + (ks + 1) * 2];
+        for (int j = 0; j < NB; ++j)
+          bv[(ss + 1) & 1][j] = *reinterpret_cast<const f32x4*>(sB + j * 32 * LDK + (ss + 1) * 8);
       }
 #pragma unroll
       for (int i = 0; i < MB; ++i)
 #pragma unroll
-        for (int j = 0; j < NB; ++j) M::run(av[ks & 1][i], bv[ks & 1][j], acc[i][j]);
+        for (int j = 0; j < NB; ++j) M::run(av[ss & 1][i][u], bv[ss & 1][j][u], acc[i][j]);
       // this step's share of the staging work: registers of chunk ch+1 go to LDS first ...
 #pragma unroll
       for (int e = 0; e < A_PER; ++e)

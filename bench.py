@@ -30,6 +30,9 @@ def parse():
     ap.add_argument("--workload", default="config4", help="config0..config4 or a comma list of layer names")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--cpu-sample-images", type=int, default=32)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run plain 256 MiB device copies (outside the timed region) so that a rocprofv3 "
+                         "--pmc FETCH_SIZE / WRITE_SIZE run of this command holds a kernel of known traffic")
     return ap.parse_args()
 
 
@@ -95,6 +98,14 @@ def main():
                     events.append((t["layer"].name, name, e0, e1))
                 else:
                     run_pass(t, name)
+
+    if args.copy_calibration:
+        src = torch.ones(64 << 20, device=dev)  # 256 MiB read + 256 MiB written per copy
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step()

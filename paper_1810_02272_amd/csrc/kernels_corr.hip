@@ -113,26 +113,34 @@ __global__ __launch_bounds__(kThreads) void corr_kernel(const CorrArgs a) {
 #pragma unroll
       for (int r = 0; r < M::NR; ++r) acc[i][j][r] = 0.f;
 
-  f32x4 ra[C::A_PER];
-  f32x4 rb[CPL];  // element e of rb[q]: k row 4*wv + e of column q*64 + lane
+  // Two register sets for the staged operands: chunks k+1 and k+2 are both in flight while chunk k
+  // is multiplied, so a load has two full iterations to arrive before its LDS write needs it.
+  // Element e of rb[q]: k row 4*wv + e of column q*64 + lane.
+  f32x4 raX[C::A_PER], raY[C::A_PER];
+  f32x4 rbX[CPL], rbY[CPL];
 
-  auto load_a = [&](int kc, int p) {
+  auto load_a = [&](f32x4(&ra)[C::A_PER], int kc, int p) {
     if (C::A_WI % 4 == 0 || wv + 4 * p < C::A_WI)
       ra[p] = *reinterpret_cast<const f32x4*>(reinterpret_cast<const char*>(Ag) + (aoff[p] + (uint32_t)kc * (BK * 4)));
   };
-  auto store_a = [&](int buf, int p) {
+  auto store_a = [&](f32x4(&ra)[C::A_PER], int buf, int p) {
     if (C::A_WI % 4 == 0 || wv + 4 * p < C::A_WI)
       *reinterpret_cast<f32x4*>(smem + buf * C::STAGE + ((wv + 4 * p) * 16 + arow) * LDK + ac4 * 4) = ra[p];
   };
   // Rows of this wave in a chunk: each tap's byte offset and (row, column) displacement come from
-  // the k table with scalar loads (the index is uniform over the wave), fetched one iteration
-  // ahead of their use so that their latency never sits in front of an MFMA.
-  KTabEntry te[RPW];
+  // the k table with scalar loads (the index is uniform over the wave).  The entries are fetched a
+  // whole iteration before their use, right after the first MFMAs of an iteration have issued, so
+  // that the scalar-memory latency never sits in front of an MFMA or the barrier.
+  KTabEntry te[RPW], te_next[RPW];
   auto load_tab = [&](int kc) {
 #pragma unroll
-    for (int e = 0; e < RPW; ++e) te[e] = a.ktab[kc * BK + wv * RPW + e];
+    for (int e = 0; e < RPW; ++e) te_next[e] = a.ktab[kc * BK + wv * RPW + e];
   };
-  auto load_b = [&](int q, int e) {
+  auto swap_tab = [&]() {
+#pragma unroll
+    for (int e = 0; e < RPW; ++e) te[e] = te_next[e];
+  };
+  auto load_b = [&](f32x4(&rb)[CPL], int q, int e) {
     uint32_t off = cbase[q] + te[e].koff;
     if (PAD) {
       const int ih = cih0[q] + te[e].idh, iw = ciw0[q] + te[e].jdw;
@@ -141,52 +149,51 @@ __global__ __launch_bounds__(kThreads) void corr_kernel(const CorrArgs a) {
     }
     rb[q][e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(in_rsrc, off, 0, 0));
   };
-  auto store_b = [&](int buf, int q) {
+  auto store_b = [&](f32x4(&rb)[CPL], int buf, int q) {
     *reinterpret_cast<f32x4*>(smem + buf * C::STAGE + BM * LDK + (q * 64 + lane) * LDK + wv * 4) = rb[q];
   };
+  auto load_all = [&](f32x4(&ra)[C::A_PER], f32x4(&rb)[CPL], int kc) {
+    load_tab(kc);
+    swap_tab();
+#pragma unroll
+    for (int p = 0; p < C::A_PER; ++p) load_a(ra, kc, p);
+#pragma unroll
+    for (int q = 0; q < CPL; ++q)
+#pragma unroll
+      for (int e = 0; e < RPW; ++e) load_b(rb, q, e);
+  };
 
-  // Software pipeline, three chunks deep: while the MFMA pipe works on chunk k out of one LDS
-  // buffer, the registers holding chunk k+1 (loaded during the previous iteration, so long since
-  // arrived) are written to the other buffer and immediately reloaded with chunk k+2.  The
-  // stores and loads are spread over the k steps of the chunk so that their address arithmetic
-  // issues in the shadow of the MFMAs of the same wave.  Chunk indices past the end are clamped:
-  // the last iterations re-load and re-store the final chunk into a buffer nobody reads.
+  // Software pipeline, four chunks deep: while the MFMA pipe works on chunk k out of one LDS buffer,
+  // the register set holding chunk k+1 (loaded two iterations ago) is written to the other buffer
+  // and immediately reloaded with chunk k+3; the other register set holds chunk k+2 meanwhile.
+  // The stores and loads are spread over the k steps of the chunk so that their address
+  // arithmetic issues in the shadow of the MFMAs of the same wave.  Chunk indices past the end
+  // are clamped: the last iterations re-load and re-store the final chunk into a buffer nobody
+  // reads.
   //
   // MFMA operands come from LDS as 16-byte reads: lane l takes row l%MT and the four k values
   // KSS*s + 4*(l/MT) .. +3, which feed four consecutive MFMAs; the k order inside a group of KSS
   // is thereby permuted, identically for both operands, which a sum does not notice.
   const int nchunks = a.KP / BK;
+  const int last = nchunks - 1;
   constexpr int NKS = C::NKS, NSS = C::NSS;
   const float* opA = smem + (wm * MB * MT + lane % MT) * LDK + (lane / MT) * 4;
   const float* opB = smem + BM * LDK + (wn * NB * MT + lane % MT) * LDK + (lane / MT) * 4;
 
-  load_tab(0);
+  load_all(raX, rbX, 0);
 #pragma unroll
-  for (int p = 0; p < C::A_PER; ++p) load_a(0, p);
+  for (int p = 0; p < C::A_PER; ++p) store_a(raX, 0, p);
 #pragma unroll
-  for (int q = 0; q < CPL; ++q)
-#pragma unroll
-    for (int e = 0; e < RPW; ++e) load_b(q, e);
-#pragma unroll
-  for (int p = 0; p < C::A_PER; ++p) store_a(0, p);
-#pragma unroll
-  for (int q = 0; q < CPL; ++q) store_b(0, q);
-  {
-    const int k1 = nchunks > 1 ? 1 : 0;
-    load_tab(k1);
-#pragma unroll
-    for (int p = 0; p < C::A_PER; ++p) load_a(k1, p);
-#pragma unroll
-    for (int q = 0; q < CPL; ++q)
-#pragma unroll
-      for (int e = 0; e < RPW; ++e) load_b(q, e);
-  }
-  load_tab(nchunks > 2 ? 2 : nchunks - 1);
+  for (int q = 0; q < CPL; ++q) store_b(rbX, 0, q);
+  load_all(raX, rbX, last < 1 ? last : 1);
+  load_all(raY, rbY, last < 2 ? last : 2);
+  load_tab(last < 3 ? last : 3);
   __syncthreads();
 
-  for (int kc = 0; kc < nchunks; ++kc) {
+  auto iteration = [&](int kc, f32x4(&ra)[C::A_PER], f32x4(&rb)[CPL]) {
     const int cur = kc & 1, nxt = cur ^ 1;
-    const int kld = kc + 2 < nchunks ? kc + 2 : nchunks - 1;
+    const int kld = kc + 3 < last ? kc + 3 : last;
+    swap_tab();  // entries for this iteration's loads (chunk kc + 3) arrived during the previous one
     const float* sA = opA + cur * C::STAGE;
     const float* sB = opB + cur * C::STAGE;
     f32x4 av[2][MB], bv[2][NB];
@@ -209,27 +216,33 @@ __global__ __launch_bounds__(kThreads) void corr_kernel(const CorrArgs a) {
       for (int i = 0; i < MB; ++i)
 #pragma unroll
         for (int j = 0; j < NB; ++j) M::run(av[ss & 1][i][u], bv[ss & 1][j][u], acc[i][j]);
+      if (ks == 0) load_tab(kc + 4 < last ? kc + 4 : last);  // for the next iteration's loads
       // this step's share of the staging work
 #pragma unroll
       for (int q = 0; q < CPL; ++q)
 #pragma unroll
         for (int e = 0; e < RPW; ++e)
           if ((q * RPW + e) * NKS / (CPL * RPW) == ks) {
-            if (e == 0) store_b(nxt, q);
-            load_b(q, e);
+            if (e == 0) store_b(rb, nxt, q);
+            load_b(rb, q, e);
           }
 #pragma unroll
       for (int p = 0; p < C::A_PER; ++p)
         if ((p * NKS + NKS / 2) / C::A_PER % NKS == ks) {
-          store_a(nxt, p);
-          load_a(kld, p);
+          store_a(ra, nxt, p);
+          load_a(ra, kld, p);
         }
       __builtin_amdgcn_sched_barrier(0);
     }
-    load_tab(kc + 3 < nchunks ? kc + 3 : nchunks - 1);  // table entries of the next iteration's loads
-    __builtin_amdgcn_sched_barrier(0);
     __syncthreads();
+  };
+
+  int kc = 0;
+  for (; kc + 1 < nchunks; kc += 2) {
+    iteration(kc, raX, rbX);
+    iteration(kc + 1, raY, rbY);
   }
+  if (kc < nchunks) iteration(kc, raX, rbX);
 
   // ---- epilogue: tables, then scatter -------------------------------------------------------
   // rowtab[m] = {offset, row shift, column shift, bias}; coltab[col] = {offset, row, column, -}

@@ -29,7 +29,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="config4", help="config0..config4 or a comma list of layer names")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
-    ap.add_argument("--cpu-sample-images", type=int, default=32)
+    ap.add_argument("--cpu-sample-images", type=int, default=128)
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run plain 256 MiB device copies (outside the timed region) so that a rocprofv3 "
                          "--pmc FETCH_SIZE / WRITE_SIZE run of this command holds a kernel of known traffic")

@@ -75,6 +75,18 @@ int32_t pick_wgrad_tile(int32_t rows, int32_t kred) {
   return best;
 }
 
+// How the gather zeroes out-of-image elements (see corr_kernel): 0 = no padding at all and the blob
+// below 2^31 bytes; 2 = at most 32 taps and the blob at most 2^29 bytes; 1 = anything else.
+// `reach` = how far (bytes) a tap of a real column can point outside the blob: mode 2 adds
+// 2^30 / 2^31 to such offsets and must neither wrap nor come back inside.
+int32_t bounds_mode(bool no_padding, int64_t taps, int64_t bytes, int64_t reach) {
+  if (no_padding && bytes < ((int64_t)1 << 31) - 4) return 0;
+  if (taps <= 32 && bytes <= ((int64_t)1 << 29) && reach < ((int64_t)1 << 28)) return 2;
+  return 1;
+}
+
+uint32_t koff_invalid(int32_t mode) { return mode == 0 ? 0x7FFFFFFCu : mode == 2 ? 0x40000000u : 0u; }
+
 int hip_fail(int e) {
   g_last_hip_error = e;
   return CONV_EHIP;
@@ -136,7 +148,8 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
     a.in_img_stride = (int32_t)(C * H * W);
     a.in_grp_stride = (int32_t)(Cg * H * W);
     a.in_bytes = (uint32_t)(4 * x_elems);
-    a.nopad = (p.pad_h == 0 && p.pad_w == 0 && 4 * x_elems < ((int64_t)1 << 31) - 4) ? 1 : 0;
+    a.bounds_mode = bounds_mode(p.pad_h == 0 && p.pad_w == 0, (int64_t)p.kernel_h * p.kernel_w, 4 * x_elems,
+                                4 * ((p.pad_h + ext_h) * W + p.pad_w + ext_w));
     a.TW = p.kernel_w;
     a.THW = p.kernel_h * p.kernel_w;
     a.mTW = make_magic(a.TW);
@@ -181,6 +194,7 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
     k.tIHW = a.IHW;
     k.tdh = a.dh;
     k.tdw = a.dw;
+    k.koff_invalid = koff_invalid(a.bounds_mode);
     const int64_t pack_elems = G * (int64_t)a.KP * a.MP;
     if (pack_elems >= kMaxElems || (int64_t)G * a.m_tiles * a.col_tiles >= ((int64_t)1 << 31)) {
       delete d;
@@ -219,6 +233,7 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
     a.in_img_stride = (int32_t)(K * OH * OW);
     a.in_grp_stride = (int32_t)(Kg * OH * OW);
     a.in_bytes = (uint32_t)(4 * y_elems);
+    a.bounds_mode = bounds_mode(false, Qh * Qw, 4 * y_elems, 4 * (2 * Qh * OW + 2 * Qw));
     a.TW = (int32_t)Qw;
     a.THW = (int32_t)(Qh * Qw);
     a.mTW = make_magic(a.TW);
@@ -267,6 +282,7 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
     k.tIHW = a.IHW;
     k.tdh = a.dh;
     k.tdw = a.dw;
+    k.koff_invalid = koff_invalid(a.bounds_mode);
     const int64_t pack_elems = G * (int64_t)a.KP * a.MP;
     if (pack_elems >= kMaxElems || (int64_t)G * a.m_tiles * a.col_tiles >= ((int64_t)1 << 31)) {
       delete d;

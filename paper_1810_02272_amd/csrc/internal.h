@@ -35,7 +35,8 @@ inline Magic make_magic(uint32_t d) {
 // row displacement that fails every bounds test.
 struct KTabEntry {
   uint32_t koff;
-  int32_t idh, jdw, pad;
+  int32_t idh, jdw;
+  int32_t tap;  // i*TW + j (mod 32): bit index into a column's tap bitmask
 };
 
 struct CorrArgs {
@@ -45,7 +46,7 @@ struct CorrArgs {
   const float* bias;  // per output channel, or null
   float* out;
   uint32_t in_bytes;  // size of `in`, the range of the gather's hardware bounds check
-  int32_t nopad;      // 1: every tap of a real column is inside the image and in_bytes < 2^31
+  int32_t bounds_mode;  // 0 no padding, 1 compares, 2 tap bitmask (see corr_kernel)
   // column space
   int32_t ncols, P, PW;  // ncols = N*P, P = PH*PW
   Magic mP, mPW;
@@ -80,6 +81,7 @@ struct PackArgs {
   float* A;
   KTabEntry* ktab;
   int32_t tTW, tTHW, tIW, tIHW, tdh, tdw;  // gather geometry for the k table
+  uint32_t koff_invalid;                   // offset of k rows past the reduction length
   int32_t mode;
   int32_t G, Kg, Cg, kh, kw;
   int32_t sh, sw, dh, dw;

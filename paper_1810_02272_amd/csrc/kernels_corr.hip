@@ -47,7 +47,9 @@ struct CorrCfg {
   static_assert(4 * (BM + BN) <= SMEM, "epilogue tables reuse the pipeline buffers");
 };
 
-template <int MT, int MB, int NB, int WM, int WN, int BK, bool PAD>
+// MODE: how a gathered element is bounds-checked (see the gather below): 0 no padding, 1 row and
+// column compares, 2 per-column tap bitmask.
+template <int MT, int MB, int NB, int WM, int WN, int BK, int MODE>
 __global__ __launch_bounds__(kThreads) void corr_kernel(const CorrArgs a) {
   using C = CorrCfg<MT, MB, NB, WM, WN, BK>;
   using M = Mfma<MT>;
@@ -67,13 +69,20 @@ __global__ __launch_bounds__(kThreads) void corr_kernel(const CorrArgs a) {
   const uint32_t col_tile = lin % (uint32_t)a.col_tiles;
   const uint32_t g = lin / (uint32_t)a.col_tiles;
 
-  // Per-lane column state of the gather (fixed for the whole reduction).  Without padding every
-  // tap of a real column is inside the image, so validity is folded into the offsets: a column
-  // past the edge gets base 2^31 and a k row past the reduction length gets offset 2^31 - 4 (from
-  // the k table); either pushes the sum beyond the buffer (which is then below 2^31 bytes) and
-  // the hardware range check returns 0.
+  // Per-lane column state of the gather (fixed for the whole reduction).  An element that must
+  // read as zero -- tap in the padding, column past the edge, k row past the reduction length --
+  // is given an offset at or beyond the buffer size, and the hardware range check of the buffer
+  // load returns 0 for it.  Three ways to get there:
+  //  MODE 0 (no padding: every tap of a real column is inside the image; buffer < 2^31 bytes):
+  //    nothing per element -- an invalid column has base 2^31, an invalid k row has offset
+  //    2^31 - 4 in the k table.
+  //  MODE 1 (general): row and column compares per element, select the buffer size.
+  //  MODE 2 (at most 32 taps; buffer <= 2^29 bytes): whether tap t is outside the image depends
+  //    only on the column, so each lane keeps one bitmask per column and adds bit t of it, shifted
+  //    to 2^31, to the offset (an invalid k row has offset 2^30 in the k table).
   uint32_t cbase[CPL];
   int cih0[CPL], ciw0[CPL];
+  uint32_t cinv[CPL];
 #pragma unroll
   for (int q = 0; q < CPL; ++q) {
     const uint32_t col = col_tile * BN + q * 64 + lane;
@@ -90,7 +99,17 @@ __global__ __launch_bounds__(kThreads) void corr_kernel(const CorrArgs a) {
     } else {
       cih0[q] = -(1 << 29);  // every bounds test fails, also with the 2^28 of an invalid k row
       ciw0[q] = 0;
-      cbase[q] = 0x80000000u;
+      cbase[q] = MODE == 0 ? 0x80000000u : 0u;
+    }
+    cinv[q] = 0;
+    if (MODE == 2) {
+      const int TH = a.THW / a.TW;
+      for (int i = 0, tap = 0; i < TH; ++i)
+        for (int j = 0; j < a.TW; ++j, ++tap) {
+          const bool ok = ((uint32_t)(cih0[q] + i * a.dh) < (uint32_t)a.IH) &
+                          ((uint32_t)(ciw0[q] + j * a.dw) < (uint32_t)a.IW);
+          cinv[q] |= ok ? 0u : (1u << tap);
+        }
     }
   }
 
@@ -142,10 +161,12 @@ __global__ __launch_bounds__(kThreads) void corr_kernel(const CorrArgs a) {
   };
   auto load_b = [&](f32x4(&rb)[CPL], int q, int e) {
     uint32_t off = cbase[q] + te[e].koff;
-    if (PAD) {
+    if (MODE == 1) {
       const int ih = cih0[q] + te[e].idh, iw = ciw0[q] + te[e].jdw;
       const bool ok = ((uint32_t)ih < (uint32_t)a.IH) & ((uint32_t)iw < (uint32_t)a.IW);
       off = ok ? off : a.in_bytes;  // the buffer size: first byte past the end, no 32-bit wrap
+    } else if (MODE == 2) {
+      off += __builtin_amdgcn_ubfe(cinv[q], (uint32_t)te[e].tap, 1u) << 31;
     }
     rb[q][e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(in_rsrc, off, 0, 0));
   };
@@ -304,11 +325,12 @@ __device__ __forceinline__ void fill_ktab(const PackArgs& a, int kk) {
   const int c = kk / a.tTHW, rem = kk % a.tTHW;
   const int i = rem / a.tTW, j = rem % a.tTW;
   KTabEntry e;
-  // k rows past the reduction length fail the row test and point beyond any buffer below 2^31 bytes
-  e.koff = kk < a.Kred ? 4u * (uint32_t)(c * a.tIHW + i * a.tdh * a.tIW + j * a.tdw) : 0x7FFFFFFCu;
+  // k rows past the reduction length fail the row test and carry the offset that the kernel's
+  // bounds mode needs to land beyond the buffer
+  e.koff = kk < a.Kred ? 4u * (uint32_t)(c * a.tIHW + i * a.tdh * a.tIW + j * a.tdw) : a.koff_invalid;
   e.idh = kk < a.Kred ? i * a.tdh : (1 << 28);
   e.jdw = j * a.tdw;
-  e.pad = 0;
+  e.tap = rem & 31;
   a.ktab[kk] = e;
 }
 
@@ -356,10 +378,12 @@ __global__ __launch_bounds__(256) void pack_bwd_kernel(const PackArgs a) {
 template <int MT, int MB, int NB, int WM, int WN, int BK>
 int launch_corr_t(const CorrArgs& a, hipStream_t s) {
   const uint32_t blocks = (uint32_t)a.G * a.m_tiles * a.col_tiles;
-  if (a.nopad)
-    hipLaunchKernelGGL((corr_kernel<MT, MB, NB, WM, WN, BK, false>), dim3(blocks), dim3(kThreads), 0, s, a);
+  if (a.bounds_mode == 0)
+    hipLaunchKernelGGL((corr_kernel<MT, MB, NB, WM, WN, BK, 0>), dim3(blocks), dim3(kThreads), 0, s, a);
+  else if (a.bounds_mode == 2)
+    hipLaunchKernelGGL((corr_kernel<MT, MB, NB, WM, WN, BK, 2>), dim3(blocks), dim3(kThreads), 0, s, a);
   else
-    hipLaunchKernelGGL((corr_kernel<MT, MB, NB, WM, WN, BK, true>), dim3(blocks), dim3(kThreads), 0, s, a);
+    hipLaunchKernelGGL((corr_kernel<MT, MB, NB, WM, WN, BK, 1>), dim3(blocks), dim3(kThreads), 0, s, a);
   return (int)hipGetLastError();
 }
 

@@ -303,6 +303,14 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
     a.mPW = make_magic(a.PW);
     a.dy_bytes = (uint32_t)(4 * y_elems);
     a.x_bytes = (uint32_t)(4 * x_elems);
+    // the dy base of a column past the split is 2^31: both blobs must stay below that for modes 0 and 2
+    a.bounds_mode = 1;
+    if (4 * y_elems < ((int64_t)1 << 31) - 4) {
+      a.bounds_mode = bounds_mode(p.pad_h == 0 && p.pad_w == 0, (int64_t)p.kernel_h * p.kernel_w, 4 * x_elems,
+                                  4 * ((p.pad_h + ext_h) * W + p.pad_w + ext_w));
+      if (a.bounds_mode == 2 && (p.dilation_h != 1 || p.dilation_w != 1 || p.kernel_h * p.kernel_w > 31))
+        a.bounds_mode = 1;
+    }
     a.Kg = (int32_t)Kg;
     a.Ktot = (int32_t)K;
     a.Cg = (int32_t)Cg;

@@ -95,6 +95,7 @@ struct WgradArgs {
   const float* x;
   float* part;
   uint32_t dy_bytes, x_bytes;  // sizes of the two blobs: the ranges of the hardware bounds checks
+  int32_t bounds_mode;         // 0 no padding, 1 compares, 2 tap bitmask (see wgrad_kernel)
   int32_t ncols, P, PW;
   Magic mP, mPW;
   int32_t Kg, Ktot;

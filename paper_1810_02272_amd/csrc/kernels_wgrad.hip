@@ -36,7 +36,10 @@ struct WgCfg {
   static_assert(WM * WN == 4, "four waves per workgroup");
 };
 
-template <int MB, int NB, int WM, int WN>
+// MODE: how a gathered x element is bounds-checked, as in the correlation kernel: 0 no padding,
+// 1 row and column compares, 2 per-column tap bitmask (dilation 1, at most 16 taps per dimension and
+// 32 in all, blobs at most 2^29 bytes).
+template <int MB, int NB, int WM, int WN, int MODE>
 __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradArgs a) {
   using C = WgCfg<MB, NB, WM, WN>;
   using M = Mfma<32>;
@@ -78,7 +81,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradArgs a) {
     const uint32_t i = mdiv(rem, a.mKW);
     const uint32_t j = rem - i * a.kw;
     boff[e] = 4u * ((g * a.Cg + c) * (uint32_t)a.HW + i * a.dh * a.W + j * a.dw);
-    bij[e] = ((i * a.dh) << 16) | (j * a.dw);
+    bij[e] = MODE == 2 ? i * a.kw + j : ((i * a.dh) << 16) | (j * a.dw);  // tap index, or packed displacement
   }
 
   const uint32_t c_begin = split * (uint32_t)a.cols_per_split;
@@ -104,10 +107,18 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradArgs a) {
 
   float ra[A_PER], rb[B_PER];
 
-  // per-lane state of the column (n, oh, ow) this lane loads in the chunk being fetched
-  uint32_t dybase = 0, xbase = 0;
+  // Per-lane state of the column (n, oh, ow) this lane loads in the chunk being fetched.  Elements
+  // that must read as zero get an offset at or beyond the blob size (hardware range check returns
+  // 0): a column past the split puts 2^31 into both bases; an x tap in the padding either selects
+  // the blob size after two compares (MODE 1) or adds bit t of the column's invalid-tap mask,
+  // shifted to 2^31 (MODE 2; the mask is the outer product of a row-range and a column-range mask).
+  uint32_t dybase = 0, xbase = 0, inv = 0;
   int ih0 = 0, iw0 = 0;
   bool colok = false;
+  const int TH = a.khw / a.kw;
+  uint32_t row_bits = 0;  // bit i*kw for every tap row i
+  if (MODE == 2)
+    for (int i = 0; i < TH; ++i) row_bits |= 1u << (i * a.kw);
   auto col_state = [&](int chunk) {
     const uint32_t col = c_begin + chunk * BK + kc;
     colok = col < c_end;
@@ -115,20 +126,44 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradArgs a) {
     const uint32_t pix = col - n * a.P;
     const uint32_t oh = mdiv(pix, a.mPW);
     const uint32_t ow = pix - oh * a.PW;
-    ih0 = colok ? (int)oh * a.sh - a.ph : -(1 << 28);  // columns past the split fail every bounds test
+    ih0 = (int)oh * a.sh - a.ph;
     iw0 = (int)ow * a.sw - a.pw;
-    dybase = 4u * ((n * a.Ktot + g * a.Kg) * (uint32_t)a.P + pix);
+    dybase = (colok || MODE == 1) ? 4u * ((n * a.Ktot + g * a.Kg) * (uint32_t)a.P + pix) : 0x80000000u;
     xbase = 4u * (uint32_t)((int)(n * (uint32_t)(a.C * a.HW)) + ih0 * a.W + iw0);
+    if (MODE == 0) {
+      if (!colok) xbase = 0x80000000u;
+    } else if (MODE == 1) {
+      if (!colok) ih0 = -(1 << 28);  // fails every bounds test
+    } else {
+      // taps (i, j) inside the image: i in [lo_i, hi_i), j in [lo_j, hi_j).  The mask over tap index
+      // i*kw + j is (bits lo_j..hi_j-1) times (bits i*kw for the valid i): the shifted copies of the
+      // column mask do not overlap, so one multiply builds the outer product.
+      int lo = -ih0, hi = a.H - ih0;
+      lo = lo < 0 ? 0 : (lo > TH ? TH : lo);
+      hi = hi < lo ? lo : (hi > TH ? TH : hi);
+      const uint32_t rows = row_bits & ((1u << (hi * a.kw)) - (1u << (lo * a.kw)));
+      lo = -iw0, hi = a.W - iw0;
+      lo = lo < 0 ? 0 : (lo > a.kw ? a.kw : lo);
+      hi = hi < lo ? lo : (hi > a.kw ? a.kw : hi);
+      const uint32_t colm = (1u << hi) - (1u << lo);
+      inv = colok ? ~(colm * rows) : ~0u;
+    }
   };
   auto load_a = [&](int e) {
-    ra[e] = __builtin_bit_cast(
-        float, __builtin_amdgcn_raw_buffer_load_b32(dy_rsrc, colok ? dybase + aoff[e] : a.dy_bytes, 0, 0));
+    uint32_t off = dybase + aoff[e];
+    if (MODE == 1) off = colok ? off : a.dy_bytes;  // blobs of 2^31 bytes and more: explicit select
+    ra[e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(dy_rsrc, off, 0, 0));
   };
   auto load_b = [&](int e) {
-    const int ih = ih0 + (int)(bij[e] >> 16), iw = iw0 + (int)(bij[e] & 0xffffu);
-    const bool ok = ((uint32_t)ih < (uint32_t)a.H) & ((uint32_t)iw < (uint32_t)a.W);
-    rb[e] = __builtin_bit_cast(
-        float, __builtin_amdgcn_raw_buffer_load_b32(x_rsrc, ok ? xbase + boff[e] : a.x_bytes, 0, 0));
+    uint32_t off = xbase + boff[e];
+    if (MODE == 1) {
+      const int ih = ih0 + (int)(bij[e] >> 16), iw = iw0 + (int)(bij[e] & 0xffffu);
+      const bool ok = ((uint32_t)ih < (uint32_t)a.H) & ((uint32_t)iw < (uint32_t)a.W);
+      off = ok ? off : a.x_bytes;
+    } else if (MODE == 2) {
+      off += __builtin_amdgcn_ubfe(inv, bij[e], 1u) << 31;
+    }
+    rb[e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(x_rsrc, off, 0, 0));
   };
   auto store_a = [&](int buf, int e) { smem[buf * C::STAGE + (rslot + 8 * e) * LDK + kc] = ra[e]; };
   auto store_b = [&](int buf, int e) { smem[buf * C::STAGE + BM * LDK + (rslot + 8 * e) * LDK + kc] = rb[e]; };
@@ -216,19 +251,26 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradArgs a) {
   }
 }
 
-template <int MB, int NB, int WM, int WN>
-int launch_wgrad_t(const WgradArgs& a, hipStream_t s) {
+template <int MB, int NB, int WM, int WN, int MODE>
+int launch_wgrad_m(const WgradArgs& a, hipStream_t s) {
   using C = WgCfg<MB, NB, WM, WN>;
   static bool configured = false;
   if (!configured) {  // more than 64 KB of LDS needs an explicit opt-in, once per process
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&wgrad_kernel<MB, NB, WM, WN>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&wgrad_kernel<MB, NB, WM, WN, MODE>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM_BYTES);
     if (e != hipSuccess) return (int)e;
     configured = true;
   }
   const uint32_t blocks = (uint32_t)a.G * a.S * a.m_tiles * a.n_tiles;
-  hipLaunchKernelGGL((wgrad_kernel<MB, NB, WM, WN>), dim3(blocks), dim3(kThreads), C::SMEM_BYTES, s, a);
+  hipLaunchKernelGGL((wgrad_kernel<MB, NB, WM, WN, MODE>), dim3(blocks), dim3(kThreads), C::SMEM_BYTES, s, a);
   return (int)hipGetLastError();
+}
+
+template <int MB, int NB, int WM, int WN>
+int launch_wgrad_t(const WgradArgs& a, hipStream_t s) {
+  if (a.bounds_mode == 0) return launch_wgrad_m<MB, NB, WM, WN, 0>(a, s);
+  if (a.bounds_mode == 2) return launch_wgrad_m<MB, NB, WM, WN, 2>(a, s);
+  return launch_wgrad_m<MB, NB, WM, WN, 1>(a, s);
 }
 
 // dst = beta*dst + sum_s part[s].  A block owns 64 consecutive elements; its four waves each add

@@ -8,8 +8,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_HERE)
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libmi355conv.so")
-SOURCES = ["api.cpp", "kernels_corr.hip", "kernels_wgrad.hip", "kernels_bias.hip"]
-HEADERS = ["internal.h", "device_utils.h"]
+SOURCES = ["api.cpp", "kernels_corr.hip", "kernels_corr_patch.hip", "kernels_wgrad.hip", "kernels_bias.hip"]
+HEADERS = ["internal.h", "device_utils.h", "corr_epilogue.h"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

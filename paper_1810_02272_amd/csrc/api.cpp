@@ -65,8 +65,8 @@ int32_t pick_wgrad_tile(int32_t rows, int32_t kred) {
     wgrad_tile_shape(t, &bm, &bn, &bk);
     int64_t work = round_up(rows, bm) * round_up(kred, bn);
     const int64_t area = (int64_t)bm * bn;
-    // a narrower tile must save at least 3 % of the padded work to be worth its extra LDS traffic
-    if (best < 0 || work * 100 < best_work * 97 || (work <= best_work && area > best_area)) {
+    // a narrower tile must save at least 8 % of the padded work to be worth its extra LDS traffic
+    if (best < 0 || work * 100 < best_work * 92 || (work <= best_work && area > best_area)) {
       best = t;
       best_work = work;
       best_area = area;
@@ -86,6 +86,43 @@ int32_t bounds_mode(bool no_padding, int64_t taps, int64_t bytes, int64_t reach)
 }
 
 uint32_t koff_invalid(int32_t mode) { return mode == 0 ? 0x7FFFFFFCu : mode == 2 ? 0x40000000u : 0u; }
+
+// Decides whether the patch-staged kernel can run this correlation and, if so, fills its fields.
+// Used for the 256-column tiles of the 16-row MFMA, where the gather kernel's per-element work is
+// largest (measured: 5x5 grouped backward-data +9 %; equal or slower on 128-column tiles).
+// Needs a stride-1, dilation-1 gather, 8-aligned channels per group, at least 3 taps, a blob of at
+// most 2^30 bytes, and a patch that fits kPatchEPT*256 floats per channel and the LDS.
+void configure_patch(CorrArgs& a, PackArgs& k, int64_t cg_in, int64_t n_img, int32_t bm, int32_t bn) {
+  a.use_patch = 0;
+  k.kperm_T = 0;
+  const int64_t T = a.THW, TH = a.THW / a.TW;
+  if (a.sh != 1 || a.sw != 1 || a.dh != 1 || a.dw != 1 || cg_in % 8 != 0 || T < 3) return;
+  if (!(bn == 256 && bm <= 48)) return;
+  if ((int64_t)a.in_bytes > ((int64_t)1 << 30) || a.ncols < 1) return;
+  const int64_t PH = a.P / a.PW, PWID = a.PW + a.TW - 1, RS = PH + TH - 1;
+  // largest patch over all column tiles
+  int64_t max_rows = 0;
+  for (int64_t c0 = 0; c0 < a.ncols; c0 += bn) {
+    const int64_t c1 = (c0 + bn < a.ncols ? c0 + bn : a.ncols) - 1;
+    const int64_t n0 = c0 / a.P, a0 = (c0 % a.P) / a.PW, n1 = c1 / a.P, a1 = (c1 % a.P) / a.PW;
+    const int64_t R0 = PH - a0 + TH - 1;
+    const int64_t rows = (n1 == n0 ? a1 - a0 : R0 + (n1 - n0 - 1) * RS + a1) + TH;
+    if (rows > max_rows) max_rows = rows;
+  }
+  const int64_t psz = max_rows * PWID;
+  const int64_t lds = (2 * (int64_t)bm * 20 + 16 * psz) * 4;
+  if (psz > kPatchEPT * 256 || lds > 80 * 1024 || lds < 16 * ((int64_t)bm + bn)) return;
+  a.use_patch = 1;
+  a.Cg_in = (int32_t)cg_in;
+  a.NS = (int32_t)(cg_in / 8 * T);
+  a.PH = (int32_t)PH;
+  a.Nimg = (int32_t)n_img;
+  a.PWID = (int32_t)PWID;
+  a.PSZ = (int32_t)psz;
+  a.mPWID = make_magic((uint32_t)PWID);
+  a.mRSEG = make_magic((uint32_t)RS);
+  k.kperm_T = (int32_t)T;
+}
 
 int hip_fail(int e) {
   g_last_hip_error = e;
@@ -195,6 +232,7 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
     k.tdh = a.dh;
     k.tdw = a.dw;
     k.koff_invalid = koff_invalid(a.bounds_mode);
+    configure_patch(a, k, Cg, N, bm, bn);
     const int64_t pack_elems = G * (int64_t)a.KP * a.MP;
     if (pack_elems >= kMaxElems || (int64_t)G * a.m_tiles * a.col_tiles >= ((int64_t)1 << 31)) {
       delete d;
@@ -283,6 +321,7 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
     k.tdh = a.dh;
     k.tdw = a.dw;
     k.koff_invalid = koff_invalid(a.bounds_mode);
+    configure_patch(a, k, Kg, N, bm, bn);
     const int64_t pack_elems = G * (int64_t)a.KP * a.MP;
     if (pack_elems >= kMaxElems || (int64_t)G * a.m_tiles * a.col_tiles >= ((int64_t)1 << 31)) {
       delete d;
@@ -371,8 +410,9 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
   if (d->bwd_ws > d->ws_bytes) d->ws_bytes = d->bwd_ws;
   if (d->wg_ws > d->ws_bytes) d->ws_bytes = d->wg_ws;
   if (d->bg_ws > d->ws_bytes) d->ws_bytes = d->bg_ws;
-  snprintf(d->names, sizeof(d->names), "fwd=%s;bwd_data=%s;bwd_filter=%s(S=%d);bwd_bias=bias_grad(S=%d)",
-           corr_tile_name(d->fwd_tile), corr_tile_name(d->bwd_tile), wgrad_tile_name(d->wg_tile), d->wg.S, d->bg.S);
+  snprintf(d->names, sizeof(d->names), "fwd=%s%s;bwd_data=%s%s;bwd_filter=%s(S=%d);bwd_bias=bias_grad(S=%d)",
+           corr_tile_name(d->fwd_tile), d->fwd.use_patch ? "_patch" : "", corr_tile_name(d->bwd_tile),
+           d->bwd.use_patch ? "_patch" : "", wgrad_tile_name(d->wg_tile), d->wg.S, d->bg.S);
   *out = d;
   return CONV_OK;
 }
@@ -419,7 +459,7 @@ int conv_forward(const conv_desc_t* d, const float* x, const float* w, const flo
   a.in = x;
   a.bias = bias;
   a.out = y;
-  e = launch_corr(d->fwd_tile, a, hip_stream);
+  e = a.use_patch ? launch_corr_patch(d->fwd_tile, a, hip_stream) : launch_corr(d->fwd_tile, a, hip_stream);
   return e ? hip_fail(e) : CONV_OK;
 }
 
@@ -441,7 +481,7 @@ int conv_backward_data(const conv_desc_t* d, const float* w, const float* dy, fl
   a.in = dy;
   a.bias = nullptr;
   a.out = dx;
-  e = launch_corr(d->bwd_tile, a, hip_stream);
+  e = a.use_patch ? launch_corr_patch(d->bwd_tile, a, hip_stream) : launch_corr(d->bwd_tile, a, hip_stream);
   return e ? hip_fail(e) : CONV_OK;
 }
 

@@ -1,0 +1,75 @@
+// Epilogue shared by the correlation kernels: bias add and scatter of the accumulator tile.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include "device_utils.h"
+#include "internal.h"
+
+namespace mi355conv {
+
+// Two LDS tables turn an accumulator into its output address with one 16-byte read per row:
+//   rowtab[m]   = {offset, row shift, column shift, bias}   (row m = (channel, row phase, column phase))
+//   coltab[col] = {offset, row, column, -}                   (column = (image, a, b))
+// An element is stored when (row shift + row, column shift + column) lies inside the output
+// image; rows past the matrix edge and columns past the batch carry a shift that fails the test.
+// Must be entered after a barrier: the tables overwrite the pipeline buffers at `smem`.
+template <int MT, int MB, int NB, int BM, int BN, typename Acc>
+__device__ __forceinline__ void corr_epilogue(const CorrArgs& a, float* smem, Acc (&acc)[MB][NB], uint32_t m_tile,
+                                              uint32_t col_tile, uint32_t g, int wm, int wn) {
+  using M = Mfma<MT>;
+  const int t = threadIdx.x, lane = t & 63;
+  int4* rowtab = reinterpret_cast<int4*>(smem);
+  int4* coltab = rowtab + BM;
+  for (int m = t; m < BM; m += 256) {
+    const uint32_t gm = m_tile * BM + m;
+    int off = 0, hh = -(1 << 28), ww = 0;
+    float bb = 0.f;
+    if (gm < (uint32_t)a.Mrows) {
+      const uint32_t c = mdiv(gm, a.mRShw);
+      const uint32_t rem = gm - c * a.RShw;
+      const uint32_t rh = mdiv(rem, a.mRSw);
+      const uint32_t rw = rem - rh * a.RSw;
+      const uint32_t chan = g * a.chan_per_grp + c;
+      hh = (int)rh - a.opad_h;
+      ww = (int)rw - a.opad_w;
+      off = (int)(chan * (uint32_t)(a.OHd * a.OWd)) + hh * a.OWd + ww;
+      if (a.bias) bb = a.bias[chan];
+    }
+    rowtab[m] = make_int4(off, hh, ww, __builtin_bit_cast(int, bb));
+  }
+  for (int cl = t; cl < BN; cl += 256) {
+    const uint32_t col = col_tile * BN + cl;
+    int off = 0, hh = -(1 << 28), ww = 0;
+    if (col < (uint32_t)a.ncols) {
+      const uint32_t n = mdiv(col, a.mP);
+      const uint32_t pix = col - n * a.P;
+      const uint32_t pa = mdiv(pix, a.mPW);
+      const uint32_t pb = pix - pa * a.PW;
+      hh = (int)pa * a.RSh;
+      ww = (int)pb * a.RSw;
+      off = (int)(n * (uint32_t)a.out_img_stride) + hh * a.OWd + ww;
+    }
+    coltab[cl] = make_int4(off, hh, ww, 0);
+  }
+  __syncthreads();
+
+  int4 ct[NB];
+#pragma unroll
+  for (int j = 0; j < NB; ++j) ct[j] = coltab[(wn * NB + j) * MT + lane % MT];
+#pragma unroll
+  for (int i = 0; i < MB; ++i)
+#pragma unroll
+    for (int r = 0; r < M::NR; ++r) {
+      const int4 rt = rowtab[(wm * MB + i) * MT + M::row(r, lane)];
+      const float bb = __builtin_bit_cast(float, rt.w);
+#pragma unroll
+      for (int j = 0; j < NB; ++j) {
+        const int hh = rt.y + ct[j].y, ww = rt.z + ct[j].z;
+        if ((uint32_t)hh < (uint32_t)a.OHd && (uint32_t)ww < (uint32_t)a.OWd)
+          a.out[rt.x + ct[j].x] = acc[i][j][r] + bb;
+      }
+    }
+}
+
+}  // namespace mi355conv

@@ -70,7 +70,17 @@ struct CorrArgs {
   int32_t chan_per_grp;
   // grid
   int32_t G, m_tiles, col_tiles;
+  // patch-staged variant (corr_patch_kernel); use_patch = 0 selects the gather kernel
+  int32_t use_patch;
+  int32_t Cg_in;       // gathered channels per group (multiple of 8)
+  int32_t NS;          // super steps = Cg_in/8 * taps
+  int32_t PH;          // rows of the column space per image (P / PW)
+  int32_t Nimg;        // images
+  int32_t PWID, PSZ;   // patch row length (PW + TW - 1); floats per channel of an LDS patch stage
+  Magic mPWID, mRSEG;  // divisions by PWID and by the patch rows of a full image (PH + TH - 1)
 };
+
+constexpr int kPatchEPT = 3;  // patch elements per thread and channel: PSZ <= 3 * 256
 
 // Packs the weights into the A operand of the correlation kernel.
 //   mode 0 (forward): A[g][m][kk] = w[g*Kg + m][kk]
@@ -87,6 +97,7 @@ struct PackArgs {
   int32_t sh, sw, dh, dw;
   int32_t Qh, Qw;
   int32_t Kred, KP, Mrows, MP;
+  int32_t kperm_T;  // 0, or the tap count T: k runs (8-channel chunk, tap, channel in chunk) instead of (c, tap)
 };
 
 // Backward filter: part[s][g][k][nn] = sum over the split's columns of dy * gathered x.
@@ -155,6 +166,7 @@ const char* wgrad_tile_name(int32_t tile);
 // Launchers (defined next to the kernels).  Each returns the hipError_t of the launch as int.
 int launch_pack(const PackArgs& a, void* stream);
 int launch_corr(int32_t tile, const CorrArgs& a, void* stream);
+int launch_corr_patch(int32_t tile, const CorrArgs& a, void* stream);
 int launch_wgrad(int32_t tile, const WgradArgs& a, void* stream);
 int launch_reduce(const ReduceArgs& a, void* stream);
 int launch_bias_grad(const BiasGradArgs& a, void* stream);

@@ -15,6 +15,7 @@
 // what lets one kernel serve both passes.
 #include <hip/hip_runtime.h>
 
+#include "corr_epilogue.h"
 #include "device_utils.h"
 #include "internal.h"
 
@@ -265,59 +266,7 @@ __global__ __launch_bounds__(kThreads) void corr_kernel(const CorrArgs a) {
   }
   if (kc < nchunks) iteration(kc, raX, rbX);
 
-  // ---- epilogue: tables, then scatter -------------------------------------------------------
-  // rowtab[m] = {offset, row shift, column shift, bias}; coltab[col] = {offset, row, column, -}
-  int4* rowtab = reinterpret_cast<int4*>(smem);
-  int4* coltab = rowtab + BM;
-  for (int m = t; m < BM; m += kThreads) {
-    const uint32_t gm = m_tile * BM + m;
-    int off = 0, hh = -(1 << 28), ww = 0;
-    float bb = 0.f;
-    if (gm < (uint32_t)a.Mrows) {
-      const uint32_t c = mdiv(gm, a.mRShw);
-      const uint32_t rem = gm - c * a.RShw;
-      const uint32_t rh = mdiv(rem, a.mRSw);
-      const uint32_t rw = rem - rh * a.RSw;
-      const uint32_t chan = g * a.chan_per_grp + c;
-      hh = (int)rh - a.opad_h;
-      ww = (int)rw - a.opad_w;
-      off = (int)(chan * (uint32_t)(a.OHd * a.OWd)) + hh * a.OWd + ww;
-      if (a.bias) bb = a.bias[chan];
-    }
-    rowtab[m] = make_int4(off, hh, ww, __builtin_bit_cast(int, bb));
-  }
-  for (int cl = t; cl < BN; cl += kThreads) {
-    const uint32_t col = col_tile * BN + cl;
-    int off = 0, hh = -(1 << 28), ww = 0;
-    if (col < (uint32_t)a.ncols) {
-      const uint32_t n = mdiv(col, a.mP);
-      const uint32_t pix = col - n * a.P;
-      const uint32_t pa = mdiv(pix, a.mPW);
-      const uint32_t pb = pix - pa * a.PW;
-      hh = (int)pa * a.RSh;
-      ww = (int)pb * a.RSw;
-      off = (int)(n * (uint32_t)a.out_img_stride) + hh * a.OWd + ww;
-    }
-    coltab[cl] = make_int4(off, hh, ww, 0);
-  }
-  __syncthreads();
-
-  int4 ct[NB];
-#pragma unroll
-  for (int j = 0; j < NB; ++j) ct[j] = coltab[(wn * NB + j) * MT + lane % MT];
-#pragma unroll
-  for (int i = 0; i < MB; ++i)
-#pragma unroll
-    for (int r = 0; r < M::NR; ++r) {
-      const int4 rt = rowtab[(wm * MB + i) * MT + M::row(r, lane)];
-      const float bb = __builtin_bit_cast(float, rt.w);
-#pragma unroll
-      for (int j = 0; j < NB; ++j) {
-        const int hh = rt.y + ct[j].y, ww = rt.z + ct[j].z;
-        if ((uint32_t)hh < (uint32_t)a.OHd && (uint32_t)ww < (uint32_t)a.OWd)
-          a.out[rt.x + ct[j].x] = acc[i][j][r] + bb;
-      }
-    }
+  corr_epilogue<MT, MB, NB, BM, BN>(a, smem, acc, m_tile, col_tile, g, wm, wn);
 }
 
 // One k-table entry: where tap kk = (c, i, j) of the gather sits relative to a column's base.
@@ -334,16 +283,26 @@ __device__ __forceinline__ void fill_ktab(const PackArgs& a, int kk) {
   a.ktab[kk] = e;
 }
 
-// Forward: A[g][m][kk] = w[g*Kg + m][kk], zero padded to [MP][KP] (the weight blob's own order).
+// Packed position kp -> reduction index (channel, tap) in the blob's own order.  The patch kernel
+// runs the reduction as (8-channel chunk, tap, channel in chunk); the gather kernel keeps (c, tap).
+__device__ __forceinline__ int source_k(const PackArgs& a, int kp) {
+  if (a.kperm_T == 0) return kp;
+  const int T = a.kperm_T;
+  const int cc = kp / (8 * T), rem = kp % (8 * T);
+  return (cc * 8 + rem % 8) * T + rem / 8;
+}
+
+// Forward: A[g][m][k] = w[g*Kg + m][k], zero padded to [MP][KP] (the weight blob's own order).
 __global__ __launch_bounds__(256) void pack_fwd_kernel(const PackArgs a) {
   const size_t total = (size_t)a.G * a.MP * a.KP;
   const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= total) return;
-  const int kk = (int)(idx % a.KP);
+  const int kp = (int)(idx % a.KP);
   const int m = (int)((idx / a.KP) % a.MP);
   const int g = (int)(idx / ((size_t)a.MP * a.KP));
-  a.A[idx] = (m < a.Mrows && kk < a.Kred) ? a.w[((size_t)g * a.Kg + m) * a.Kred + kk] : 0.f;
-  if (m == 0 && g == 0) fill_ktab(a, kk);
+  const int kk = source_k(a, kp);
+  a.A[idx] = (m < a.Mrows && kp < a.Kred) ? a.w[((size_t)g * a.Kg + m) * a.Kred + kk] : 0.f;
+  if (m == 0 && g == 0) fill_ktab(a, kp);
 }
 
 // Backward data: rows are (input channel, row phase, column phase), k is (output channel,
@@ -354,11 +313,12 @@ __global__ __launch_bounds__(256) void pack_bwd_kernel(const PackArgs a) {
   const size_t total = (size_t)a.G * a.MP * a.KP;
   const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= total) return;
-  const int kk = (int)(idx % a.KP);
+  const int kp = (int)(idx % a.KP);
   const int m = (int)((idx / a.KP) % a.MP);
   const int g = (int)(idx / ((size_t)a.MP * a.KP));
+  const int kk = source_k(a, kp);
   float v = 0.f;
-  if (m < a.Mrows && kk < a.Kred) {
+  if (m < a.Mrows && kp < a.Kred) {
     const int QQ = a.Qh * a.Qw;
     const int k = kk / QQ, qr = kk % QQ;
     const int qh = a.Qh - 1 - qr / a.Qw, qw = a.Qw - 1 - qr % a.Qw;
@@ -372,7 +332,7 @@ __global__ __launch_bounds__(256) void pack_bwd_kernel(const PackArgs a) {
     }
   }
   a.A[idx] = v;
-  if (m == 0 && g == 0) fill_ktab(a, kk);
+  if (m == 0 && g == 0) fill_ktab(a, kp);
 }
 
 template <int MT, int MB, int NB, int WM, int WN, int BK>

@@ -100,12 +100,31 @@ SWEEP = [
     P(1, 200, 7, 7, 50, 3, 3, 1, 1, 1, 1),                  # long reduction, 50 rows
 ]
 
+# Shapes that select the patch-staged kernel (256-column tiles of the 16-row MFMA): 48 or <= 16
+# rows, 8-aligned reduction channels, enough columns for the wide tile to win.
+PATCH_CASES = [
+    (P(14, 48, 60, 45, 16, 5, 5, 1, 1, 2, 2), "bwd_data"),             # 5x5, one image per many tiles
+    (P(400, 96, 9, 9, 16, 3, 3, 1, 1, 1, 1, 1, 1, 2), "bwd_data"),     # grouped, tiles span 4 images
+    (P(49, 8, 32, 32, 8, 3, 3, 1, 1, 1, 1), "bwd_data"),               # 16-row tile
+    (P(9, 16, 70, 61, 48, 3, 5, 1, 1, 0, 3), "fwd"),                   # forward with 48 rows, ragged pad
+]
+
 
 @pytest.mark.parametrize("i", range(len(SWEEP)))
 def test_sweep_full_compare(i):
     pd = SWEEP[i]
     print("case", i, pd, flush=True)
     check_full(pd, seed=7000 + 10 * i, bias=bool(pd["bias_term"]))
+
+
+@pytest.mark.parametrize("i", range(len(PATCH_CASES)))
+def test_patch_kernel_full_compare(i):
+    pd, which = PATCH_CASES[i]
+    print("patch case", i, pd, flush=True)
+    d = conv.conv_desc_create(conv.ConvParams(**pd))
+    names = dict(kv.split("=", 1) for kv in conv.conv_desc_kernel_names(d).split(";"))
+    assert names[which].endswith("_patch"), names
+    check_full(pd, seed=9000 + 10 * i)
 
 
 @pytest.mark.parametrize("name", [l.name for l in workloads.LAYERS if l.config <= 3])

@@ -124,6 +124,24 @@ void configure_patch(CorrArgs& a, PackArgs& k, int64_t cg_in, int64_t n_img, int
   k.kperm_T = (int32_t)T;
 }
 
+// Split of the reduction for small problems: with few workgroups and a long chunk loop the chip
+// idles while each workgroup walks its chunks one barrier at a time; S slices run side by side and
+// a reduce kernel adds them.  Only worth an extra launch when the grid is well under one
+// workgroup per compute unit.
+void configure_ksplit(CorrArgs& a, int64_t out_elems) {
+  a.ksplit = 1;
+  a.chunks_per_split = a.KP / 16;
+  a.out_elems = (int32_t)out_elems;
+  const int64_t units = (int64_t)a.G * a.m_tiles * a.col_tiles, chunks = a.KP / 16;
+  if (a.use_patch || units > 160 || chunks < 8 || a.ncols < 1) return;
+  int64_t S = ceil_div(512, units);
+  if (S > chunks / 4) S = chunks / 4;
+  if (S > 16) S = 16;
+  if (S < 2) return;
+  a.chunks_per_split = (int32_t)ceil_div(chunks, S);
+  a.ksplit = (int32_t)ceil_div(chunks, a.chunks_per_split);
+}
+
 int hip_fail(int e) {
   g_last_hip_error = e;
   return CONV_EHIP;
@@ -233,12 +251,14 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
     k.tdw = a.dw;
     k.koff_invalid = koff_invalid(a.bounds_mode);
     configure_patch(a, k, Cg, N, bm, bn);
+    configure_ksplit(a, y_elems);
     const int64_t pack_elems = G * (int64_t)a.KP * a.MP;
     if (pack_elems >= kMaxElems || (int64_t)G * a.m_tiles * a.col_tiles >= ((int64_t)1 << 31)) {
       delete d;
       return CONV_ESHAPE;
     }
-    d->fwd_ws = (size_t)pack_elems * 4 + (size_t)a.KP * sizeof(KTabEntry);
+    d->fwd_pack_bytes = (size_t)pack_elems * 4 + (size_t)a.KP * sizeof(KTabEntry);
+    d->fwd_ws = d->fwd_pack_bytes + (a.ksplit > 1 ? (size_t)a.ksplit * y_elems * 4 : 0);
   }
 
   // ---- backward data: a stride-1 correlation over dy whose rows are (c, row phase, column
@@ -322,12 +342,14 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
     k.tdw = a.dw;
     k.koff_invalid = koff_invalid(a.bounds_mode);
     configure_patch(a, k, Kg, N, bm, bn);
+    configure_ksplit(a, x_elems);
     const int64_t pack_elems = G * (int64_t)a.KP * a.MP;
     if (pack_elems >= kMaxElems || (int64_t)G * a.m_tiles * a.col_tiles >= ((int64_t)1 << 31)) {
       delete d;
       return CONV_ESHAPE;
     }
-    d->bwd_ws = (size_t)pack_elems * 4 + (size_t)a.KP * sizeof(KTabEntry);
+    d->bwd_pack_bytes = (size_t)pack_elems * 4 + (size_t)a.KP * sizeof(KTabEntry);
+    d->bwd_ws = d->bwd_pack_bytes + (a.ksplit > 1 ? (size_t)a.ksplit * x_elems * 4 : 0);
   }
 
   // ---- backward filter: rows = output channels, columns = (c, i, j), reduction over (n, oh, ow)
@@ -381,6 +403,7 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
     const int64_t max_by_ws = ((int64_t)8 << 20) / (w_elems > 0 ? w_elems : 1);
     if (S > max_by_len) S = max_by_len;
     if (S > max_by_ws) S = max_by_ws;
+    if (S > 256) S = 256;  // beyond one split per compute unit the reduce kernel only gets slower
     if (S < 1) S = 1;
     while (S > 1 && tiles * S > 256 && (tiles * S) % 256 != 0 && (tiles * S) % 256 < 64) --S;
     a.cols_per_split = (int32_t)round_up(ceil_div((int64_t)a.ncols > 0 ? a.ncols : 1, S), bk);
@@ -410,9 +433,9 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
   if (d->bwd_ws > d->ws_bytes) d->ws_bytes = d->bwd_ws;
   if (d->wg_ws > d->ws_bytes) d->ws_bytes = d->wg_ws;
   if (d->bg_ws > d->ws_bytes) d->ws_bytes = d->bg_ws;
-  snprintf(d->names, sizeof(d->names), "fwd=%s%s;bwd_data=%s%s;bwd_filter=%s(S=%d);bwd_bias=bias_grad(S=%d)",
-           corr_tile_name(d->fwd_tile), d->fwd.use_patch ? "_patch" : "", corr_tile_name(d->bwd_tile),
-           d->bwd.use_patch ? "_patch" : "", wgrad_tile_name(d->wg_tile), d->wg.S, d->bg.S);
+  snprintf(d->names, sizeof(d->names), "fwd=%s%s(S=%d);bwd_data=%s%s(S=%d);bwd_filter=%s(S=%d);bwd_bias=bias_grad(S=%d)",
+           corr_tile_name(d->fwd_tile), d->fwd.use_patch ? "_patch" : "", d->fwd.ksplit, corr_tile_name(d->bwd_tile),
+           d->bwd.use_patch ? "_patch" : "", d->bwd.ksplit, wgrad_tile_name(d->wg_tile), d->wg.S, d->bg.S);
   *out = d;
   return CONV_OK;
 }
@@ -459,7 +482,23 @@ int conv_forward(const conv_desc_t* d, const float* x, const float* w, const flo
   a.in = x;
   a.bias = bias;
   a.out = y;
+  a.part = reinterpret_cast<float*>(static_cast<char*>(ws) + d->fwd_pack_bytes);
   e = a.use_patch ? launch_corr_patch(d->fwd_tile, a, hip_stream) : launch_corr(d->fwd_tile, a, hip_stream);
+  if (e) return hip_fail(e);
+  if (a.ksplit > 1) {  // add the split partials and the bias
+    ReduceArgs r = {};
+    r.part = a.part;
+    r.dst = y;
+    r.count = a.out_elems;
+    r.S = a.ksplit;
+    r.beta = 0.f;
+    r.bias = bias;
+    r.chan_elems = d->OH * d->OW;
+    r.channels = d->p.num_output;
+    r.mChanElems = make_magic(r.chan_elems);
+    r.mChannels = make_magic(r.channels);
+    e = launch_reduce(r, hip_stream);
+  }
   return e ? hip_fail(e) : CONV_OK;
 }
 
@@ -481,7 +520,18 @@ int conv_backward_data(const conv_desc_t* d, const float* w, const float* dy, fl
   a.in = dy;
   a.bias = nullptr;
   a.out = dx;
+  a.part = reinterpret_cast<float*>(static_cast<char*>(ws) + d->bwd_pack_bytes);
   e = a.use_patch ? launch_corr_patch(d->bwd_tile, a, hip_stream) : launch_corr(d->bwd_tile, a, hip_stream);
+  if (e) return hip_fail(e);
+  if (a.ksplit > 1) {
+    ReduceArgs r = {};
+    r.part = a.part;
+    r.dst = dx;
+    r.count = a.out_elems;
+    r.S = a.ksplit;
+    r.beta = 0.f;
+    e = launch_reduce(r, hip_stream);
+  }
   return e ? hip_fail(e) : CONV_OK;
 }
 
@@ -498,7 +548,7 @@ int conv_backward_filter(const conv_desc_t* d, const float* x, const float* dy, 
   a.part = static_cast<float*>(ws);
   int e = empty ? 0 : launch_wgrad(d->wg_tile, a, hip_stream);
   if (e) return hip_fail(e);
-  ReduceArgs r;
+  ReduceArgs r = {};
   r.part = a.part;
   r.dst = dw;
   r.count = (int32_t)((int64_t)d->p.num_output * d->wg.Kred);
@@ -521,7 +571,7 @@ int conv_backward_bias(const conv_desc_t* d, const float* dy, float* db, float b
   a.part = static_cast<float*>(ws);
   int e = empty ? 0 : launch_bias_grad(a, hip_stream);
   if (e) return hip_fail(e);
-  ReduceArgs r;
+  ReduceArgs r = {};
   r.part = a.part;
   r.dst = db;
   r.count = d->p.num_output;

@@ -16,8 +16,12 @@ namespace mi355conv {
 // Must be entered after a barrier: the tables overwrite the pipeline buffers at `smem`.
 template <int MT, int MB, int NB, int BM, int BN, typename Acc>
 __device__ __forceinline__ void corr_epilogue(const CorrArgs& a, float* smem, Acc (&acc)[MB][NB], uint32_t m_tile,
-                                              uint32_t col_tile, uint32_t g, int wm, int wn) {
+                                              uint32_t col_tile, uint32_t g, int wm, int wn, uint32_t split = 0) {
   using M = Mfma<MT>;
+  // With a split reduction every split writes its raw partial sums, in the output blob's own
+  // layout, to its slice of the workspace; a reduce kernel adds the slices and the bias.
+  float* const out = a.ksplit > 1 ? a.part + (size_t)split * a.out_elems : a.out;
+  const float* const bias = a.ksplit > 1 ? nullptr : a.bias;
   const int t = threadIdx.x, lane = t & 63;
   int4* rowtab = reinterpret_cast<int4*>(smem);
   int4* coltab = rowtab + BM;
@@ -34,7 +38,7 @@ __device__ __forceinline__ void corr_epilogue(const CorrArgs& a, float* smem, Ac
       hh = (int)rh - a.opad_h;
       ww = (int)rw - a.opad_w;
       off = (int)(chan * (uint32_t)(a.OHd * a.OWd)) + hh * a.OWd + ww;
-      if (a.bias) bb = a.bias[chan];
+      if (bias) bb = bias[chan];
     }
     rowtab[m] = make_int4(off, hh, ww, __builtin_bit_cast(int, bb));
   }
@@ -67,7 +71,7 @@ __device__ __forceinline__ void corr_epilogue(const CorrArgs& a, float* smem, Ac
       for (int j = 0; j < NB; ++j) {
         const int hh = rt.y + ct[j].y, ww = rt.z + ct[j].z;
         if ((uint32_t)hh < (uint32_t)a.OHd && (uint32_t)ww < (uint32_t)a.OWd)
-          a.out[rt.x + ct[j].x] = acc[i][j][r] + bb;
+          out[rt.x + ct[j].x] = acc[i][j][r] + bb;
       }
     }
 }

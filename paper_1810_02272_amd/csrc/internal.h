@@ -70,6 +70,11 @@ struct CorrArgs {
   int32_t chan_per_grp;
   // grid
   int32_t G, m_tiles, col_tiles;
+  // split reduction (small problems): ksplit slices of chunks_per_split k chunks each write partial
+  // outputs to part[split][out_elems]; a reduce kernel finishes.  ksplit = 1: none of this.
+  int32_t ksplit, chunks_per_split;
+  int32_t out_elems;
+  float* part;
   // patch-staged variant (corr_patch_kernel); use_patch = 0 selects the gather kernel
   int32_t use_patch;
   int32_t Cg_in;       // gathered channels per group (multiple of 8)
@@ -124,6 +129,10 @@ struct ReduceArgs {
   float* dst;         // [count]
   int32_t count, S;
   float beta;
+  // optional per-channel bias for blobs laid out [..][channel][chan_elems]: dst += bias[(i / chan_elems) % channels]
+  const float* bias;
+  int32_t chan_elems, channels;
+  Magic mChanElems, mChannels;
 };
 
 struct BiasGradArgs {
@@ -182,12 +191,12 @@ struct conv_desc {
   int32_t fwd_tile;
   mi355conv::CorrArgs fwd;  // pointers left null
   mi355conv::PackArgs fwd_pack;
-  size_t fwd_ws;
+  size_t fwd_ws, fwd_pack_bytes;
   // backward data
   int32_t bwd_tile;
   mi355conv::CorrArgs bwd;
   mi355conv::PackArgs bwd_pack;
-  size_t bwd_ws;
+  size_t bwd_ws, bwd_pack_bytes;
   // backward filter
   int32_t wg_tile;
   mi355conv::WgradArgs wg;

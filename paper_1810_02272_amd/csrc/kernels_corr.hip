@@ -68,7 +68,9 @@ __global__ __launch_bounds__(kThreads) void corr_kernel(const CorrArgs a) {
   const uint32_t m_tile = lin % (uint32_t)a.m_tiles;
   lin /= (uint32_t)a.m_tiles;
   const uint32_t col_tile = lin % (uint32_t)a.col_tiles;
-  const uint32_t g = lin / (uint32_t)a.col_tiles;
+  lin /= (uint32_t)a.col_tiles;
+  const uint32_t g = lin % (uint32_t)a.G;
+  const uint32_t split = lin / (uint32_t)a.G;  // which part of the reduction (split-K; usually the only one)
 
   // Per-lane column state of the gather (fixed for the whole reduction).  An element that must
   // read as zero -- tap in the padding, column past the edge, k row past the reduction length --
@@ -116,7 +118,8 @@ __global__ __launch_bounds__(kThreads) void corr_kernel(const CorrArgs a) {
 
   // A tile: [row][k], 16 bytes (four k) per lane; a wave-wide load covers 16 rows x 16 k with
   // 8 consecutive lanes on 8 consecutive rows (conflict-free LDS write, 64-byte runs in memory).
-  const float* Ag = a.A + ((size_t)g * a.MP + (size_t)m_tile * BM) * a.KP;
+  const int kc_first = (int)split * a.chunks_per_split;
+  const float* Ag = a.A + ((size_t)g * a.MP + (size_t)m_tile * BM) * a.KP + (size_t)kc_first * BK;
   const int arow = (lane & 7) + 8 * (lane >> 5), ac4 = (lane >> 3) & 3;
   uint32_t aoff[C::A_PER];
 #pragma unroll
@@ -154,7 +157,7 @@ __global__ __launch_bounds__(kThreads) void corr_kernel(const CorrArgs a) {
   KTabEntry te[RPW], te_next[RPW];
   auto load_tab = [&](int kc) {
 #pragma unroll
-    for (int e = 0; e < RPW; ++e) te_next[e] = a.ktab[kc * BK + wv * RPW + e];
+    for (int e = 0; e < RPW; ++e) te_next[e] = a.ktab[(kc_first + kc) * BK + wv * RPW + e];
   };
   auto swap_tab = [&]() {
 #pragma unroll
@@ -196,7 +199,8 @@ __global__ __launch_bounds__(kThreads) void corr_kernel(const CorrArgs a) {
   // MFMA operands come from LDS as 16-byte reads: lane l takes row l%MT and the four k values
   // KSS*s + 4*(l/MT) .. +3, which feed four consecutive MFMAs; the k order inside a group of KSS
   // is thereby permuted, identically for both operands, which a sum does not notice.
-  const int nchunks = a.KP / BK;
+  int nchunks = a.KP / BK - kc_first;  // chunks of this split (chunk indices below are relative to it)
+  if (nchunks > a.chunks_per_split) nchunks = a.chunks_per_split;
   const int last = nchunks - 1;
   constexpr int NKS = C::NKS, NSS = C::NSS;
   const float* opA = smem + (wm * MB * MT + lane % MT) * LDK + (lane / MT) * 4;
@@ -266,7 +270,7 @@ __global__ __launch_bounds__(kThreads) void corr_kernel(const CorrArgs a) {
   }
   if (kc < nchunks) iteration(kc, raX, rbX);
 
-  corr_epilogue<MT, MB, NB, BM, BN>(a, smem, acc, m_tile, col_tile, g, wm, wn);
+  corr_epilogue<MT, MB, NB, BM, BN>(a, smem, acc, m_tile, col_tile, g, wm, wn, split);
 }
 
 // One k-table entry: where tap kk = (c, i, j) of the gather sits relative to a column's base.
@@ -337,7 +341,7 @@ __global__ __launch_bounds__(256) void pack_bwd_kernel(const PackArgs a) {
 
 template <int MT, int MB, int NB, int WM, int WN, int BK>
 int launch_corr_t(const CorrArgs& a, hipStream_t s) {
-  const uint32_t blocks = (uint32_t)a.G * a.m_tiles * a.col_tiles;
+  const uint32_t blocks = (uint32_t)a.G * a.m_tiles * a.col_tiles * a.ksplit;
   if (a.bounds_mode == 0)
     hipLaunchKernelGGL((corr_kernel<MT, MB, NB, WM, WN, BK, 0>), dim3(blocks), dim3(kThreads), 0, s, a);
   else if (a.bounds_mode == 2)

@@ -299,7 +299,11 @@ __global__ __launch_bounds__(256) void reduce_kernel(const ReduceArgs a) {
   quarter[q][lane] = (acc0 + acc1) + (acc2 + acc3);
   __syncthreads();
   if (q == 0 && i < a.count) {
-    const float s = (quarter[0][lane] + quarter[1][lane]) + (quarter[2][lane] + quarter[3][lane]);
+    float s = (quarter[0][lane] + quarter[1][lane]) + (quarter[2][lane] + quarter[3][lane]);
+    if (a.bias) {
+      const uint32_t c = mdiv((uint32_t)i, a.mChanElems);
+      s += a.bias[c - mdiv(c, a.mChannels) * a.channels];
+    }
     a.dst[i] = (a.beta == 0.f) ? s : a.beta * a.dst[i] + s;
   }
 }

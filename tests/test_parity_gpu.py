@@ -123,7 +123,7 @@ def test_patch_kernel_full_compare(i):
     print("patch case", i, pd, flush=True)
     d = conv.conv_desc_create(conv.ConvParams(**pd))
     names = dict(kv.split("=", 1) for kv in conv.conv_desc_kernel_names(d).split(";"))
-    assert names[which].endswith("_patch"), names
+    assert "_patch" in names[which], names
     check_full(pd, seed=9000 + 10 * i)
 
 

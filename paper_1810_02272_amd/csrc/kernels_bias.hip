@@ -30,24 +30,27 @@ __device__ __forceinline__ float wave_sum(float v) {
 __global__ __launch_bounds__(256) void bias_grad_kernel(const BiasGradArgs a) {
   __shared__ float wsum[4];
   const int k = blockIdx.x, s = blockIdx.y;
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   const int n0 = s * a.n_per_split;
   int n1 = n0 + a.n_per_split;
   if (n1 > a.N) n1 = a.N;
-  // four independent accumulators per thread keep several loads in flight
+  // Each wave walks whole images (one contiguous run of P floats per image and channel), the four
+  // waves of the block taking every fourth image, so small feature maps still keep all lanes of
+  // a wave busy; four independent accumulators per lane keep several loads in flight.
   float acc0 = 0.f, acc1 = 0.f, acc2 = 0.f, acc3 = 0.f;
-  for (int n = n0; n < n1; ++n) {
+  for (int n = n0 + wv; n < n1; n += 4) {
     const float* src = a.dy + ((size_t)n * a.K + k) * a.P;
-    int p = threadIdx.x;
-    for (; p + 768 < a.P; p += 1024) {
+    int p = lane;
+    for (; p + 192 < a.P; p += 256) {
       acc0 += src[p];
-      acc1 += src[p + 256];
-      acc2 += src[p + 512];
-      acc3 += src[p + 768];
+      acc1 += src[p + 64];
+      acc2 += src[p + 128];
+      acc3 += src[p + 192];
     }
-    for (; p < a.P; p += 256) acc0 += src[p];
+    for (; p < a.P; p += 64) acc0 += src[p];
   }
   const float w = wave_sum((acc0 + acc1) + (acc2 + acc3));
-  if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = w;
+  if (lane == 0) wsum[wv] = w;
   __syncthreads();
   if (threadIdx.x == 0) a.part[(size_t)s * a.K + k] = (wsum[0] + wsum[1]) + (wsum[2] + wsum[3]);
 }

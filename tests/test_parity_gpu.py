@@ -97,7 +97,9 @@ SWEEP = [
     P(3, 32, 20, 20, 64, 4, 4, 2, 2),                       # layer 3.b-like
     P(1, 1, 5, 7, 1, 2, 3, 3, 2, 0, 1),                     # tiny, stride > kernel
     P(2, 3, 10, 10, 5, 3, 3, 3, 3, 0, 0, 1, 1, 1, 0),       # no bias, stride leaves unread rows
-    P(1, 200, 7, 7, 50, 3, 3, 1, 1, 1, 1),                  # long reduction, 50 rows
+    P(1, 200, 7, 7, 50, 3, 3, 1, 1, 1, 1),                  # long reduction, 50 rows (split reduction)
+    P(3, 5, 30, 27, 12, 7, 7, 2, 2, 3, 3),                  # 49 taps with padding: compare-based bounds mode
+    P(2, 16, 24, 24, 8, 6, 6, 1, 1, 2, 2),                  # 36 taps at stride 1: backward-data bitmask does not apply
 ]
 
 # Shapes that select the patch-staged kernel (256-column tiles of the 16-row MFMA): 48 or <= 16

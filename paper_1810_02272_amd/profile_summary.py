@@ -23,7 +23,7 @@ import os
 import sys
 from collections import OrderedDict
 
-MAIN = ("corr_kernel", "wgrad_kernel", "bias_grad_kernel")
+MAIN = ("corr_kernel", "corr_patch_kernel", "wgrad_kernel", "bias_grad_kernel")
 PASSES = ("fwd", "bwd_data", "bwd_filter", "bwd_bias")
 COPY_BYTES = 256 * 1024 * 1024
 
@@ -93,7 +93,7 @@ def sq(directory: str) -> None:
     agg: "OrderedDict[tuple, dict]" = OrderedDict()
     for r in rows:
         name = _short(r["Kernel_Name"])
-        if not any(m in name for m in MAIN[:2]):
+        if not any(m in name for m in MAIN[:3]):
             continue
         key = (name[:50], int(r["Grid_Size"]) // max(int(r["Workgroup_Size"]), 1))
         agg.setdefault(key, {}).setdefault(r["Counter_Name"], []).append(float(r["Counter_Value"]))

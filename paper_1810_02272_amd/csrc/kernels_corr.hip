@@ -3,13 +3,13 @@
 // convolution layer (paper Table 1, "vision layers"; lowering + GEMM + bias are the steps the
 // low-level math library of the paper's "General Architecture" section performs).
 //
-//   D[m][col] = sum_kk A[kk][m] * B[kk][col]
+//   D[m][col] = sum_kk A[m][kk] * B[kk][col]
 //   B[kk][col] = in[n, g*Cg + c, a*sh - ph + i*dh, b*sw - pw + j*dw]  (0 outside the image)
 //   kk = (c, i, j), col = (n, a, b)
 //
 // B is never materialised: each workgroup gathers BK x BN elements of it straight from the NCHW
-// blob into LDS, double buffered, while the fp32 MFMA pipe works on the previous chunk.  A is the
-// weight matrix, packed beforehand into zero-padded [row][k] form so that its tiles are plain
+// blob through registers into a two-stage LDS ring, two chunks ahead of the fp32 MFMA pipe.  A is
+// the weight matrix, packed beforehand into zero-padded [row][k] form so that its tiles are plain
 // 16-byte copies.  The epilogue adds the bias and scatters each accumulator through two
 // small LDS tables (row -> channel/sub-pixel offset, column -> image/pixel offset), which is
 // what lets one kernel serve both passes.

@@ -61,14 +61,12 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
-_lib = None
+class OracleLib:
+    """ctypes front end for one build of conv_oracle.c (the module-level functions use the in-tree build;
+    the mutation tests load deliberately broken builds through this class)."""
 
-
-def _load():
-    global _lib
-    if _lib is None:
-        build()
-        lib = ctypes.CDLL(_LIB)
+    def __init__(self, path: str):
+        lib = ctypes.CDLL(path)
         dp = ctypes.POINTER(ctypes.c_double)
         ip = ctypes.POINTER(ctypes.c_int64)
         pp = ctypes.POINTER(_CParams)
@@ -83,8 +81,86 @@ def _load():
         lib.oracle_conv_backward_data_at.argtypes = [pp, dp, dp, ip, ctypes.c_int64, dp]
         lib.oracle_conv_backward_filter_at.argtypes = [pp, dp, dp, ip, ctypes.c_int64, dp]
         lib.oracle_num_threads.restype = ctypes.c_int
-        _lib = lib
-    return _lib
+        self.lib = lib
+
+    def num_threads(self) -> int:
+        return int(self.lib.oracle_num_threads())
+
+    def out_size(self, in_size: int, kernel: int, stride: int = 1, pad: int = 0, dilation: int = 1) -> int:
+        return int(self.lib.oracle_conv_out_size(in_size, kernel, stride, pad, dilation))
+
+    def output_shape(self, p: OracleParams):
+        oh, ow = ctypes.c_int64(), ctypes.c_int64()
+        c = p._c()
+        _check(self.lib.oracle_conv_output_shape(ctypes.byref(c), ctypes.byref(oh), ctypes.byref(ow)), "output_shape")
+        return (p.n, p.num_output, int(oh.value), int(ow.value))
+
+    def forward(self, p: OracleParams, x, w, b=None) -> np.ndarray:
+        ys = self.output_shape(p)
+        x, w = _f64(x, x_shape(p)), _f64(w, w_shape(p))
+        b = _f64(b, (p.num_output,)) if b is not None else None
+        y = np.empty(ys, dtype=np.float64)
+        c = p._c()
+        _check(self.lib.oracle_conv_forward(ctypes.byref(c), _dp(x), _dp(w), _dp(b), _dp(y)), "forward")
+        return y
+
+    def backward_data(self, p: OracleParams, w, dy) -> np.ndarray:
+        w, dy = _f64(w, w_shape(p)), _f64(dy, self.output_shape(p))
+        dx = np.empty(x_shape(p), dtype=np.float64)
+        c = p._c()
+        _check(self.lib.oracle_conv_backward_data(ctypes.byref(c), _dp(w), _dp(dy), _dp(dx)), "backward_data")
+        return dx
+
+    def backward_filter(self, p: OracleParams, x, dy, dw=None, beta: float = 0.0) -> np.ndarray:
+        x, dy = _f64(x, x_shape(p)), _f64(dy, self.output_shape(p))
+        out = np.zeros(w_shape(p), dtype=np.float64) if dw is None else _f64(dw, w_shape(p)).copy()
+        c = p._c()
+        _check(self.lib.oracle_conv_backward_filter(ctypes.byref(c), _dp(x), _dp(dy), _dp(out), float(beta)),
+               "backward_filter")
+        return out
+
+    def backward_bias(self, p: OracleParams, dy, db=None, beta: float = 0.0) -> np.ndarray:
+        dy = _f64(dy, self.output_shape(p))
+        out = np.zeros((p.num_output,), dtype=np.float64) if db is None else _f64(db, (p.num_output,)).copy()
+        c = p._c()
+        _check(self.lib.oracle_conv_backward_bias(ctypes.byref(c), _dp(dy), _dp(out), float(beta)), "backward_bias")
+        return out
+
+    def forward_at(self, p: OracleParams, x, w, b, idx) -> np.ndarray:
+        x, w = _f64(x, x_shape(p)), _f64(w, w_shape(p))
+        b = _f64(b, (p.num_output,)) if b is not None else None
+        idx, ip = _i64(idx)
+        out = np.empty(idx.shape, dtype=np.float64)
+        c = p._c()
+        _check(self.lib.oracle_conv_forward_at(ctypes.byref(c), _dp(x), _dp(w), _dp(b), ip, idx.size, _dp(out)),
+               "forward_at")
+        return out
+
+    def backward_data_at(self, p: OracleParams, w, dy, idx) -> np.ndarray:
+        w, dy = _f64(w, w_shape(p)), _f64(dy, self.output_shape(p))
+        idx, ip = _i64(idx)
+        out = np.empty(idx.shape, dtype=np.float64)
+        c = p._c()
+        _check(self.lib.oracle_conv_backward_data_at(ctypes.byref(c), _dp(w), _dp(dy), ip, idx.size, _dp(out)),
+               "backward_data_at")
+        return out
+
+    def backward_filter_at(self, p: OracleParams, x, dy, idx) -> np.ndarray:
+        x, dy = _f64(x, x_shape(p)), _f64(dy, self.output_shape(p))
+        idx, ip = _i64(idx)
+        out = np.empty(idx.shape, dtype=np.float64)
+        c = p._c()
+        _check(self.lib.oracle_conv_backward_filter_at(ctypes.byref(c), _dp(x), _dp(dy), ip, idx.size, _dp(out)),
+               "backward_filter_at")
+        return out
+
+
+def x_shape(p: OracleParams):
+    return (p.n, p.c, p.h, p.w)
+
+
+def w_shape(p: OracleParams):
+    return (p.num_output, p.c // p.group, p.kernel_h, p.kernel_w)
 
 
 def _f64(a, shape=None):
@@ -108,90 +184,52 @@ def _check(rc, what):
         raise ValueError(f"oracle {what}: invalid parameters or arguments")
 
 
+_default = None
+
+
+def _load() -> OracleLib:
+    global _default
+    if _default is None:
+        build()
+        _default = OracleLib(_LIB)
+    return _default
+
+
 def num_threads() -> int:
-    return int(_load().oracle_num_threads())
+    return _load().num_threads()
 
 
 def out_size(in_size: int, kernel: int, stride: int = 1, pad: int = 0, dilation: int = 1) -> int:
-    return int(_load().oracle_conv_out_size(in_size, kernel, stride, pad, dilation))
+    return _load().out_size(in_size, kernel, stride, pad, dilation)
 
 
 def output_shape(p: OracleParams):
-    oh, ow = ctypes.c_int64(), ctypes.c_int64()
-    c = p._c()
-    _check(_load().oracle_conv_output_shape(ctypes.byref(c), ctypes.byref(oh), ctypes.byref(ow)), "output_shape")
-    return (p.n, p.num_output, int(oh.value), int(ow.value))
-
-
-def x_shape(p: OracleParams):
-    return (p.n, p.c, p.h, p.w)
-
-
-def w_shape(p: OracleParams):
-    return (p.num_output, p.c // p.group, p.kernel_h, p.kernel_w)
+    return _load().output_shape(p)
 
 
 def forward(p: OracleParams, x, w, b=None) -> np.ndarray:
-    ys = output_shape(p)
-    x, w = _f64(x, x_shape(p)), _f64(w, w_shape(p))
-    b = _f64(b, (p.num_output,)) if b is not None else None
-    y = np.empty(ys, dtype=np.float64)
-    c = p._c()
-    _check(_load().oracle_conv_forward(ctypes.byref(c), _dp(x), _dp(w), _dp(b), _dp(y)), "forward")
-    return y
+    return _load().forward(p, x, w, b)
 
 
 def backward_data(p: OracleParams, w, dy) -> np.ndarray:
-    w, dy = _f64(w, w_shape(p)), _f64(dy, output_shape(p))
-    dx = np.empty(x_shape(p), dtype=np.float64)
-    c = p._c()
-    _check(_load().oracle_conv_backward_data(ctypes.byref(c), _dp(w), _dp(dy), _dp(dx)), "backward_data")
-    return dx
+    return _load().backward_data(p, w, dy)
 
 
 def backward_filter(p: OracleParams, x, dy, dw=None, beta: float = 0.0) -> np.ndarray:
-    x, dy = _f64(x, x_shape(p)), _f64(dy, output_shape(p))
-    out = np.zeros(w_shape(p), dtype=np.float64) if dw is None else _f64(dw, w_shape(p)).copy()
-    c = p._c()
-    _check(_load().oracle_conv_backward_filter(ctypes.byref(c), _dp(x), _dp(dy), _dp(out), float(beta)),
-           "backward_filter")
-    return out
+    return _load().backward_filter(p, x, dy, dw, beta)
 
 
 def backward_bias(p: OracleParams, dy, db=None, beta: float = 0.0) -> np.ndarray:
-    dy = _f64(dy, output_shape(p))
-    out = np.zeros((p.num_output,), dtype=np.float64) if db is None else _f64(db, (p.num_output,)).copy()
-    c = p._c()
-    _check(_load().oracle_conv_backward_bias(ctypes.byref(c), _dp(dy), _dp(out), float(beta)), "backward_bias")
-    return out
+    return _load().backward_bias(p, dy, db, beta)
 
 
 def forward_at(p: OracleParams, x, w, b, idx) -> np.ndarray:
-    x, w = _f64(x, x_shape(p)), _f64(w, w_shape(p))
-    b = _f64(b, (p.num_output,)) if b is not None else None
-    idx, ip = _i64(idx)
-    out = np.empty(idx.shape, dtype=np.float64)
-    c = p._c()
-    _check(_load().oracle_conv_forward_at(ctypes.byref(c), _dp(x), _dp(w), _dp(b), ip, idx.size, _dp(out)),
-           "forward_at")
-    return out
+    return _load().forward_at(p, x, w, b, idx)
 
 
 def backward_data_at(p: OracleParams, w, dy, idx) -> np.ndarray:
-    w, dy = _f64(w, w_shape(p)), _f64(dy, output_shape(p))
-    idx, ip = _i64(idx)
-    out = np.empty(idx.shape, dtype=np.float64)
-    c = p._c()
-    _check(_load().oracle_conv_backward_data_at(ctypes.byref(c), _dp(w), _dp(dy), ip, idx.size, _dp(out)),
-           "backward_data_at")
-    return out
+    return _load().backward_data_at(p, w, dy, idx)
 
 
 def backward_filter_at(p: OracleParams, x, dy, idx) -> np.ndarray:
-    x, dy = _f64(x, x_shape(p)), _f64(dy, output_shape(p))
-    idx, ip = _i64(idx)
-    out = np.empty(idx.shape, dtype=np.float64)
-    c = p._c()
-    _check(_load().oracle_conv_backward_filter_at(ctypes.byref(c), _dp(x), _dp(dy), ip, idx.size, _dp(out)),
-           "backward_filter_at")
-    return out
+    return _load().backward_filter_at(p, x, dy, idx)

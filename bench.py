@@ -30,6 +30,10 @@ def parse():
     ap.add_argument("--workload", default="config4", help="config0..config4 or a comma list of layer names")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--cpu-sample-images", type=int, default=128)
+    ap.add_argument("--cold-cache", action="store_true",
+                    help="rotate every step among enough distinct sets of tensors that one pass over all sets "
+                         "exceeds 512 MB (twice the 256 MB last-level cache), so no operand of a pass is still "
+                         "cached from the step before")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run plain 256 MiB device copies (outside the timed region) so that a rocprofv3 "
                          "--pmc FETCH_SIZE / WRITE_SIZE run of this command holds a kernel of known traffic")
@@ -63,6 +67,7 @@ def main():
     # ---- set-up (untimed): descriptors, inputs resident in HBM, one shared workspace ----
     state = []
     ws_bytes = 0
+    tensor_keys = ("x", "w", "b", "dy", "y", "dx", "dw", "db")
     for l in layers:
         d = conv.conv_desc_create(conv.ConvParams(**l.params_dict()))
         ws_bytes = max(ws_bytes, conv.conv_desc_workspace_bytes(d))
@@ -70,6 +75,12 @@ def main():
         t = dict(layer=l, desc=d, x=x.to(dev), w=w.to(dev), b=b.to(dev), dy=dy.to(dev),
                  y=torch.empty(l.y_shape, device=dev), dx=torch.empty(l.x_shape, device=dev),
                  dw=torch.empty(l.w_shape, device=dev), db=torch.empty(l.k, device=dev))
+        sets = [{k: t[k] for k in tensor_keys}]
+        if args.cold_cache:
+            set_bytes = sum(v.numel() * 4 for v in sets[0].values())
+            while len(sets) * set_bytes < (512 << 20) and len(sets) < 64:
+                sets.append({k: v.clone() for k, v in sets[0].items()})
+        t["sets"] = sets
         state.append(t)
     ws = torch.empty(max(ws_bytes // 4, 1), device=dev)
     stream = torch.cuda.current_stream()
@@ -87,8 +98,12 @@ def main():
         else:
             conv.conv_backward_bias(d, t["dy"], t["db"], 0.0, ws, stream)
 
+    step_no = [0]
+
     def step(events=None):
+        step_no[0] += 1
         for t in state:
+            t.update(t["sets"][step_no[0] % len(t["sets"])])
             for name in passes:
                 if events is not None:
                     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -106,6 +121,19 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+
+    # Cost of one empty dispatch on this machine, for reading the microsecond-scale layers: a one-element
+    # fill, enqueued back to back.
+    one = torch.zeros(1, device=dev)
+    for _ in range(20):
+        one.zero_()
+    le0, le1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    le0.record(stream)
+    for _ in range(200):
+        one.zero_()
+    le1.record(stream)
+    torch.cuda.synchronize()
+    launch_us = le0.elapsed_time(le1) * 1e3 / 200
 
     for _ in range(args.warmup):
         step()
@@ -141,6 +169,8 @@ def main():
             tot += ms
             if name != "bwd_bias":
                 row[name + "_tflops"] = round(l.flop_per_pass / ms / 1e9, 2)
+            else:  # one read of dy: the HBM-bound pass
+                row["bwd_bias_GBps"] = round(4.0 * l.n * l.k * l.out_hw * l.out_hw / ms / 1e6, 1)
         row["fwd_bwd_tflops"] = round(3 * l.flop_per_pass / tot / 1e9, 2)
         row["fwd_bwd_frac_of_fp32_mfma_peak"] = round(3 * l.flop_per_pass / tot / 1e9 / PEAK_FP32_MFMA_TFLOPS, 4)
         per_layer.append(row)
@@ -176,7 +206,11 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{args.workload}: layers " + ",".join(l.name for l in layers)
                                + " (N=%d each), fwd+bwd_data+bwd_filter+bwd_bias, beta=0, bias=0" % layers[0].n,
-                   "frac_of_fp32_mfma_peak": round(value / 1e3 / PEAK_FP32_MFMA_TFLOPS, 4)},
+                   "frac_of_fp32_mfma_peak": round(value / 1e3 / PEAK_FP32_MFMA_TFLOPS, 4),
+                   "cache": ("cold: %s tensor sets per layer rotated every step"
+                             % "/".join(str(len(t["sets"])) for t in state)) if args.cold_cache
+                            else "warm: the same tensors every step",
+                   "empty_dispatch_us": round(launch_us, 2)},
         "roofline": roofline,
         "per_layer": per_layer,
     }
@@ -196,6 +230,7 @@ def cpu_baseline(layers, n_sample):
 
     flop = 0.0
     secs = 0.0
+    per_layer = {}
     for l in layers:
         n = min(n_sample, l.n)
         pd = l.params_dict()
@@ -209,9 +244,12 @@ def cpu_baseline(layers, n_sample):
         oracle.backward_data(op, w, dy)
         oracle.backward_filter(op, x, dy)
         oracle.backward_bias(op, dy)
-        secs += time.perf_counter() - t0
+        dt = time.perf_counter() - t0
+        secs += dt
         flop += 3.0 * l.flop_per_pass * n / l.n
+        per_layer[l.name] = round(3.0 * l.flop_per_pass * n / l.n / dt / 1e9, 3)
     return {"value": round(flop / secs / 1e9, 3), "unit": "GFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "per_layer_gflops": per_layer,
             "sample": f"first {n_sample} images of each layer, fwd+bwd_data+bwd_filter+bwd_bias, "
                       f"double-precision nested loops, {secs:.1f} s"}
 

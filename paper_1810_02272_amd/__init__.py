@@ -1,4 +1,4 @@
-"""MI355X-native Caffe-semantics convolution layer (fp32): thin Python binding over libmi355conv.so.
+"""MI355X-native Caffe-semantics convolution and InnerProduct layers (fp32): thin Python binding over libmi355conv.so.
 
 The package holds the HIP sources (``csrc/``), the build step (``build.py``), the ctypes binding
 (``binding.py``: same names as the C entry points, argument marshalling only) and the seeded
@@ -19,4 +19,16 @@ from .binding import (  # noqa: F401
     conv_forward,
     conv_status_string,
     library_path,
+)
+from .ip_binding import (  # noqa: F401
+    IpParams,
+    ip_backward_bias,
+    ip_backward_data,
+    ip_backward_filter,
+    ip_desc_create,
+    ip_desc_destroy,
+    ip_desc_kernel_names,
+    ip_desc_workspace_bytes,
+    ip_forward,
+    ip_relu_backward,
 )

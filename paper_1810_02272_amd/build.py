@@ -8,7 +8,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_HERE)
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libmi355conv.so")
-SOURCES = ["api.cpp", "kernels_corr.hip", "kernels_corr_patch.hip", "kernels_wgrad.hip", "kernels_bias.hip"]
+SOURCES = ["api.cpp", "api_ip.cpp", "kernels_corr.hip", "kernels_corr_patch.hip", "kernels_wgrad.hip", "kernels_bias.hip",
+           "kernels_ip.hip"]
 HEADERS = ["internal.h", "device_utils.h", "corr_epilogue.h"]
 
 HIPCC_FLAGS = [
@@ -30,7 +31,8 @@ def is_stale() -> bool:
     if not os.path.exists(LIB):
         return True
     t = os.path.getmtime(LIB)
-    deps = [os.path.join(CSRC, s) for s in SOURCES + HEADERS] + [os.path.join(_ROOT, "include", "mi355conv.h")]
+    deps = [os.path.join(CSRC, s) for s in SOURCES + HEADERS] + [
+        os.path.join(_ROOT, "include", h) for h in ("mi355conv.h", "mi355ip.h")]
     return any(os.path.getmtime(d) > t for d in deps)
 
 

@@ -25,7 +25,8 @@ int64_t floor_div(int64_t a, int64_t b) {
 int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 int64_t round_up(int64_t a, int64_t b) { return ceil_div(a, b) * b; }
 
-// Row tile: the smallest padded row count wins, ties go to the taller tile.  Column tile, among
+// Row tile: the smallest padded row count wins; a taller tile is taken over a shorter one when it
+// pads at most 3 % more rows (the 32-row MFMA tiles it brings are worth that).  Column tile, among
 // the variants of that height: the one with the smallest estimated makespan on 256 compute
 // units -- rounds of workgroups times tile width -- with a 6 % handicap per halving of the
 // width (narrow tiles re-read the packed weights more often per FLOP).
@@ -36,6 +37,16 @@ int32_t pick_corr_tile(int32_t rows, int64_t groups, int64_t ncols) {
     corr_tile_shape(t, &bm, &bn, &bk);
     const int64_t pad = round_up(rows, bm);
     if (best_bm == 0 || pad < best_pad || (pad == best_pad && bm > best_bm)) {
+      best_pad = pad;
+      best_bm = bm;
+    }
+  }
+  const int64_t min_pad = best_pad;
+  for (int32_t t = 0; t < CORR_TILE_COUNT; ++t) {
+    int32_t bm, bn, bk;
+    corr_tile_shape(t, &bm, &bn, &bk);
+    const int64_t pad = round_up(rows, bm);
+    if (bm > best_bm && pad * 100 <= min_pad * 103) {
       best_pad = pad;
       best_bm = bm;
     }
@@ -142,12 +153,119 @@ void configure_ksplit(CorrArgs& a, int64_t out_elems) {
   a.ksplit = (int32_t)ceil_div(chunks, a.chunks_per_split);
 }
 
-int hip_fail(int e) {
+}  // namespace
+
+namespace mi355conv {
+
+int record_hip_error(int e) {
   g_last_hip_error = e;
   return CONV_EHIP;
 }
 
-}  // namespace
+int run_forward(const conv_desc* d, const float* x, const float* w, const float* bias, float* y, void* ws,
+                size_t ws_bytes, void* hip_stream) {
+  if (!d || !w) return CONV_EINVAL;
+  if ((d->p.bias_term != 0) != (bias != nullptr)) return CONV_EINVAL;
+  if (d->p.n == 0) return CONV_OK;  // empty blobs: nothing to read or write
+  if (!x || !y) return CONV_EINVAL;
+  if (d->fwd_ws > 0 && (!ws || ws_bytes < d->fwd_ws)) return CONV_EWORKSPACE;
+  PackArgs k = d->fwd_pack;
+  k.w = w;
+  k.A = static_cast<float*>(ws);
+  k.ktab = reinterpret_cast<KTabEntry*>(k.A + (size_t)k.G * k.KP * k.MP);
+  int e = launch_pack(k, hip_stream);
+  if (e) return record_hip_error(e);
+  CorrArgs a = d->fwd;
+  a.A = k.A;
+  a.ktab = k.ktab;
+  a.in = x;
+  a.bias = bias;
+  a.out = y;
+  a.part = reinterpret_cast<float*>(static_cast<char*>(ws) + d->fwd_pack_bytes);
+  e = a.use_patch ? launch_corr_patch(d->fwd_tile, a, hip_stream) : launch_corr(d->fwd_tile, a, hip_stream);
+  if (e) return record_hip_error(e);
+  if (a.ksplit > 1) {  // add the split partials and the bias
+    ReduceArgs r = {};
+    r.part = a.part;
+    r.dst = y;
+    r.count = a.out_elems;
+    r.S = a.ksplit;
+    r.beta = 0.f;
+    r.bias = bias;
+    r.chan_elems = d->OH * d->OW;
+    r.channels = d->p.num_output;
+    r.mChanElems = make_magic(r.chan_elems);
+    r.mChannels = make_magic(r.channels);
+    e = launch_reduce(r, hip_stream);
+  }
+  return e ? record_hip_error(e) : CONV_OK;
+}
+
+int run_backward_data(const conv_desc* d, const float* w, const float* dy, float* dx, float beta, void* ws,
+                      size_t ws_bytes, void* hip_stream) {
+  if (!d || !w) return CONV_EINVAL;
+  if (!(beta == 0.f || beta == 1.f)) return CONV_EINVAL;
+  if (d->p.n == 0) return CONV_OK;
+  if (!dy || !dx) return CONV_EINVAL;
+  if (d->bwd_ws > 0 && (!ws || ws_bytes < d->bwd_ws)) return CONV_EWORKSPACE;
+  PackArgs k = d->bwd_pack;
+  k.w = w;
+  k.A = static_cast<float*>(ws);
+  k.ktab = reinterpret_cast<KTabEntry*>(k.A + (size_t)k.G * k.KP * k.MP);
+  int e = launch_pack(k, hip_stream);
+  if (e) return record_hip_error(e);
+  CorrArgs a = d->bwd;
+  a.A = k.A;
+  a.ktab = k.ktab;
+  a.in = dy;
+  a.bias = nullptr;
+  a.out = dx;
+  a.accumulate = beta != 0.f;
+  a.part = reinterpret_cast<float*>(static_cast<char*>(ws) + d->bwd_pack_bytes);
+  e = a.use_patch ? launch_corr_patch(d->bwd_tile, a, hip_stream) : launch_corr(d->bwd_tile, a, hip_stream);
+  if (e) return record_hip_error(e);
+  if (a.ksplit > 1) {
+    ReduceArgs r = {};
+    r.part = a.part;
+    r.dst = dx;
+    r.count = a.out_elems;
+    r.S = a.ksplit;
+    r.beta = beta;
+    e = launch_reduce(r, hip_stream);
+  }
+  return e ? record_hip_error(e) : CONV_OK;
+}
+
+int run_backward_filter(const conv_desc* d, const float* x, const float* dy, float* dw, float beta, void* ws,
+                        size_t ws_bytes, void* hip_stream, const ReduceExtras& extras) {
+  if (!d || !dw) return CONV_EINVAL;
+  if (!(beta == 0.f || beta == 1.f)) return CONV_EINVAL;
+  const bool empty = d->p.n == 0;  // the gradient sum is empty: dw = beta*dw
+  if (!empty && (!x || !dy)) return CONV_EINVAL;
+  if (!empty && d->wg_ws > 0 && (!ws || ws_bytes < d->wg_ws)) return CONV_EWORKSPACE;
+  WgradArgs a = d->wg;
+  a.dy = dy;
+  a.x = x;
+  a.part = static_cast<float*>(ws);
+  int e = empty ? 0 : launch_wgrad(d->wg_tile, a, hip_stream);
+  if (e) return record_hip_error(e);
+  ReduceArgs r = {};
+  r.part = a.part;
+  r.dst = dw;
+  r.count = (int32_t)((int64_t)d->p.num_output * d->wg.Kred);
+  r.S = empty ? 0 : a.S;
+  r.beta = beta;
+  r.bias = extras.bias;
+  r.chan_elems = extras.chan_elems;
+  r.channels = extras.channels;
+  r.mChanElems = make_magic(r.chan_elems);
+  r.mChannels = make_magic(r.channels);
+  r.relu = extras.relu;
+  e = launch_reduce(r, hip_stream);
+  return e ? record_hip_error(e) : CONV_OK;
+}
+
+}  // namespace mi355conv
 
 extern "C" {
 
@@ -465,97 +583,17 @@ const char* conv_desc_kernel_names(const conv_desc_t* d) { return d ? d->names :
 
 int conv_forward(const conv_desc_t* d, const float* x, const float* w, const float* bias, float* y, void* ws,
                  size_t ws_bytes, void* hip_stream) {
-  if (!d || !w) return CONV_EINVAL;
-  if ((d->p.bias_term != 0) != (bias != nullptr)) return CONV_EINVAL;
-  if (d->p.n == 0) return CONV_OK;  // empty blobs: nothing to read or write
-  if (!x || !y) return CONV_EINVAL;
-  if (d->fwd_ws > 0 && (!ws || ws_bytes < d->fwd_ws)) return CONV_EWORKSPACE;
-  PackArgs k = d->fwd_pack;
-  k.w = w;
-  k.A = static_cast<float*>(ws);
-  k.ktab = reinterpret_cast<KTabEntry*>(k.A + (size_t)k.G * k.KP * k.MP);
-  int e = launch_pack(k, hip_stream);
-  if (e) return hip_fail(e);
-  CorrArgs a = d->fwd;
-  a.A = k.A;
-  a.ktab = k.ktab;
-  a.in = x;
-  a.bias = bias;
-  a.out = y;
-  a.part = reinterpret_cast<float*>(static_cast<char*>(ws) + d->fwd_pack_bytes);
-  e = a.use_patch ? launch_corr_patch(d->fwd_tile, a, hip_stream) : launch_corr(d->fwd_tile, a, hip_stream);
-  if (e) return hip_fail(e);
-  if (a.ksplit > 1) {  // add the split partials and the bias
-    ReduceArgs r = {};
-    r.part = a.part;
-    r.dst = y;
-    r.count = a.out_elems;
-    r.S = a.ksplit;
-    r.beta = 0.f;
-    r.bias = bias;
-    r.chan_elems = d->OH * d->OW;
-    r.channels = d->p.num_output;
-    r.mChanElems = make_magic(r.chan_elems);
-    r.mChannels = make_magic(r.channels);
-    e = launch_reduce(r, hip_stream);
-  }
-  return e ? hip_fail(e) : CONV_OK;
+  return run_forward(d, x, w, bias, y, ws, ws_bytes, hip_stream);
 }
 
 int conv_backward_data(const conv_desc_t* d, const float* w, const float* dy, float* dx, void* ws, size_t ws_bytes,
                        void* hip_stream) {
-  if (!d || !w) return CONV_EINVAL;
-  if (d->p.n == 0) return CONV_OK;
-  if (!dy || !dx) return CONV_EINVAL;
-  if (d->bwd_ws > 0 && (!ws || ws_bytes < d->bwd_ws)) return CONV_EWORKSPACE;
-  PackArgs k = d->bwd_pack;
-  k.w = w;
-  k.A = static_cast<float*>(ws);
-  k.ktab = reinterpret_cast<KTabEntry*>(k.A + (size_t)k.G * k.KP * k.MP);
-  int e = launch_pack(k, hip_stream);
-  if (e) return hip_fail(e);
-  CorrArgs a = d->bwd;
-  a.A = k.A;
-  a.ktab = k.ktab;
-  a.in = dy;
-  a.bias = nullptr;
-  a.out = dx;
-  a.part = reinterpret_cast<float*>(static_cast<char*>(ws) + d->bwd_pack_bytes);
-  e = a.use_patch ? launch_corr_patch(d->bwd_tile, a, hip_stream) : launch_corr(d->bwd_tile, a, hip_stream);
-  if (e) return hip_fail(e);
-  if (a.ksplit > 1) {
-    ReduceArgs r = {};
-    r.part = a.part;
-    r.dst = dx;
-    r.count = a.out_elems;
-    r.S = a.ksplit;
-    r.beta = 0.f;
-    e = launch_reduce(r, hip_stream);
-  }
-  return e ? hip_fail(e) : CONV_OK;
+  return run_backward_data(d, w, dy, dx, 0.f, ws, ws_bytes, hip_stream);
 }
 
 int conv_backward_filter(const conv_desc_t* d, const float* x, const float* dy, float* dw, float beta, void* ws,
                          size_t ws_bytes, void* hip_stream) {
-  if (!d || !dw) return CONV_EINVAL;
-  if (!(beta == 0.f || beta == 1.f)) return CONV_EINVAL;
-  const bool empty = d->p.n == 0;  // the gradient sum is empty: dw = beta*dw
-  if (!empty && (!x || !dy)) return CONV_EINVAL;
-  if (!empty && d->wg_ws > 0 && (!ws || ws_bytes < d->wg_ws)) return CONV_EWORKSPACE;
-  WgradArgs a = d->wg;
-  a.dy = dy;
-  a.x = x;
-  a.part = static_cast<float*>(ws);
-  int e = empty ? 0 : launch_wgrad(d->wg_tile, a, hip_stream);
-  if (e) return hip_fail(e);
-  ReduceArgs r = {};
-  r.part = a.part;
-  r.dst = dw;
-  r.count = (int32_t)((int64_t)d->p.num_output * d->wg.Kred);
-  r.S = empty ? 0 : a.S;
-  r.beta = beta;
-  e = launch_reduce(r, hip_stream);
-  return e ? hip_fail(e) : CONV_OK;
+  return run_backward_filter(d, x, dy, dw, beta, ws, ws_bytes, hip_stream, ReduceExtras());
 }
 
 int conv_backward_bias(const conv_desc_t* d, const float* dy, float* db, float beta, void* ws, size_t ws_bytes,
@@ -570,7 +608,7 @@ int conv_backward_bias(const conv_desc_t* d, const float* dy, float* db, float b
   a.dy = dy;
   a.part = static_cast<float*>(ws);
   int e = empty ? 0 : launch_bias_grad(a, hip_stream);
-  if (e) return hip_fail(e);
+  if (e) return record_hip_error(e);
   ReduceArgs r = {};
   r.part = a.part;
   r.dst = db;
@@ -578,7 +616,7 @@ int conv_backward_bias(const conv_desc_t* d, const float* dy, float* db, float b
   r.S = empty ? 0 : a.S;
   r.beta = beta;
   e = launch_reduce(r, hip_stream);
-  return e ? hip_fail(e) : CONV_OK;
+  return e ? record_hip_error(e) : CONV_OK;
 }
 
 const char* conv_status_string(int status) {

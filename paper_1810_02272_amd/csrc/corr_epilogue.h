@@ -22,6 +22,7 @@ __device__ __forceinline__ void corr_epilogue(const CorrArgs& a, float* smem, Ac
   // layout, to its slice of the workspace; a reduce kernel adds the slices and the bias.
   float* const out = a.ksplit > 1 ? a.part + (size_t)split * a.out_elems : a.out;
   const float* const bias = a.ksplit > 1 ? nullptr : a.bias;
+  const bool accumulate = a.accumulate != 0 && a.ksplit <= 1;
   const int t = threadIdx.x, lane = t & 63;
   int4* rowtab = reinterpret_cast<int4*>(smem);
   int4* coltab = rowtab + BM;
@@ -70,8 +71,11 @@ __device__ __forceinline__ void corr_epilogue(const CorrArgs& a, float* smem, Ac
 #pragma unroll
       for (int j = 0; j < NB; ++j) {
         const int hh = rt.y + ct[j].y, ww = rt.z + ct[j].z;
-        if ((uint32_t)hh < (uint32_t)a.OHd && (uint32_t)ww < (uint32_t)a.OWd)
-          out[rt.x + ct[j].x] = acc[i][j][r] + bb;
+        if ((uint32_t)hh < (uint32_t)a.OHd && (uint32_t)ww < (uint32_t)a.OWd) {
+          float* const dst = out + (rt.x + ct[j].x);
+          const float v = acc[i][j][r] + bb;
+          *dst = accumulate ? *dst + v : v;
+        }
       }
     }
 }

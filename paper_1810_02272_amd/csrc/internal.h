@@ -75,6 +75,9 @@ struct CorrArgs {
   int32_t ksplit, chunks_per_split;
   int32_t out_elems;
   float* part;
+  // add to what the output already holds instead of overwriting it (unsplit launches only; a
+  // split launch accumulates in its reduce kernel)
+  int32_t accumulate;
   // patch-staged variant (corr_patch_kernel); use_patch = 0 selects the gather kernel
   int32_t use_patch;
   int32_t Cg_in;       // gathered channels per group (multiple of 8)
@@ -133,6 +136,21 @@ struct ReduceArgs {
   const float* bias;
   int32_t chan_elems, channels;
   Magic mChanElems, mChannels;
+  int32_t relu;  // clamp the finished value at zero from below
+};
+
+// Element-wise and column-sum helpers of the InnerProduct layer.
+struct ReluBwdArgs {
+  const float* y;   // [count] output of the forward pass
+  const float* dy;  // [count]
+  float* dz;        // [count] = y > 0 ? dy : 0   (may alias dy)
+  int32_t count;
+};
+
+struct ColSumArgs {
+  const float* src;  // [rows][cols]
+  float* part;       // [S][cols]
+  int32_t rows, cols, S, rows_per_split;
 };
 
 struct BiasGradArgs {
@@ -179,6 +197,25 @@ int launch_corr_patch(int32_t tile, const CorrArgs& a, void* stream);
 int launch_wgrad(int32_t tile, const WgradArgs& a, void* stream);
 int launch_reduce(const ReduceArgs& a, void* stream);
 int launch_bias_grad(const BiasGradArgs& a, void* stream);
+int launch_relu_bwd(const ReluBwdArgs& a, void* stream);
+int launch_colsum(const ColSumArgs& a, void* stream);
+
+// What the reduce kernel of a pass adds on top of the plain sum (all optional).
+struct ReduceExtras {
+  const float* bias = nullptr;  // bias[(i / chan_elems) % channels]
+  int32_t chan_elems = 1, channels = 1;
+  int32_t relu = 0;
+};
+
+// The passes behind the C entry points, with the extra knobs the InnerProduct layer needs
+// (it runs as the same three contractions with the operand roles exchanged).
+int run_forward(const conv_desc* d, const float* x, const float* w, const float* bias, float* y, void* ws,
+                size_t ws_bytes, void* stream);
+int run_backward_data(const conv_desc* d, const float* w, const float* dy, float* dx, float beta, void* ws,
+                      size_t ws_bytes, void* stream);
+int run_backward_filter(const conv_desc* d, const float* x, const float* dy, float* dw, float beta, void* ws,
+                        size_t ws_bytes, void* stream, const ReduceExtras& extras);
+int record_hip_error(int e);  // remembers e for conv_last_hip_error and returns CONV_EHIP
 
 }  // namespace mi355conv
 

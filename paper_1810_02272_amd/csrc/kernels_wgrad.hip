@@ -304,7 +304,9 @@ __global__ __launch_bounds__(256) void reduce_kernel(const ReduceArgs a) {
       const uint32_t c = mdiv((uint32_t)i, a.mChanElems);
       s += a.bias[c - mdiv(c, a.mChannels) * a.channels];
     }
-    a.dst[i] = (a.beta == 0.f) ? s : a.beta * a.dst[i] + s;
+    if (a.beta != 0.f) s += a.beta * a.dst[i];
+    if (a.relu) s = s > 0.f ? s : 0.f;
+    a.dst[i] = s;
   }
 }
 

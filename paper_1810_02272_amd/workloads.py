@@ -122,3 +122,54 @@ def random_inputs(x_shape, w_shape, y_shape, seed: int, bias: bool = True):
     b = draw((w_shape[0],), "uniform_pm", seed + 2, 1.0) if bias else None
     dy = draw(y_shape, "normal", seed + 3)
     return x, w, b, dy
+
+
+# ---- InnerProduct layers that follow the convolution stacks above ----
+# The fully connected layers of the network shape behind configuration 4 (256x6x6 = 9216 inputs ->
+# 4096 -> 4096 -> 1000, ReLU after the first two) at its batch of 128, and of the small digit
+# network behind configurations 0/1 (50x4x4 = 800 -> 500 with ReLU -> 10) at its batch of 64.
+@dataclass(frozen=True)
+class IpLayer:
+    name: str
+    m: int           # batch rows
+    k: int           # inputs per row
+    num_output: int
+    relu: int
+
+    @property
+    def flop_per_pass(self) -> int:
+        return 2 * self.m * self.k * self.num_output
+
+    def params_dict(self, bias_term: int = 1) -> dict:
+        return dict(m=self.m, k=self.k, num_output=self.num_output, bias_term=bias_term, relu=self.relu)
+
+
+IP_LAYERS = [
+    IpLayer("ip5.6", 128, 9216, 4096, 1),
+    IpLayer("ip5.7", 128, 4096, 4096, 1),
+    IpLayer("ip5.8", 128, 4096, 1000, 0),
+    IpLayer("ip1.1", 64, 800, 500, 1),
+    IpLayer("ip1.2", 64, 500, 10, 0),
+]
+IP_BY_NAME = {l.name: l for l in IP_LAYERS}
+
+
+def ip_inputs(layer: IpLayer, bias: str = "zero"):
+    """(x, w, b, dy) fp32 CPU tensors: x ~ N(0,1), w ~ N(0, 0.01^2), dy ~ N(0, 0.1^2) as for the
+    convolution layers of configuration 4; bias zero (benchmark) or U[-0.1, 0.1) (parity)."""
+    seed = BASE_SEED + 100000 + 1000 * IP_LAYERS.index(layer)
+    x = draw((layer.m, layer.k), "normal", seed + 0)
+    w = draw((layer.num_output, layer.k), "normal", seed + 1, 0.01)
+    b = (torch.zeros(layer.num_output, dtype=torch.float32) if bias == "zero"
+         else draw((layer.num_output,), "uniform_pm", seed + 2, 0.1))
+    dy = draw((layer.m, layer.num_output), "normal", seed + 3, 0.1)
+    return x, w, b, dy
+
+
+def ip_random_inputs(m: int, k: int, num_output: int, seed: int, bias: bool = True):
+    """Inputs for an arbitrary InnerProduct shape (property tests)."""
+    x = draw((m, k), "normal", seed)
+    w = draw((num_output, k), "normal", seed + 1, 0.1)
+    b = draw((num_output,), "uniform_pm", seed + 2, 1.0) if bias else None
+    dy = draw((m, num_output), "normal", seed + 3)
+    return x, w, b, dy

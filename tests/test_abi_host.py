@@ -92,3 +92,62 @@ def test_binding_refuses_cpu_tensors():
     x = torch.zeros(1, 1, 4, 4)
     with pytest.raises(TypeError):
         conv.conv_forward(d, x, torch.zeros(1, 1, 3, 3), torch.zeros(1), torch.zeros(1, 1, 2, 2))
+
+
+# ---- InnerProduct boundary (include/mi355ip.h) ----
+
+def test_library_exports_every_declared_ip_symbol():
+    header = open(os.path.join(ROOT, "include", "mi355ip.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(ip_[a-z_]+)\s*\(", header))
+    assert {"ip_desc_create", "ip_desc_destroy", "ip_desc_workspace_bytes", "ip_desc_kernel_names", "ip_forward",
+            "ip_relu_backward", "ip_backward_data", "ip_backward_filter", "ip_backward_bias"} <= declared
+    lib = ctypes.CDLL(conv.library_path())
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_ip_descriptors_and_workspace():
+    for m, k, o in [(128, 9216, 4096), (64, 800, 500), (64, 500, 10), (1, 4, 1), (0, 5, 3), (7, 33, 129)]:
+        d = conv.ip_desc_create(conv.IpParams(m, k, o, 1, 1))
+        assert 0 < conv.ip_desc_workspace_bytes(d) < (1 << 30)
+        names = conv.ip_desc_kernel_names(d)
+        assert all(key in names for key in ("fwd=", "bwd_data=", "bwd_filter=", "bwd_bias="))
+        conv.ip_desc_destroy(d)
+        conv.ip_desc_destroy(d)  # idempotent through the binding
+
+
+@pytest.mark.parametrize("bad", [dict(m=-1), dict(k=0), dict(num_output=0), dict(bias_term=2), dict(relu=-1)])
+def test_ip_invalid_parameters_are_rejected(bad):
+    base = dict(m=4, k=8, num_output=3, bias_term=1, relu=0)
+    base.update(bad)
+    with pytest.raises(conv.ConvError) as e:
+        conv.ip_desc_create(conv.IpParams(**base))
+    assert e.value.status == binding.CONV_EINVAL
+
+
+def test_ip_too_large_is_a_shape_error():
+    with pytest.raises(conv.ConvError) as e:
+        conv.ip_desc_create(conv.IpParams(m=1 << 16, k=1 << 15, num_output=8))
+    assert e.value.status == binding.CONV_ESHAPE
+
+
+def test_ip_null_arguments_and_flags():
+    lib = binding._load()
+    conv.ip_desc_create(conv.IpParams(1, 1, 1))  # sets the argtypes
+    d = conv.ip_desc_create(conv.IpParams(4, 8, 3, 1, 1))
+    dn = conv.ip_desc_create(conv.IpParams(4, 8, 3, 0, 0))
+    fake = ctypes.c_void_p(256)  # never dereferenced: every call below must fail before any launch
+    assert lib.ip_desc_create(None, None) == binding.CONV_EINVAL
+    assert lib.ip_forward(None, fake, fake, fake, fake, None, 0, None) == binding.CONV_EINVAL
+    assert lib.ip_forward(d.handle, fake, fake, None, fake, None, 0, None) == binding.CONV_EINVAL      # bias missing
+    assert lib.ip_forward(dn.handle, fake, fake, fake, fake, None, 0, None) == binding.CONV_EINVAL     # bias unexpected
+    assert lib.ip_forward(d.handle, fake, fake, fake, fake, None, 0, None) == binding.CONV_EWORKSPACE
+    assert lib.ip_relu_backward(d.handle, None, fake, fake, None) == binding.CONV_EINVAL               # relu needs y
+    assert lib.ip_backward_data(d.handle, fake, None, fake, None, 0, None) == binding.CONV_EINVAL
+    assert lib.ip_backward_data(d.handle, fake, fake, fake, None, 0, None) == binding.CONV_EWORKSPACE
+    assert lib.ip_backward_filter(d.handle, fake, fake, fake, 0.5, fake, 1 << 20, None) == binding.CONV_EINVAL
+    assert lib.ip_backward_filter(d.handle, fake, fake, fake, 1.0, None, 0, None) == binding.CONV_EWORKSPACE
+    assert lib.ip_backward_bias(dn.handle, fake, fake, 0.0, fake, 1 << 20, None) == binding.CONV_EINVAL
+    assert lib.ip_backward_bias(d.handle, fake, fake, 0.0, None, 0, None) == binding.CONV_EWORKSPACE
+    assert lib.ip_desc_workspace_bytes(None, None) == binding.CONV_EINVAL

@@ -8,6 +8,10 @@ metric is about).  The metric is fwd+bwd GFLOP/s = 3 * (multiply-add FLOPs of on
 counting only algorithmic FLOPs (no credit for tile padding; bias adds and the bias-gradient
 reduction add time but no FLOPs).
 
+``--workload ip5`` / ``ip1`` (or a comma list of ip layer names) times the InnerProduct layers that
+follow those convolution stacks instead: forward (bias + ReLU fused), ReLU backward, backward data,
+backward filter, backward bias; same FLOP rule (2*m*k*num_output per contraction, three of them).
+
 Prints ONE JSON line (rank 0 is the only rank: this benchmark is single-GPU).
 """
 from __future__ import annotations
@@ -27,7 +31,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="config4", help="config0..config4 or a comma list of layer names")
+    ap.add_argument("--workload", default="config4", help="config0..config4, ip5, ip1, or a comma list of layer names (all conv or all ip)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--cpu-sample-images", type=int, default=128)
     ap.add_argument("--cold-cache", action="store_true",
@@ -58,24 +62,37 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
 
+    is_ip = args.workload.startswith("ip")
     if args.workload.startswith("config"):
         cfg = int(args.workload[len("config"):])
         layers = [l for l in workloads.LAYERS if l.config == cfg]
+    elif args.workload in ("ip5", "ip1"):
+        layers = [l for l in workloads.IP_LAYERS if l.name.startswith(args.workload + ".")]
+    elif is_ip:
+        layers = [workloads.IP_BY_NAME[n] for n in args.workload.split(",")]
     else:
         layers = [workloads.BY_NAME[n] for n in args.workload.split(",")]
 
     # ---- set-up (untimed): descriptors, inputs resident in HBM, one shared workspace ----
     state = []
     ws_bytes = 0
-    tensor_keys = ("x", "w", "b", "dy", "y", "dx", "dw", "db")
     for l in layers:
-        d = conv.conv_desc_create(conv.ConvParams(**l.params_dict()))
-        ws_bytes = max(ws_bytes, conv.conv_desc_workspace_bytes(d))
-        x, w, b, dy = workloads.layer_inputs(l, bias="zero")
-        t = dict(layer=l, desc=d, x=x.to(dev), w=w.to(dev), b=b.to(dev), dy=dy.to(dev),
-                 y=torch.empty(l.y_shape, device=dev), dx=torch.empty(l.x_shape, device=dev),
-                 dw=torch.empty(l.w_shape, device=dev), db=torch.empty(l.k, device=dev))
-        sets = [{k: t[k] for k in tensor_keys}]
+        if is_ip:
+            d = conv.ip_desc_create(conv.IpParams(**l.params_dict()))
+            ws_bytes = max(ws_bytes, conv.ip_desc_workspace_bytes(d))
+            x, w, b, dy = workloads.ip_inputs(l, bias="zero")
+            t = dict(layer=l, desc=d, x=x.to(dev), w=w.to(dev), b=b.to(dev), dy=dy.to(dev),
+                     y=torch.empty((l.m, l.num_output), device=dev), dz=torch.empty((l.m, l.num_output), device=dev),
+                     dx=torch.empty((l.m, l.k), device=dev), dw=torch.empty((l.num_output, l.k), device=dev),
+                     db=torch.empty(l.num_output, device=dev))
+        else:
+            d = conv.conv_desc_create(conv.ConvParams(**l.params_dict()))
+            ws_bytes = max(ws_bytes, conv.conv_desc_workspace_bytes(d))
+            x, w, b, dy = workloads.layer_inputs(l, bias="zero")
+            t = dict(layer=l, desc=d, x=x.to(dev), w=w.to(dev), b=b.to(dev), dy=dy.to(dev),
+                     y=torch.empty(l.y_shape, device=dev), dx=torch.empty(l.x_shape, device=dev),
+                     dw=torch.empty(l.w_shape, device=dev), db=torch.empty(l.k, device=dev))
+        sets = [{k: v for k, v in t.items() if isinstance(v, torch.Tensor)}]
         if args.cold_cache:
             set_bytes = sum(v.numel() * 4 for v in sets[0].values())
             while len(sets) * set_bytes < (512 << 20) and len(sets) < 64:
@@ -85,11 +102,25 @@ def main():
     ws = torch.empty(max(ws_bytes // 4, 1), device=dev)
     stream = torch.cuda.current_stream()
 
-    passes = ("fwd", "bwd_data", "bwd_filter", "bwd_bias")
+    passes = ("fwd", "relu_bwd", "bwd_data", "bwd_filter", "bwd_bias") if is_ip else (
+        "fwd", "bwd_data", "bwd_filter", "bwd_bias")
+    flop_passes = ("fwd", "bwd_data", "bwd_filter")
+    kernel_names_of = conv.ip_desc_kernel_names if is_ip else conv.conv_desc_kernel_names
 
     def run_pass(t, name):
         d = t["desc"]
-        if name == "fwd":
+        if is_ip:
+            if name == "fwd":
+                conv.ip_forward(d, t["x"], t["w"], t["b"], t["y"], ws, stream)
+            elif name == "relu_bwd":
+                conv.ip_relu_backward(d, t["y"] if t["layer"].relu else None, t["dy"], t["dz"], stream)
+            elif name == "bwd_data":
+                conv.ip_backward_data(d, t["w"], t["dz"], t["dx"], ws, stream)
+            elif name == "bwd_filter":
+                conv.ip_backward_filter(d, t["x"], t["dz"], t["dw"], 0.0, ws, stream)
+            else:
+                conv.ip_backward_bias(d, t["dz"], t["db"], 0.0, ws, stream)
+        elif name == "fwd":
             conv.conv_forward(d, t["x"], t["w"], t["b"], t["y"], ws, stream)
         elif name == "bwd_data":
             conv.conv_backward_data(d, t["w"], t["dy"], t["dx"], ws, stream)
@@ -161,27 +192,27 @@ def main():
     for t in state:
         l = t["layer"]
         row = {"layer": l.name, "gflop_per_pass": l.flop_per_pass / 1e9,
-               "kernels": conv.conv_desc_kernel_names(t["desc"])}
+               "kernels": kernel_names_of(t["desc"])}
         tot = 0.0
         for name in passes:
             ms = sum(acc[(l.name, name)]) / len(acc[(l.name, name)])
             row[name + "_ms"] = round(ms, 5)
             tot += ms
-            if name != "bwd_bias":
+            if name in flop_passes:
                 row[name + "_tflops"] = round(l.flop_per_pass / ms / 1e9, 2)
-            else:  # one read of dy: the HBM-bound pass
-                row["bwd_bias_GBps"] = round(4.0 * l.n * l.k * l.out_hw * l.out_hw / ms / 1e6, 1)
+            elif name == "bwd_bias":  # one read of dy: the HBM-bound pass
+                row["bwd_bias_GBps"] = round(dy_bytes(l) / ms / 1e6, 1)
         row["fwd_bwd_tflops"] = round(3 * l.flop_per_pass / tot / 1e9, 2)
         row["fwd_bwd_frac_of_fp32_mfma_peak"] = round(3 * l.flop_per_pass / tot / 1e9 / PEAK_FP32_MFMA_TFLOPS, 4)
         per_layer.append(row)
 
     # dominant launch: the (layer, pass) with the largest average duration
     (dl, dp), dms = max(((k, sum(v) / len(v)) for k, v in acc.items()), key=lambda kv: kv[1])
-    dlayer = workloads.BY_NAME[dl]
     dstate = next(t for t in state if t["layer"].name == dl)
-    kernel_names = dict(kv.split("=", 1) for kv in conv.conv_desc_kernel_names(dstate["desc"]).split(";"))
-    if dp == "bwd_bias":
-        bytes_launch = 4 * dlayer.n * dlayer.k * dlayer.out_hw * dlayer.out_hw
+    dlayer = dstate["layer"]
+    kernel_names = dict(kv.split("=", 1) for kv in kernel_names_of(dstate["desc"]).split(";"))
+    if dp in ("bwd_bias", "relu_bwd"):
+        bytes_launch = dy_bytes(dlayer) * (1 if dp == "bwd_bias" else 3)
         achieved = bytes_launch / (dms * 1e-3) / 1e9
         roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                     "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": None}
@@ -200,12 +231,15 @@ def main():
             pass
 
     out = {
-        "metric": "conv fwd+bwd GFLOP/s (forward + backward data + backward filter + backward bias), fp32",
+        "metric": ("inner-product fwd+bwd GFLOP/s (forward + ReLU backward + backward data + backward filter + "
+                   "backward bias), fp32") if is_ip else
+                  "conv fwd+bwd GFLOP/s (forward + backward data + backward filter + backward bias), fp32",
         "value": round(value, 1), "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{args.workload}: layers " + ",".join(l.name for l in layers)
-                               + " (N=%d each), fwd+bwd_data+bwd_filter+bwd_bias, beta=0, bias=0" % layers[0].n,
+                               + " (N=%d each), %s, beta=0, bias=0" % (layers[0].m if is_ip else layers[0].n,
+                                                                       "+".join(passes)),
                    "frac_of_fp32_mfma_peak": round(value / 1e3 / PEAK_FP32_MFMA_TFLOPS, 4),
                    "cache": ("cold: %s tensor sets per layer rotated every step"
                              % "/".join(str(len(t["sets"])) for t in state)) if args.cold_cache
@@ -216,8 +250,42 @@ def main():
     }
 
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(layers, args.cpu_sample_images)
+        out["cpu_baseline"] = cpu_baseline_ip(layers) if is_ip else cpu_baseline(layers, args.cpu_sample_images)
     print(json.dumps(out))
+
+
+def dy_bytes(l):
+    """Bytes of the top gradient blob of a conv or ip layer."""
+    if hasattr(l, "out_hw"):
+        return 4.0 * l.n * l.k * l.out_hw * l.out_hw
+    return 4.0 * l.m * l.num_output
+
+
+def cpu_baseline_ip(layers):
+    """The CPU InnerProduct oracle, as it stands, on the full batch of each layer of the workload."""
+    import numpy as np
+
+    from oracle import inner_product as ipo
+    from paper_1810_02272_amd import workloads
+
+    flop, secs, per_layer = 0.0, 0.0, {}
+    for l in layers:
+        op = ipo.IpOracleParams(**l.params_dict())
+        x, w, b, dy = (t.numpy().astype(np.float64) for t in workloads.ip_inputs(l, bias="zero"))
+        t0 = time.perf_counter()
+        y = ipo.forward(op, x, w, b)
+        dz = ipo.relu_backward(op, y, dy)
+        ipo.backward_data(op, w, dz)
+        ipo.backward_filter(op, x, dz)
+        ipo.backward_bias(op, dz)
+        dt = time.perf_counter() - t0
+        secs += dt
+        flop += 3.0 * l.flop_per_pass
+        per_layer[l.name] = round(3.0 * l.flop_per_pass / dt / 1e9, 3)
+    return {"value": round(flop / secs / 1e9, 3), "unit": "GFLOP/s", "cores": ipo.num_threads(), "kind": "oracle",
+            "per_layer_gflops": per_layer,
+            "sample": f"all rows of each layer, fwd+relu_bwd+bwd_data+bwd_filter+bwd_bias, double-precision loops, "
+                      f"{secs:.1f} s"}
 
 
 def cpu_baseline(layers, n_sample):

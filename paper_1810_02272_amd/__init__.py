@@ -1,4 +1,4 @@
-"""MI355X-native Caffe-semantics convolution and InnerProduct layers (fp32): thin Python binding over libmi355conv.so.
+"""MI355X-native Caffe-semantics convolution and InnerProduct layers and policy-gradient loss kernels (fp32): thin Python binding over libmi355conv.so.
 
 The package holds the HIP sources (``csrc/``), the build step (``build.py``), the ctypes binding
 (``binding.py``: same names as the C entry points, argument marshalling only) and the seeded
@@ -31,4 +31,10 @@ from .ip_binding import (  # noqa: F401
     ip_desc_workspace_bytes,
     ip_forward,
     ip_relu_backward,
+)
+from .pg_binding import (  # noqa: F401
+    pg_discount_rewards,
+    pg_sigmoid_bottom_diff,
+    pg_sigmoid_sample_action,
+    pg_softmax_bottom_diff,
 )

@@ -9,7 +9,7 @@ _ROOT = os.path.dirname(_HERE)
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libmi355conv.so")
 SOURCES = ["api.cpp", "api_ip.cpp", "kernels_corr.hip", "kernels_corr_patch.hip", "kernels_wgrad.hip", "kernels_bias.hip",
-           "kernels_ip.hip"]
+           "kernels_ip.hip", "kernels_pg.hip"]
 HEADERS = ["internal.h", "device_utils.h", "corr_epilogue.h"]
 
 HIPCC_FLAGS = [
@@ -32,7 +32,7 @@ def is_stale() -> bool:
         return True
     t = os.path.getmtime(LIB)
     deps = [os.path.join(CSRC, s) for s in SOURCES + HEADERS] + [
-        os.path.join(_ROOT, "include", h) for h in ("mi355conv.h", "mi355ip.h")]
+        os.path.join(_ROOT, "include", h) for h in ("mi355conv.h", "mi355ip.h", "mi355pg.h")]
     return any(os.path.getmtime(d) > t for d in deps)
 
 

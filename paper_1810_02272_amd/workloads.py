@@ -173,3 +173,30 @@ def ip_random_inputs(m: int, k: int, num_output: int, seed: int, bias: bool = Tr
     b = draw((num_output,), "uniform_pm", seed + 2, 1.0) if bias else None
     dy = draw((m, num_output), "normal", seed + 3)
     return x, w, b, dy
+
+
+# ---- policy-gradient batches (paper Appendix A / B) ----
+def pg_batch(episodes: int, min_len: int, max_len: int, actions: int, seed: int):
+    """A batch of finished episodes stored back to back, shaped like the pole-balancing task the
+    paper describes (Appendix A step 5): a reward of 1 for every step but the last of an episode,
+    0 for the step that ended it; lengths uniform in [min_len, max_len].  Returns fp32/int32 CPU
+    tensors: offsets [episodes+1], reward [steps], aprob [steps] in (0,1), random [steps] in
+    [0,1), logits [steps][actions] ~ N(0, 2^2), action [steps] uniform over the actions."""
+    g = _gen(seed)
+    lengths = torch.randint(min_len, max_len + 1, (episodes,), generator=g, dtype=torch.int64)
+    offsets = torch.zeros(episodes + 1, dtype=torch.int64)
+    offsets[1:] = torch.cumsum(lengths, 0)
+    steps = int(offsets[-1])
+    reward = torch.ones(steps, dtype=torch.float32)
+    ends = offsets[1:][lengths > 0] - 1
+    reward[ends] = 0.0
+    aprob = torch.rand(steps, generator=g, dtype=torch.float32) * 0.98 + 0.01
+    random = torch.rand(steps, generator=g, dtype=torch.float32)
+    logits = torch.randn((steps, actions), generator=g, dtype=torch.float32) * 2.0
+    action = torch.randint(0, actions, (steps,), generator=g, dtype=torch.int32)
+    return offsets.to(torch.int32), reward, aprob, random, logits, action
+
+
+# benchmark batch: 65536 episodes of 8..500 steps (about 16.6 M steps), 6 actions for the Softmax model
+PG_BENCH = (65536, 8, 500, 6)
+PG_SEED = BASE_SEED + 200000

@@ -151,3 +151,27 @@ def test_ip_null_arguments_and_flags():
     assert lib.ip_backward_bias(dn.handle, fake, fake, 0.0, fake, 1 << 20, None) == binding.CONV_EINVAL
     assert lib.ip_backward_bias(d.handle, fake, fake, 0.0, None, 0, None) == binding.CONV_EWORKSPACE
     assert lib.ip_desc_workspace_bytes(None, None) == binding.CONV_EINVAL
+
+
+# ---- policy-gradient boundary (include/mi355pg.h) ----
+
+def test_library_exports_every_declared_pg_symbol_and_checks_arguments():
+    header = open(os.path.join(ROOT, "include", "mi355pg.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(pg_[a-z_]+)\s*\(", header))
+    assert {"pg_sigmoid_sample_action", "pg_discount_rewards", "pg_sigmoid_bottom_diff",
+            "pg_softmax_bottom_diff"} == declared
+    from paper_1810_02272_amd import pg_binding
+    lib = pg_binding._load()
+    for name in declared:
+        assert hasattr(lib, name), name
+    fake = ctypes.c_void_p(256)  # never dereferenced: every call below returns before any launch
+    assert lib.pg_sigmoid_sample_action(fake, fake, fake, -1, None) == binding.CONV_EINVAL
+    assert lib.pg_sigmoid_sample_action(None, fake, fake, 4, None) == binding.CONV_EINVAL
+    assert lib.pg_sigmoid_sample_action(None, None, None, 0, None) == binding.CONV_OK
+    assert lib.pg_discount_rewards(fake, None, 2, 8, 0.9, fake, None) == binding.CONV_EINVAL
+    assert lib.pg_discount_rewards(None, None, 0, 0, 0.9, None, None) == binding.CONV_OK
+    assert lib.pg_sigmoid_bottom_diff(fake, fake, None, None, None, 4, None) == binding.CONV_EINVAL
+    assert lib.pg_softmax_bottom_diff(fake, fake, None, None, fake, 4, 0, None) == binding.CONV_EINVAL
+    assert lib.pg_softmax_bottom_diff(fake, fake, None, None, fake, 1 << 30, 2, None) == binding.CONV_ESHAPE
+    assert lib.pg_softmax_bottom_diff(None, None, None, None, None, 0, 3, None) == binding.CONV_OK

@@ -12,6 +12,9 @@ reduction add time but no FLOPs).
 follow those convolution stacks instead: forward (bias + ReLU fused), ReLU backward, backward data,
 backward filter, backward bias; same FLOP rule (2*m*k*num_output per contraction, three of them).
 
+``--workload pg`` times the policy-gradient loss kernels on a batch of 65536 synthetic episodes
+(HBM-bound: the metric there is algorithmic GB/s).
+
 Prints ONE JSON line (rank 0 is the only rank: this benchmark is single-GPU).
 """
 from __future__ import annotations
@@ -31,7 +34,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="config4", help="config0..config4, ip5, ip1, or a comma list of layer names (all conv or all ip)")
+    ap.add_argument("--workload", default="config4", help="config0..config4, ip5, ip1, pg, or a comma list of layer names (all conv or all ip)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--cpu-sample-images", type=int, default=128)
     ap.add_argument("--cold-cache", action="store_true",
@@ -62,6 +65,8 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
 
+    if args.workload == "pg":
+        return bench_pg(args, torch, conv, workloads, dev)
     is_ip = args.workload.startswith("ip")
     if args.workload.startswith("config"):
         cfg = int(args.workload[len("config"):])
@@ -252,6 +257,94 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline_ip(layers) if is_ip else cpu_baseline(layers, args.cpu_sample_images)
     print(json.dumps(out))
+
+
+def bench_pg(args, torch, lib, workloads, dev):
+    """Policy-gradient loss step (paper Appendix A/B) over one batch of finished episodes: action
+    sampling, discounted rewards, Sigmoid Bottom.diff, Softmax Bottom.diff (+probabilities).
+    Everything is HBM-bound: the metric is algorithmic bytes moved per second."""
+    episodes, lo, hi, actions = workloads.PG_BENCH
+    gamma = 0.99
+    offsets, reward, aprob, random, logits, action = workloads.pg_batch(episodes, lo, hi, actions, workloads.PG_SEED)
+    steps = reward.numel()
+    d = {k: v.to(dev) for k, v in dict(offsets=offsets, reward=reward, aprob=aprob, random=random, logits=logits,
+                                       action=action).items()}
+    out = dict(act=torch.empty(steps, dtype=torch.int32, device=dev), R=torch.empty(steps, device=dev),
+               bd=torch.empty(steps, device=dev), probs=torch.empty((steps, actions), device=dev),
+               sbd=torch.empty((steps, actions), device=dev))
+    stream = torch.cuda.current_stream()
+    # algorithmic bytes per time step: every input read once, every output written once
+    passes = {
+        "sample_action": (lambda: lib.pg_sigmoid_sample_action(d["aprob"], d["random"], out["act"], stream), 12),
+        "discount_rewards": (lambda: lib.pg_discount_rewards(d["reward"], d["offsets"], gamma, out["R"], stream), 8),
+        "sigmoid_bottom_diff": (lambda: lib.pg_sigmoid_bottom_diff(d["aprob"], out["act"], out["R"], None, out["bd"],
+                                                                   stream), 16),
+        "softmax_bottom_diff": (lambda: lib.pg_softmax_bottom_diff(d["logits"], d["action"], out["R"], out["probs"],
+                                                                   out["sbd"], stream), 8 + 12 * actions),
+    }
+
+    def step(events=None):
+        for name, (fn, _) in passes.items():
+            if events is None:
+                fn()
+            else:
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                fn()
+                e1.record(stream)
+                events.append((name, e0, e1))
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(events)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    acc = {}
+    for name, e0, e1 in events:
+        acc.setdefault(name, []).append(e0.elapsed_time(e1))
+    per_pass = {}
+    for name, (_, bps) in passes.items():
+        ms = sum(acc[name]) / len(acc[name])
+        per_pass[name] = {"ms": round(ms, 5), "GBps": round(bps * steps / ms / 1e6, 1), "bytes_per_step": bps}
+    dom = max(per_pass, key=lambda k: per_pass[k]["ms"])
+    bytes_step = sum(b for _, b in passes.values()) * steps
+    value = bytes_step * args.steps / wall / 1e9
+    res = {
+        "metric": "policy-gradient loss step (sample action + discounted rewards + Sigmoid and Softmax Bottom.diff), "
+                  "algorithmic GB/s, fp32",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(wall / args.steps * 1e3, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"pg: {episodes} episodes of {lo}..{hi} steps = {steps} time steps, {actions} actions, "
+                               f"gamma {gamma}", "time_steps_per_s": round(steps * args.steps / wall, 1)},
+        "roofline": {"bound": "hbm", "achieved": per_pass[dom]["GBps"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                     "frac": round(per_pass[dom]["GBps"] / PEAK_HBM_GBS, 4), "traffic": None, "kernel": dom,
+                     "avg_ms": per_pass[dom]["ms"]},
+        "per_pass": per_pass,
+    }
+    if not args.no_cpu_baseline:
+        import numpy as np
+
+        from oracle import policy_gradient as pgo
+        n = min(steps, int(offsets[min(episodes, 8192)]))  # the first 8192 episodes
+        off = offsets[:min(episodes, 8192) + 1].numpy()
+        f64 = lambda t: t[:n].numpy().astype(np.float64)
+        c0 = time.perf_counter()
+        act = pgo.sigmoid_sample_action(f64(aprob), f64(random))
+        R = pgo.discount_rewards(f64(reward), off, gamma)
+        pgo.bottom_diff(pgo.sigmoid_dlogps(f64(aprob), act), R, True)
+        _, dl = pgo.softmax_dlogps(f64(logits), action[:n].numpy())
+        pgo.bottom_diff(dl, R, False)
+        secs = time.perf_counter() - c0
+        res["cpu_baseline"] = {"value": round(sum(b for _, b in passes.values()) * n / secs / 1e9, 3), "unit": "GB/s",
+                               "cores": 1, "kind": "oracle",
+                               "sample": f"first {len(off) - 1} episodes ({n} time steps), same fp32-sized byte count, "
+                                         f"double-precision loops, {secs:.1f} s"}
+    print(json.dumps(res))
 
 
 def dy_bytes(l):

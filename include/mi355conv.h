@@ -99,6 +99,23 @@ int conv_backward_filter(const conv_desc_t* d, const float* x, const float* dy, 
 int conv_backward_bias(const conv_desc_t* d, const float* dy, float* db, float beta,
                        void* ws, size_t ws_bytes, void* hip_stream);
 
+/*
+ * Double base type (the paper builds every layer for a "float or double base type", section after
+ * Table 1).  The same descriptor, semantics, layouts, ownership, execution and error rules as the
+ * fp32 passes above, with every blob in doubles; products and sums are fp64 (fp64 matrix
+ * instructions).  The workspace size differs: use conv_desc_workspace_bytes_f64.  A descriptor
+ * with a blob of 2^29 or more elements has no double path: these functions return CONV_ESHAPE.
+ */
+int conv_desc_workspace_bytes_f64(const conv_desc_t* d, size_t* bytes);
+int conv_forward_f64(const conv_desc_t* d, const double* x, const double* w, const double* bias, double* y, void* ws,
+                     size_t ws_bytes, void* hip_stream);
+int conv_backward_data_f64(const conv_desc_t* d, const double* w, const double* dy, double* dx, void* ws,
+                           size_t ws_bytes, void* hip_stream);
+int conv_backward_filter_f64(const conv_desc_t* d, const double* x, const double* dy, double* dw, double beta,
+                             void* ws, size_t ws_bytes, void* hip_stream);
+int conv_backward_bias_f64(const conv_desc_t* d, const double* dy, double* db, double beta, void* ws, size_t ws_bytes,
+                           void* hip_stream);
+
 const char* conv_status_string(int status);
 /* hipError_t value of the most recent CONV_EHIP on the calling thread (0 if none). */
 int conv_last_hip_error(void);

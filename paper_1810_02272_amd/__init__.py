@@ -9,6 +9,11 @@ from .binding import (  # noqa: F401
     ConvError,
     ConvParams,
     conv_backward_bias,
+    conv_backward_bias_f64,
+    conv_backward_data_f64,
+    conv_backward_filter_f64,
+    conv_desc_workspace_bytes_f64,
+    conv_forward_f64,
     conv_backward_data,
     conv_backward_filter,
     conv_desc_create,

@@ -70,13 +70,21 @@ def _load():
     lib.conv_backward_data.argtypes = [vp, vp, vp, vp, vp, sz, vp]
     lib.conv_backward_filter.argtypes = [vp, vp, vp, vp, fp, vp, sz, vp]
     lib.conv_backward_bias.argtypes = [vp, vp, vp, fp, vp, sz, vp]
+    dbl = ctypes.c_double
+    lib.conv_desc_workspace_bytes_f64.argtypes = [vp, ctypes.POINTER(sz)]
+    lib.conv_forward_f64.argtypes = [vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.conv_backward_data_f64.argtypes = [vp, vp, vp, vp, vp, sz, vp]
+    lib.conv_backward_filter_f64.argtypes = [vp, vp, vp, vp, dbl, vp, sz, vp]
+    lib.conv_backward_bias_f64.argtypes = [vp, vp, vp, dbl, vp, sz, vp]
     lib.conv_status_string.restype = ctypes.c_char_p
     lib.conv_status_string.argtypes = [ctypes.c_int]
     lib.conv_last_hip_error.restype = ctypes.c_int
     lib.conv_desc_kernel_names.restype = ctypes.c_char_p
     lib.conv_desc_kernel_names.argtypes = [vp]
     for name in ("conv_desc_create", "conv_desc_destroy", "conv_desc_output_shape", "conv_desc_workspace_bytes",
-                 "conv_forward", "conv_backward_data", "conv_backward_filter", "conv_backward_bias"):
+                 "conv_forward", "conv_backward_data", "conv_backward_filter", "conv_backward_bias",
+                 "conv_desc_workspace_bytes_f64", "conv_forward_f64", "conv_backward_data_f64",
+                 "conv_backward_filter_f64", "conv_backward_bias_f64"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
     return lib
@@ -144,13 +152,13 @@ def _w_shape(p):
     return (p.num_output, p.c // p.group, p.kernel_h, p.kernel_w)
 
 
-def _ptr(t, shape, name):
+def _ptr(t, shape, name, dtype=torch.float32):
     if t is None:
         return None
     if not isinstance(t, torch.Tensor) or not t.is_cuda:
         raise TypeError(f"{name}: expected a CUDA/HIP tensor (there is no CPU path)")
-    if t.dtype != torch.float32 or not t.is_contiguous():
-        raise TypeError(f"{name}: expected a contiguous float32 tensor")
+    if t.dtype != dtype or not t.is_contiguous():
+        raise TypeError(f"{name}: expected a contiguous {dtype} tensor")
     if shape is not None and tuple(t.shape) != tuple(shape):
         raise ValueError(f"{name}: expected shape {tuple(shape)}, got {tuple(t.shape)}")
     return t.data_ptr() or None
@@ -200,3 +208,48 @@ def conv_backward_bias(desc, dy, db, beta=0.0, ws=None, stream=None) -> None:
     _check(_load().conv_backward_bias(desc.handle, _ptr(dy, conv_desc_output_shape(desc), "dy"),
                                       _ptr(db, (p.num_output,), "db"), float(beta), wp, wb, _stream(stream)),
            "conv_backward_bias")
+
+
+# ---- double base type: the same calls on float64 tensors ----
+_F64 = torch.float64
+
+
+def conv_desc_workspace_bytes_f64(desc: ConvDesc) -> int:
+    b = ctypes.c_size_t()
+    _check(_load().conv_desc_workspace_bytes_f64(desc.handle, ctypes.byref(b)), "conv_desc_workspace_bytes_f64")
+    return int(b.value)
+
+
+def conv_forward_f64(desc, x, w, bias, y, ws=None, stream=None) -> None:
+    p = desc.params
+    wp, wb = _ws(ws)
+    _check(_load().conv_forward_f64(desc.handle, _ptr(x, _x_shape(p), "x", _F64), _ptr(w, _w_shape(p), "w", _F64),
+                                    _ptr(bias, (p.num_output,), "bias", _F64),
+                                    _ptr(y, conv_desc_output_shape(desc), "y", _F64), wp, wb, _stream(stream)),
+           "conv_forward_f64")
+
+
+def conv_backward_data_f64(desc, w, dy, dx, ws=None, stream=None) -> None:
+    p = desc.params
+    wp, wb = _ws(ws)
+    _check(_load().conv_backward_data_f64(desc.handle, _ptr(w, _w_shape(p), "w", _F64),
+                                          _ptr(dy, conv_desc_output_shape(desc), "dy", _F64),
+                                          _ptr(dx, _x_shape(p), "dx", _F64), wp, wb, _stream(stream)),
+           "conv_backward_data_f64")
+
+
+def conv_backward_filter_f64(desc, x, dy, dw, beta=0.0, ws=None, stream=None) -> None:
+    p = desc.params
+    wp, wb = _ws(ws)
+    _check(_load().conv_backward_filter_f64(desc.handle, _ptr(x, _x_shape(p), "x", _F64),
+                                            _ptr(dy, conv_desc_output_shape(desc), "dy", _F64),
+                                            _ptr(dw, _w_shape(p), "dw", _F64), float(beta), wp, wb, _stream(stream)),
+           "conv_backward_filter_f64")
+
+
+def conv_backward_bias_f64(desc, dy, db, beta=0.0, ws=None, stream=None) -> None:
+    p = desc.params
+    wp, wb = _ws(ws)
+    _check(_load().conv_backward_bias_f64(desc.handle, _ptr(dy, conv_desc_output_shape(desc), "dy", _F64),
+                                          _ptr(db, (p.num_output,), "db", _F64), float(beta), wp, wb,
+                                          _stream(stream)), "conv_backward_bias_f64")

@@ -547,6 +547,63 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
     d->bg_ws = p.bias_term ? (size_t)a.S * K * 4 : 0;
   }
 
+  // ---- double base type: the same geometry on the one fp64 tile, compare-style bounds checks,
+  // no split of the correlation's reduction ----
+  {
+    int32_t bm64, bn64, bk64;
+    f64_tile_shape(&bm64, &bn64, &bk64);
+    const int64_t max64 = (int64_t)1 << 29;  // 32-bit byte offsets of 8-byte elements
+    d->f64_ok = x_elems < max64 && y_elems < max64 && w_elems < max64;
+    auto corr64 = [&](const CorrArgs& src, const PackArgs& psrc, CorrArgs& a, PackArgs& k, int64_t in_elems,
+                      size_t& ws) {
+      a = src;
+      a.in_bytes = (uint32_t)(8 * in_elems);
+      a.bounds_mode = 1;
+      a.KP = (int32_t)round_up(a.Kred, bk64);
+      a.MP = (int32_t)round_up(a.Mrows, bm64);
+      a.m_tiles = a.MP / bm64;
+      a.col_tiles = (int32_t)ceil_div(a.ncols, bn64);
+      a.ksplit = 1;
+      a.chunks_per_split = a.KP / bk64;
+      a.use_patch = 0;
+      a.accumulate = 0;
+      k = psrc;
+      k.KP = a.KP;
+      k.MP = a.MP;
+      k.kperm_T = 0;
+      k.koff_invalid = 0;
+      const int64_t pack_elems = (int64_t)a.G * a.KP * a.MP;
+      if (pack_elems >= max64 || (int64_t)a.G * a.m_tiles * a.col_tiles >= ((int64_t)1 << 31)) d->f64_ok = 0;
+      ws = (size_t)pack_elems * 8 + (size_t)a.KP * sizeof(KTabEntry);
+    };
+    corr64(d->fwd, d->fwd_pack, d->fwd64, d->fwd64_pack, x_elems, d->fwd64_ws);
+    corr64(d->bwd, d->bwd_pack, d->bwd64, d->bwd64_pack, y_elems, d->bwd64_ws);
+    WgradArgs& a = d->wg64;
+    a = d->wg;
+    a.dy_bytes = (uint32_t)(8 * y_elems);
+    a.x_bytes = (uint32_t)(8 * x_elems);
+    a.bounds_mode = 1;
+    a.m_tiles = (int32_t)ceil_div(Kg, bm64);
+    a.n_tiles = (int32_t)ceil_div(kred, bn64);
+    const int64_t tiles = G * a.m_tiles * a.n_tiles;
+    int64_t S = 1024 / tiles;
+    const int64_t max_by_len = ceil_div((int64_t)a.ncols, 4 * bk64);
+    const int64_t max_by_ws = ((int64_t)8 << 20) / (w_elems > 0 ? w_elems : 1);
+    if (S > max_by_len) S = max_by_len;
+    if (S > max_by_ws) S = max_by_ws;
+    if (S > 256) S = 256;
+    if (S < 1) S = 1;
+    a.cols_per_split = (int32_t)round_up(ceil_div((int64_t)a.ncols > 0 ? a.ncols : 1, S), bk64);
+    a.S = (int32_t)ceil_div((int64_t)a.ncols > 0 ? a.ncols : 1, a.cols_per_split);
+    if (a.S * w_elems >= max64 || tiles * a.S >= ((int64_t)1 << 31)) d->f64_ok = 0;
+    d->wg64_ws = (size_t)a.S * (size_t)w_elems * 8;
+    d->bg64_ws = 2 * d->bg_ws;
+    d->ws_bytes64 = d->fwd64_ws;
+    if (d->bwd64_ws > d->ws_bytes64) d->ws_bytes64 = d->bwd64_ws;
+    if (d->wg64_ws > d->ws_bytes64) d->ws_bytes64 = d->wg64_ws;
+    if (d->bg64_ws > d->ws_bytes64) d->ws_bytes64 = d->bg64_ws;
+  }
+
   d->ws_bytes = d->fwd_ws;
   if (d->bwd_ws > d->ws_bytes) d->ws_bytes = d->bwd_ws;
   if (d->wg_ws > d->ws_bytes) d->ws_bytes = d->wg_ws;
@@ -616,6 +673,101 @@ int conv_backward_bias(const conv_desc_t* d, const float* dy, float* db, float b
   r.S = empty ? 0 : a.S;
   r.beta = beta;
   e = launch_reduce(r, hip_stream);
+  return e ? record_hip_error(e) : CONV_OK;
+}
+
+// ---- double base type ----
+
+int conv_desc_workspace_bytes_f64(const conv_desc_t* d, size_t* bytes) {
+  if (!d || !bytes) return CONV_EINVAL;
+  if (!d->f64_ok) return CONV_ESHAPE;
+  *bytes = d->ws_bytes64;
+  return CONV_OK;
+}
+
+static int run_corr64(const conv_desc_t* d, const CorrArgs& args, const PackArgs& pack, size_t need,
+                      const double* w, const double* in, const double* bias, double* out, void* ws,
+                      size_t ws_bytes, void* hip_stream) {
+  if (!d->f64_ok) return CONV_ESHAPE;
+  if (!ws || ws_bytes < need) return CONV_EWORKSPACE;
+  PackArgs k = pack;
+  k.w = reinterpret_cast<const float*>(w);
+  k.A = static_cast<float*>(ws);
+  k.ktab = reinterpret_cast<KTabEntry*>(static_cast<double*>(ws) + (size_t)k.G * k.KP * k.MP);
+  int e = launch_pack(k, hip_stream, true);
+  if (e) return record_hip_error(e);
+  CorrArgs a = args;
+  a.A = k.A;
+  a.ktab = k.ktab;
+  a.in = reinterpret_cast<const float*>(in);
+  a.bias = reinterpret_cast<const float*>(bias);
+  a.out = reinterpret_cast<float*>(out);
+  e = launch_corr64(a, hip_stream);
+  return e ? record_hip_error(e) : CONV_OK;
+}
+
+int conv_forward_f64(const conv_desc_t* d, const double* x, const double* w, const double* bias, double* y, void* ws,
+                     size_t ws_bytes, void* hip_stream) {
+  if (!d || !w) return CONV_EINVAL;
+  if ((d->p.bias_term != 0) != (bias != nullptr)) return CONV_EINVAL;
+  if (d->p.n == 0) return CONV_OK;
+  if (!x || !y) return CONV_EINVAL;
+  return run_corr64(d, d->fwd64, d->fwd64_pack, d->fwd64_ws, w, x, bias, y, ws, ws_bytes, hip_stream);
+}
+
+int conv_backward_data_f64(const conv_desc_t* d, const double* w, const double* dy, double* dx, void* ws,
+                           size_t ws_bytes, void* hip_stream) {
+  if (!d || !w) return CONV_EINVAL;
+  if (d->p.n == 0) return CONV_OK;
+  if (!dy || !dx) return CONV_EINVAL;
+  return run_corr64(d, d->bwd64, d->bwd64_pack, d->bwd64_ws, w, dy, nullptr, dx, ws, ws_bytes, hip_stream);
+}
+
+int conv_backward_filter_f64(const conv_desc_t* d, const double* x, const double* dy, double* dw, double beta,
+                             void* ws, size_t ws_bytes, void* hip_stream) {
+  if (!d || !dw) return CONV_EINVAL;
+  if (!(beta == 0.0 || beta == 1.0)) return CONV_EINVAL;
+  if (!d->f64_ok) return CONV_ESHAPE;
+  const bool empty = d->p.n == 0;
+  if (!empty && (!x || !dy)) return CONV_EINVAL;
+  if (!empty && (!ws || ws_bytes < d->wg64_ws)) return CONV_EWORKSPACE;
+  WgradArgs a = d->wg64;
+  a.dy = reinterpret_cast<const float*>(dy);
+  a.x = reinterpret_cast<const float*>(x);
+  a.part = static_cast<float*>(ws);
+  int e = empty ? 0 : launch_wgrad64(a, hip_stream);
+  if (e) return record_hip_error(e);
+  ReduceArgs r = {};
+  r.part = a.part;
+  r.dst = reinterpret_cast<float*>(dw);
+  r.count = (int32_t)((int64_t)d->p.num_output * d->wg64.Kred);
+  r.S = empty ? 0 : a.S;
+  r.beta = (float)beta;
+  e = launch_reduce64(r, hip_stream);
+  return e ? record_hip_error(e) : CONV_OK;
+}
+
+int conv_backward_bias_f64(const conv_desc_t* d, const double* dy, double* db, double beta, void* ws, size_t ws_bytes,
+                           void* hip_stream) {
+  if (!d || !db) return CONV_EINVAL;
+  if (!d->p.bias_term) return CONV_EINVAL;
+  if (!(beta == 0.0 || beta == 1.0)) return CONV_EINVAL;
+  if (!d->f64_ok) return CONV_ESHAPE;
+  const bool empty = d->p.n == 0;
+  if (!empty && !dy) return CONV_EINVAL;
+  if (!empty && (!ws || ws_bytes < d->bg64_ws)) return CONV_EWORKSPACE;
+  BiasGradArgs a = d->bg;
+  a.dy = reinterpret_cast<const float*>(dy);
+  a.part = static_cast<float*>(ws);
+  int e = empty ? 0 : launch_bias_grad64(a, hip_stream);
+  if (e) return record_hip_error(e);
+  ReduceArgs r = {};
+  r.part = a.part;
+  r.dst = reinterpret_cast<float*>(db);
+  r.count = d->p.num_output;
+  r.S = empty ? 0 : a.S;
+  r.beta = (float)beta;
+  e = launch_reduce64(r, hip_stream);
   return e ? record_hip_error(e) : CONV_OK;
 }
 

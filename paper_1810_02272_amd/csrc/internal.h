@@ -191,12 +191,18 @@ const char* corr_tile_name(int32_t tile);
 const char* wgrad_tile_name(int32_t tile);
 
 // Launchers (defined next to the kernels).  Each returns the hipError_t of the launch as int.
-int launch_pack(const PackArgs& a, void* stream);
+int launch_pack(const PackArgs& a, void* stream, bool f64 = false);
 int launch_corr(int32_t tile, const CorrArgs& a, void* stream);
 int launch_corr_patch(int32_t tile, const CorrArgs& a, void* stream);
 int launch_wgrad(int32_t tile, const WgradArgs& a, void* stream);
 int launch_reduce(const ReduceArgs& a, void* stream);
 int launch_bias_grad(const BiasGradArgs& a, void* stream);
+// double base type: the same argument structs, pointer members addressing doubles
+void f64_tile_shape(int32_t* bm, int32_t* bn, int32_t* bk);
+int launch_corr64(const CorrArgs& a, void* stream);
+int launch_wgrad64(const WgradArgs& a, void* stream);
+int launch_reduce64(const ReduceArgs& a, void* stream);
+int launch_bias_grad64(const BiasGradArgs& a, void* stream);
 int launch_relu_bwd(const ReluBwdArgs& a, void* stream);
 int launch_colsum(const ColSumArgs& a, void* stream);
 
@@ -243,4 +249,11 @@ struct conv_desc {
   size_t bg_ws;
   size_t ws_bytes;
   char names[256];
+  // double base type: one 64x64x16 tile for every pass (f64_ok = 0: a blob of 2^29 or more elements)
+  int32_t f64_ok;
+  mi355conv::CorrArgs fwd64, bwd64;
+  mi355conv::PackArgs fwd64_pack, bwd64_pack;
+  size_t fwd64_ws, bwd64_ws;
+  mi355conv::WgradArgs wg64;
+  size_t wg64_ws, bg64_ws, ws_bytes64;
 };

@@ -297,6 +297,8 @@ __device__ __forceinline__ int source_k(const PackArgs& a, int kp) {
 }
 
 // Forward: A[g][m][k] = w[g*Kg + m][k], zero padded to [MP][KP] (the weight blob's own order).
+// T is the base type of the blob (the pointer members of PackArgs address floats or doubles).
+template <typename T>
 __global__ __launch_bounds__(256) void pack_fwd_kernel(const PackArgs a) {
   const size_t total = (size_t)a.G * a.MP * a.KP;
   const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -305,7 +307,8 @@ __global__ __launch_bounds__(256) void pack_fwd_kernel(const PackArgs a) {
   const int m = (int)((idx / a.KP) % a.MP);
   const int g = (int)(idx / ((size_t)a.MP * a.KP));
   const int kk = source_k(a, kp);
-  a.A[idx] = (m < a.Mrows && kp < a.Kred) ? a.w[((size_t)g * a.Kg + m) * a.Kred + kk] : 0.f;
+  const T* w = reinterpret_cast<const T*>(a.w);
+  reinterpret_cast<T*>(a.A)[idx] = (m < a.Mrows && kp < a.Kred) ? w[((size_t)g * a.Kg + m) * a.Kred + kk] : T(0);
   if (m == 0 && g == 0) fill_ktab(a, kp);
 }
 
@@ -313,6 +316,7 @@ __global__ __launch_bounds__(256) void pack_fwd_kernel(const PackArgs a) {
 // flipped reduced tap).  Phase (rh, rw) of input position h + pad = stride*a + rh is reached by
 // tap i exactly when i*dilation = stride*q + rh for an integer q >= 0; the gather then reads
 // dy at a - q.  Entries with no such tap are zero.
+template <typename T>
 __global__ __launch_bounds__(256) void pack_bwd_kernel(const PackArgs a) {
   const size_t total = (size_t)a.G * a.MP * a.KP;
   const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -321,7 +325,8 @@ __global__ __launch_bounds__(256) void pack_bwd_kernel(const PackArgs a) {
   const int m = (int)((idx / a.KP) % a.MP);
   const int g = (int)(idx / ((size_t)a.MP * a.KP));
   const int kk = source_k(a, kp);
-  float v = 0.f;
+  const T* w = reinterpret_cast<const T*>(a.w);
+  T v = T(0);
   if (m < a.Mrows && kp < a.Kred) {
     const int QQ = a.Qh * a.Qw;
     const int k = kk / QQ, qr = kk % QQ;
@@ -332,10 +337,10 @@ __global__ __launch_bounds__(256) void pack_bwd_kernel(const PackArgs a) {
     const int th = a.sh * qh + rh, tw = a.sw * qw + rw;
     if (th % a.dh == 0 && tw % a.dw == 0) {
       const int i = th / a.dh, j = tw / a.dw;
-      if (i < a.kh && j < a.kw) v = a.w[((((size_t)g * a.Kg + k) * a.Cg + c) * a.kh + i) * a.kw + j];
+      if (i < a.kh && j < a.kw) v = w[((((size_t)g * a.Kg + k) * a.Cg + c) * a.kh + i) * a.kw + j];
     }
   }
-  a.A[idx] = v;
+  reinterpret_cast<T*>(a.A)[idx] = v;
   if (m == 0 && g == 0) fill_ktab(a, kp);
 }
 
@@ -388,14 +393,21 @@ int launch_corr(int32_t tile, const CorrArgs& a, void* stream) {
   }
 }
 
-int launch_pack(const PackArgs& a, void* stream) {
+int launch_pack(const PackArgs& a, void* stream, bool f64) {
   hipStream_t s = (hipStream_t)stream;
   const size_t total = (size_t)a.G * a.KP * a.MP;
   const dim3 grid((uint32_t)((total + 255) / 256));
-  if (a.mode == 0)
-    hipLaunchKernelGGL(pack_fwd_kernel, grid, dim3(256), 0, s, a);
-  else
-    hipLaunchKernelGGL(pack_bwd_kernel, grid, dim3(256), 0, s, a);
+  if (a.mode == 0) {
+    if (f64)
+      hipLaunchKernelGGL(pack_fwd_kernel<double>, grid, dim3(256), 0, s, a);
+    else
+      hipLaunchKernelGGL(pack_fwd_kernel<float>, grid, dim3(256), 0, s, a);
+  } else {
+    if (f64)
+      hipLaunchKernelGGL(pack_bwd_kernel<double>, grid, dim3(256), 0, s, a);
+    else
+      hipLaunchKernelGGL(pack_bwd_kernel<float>, grid, dim3(256), 0, s, a);
+  }
   return (int)hipGetLastError();
 }
 

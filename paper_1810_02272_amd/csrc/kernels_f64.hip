@@ -1,0 +1,374 @@
+// Double-precision base type for the convolution layer (the paper builds every layer for a
+// "float or double base type", section after Table 1): the same four passes on the fp64 matrix
+// instruction v_mfma_f64_16x16x4f64.  One tile shape per kernel, MODE-1 style bounds checks (row
+// and column compares, out-of-image elements read as 0 through the buffer range check), a
+// two-stage LDS ring with a register prefetch.  The argument structs are those of the fp32
+// kernels; their pointer members address doubles here and the byte counts are those of doubles.
+//
+// fp64 MFMA lane layout (one wave computes a 16x16 tile, 4 k values per instruction):
+//   lane l feeds A[l%16][l/16] and B[l/16][l%16]; accumulator register r of lane l holds
+//   D[4*r + l/16][l%16].
+#include <hip/hip_runtime.h>
+
+#include "device_utils.h"
+#include "internal.h"
+
+namespace mi355conv {
+
+namespace {
+
+typedef double f64x2 __attribute__((ext_vector_type(2)));
+typedef double f64x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kThreads = 256;
+constexpr int BM = 64, BN = 64, BK = 16;
+// LDS tiles are [row][k] with rows of 18 doubles: for the 8-byte operand reads (lane -> row l%16,
+// k 4s + l/16) the 16 rows of a quarter wave start on 16 distinct bank pairs, and the next quarter
+// is shifted by one pair.
+constexpr int LDK = BK + 2;
+constexpr int STAGE = (BM + BN) * LDK;  // doubles per stage
+
+__device__ __forceinline__ double buffer_load_f64(__amdgpu_buffer_rsrc_t rsrc, uint32_t off) {
+  return __builtin_bit_cast(double, __builtin_amdgcn_raw_buffer_load_b64(rsrc, off, 0, 0));
+}
+
+__device__ __forceinline__ void mfma64(double a, double b, f64x4& c) {
+  c = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0);
+}
+
+// One chunk (BK k values) of the 64x64 workgroup tile: each wave owns a 32x32 quarter as 2x2
+// MFMA tiles.
+__device__ __forceinline__ void chunk_mfma(const double* sA, const double* sB, f64x4 (&acc)[2][2]) {
+#pragma unroll
+  for (int s = 0; s < BK / 4; ++s) {
+    double av[2], bv[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) av[i] = sA[i * 16 * LDK + 4 * s];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) bv[j] = sB[j * 16 * LDK + 4 * s];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) mfma64(av[i], bv[j], acc[i][j]);
+  }
+}
+
+// D[m][col] = sum_kk A[m][kk] * gather(in)[kk][col]: forward and backward data (see corr_kernel
+// for the fp32 version and the meaning of every CorrArgs field).
+__global__ __launch_bounds__(kThreads) void corr64_kernel(const CorrArgs a) {
+  __shared__ __align__(16) double smem[2 * STAGE];
+  const int t = threadIdx.x, lane = t & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(t >> 6);
+  const int wm = wv >> 1, wn = wv & 1;
+
+  uint32_t lin = xcd_contiguous_block_id();
+  const uint32_t m_tile = lin % (uint32_t)a.m_tiles;
+  lin /= (uint32_t)a.m_tiles;
+  const uint32_t col_tile = lin % (uint32_t)a.col_tiles;
+  const uint32_t g = lin / (uint32_t)a.col_tiles;
+
+  // the column this lane gathers
+  uint32_t cbase = 0;
+  int cih0 = -(1 << 29), ciw0 = 0;
+  {
+    const uint32_t col = col_tile * BN + lane;
+    if (col < (uint32_t)a.ncols) {
+      const uint32_t n = mdiv(col, a.mP);
+      const uint32_t pix = col - n * a.P;
+      const uint32_t pa = mdiv(pix, a.mPW);
+      const uint32_t pb = pix - pa * a.PW;
+      cih0 = (int)pa * a.sh - a.ph;
+      ciw0 = (int)pb * a.sw - a.pw;
+      cbase = 8u * (uint32_t)((int)(n * a.in_img_stride + g * a.in_grp_stride) + cih0 * a.IW + ciw0);
+    }
+  }
+  const double* Ag = reinterpret_cast<const double*>(a.A) + ((size_t)g * a.MP + (size_t)m_tile * BM) * a.KP;
+  const int arow = t >> 2, ak = (t & 3) * 4;
+  const __amdgpu_buffer_rsrc_t in_rsrc =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(a.in), 0, (int)a.in_bytes, 0x00020000);
+
+  f64x4 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) acc[i][j] = f64x4{0., 0., 0., 0.};
+
+  f64x2 ra[2];
+  double rb[4];
+  auto load_chunk = [&](int kc) {
+    const double* src = Ag + (size_t)arow * a.KP + kc * BK + ak;
+    ra[0] = *reinterpret_cast<const f64x2*>(src);
+    ra[1] = *reinterpret_cast<const f64x2*>(src + 2);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const KTabEntry te = a.ktab[kc * BK + wv * 4 + e];  // uniform over the wave: scalar loads
+      const int ih = cih0 + te.idh, iw = ciw0 + te.jdw;
+      const bool ok = ((uint32_t)ih < (uint32_t)a.IH) & ((uint32_t)iw < (uint32_t)a.IW);
+      // the k table holds byte offsets of 4-byte elements
+      rb[e] = buffer_load_f64(in_rsrc, ok ? cbase + 2u * te.koff : a.in_bytes);
+    }
+  };
+  auto store_chunk = [&](int buf) {
+    double* sa = smem + buf * STAGE + arow * LDK + ak;
+    *reinterpret_cast<f64x2*>(sa) = ra[0];
+    *reinterpret_cast<f64x2*>(sa + 2) = ra[1];
+    double* sb = smem + buf * STAGE + BM * LDK + lane * LDK + wv * 4;
+    *reinterpret_cast<f64x2*>(sb) = f64x2{rb[0], rb[1]};
+    *reinterpret_cast<f64x2*>(sb + 2) = f64x2{rb[2], rb[3]};
+  };
+
+  const int nchunks = a.KP / BK;
+  const double* opA = smem + (wm * 32 + (lane & 15)) * LDK + (lane >> 4);
+  const double* opB = smem + BM * LDK + (wn * 32 + (lane & 15)) * LDK + (lane >> 4);
+  load_chunk(0);
+  store_chunk(0);
+  __syncthreads();
+  for (int kc = 0; kc < nchunks; ++kc) {
+    const int cur = kc & 1;
+    if (kc + 1 < nchunks) load_chunk(kc + 1);  // in flight while this chunk is multiplied
+    chunk_mfma(opA + cur * STAGE, opB + cur * STAGE, acc);
+    if (kc + 1 < nchunks) store_chunk(cur ^ 1);
+    __syncthreads();
+  }
+
+  // Epilogue: the same two LDS tables as the fp32 kernel (row -> channel / sub-pixel offset,
+  // column -> image / pixel offset), the bias kept beside them as doubles.
+  int4* rowtab = reinterpret_cast<int4*>(smem);
+  int4* coltab = rowtab + BM;
+  double* rowbias = reinterpret_cast<double*>(coltab + BN);
+  const double* bias = reinterpret_cast<const double*>(a.bias);
+  double* const out = reinterpret_cast<double*>(a.out);
+  if (t < BM) {
+    const uint32_t gm = m_tile * BM + t;
+    int off = 0, hh = -(1 << 28), ww = 0;
+    double bb = 0.;
+    if (gm < (uint32_t)a.Mrows) {
+      const uint32_t c = mdiv(gm, a.mRShw);
+      const uint32_t rem = gm - c * a.RShw;
+      const uint32_t rh = mdiv(rem, a.mRSw);
+      const uint32_t rw = rem - rh * a.RSw;
+      const uint32_t chan = g * a.chan_per_grp + c;
+      hh = (int)rh - a.opad_h;
+      ww = (int)rw - a.opad_w;
+      off = (int)(chan * (uint32_t)(a.OHd * a.OWd)) + hh * a.OWd + ww;
+      if (bias) bb = bias[chan];
+    }
+    rowtab[t] = make_int4(off, hh, ww, 0);
+    rowbias[t] = bb;
+  } else if (t < BM + BN) {
+    const int cl = t - BM;
+    const uint32_t col = col_tile * BN + cl;
+    int off = 0, hh = -(1 << 28), ww = 0;
+    if (col < (uint32_t)a.ncols) {
+      const uint32_t n = mdiv(col, a.mP);
+      const uint32_t pix = col - n * a.P;
+      const uint32_t pa = mdiv(pix, a.mPW);
+      const uint32_t pb = pix - pa * a.PW;
+      hh = (int)pa * a.RSh;
+      ww = (int)pb * a.RSw;
+      off = (int)(n * (uint32_t)a.out_img_stride) + hh * a.OWd + ww;
+    }
+    coltab[cl] = make_int4(off, hh, ww, 0);
+  }
+  __syncthreads();
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int4 ct = coltab[wn * 32 + j * 16 + (lane & 15)];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int m = wm * 32 + i * 16 + 4 * r + (lane >> 4);
+        const int4 rt = rowtab[m];
+        const int hh = rt.y + ct.y, ww = rt.z + ct.z;
+        if ((uint32_t)hh < (uint32_t)a.OHd && (uint32_t)ww < (uint32_t)a.OWd)
+          out[rt.x + ct.x] = acc[i][j][r] + rowbias[m];
+      }
+  }
+}
+
+// Backward filter: part[split][g][k][nn] = sum over the split's columns (n, oh, ow) of
+// dy[n, g*Kg + k, oh, ow] * x[n, g*Cg + c, oh*sh - ph + i*dh, ow*sw - pw + j*dw], nn = (c, i, j).
+// Lanes run along the reduction index (16 columns per chunk), 16 row slots per operand.
+__global__ __launch_bounds__(kThreads) void wgrad64_kernel(const WgradArgs a) {
+  __shared__ __align__(16) double smem[2 * STAGE];
+  const int t = threadIdx.x, lane = t & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(t >> 6);
+  const int wm = wv >> 1, wn = wv & 1;
+  const int kc = t & 15, rslot = t >> 4;
+
+  uint32_t lin = xcd_contiguous_block_id();
+  const uint32_t m_tile = lin % (uint32_t)a.m_tiles;
+  lin /= (uint32_t)a.m_tiles;
+  const uint32_t n_tile = lin % (uint32_t)a.n_tiles;
+  lin /= (uint32_t)a.n_tiles;
+  const uint32_t split = lin % (uint32_t)a.S;
+  const uint32_t g = lin / (uint32_t)a.S;
+
+  // rows this thread loads (rows past the matrix edge are clamped: they feed accumulators that
+  // are never stored)
+  uint32_t aoff[4], boff[4], bij[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    uint32_t m = m_tile * BM + rslot + 16 * e;
+    if (m > (uint32_t)a.Kg - 1) m = (uint32_t)a.Kg - 1;
+    aoff[e] = 8u * m * (uint32_t)a.P;
+    uint32_t nn = n_tile * BN + rslot + 16 * e;
+    if (nn > (uint32_t)a.Kred - 1) nn = (uint32_t)a.Kred - 1;
+    const uint32_t c = mdiv(nn, a.mKHW);
+    const uint32_t rem = nn - c * a.khw;
+    const uint32_t i = mdiv(rem, a.mKW);
+    const uint32_t j = rem - i * a.kw;
+    boff[e] = 8u * ((g * a.Cg + c) * (uint32_t)a.HW + i * a.dh * a.W + j * a.dw);
+    bij[e] = ((i * a.dh) << 16) | (j * a.dw);
+  }
+  const uint32_t c_begin = split * (uint32_t)a.cols_per_split;
+  uint32_t c_end = c_begin + (uint32_t)a.cols_per_split;
+  if (c_end > (uint32_t)a.ncols) c_end = (uint32_t)a.ncols;
+  const int nchunks = c_begin < c_end ? (int)((c_end - c_begin + BK - 1) / BK) : 0;
+
+  const __amdgpu_buffer_rsrc_t dy_rsrc =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(a.dy), 0, (int)a.dy_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t x_rsrc =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(a.x), 0, (int)a.x_bytes, 0x00020000);
+
+  f64x4 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) acc[i][j] = f64x4{0., 0., 0., 0.};
+
+  double ra[4], rb[4];
+  auto load_chunk = [&](int chunk) {
+    const uint32_t col = c_begin + chunk * BK + kc;
+    const bool colok = col < c_end;
+    const uint32_t n = mdiv(col, a.mP);
+    const uint32_t pix = col - n * a.P;
+    const uint32_t oh = mdiv(pix, a.mPW);
+    const uint32_t ow = pix - oh * a.PW;
+    const int ih0 = (int)oh * a.sh - a.ph;
+    const int iw0 = (int)ow * a.sw - a.pw;
+    const uint32_t dybase = 8u * ((n * a.Ktot + g * a.Kg) * (uint32_t)a.P + pix);
+    const uint32_t xbase = 8u * (uint32_t)((int)(n * (uint32_t)(a.C * a.HW)) + ih0 * a.W + iw0);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      ra[e] = buffer_load_f64(dy_rsrc, colok ? dybase + aoff[e] : a.dy_bytes);
+      const int ih = ih0 + (int)(bij[e] >> 16), iw = iw0 + (int)(bij[e] & 0xffffu);
+      const bool ok = colok & ((uint32_t)ih < (uint32_t)a.H) & ((uint32_t)iw < (uint32_t)a.W);
+      rb[e] = buffer_load_f64(x_rsrc, ok ? xbase + boff[e] : a.x_bytes);
+    }
+  };
+  auto store_chunk = [&](int buf) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      smem[buf * STAGE + (rslot + 16 * e) * LDK + kc] = ra[e];
+      smem[buf * STAGE + BM * LDK + (rslot + 16 * e) * LDK + kc] = rb[e];
+    }
+  };
+
+  const double* opA = smem + (wm * 32 + (lane & 15)) * LDK + (lane >> 4);
+  const double* opB = smem + BM * LDK + (wn * 32 + (lane & 15)) * LDK + (lane >> 4);
+  if (nchunks > 0) {
+    load_chunk(0);
+    store_chunk(0);
+  }
+  __syncthreads();
+  for (int ch = 0; ch < nchunks; ++ch) {
+    const int cur = ch & 1;
+    if (ch + 1 < nchunks) load_chunk(ch + 1);
+    chunk_mfma(opA + cur * STAGE, opB + cur * STAGE, acc);
+    if (ch + 1 < nchunks) store_chunk(cur ^ 1);
+    __syncthreads();
+  }
+
+  double* dst = reinterpret_cast<double*>(a.part) + ((size_t)split * a.G + g) * ((size_t)a.Kg * a.Kred);
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const uint32_t nn = n_tile * BN + wn * 32 + j * 16 + (lane & 15);
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const uint32_t k = m_tile * BM + wm * 32 + i * 16 + 4 * r + (lane >> 4);
+        if (k < (uint32_t)a.Kg && nn < (uint32_t)a.Kred) dst[(size_t)k * a.Kred + nn] = acc[i][j][r];
+      }
+  }
+}
+
+// dst = beta*dst + sum_s part[s] (+ bias), in a fixed order: one thread per element.
+__global__ __launch_bounds__(256) void reduce64_kernel(const ReduceArgs a) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= a.count) return;
+  const double* src = reinterpret_cast<const double*>(a.part) + i;
+  double* dst = reinterpret_cast<double*>(a.dst);
+  double acc0 = 0., acc1 = 0.;
+  int s = 0;
+  for (; s + 1 < a.S; s += 2) {
+    acc0 += src[(size_t)s * a.count];
+    acc1 += src[(size_t)(s + 1) * a.count];
+  }
+  if (s < a.S) acc0 += src[(size_t)s * a.count];
+  double v = acc0 + acc1;
+  if (a.beta != 0.f) v += (double)a.beta * dst[i];
+  dst[i] = v;
+}
+
+// part[s][k] = sum of dy[n][k][:] over the images of split s: one wave per image at a time.
+__global__ __launch_bounds__(256) void bias_grad64_kernel(const BiasGradArgs a) {
+  __shared__ double wsum[4];
+  const int k = blockIdx.x, s = blockIdx.y;
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const int n0 = s * a.n_per_split;
+  int n1 = n0 + a.n_per_split;
+  if (n1 > a.N) n1 = a.N;
+  const double* dy = reinterpret_cast<const double*>(a.dy);
+  double acc0 = 0., acc1 = 0.;
+  for (int n = n0 + wv; n < n1; n += 4) {
+    const double* src = dy + ((size_t)n * a.K + k) * a.P;
+    int p = lane;
+    for (; p + 64 < a.P; p += 128) {
+      acc0 += src[p];
+      acc1 += src[p + 64];
+    }
+    for (; p < a.P; p += 64) acc0 += src[p];
+  }
+  double v = acc0 + acc1;
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
+  if (lane == 0) wsum[wv] = v;
+  __syncthreads();
+  if (threadIdx.x == 0)
+    reinterpret_cast<double*>(a.part)[(size_t)s * a.K + k] = (wsum[0] + wsum[1]) + (wsum[2] + wsum[3]);
+}
+
+}  // namespace
+
+void f64_tile_shape(int32_t* bm, int32_t* bn, int32_t* bk) {
+  *bm = BM;
+  *bn = BN;
+  *bk = BK;
+}
+
+int launch_corr64(const CorrArgs& a, void* stream) {
+  const uint32_t blocks = (uint32_t)a.G * a.m_tiles * a.col_tiles;
+  hipLaunchKernelGGL(corr64_kernel, dim3(blocks), dim3(kThreads), 0, (hipStream_t)stream, a);
+  return (int)hipGetLastError();
+}
+
+int launch_wgrad64(const WgradArgs& a, void* stream) {
+  const uint32_t blocks = (uint32_t)a.G * a.S * a.m_tiles * a.n_tiles;
+  hipLaunchKernelGGL(wgrad64_kernel, dim3(blocks), dim3(kThreads), 0, (hipStream_t)stream, a);
+  return (int)hipGetLastError();
+}
+
+int launch_reduce64(const ReduceArgs& a, void* stream) {
+  hipLaunchKernelGGL(reduce64_kernel, dim3((a.count + 255) / 256), dim3(256), 0, (hipStream_t)stream, a);
+  return (int)hipGetLastError();
+}
+
+int launch_bias_grad64(const BiasGradArgs& a, void* stream) {
+  hipLaunchKernelGGL(bias_grad64_kernel, dim3(a.K, a.S), dim3(256), 0, (hipStream_t)stream, a);
+  return (int)hipGetLastError();
+}
+
+}  // namespace mi355conv

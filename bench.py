@@ -26,6 +26,7 @@ import sys
 import time
 
 PEAK_FP32_MFMA_TFLOPS = 157.3  # MI355X published dense fp32 matrix peak
+PEAK_FP64_MFMA_TFLOPS = 78.6   # ... and fp64
 PEAK_HBM_GBS = 8000.0
 
 
@@ -35,6 +36,8 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="config4", help="config0..config4, ip5, ip1, pg, or a comma list of layer names (all conv or all ip)")
+    ap.add_argument("--dtype", default="f32", choices=["f32", "f64"],
+                    help="base type of the convolution workloads (f64: the conv_*_f64 entry points)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--cpu-sample-images", type=int, default=128)
     ap.add_argument("--cold-cache", action="store_true",
@@ -68,6 +71,12 @@ def main():
     if args.workload == "pg":
         return bench_pg(args, torch, conv, workloads, dev)
     is_ip = args.workload.startswith("ip")
+    f64 = args.dtype == "f64"
+    if f64 and is_ip:
+        print("--dtype f64 applies to the convolution workloads only", file=sys.stderr)
+        sys.exit(2)
+    tdt = torch.float64 if f64 else torch.float32
+    peak = PEAK_FP64_MFMA_TFLOPS if f64 else PEAK_FP32_MFMA_TFLOPS
     if args.workload.startswith("config"):
         cfg = int(args.workload[len("config"):])
         layers = [l for l in workloads.LAYERS if l.config == cfg]
@@ -92,14 +101,15 @@ def main():
                      db=torch.empty(l.num_output, device=dev))
         else:
             d = conv.conv_desc_create(conv.ConvParams(**l.params_dict()))
-            ws_bytes = max(ws_bytes, conv.conv_desc_workspace_bytes(d))
-            x, w, b, dy = workloads.layer_inputs(l, bias="zero")
+            ws_bytes = max(ws_bytes, conv.conv_desc_workspace_bytes_f64(d) if f64 else
+                           conv.conv_desc_workspace_bytes(d))
+            x, w, b, dy = (v.to(tdt) for v in workloads.layer_inputs(l, bias="zero"))
             t = dict(layer=l, desc=d, x=x.to(dev), w=w.to(dev), b=b.to(dev), dy=dy.to(dev),
-                     y=torch.empty(l.y_shape, device=dev), dx=torch.empty(l.x_shape, device=dev),
-                     dw=torch.empty(l.w_shape, device=dev), db=torch.empty(l.k, device=dev))
+                     y=torch.empty(l.y_shape, device=dev, dtype=tdt), dx=torch.empty(l.x_shape, device=dev, dtype=tdt),
+                     dw=torch.empty(l.w_shape, device=dev, dtype=tdt), db=torch.empty(l.k, device=dev, dtype=tdt))
         sets = [{k: v for k, v in t.items() if isinstance(v, torch.Tensor)}]
         if args.cold_cache:
-            set_bytes = sum(v.numel() * 4 for v in sets[0].values())
+            set_bytes = sum(v.numel() * v.element_size() for v in sets[0].values())
             while len(sets) * set_bytes < (512 << 20) and len(sets) < 64:
                 sets.append({k: v.clone() for k, v in sets[0].items()})
         t["sets"] = sets
@@ -125,6 +135,15 @@ def main():
                 conv.ip_backward_filter(d, t["x"], t["dz"], t["dw"], 0.0, ws, stream)
             else:
                 conv.ip_backward_bias(d, t["dz"], t["db"], 0.0, ws, stream)
+        elif f64:
+            if name == "fwd":
+                conv.conv_forward_f64(d, t["x"], t["w"], t["b"], t["y"], ws, stream)
+            elif name == "bwd_data":
+                conv.conv_backward_data_f64(d, t["w"], t["dy"], t["dx"], ws, stream)
+            elif name == "bwd_filter":
+                conv.conv_backward_filter_f64(d, t["x"], t["dy"], t["dw"], 0.0, ws, stream)
+            else:
+                conv.conv_backward_bias_f64(d, t["dy"], t["db"], 0.0, ws, stream)
         elif name == "fwd":
             conv.conv_forward(d, t["x"], t["w"], t["b"], t["y"], ws, stream)
         elif name == "bwd_data":
@@ -206,9 +225,10 @@ def main():
             if name in flop_passes:
                 row[name + "_tflops"] = round(l.flop_per_pass / ms / 1e9, 2)
             elif name == "bwd_bias":  # one read of dy: the HBM-bound pass
-                row["bwd_bias_GBps"] = round(dy_bytes(l) / ms / 1e6, 1)
+                row["bwd_bias_GBps"] = round(dy_bytes(l) * (2 if f64 else 1) / ms / 1e6, 1)
         row["fwd_bwd_tflops"] = round(3 * l.flop_per_pass / tot / 1e9, 2)
-        row["fwd_bwd_frac_of_fp32_mfma_peak"] = round(3 * l.flop_per_pass / tot / 1e9 / PEAK_FP32_MFMA_TFLOPS, 4)
+        row["fwd_bwd_frac_of_%s_mfma_peak" % ("fp64" if f64 else "fp32")] = round(
+            3 * l.flop_per_pass / tot / 1e9 / peak, 4)
         per_layer.append(row)
 
     # dominant launch: the (layer, pass) with the largest average duration
@@ -217,18 +237,21 @@ def main():
     dlayer = dstate["layer"]
     kernel_names = dict(kv.split("=", 1) for kv in kernel_names_of(dstate["desc"]).split(";"))
     if dp in ("bwd_bias", "relu_bwd"):
-        bytes_launch = dy_bytes(dlayer) * (1 if dp == "bwd_bias" else 3)
+        bytes_launch = dy_bytes(dlayer) * (1 if dp == "bwd_bias" else 3) * (2 if f64 else 1)
         achieved = bytes_launch / (dms * 1e-3) / 1e9
         roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                     "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": None}
     else:
         achieved = dlayer.flop_per_pass / (dms * 1e-3) / 1e12
-        roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_FP32_MFMA_TFLOPS,
-                    "unit": "TFLOP/s", "frac": round(achieved / PEAK_FP32_MFMA_TFLOPS, 4), "traffic": None}
+        roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": peak,
+                    "unit": "TFLOP/s", "frac": round(achieved / peak, 4), "traffic": None}
+    if f64:  # the double path has one tile shape per kernel
+        kernel_names = {"fwd": "corr64_64x64x16", "bwd_data": "corr64_64x64x16", "bwd_filter": "wgrad64_64x64x16",
+                        "bwd_bias": "bias_grad64"}
     roofline.update({"kernel": kernel_names.get(dp, dp), "layer": dl, "pass": dp, "avg_ms": round(dms, 5),
                      "algorithmic_gflop_per_launch": dlayer.flop_per_pass / 1e9})
     traffic_file = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "hbm_traffic.json")
-    if os.path.exists(traffic_file):  # measured separately with rocprofv3 --pmc (see profiles/)
+    if os.path.exists(traffic_file) and not f64 and not is_ip:  # measured separately with rocprofv3 --pmc (see profiles/)
         try:
             tr = json.load(open(traffic_file))
             roofline["traffic"] = tr.get(f"{dl}:{dp}")
@@ -238,14 +261,15 @@ def main():
     out = {
         "metric": ("inner-product fwd+bwd GFLOP/s (forward + ReLU backward + backward data + backward filter + "
                    "backward bias), fp32") if is_ip else
-                  "conv fwd+bwd GFLOP/s (forward + backward data + backward filter + backward bias), fp32",
+                  "conv fwd+bwd GFLOP/s (forward + backward data + backward filter + backward bias), "
+                  + ("fp64" if f64 else "fp32"),
         "value": round(value, 1), "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
+        "dtype": args.dtype, "data": "synthetic",
         "config": {"workload": f"{args.workload}: layers " + ",".join(l.name for l in layers)
                                + " (N=%d each), %s, beta=0, bias=0" % (layers[0].m if is_ip else layers[0].n,
                                                                        "+".join(passes)),
-                   "frac_of_fp32_mfma_peak": round(value / 1e3 / PEAK_FP32_MFMA_TFLOPS, 4),
+                   "frac_of_%s_mfma_peak" % ("fp64" if f64 else "fp32"): round(value / 1e3 / peak, 4),
                    "cache": ("cold: %s tensor sets per layer rotated every step"
                              % "/".join(str(len(t["sets"])) for t in state)) if args.cold_cache
                             else "warm: the same tensors every step",

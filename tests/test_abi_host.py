@@ -17,9 +17,10 @@ GOLDEN = os.path.join(ROOT, "tests", "golden")
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "mi355conv.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = set(re.findall(r"\b(conv_[a-z_]+)\s*\(", header))
+    declared = set(re.findall(r"\b(conv_[a-z0-9_]+)\s*\(", header))
     assert {"conv_desc_create", "conv_forward", "conv_backward_data", "conv_backward_filter",
-            "conv_backward_bias"} <= declared
+            "conv_backward_bias", "conv_desc_workspace_bytes_f64", "conv_forward_f64", "conv_backward_data_f64",
+            "conv_backward_filter_f64", "conv_backward_bias_f64"} <= declared
     lib = ctypes.CDLL(conv.library_path())
     for name in declared:
         assert hasattr(lib, name), name
@@ -175,3 +176,27 @@ def test_library_exports_every_declared_pg_symbol_and_checks_arguments():
     assert lib.pg_softmax_bottom_diff(fake, fake, None, None, fake, 4, 0, None) == binding.CONV_EINVAL
     assert lib.pg_softmax_bottom_diff(fake, fake, None, None, fake, 1 << 30, 2, None) == binding.CONV_ESHAPE
     assert lib.pg_softmax_bottom_diff(None, None, None, None, None, 0, 3, None) == binding.CONV_OK
+
+
+def test_f64_entry_points_check_arguments():
+    lib = binding._load()
+    d = conv.conv_desc_create(conv.ConvParams(2, 4, 8, 8, 4, 3, 3))
+    dn = conv.conv_desc_create(conv.ConvParams(2, 4, 8, 8, 4, 3, 3, bias_term=0))
+    assert conv.conv_desc_workspace_bytes_f64(d) > 0
+    fake = ctypes.c_void_p(256)  # never dereferenced: every call below fails before any launch
+    assert lib.conv_forward_f64(None, fake, fake, fake, fake, None, 0, None) == binding.CONV_EINVAL
+    assert lib.conv_forward_f64(d.handle, fake, fake, None, fake, None, 0, None) == binding.CONV_EINVAL
+    assert lib.conv_forward_f64(dn.handle, fake, fake, fake, fake, None, 0, None) == binding.CONV_EINVAL
+    assert lib.conv_forward_f64(d.handle, fake, fake, fake, fake, None, 0, None) == binding.CONV_EWORKSPACE
+    assert lib.conv_backward_data_f64(d.handle, fake, None, fake, None, 0, None) == binding.CONV_EINVAL
+    assert lib.conv_backward_data_f64(d.handle, fake, fake, fake, fake, 8, None) == binding.CONV_EWORKSPACE
+    assert lib.conv_backward_filter_f64(d.handle, fake, fake, fake, 0.5, fake, 1 << 20, None) == binding.CONV_EINVAL
+    assert lib.conv_backward_filter_f64(d.handle, fake, fake, fake, 1.0, None, 0, None) == binding.CONV_EWORKSPACE
+    assert lib.conv_backward_bias_f64(dn.handle, fake, fake, 0.0, fake, 1 << 20, None) == binding.CONV_EINVAL
+    assert lib.conv_backward_bias_f64(d.handle, fake, fake, 0.0, None, 0, None) == binding.CONV_EWORKSPACE
+    # a blob of 2^29 elements or more has no double path
+    big = conv.conv_desc_create(conv.ConvParams(1 << 10, 1 << 9, 32, 32, 1, 1, 1))
+    with pytest.raises(conv.ConvError) as e:
+        conv.conv_desc_workspace_bytes_f64(big)
+    assert e.value.status == binding.CONV_ESHAPE
+    assert lib.conv_forward_f64(big.handle, fake, fake, fake, fake, fake, 1 << 40, None) == binding.CONV_ESHAPE

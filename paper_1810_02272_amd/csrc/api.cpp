@@ -550,13 +550,13 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
   // ---- double base type: the same geometry on the one fp64 tile, compare-style bounds checks,
   // no split of the correlation's reduction ----
   {
-    int32_t bm64, bn64, bk64;
-    f64_tile_shape(&bm64, &bn64, &bk64);
+    const int32_t bn64 = kF64TileCols, bk64 = kF64TileK;
     const int64_t max64 = (int64_t)1 << 29;  // 32-bit byte offsets of 8-byte elements
     d->f64_ok = x_elems < max64 && y_elems < max64 && w_elems < max64;
     auto corr64 = [&](const CorrArgs& src, const PackArgs& psrc, CorrArgs& a, PackArgs& k, int64_t in_elems,
-                      size_t& ws) {
+                      size_t& ws, int32_t& tile_rows) {
       a = src;
+      const int32_t bm64 = tile_rows = f64_pick_rows(src.Mrows, false);
       a.in_bytes = (uint32_t)(8 * in_elems);
       a.bounds_mode = 1;
       a.KP = (int32_t)round_up(a.Kred, bk64);
@@ -576,8 +576,9 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
       if (pack_elems >= max64 || (int64_t)a.G * a.m_tiles * a.col_tiles >= ((int64_t)1 << 31)) d->f64_ok = 0;
       ws = (size_t)pack_elems * 8 + (size_t)a.KP * sizeof(KTabEntry);
     };
-    corr64(d->fwd, d->fwd_pack, d->fwd64, d->fwd64_pack, x_elems, d->fwd64_ws);
-    corr64(d->bwd, d->bwd_pack, d->bwd64, d->bwd64_pack, y_elems, d->bwd64_ws);
+    corr64(d->fwd, d->fwd_pack, d->fwd64, d->fwd64_pack, x_elems, d->fwd64_ws, d->fwd64_rows);
+    corr64(d->bwd, d->bwd_pack, d->bwd64, d->bwd64_pack, y_elems, d->bwd64_ws, d->bwd64_rows);
+    const int32_t bm64 = d->wg64_rows = f64_pick_rows(Kg, true);
     WgradArgs& a = d->wg64;
     a = d->wg;
     a.dy_bytes = (uint32_t)(8 * y_elems);
@@ -685,7 +686,7 @@ int conv_desc_workspace_bytes_f64(const conv_desc_t* d, size_t* bytes) {
   return CONV_OK;
 }
 
-static int run_corr64(const conv_desc_t* d, const CorrArgs& args, const PackArgs& pack, size_t need,
+static int run_corr64(const conv_desc_t* d, int32_t tile_rows, const CorrArgs& args, const PackArgs& pack, size_t need,
                       const double* w, const double* in, const double* bias, double* out, void* ws,
                       size_t ws_bytes, void* hip_stream) {
   if (!d->f64_ok) return CONV_ESHAPE;
@@ -702,7 +703,7 @@ static int run_corr64(const conv_desc_t* d, const CorrArgs& args, const PackArgs
   a.in = reinterpret_cast<const float*>(in);
   a.bias = reinterpret_cast<const float*>(bias);
   a.out = reinterpret_cast<float*>(out);
-  e = launch_corr64(a, hip_stream);
+  e = launch_corr64(tile_rows, a, hip_stream);
   return e ? record_hip_error(e) : CONV_OK;
 }
 
@@ -712,7 +713,7 @@ int conv_forward_f64(const conv_desc_t* d, const double* x, const double* w, con
   if ((d->p.bias_term != 0) != (bias != nullptr)) return CONV_EINVAL;
   if (d->p.n == 0) return CONV_OK;
   if (!x || !y) return CONV_EINVAL;
-  return run_corr64(d, d->fwd64, d->fwd64_pack, d->fwd64_ws, w, x, bias, y, ws, ws_bytes, hip_stream);
+  return run_corr64(d, d->fwd64_rows, d->fwd64, d->fwd64_pack, d->fwd64_ws, w, x, bias, y, ws, ws_bytes, hip_stream);
 }
 
 int conv_backward_data_f64(const conv_desc_t* d, const double* w, const double* dy, double* dx, void* ws,
@@ -720,7 +721,7 @@ int conv_backward_data_f64(const conv_desc_t* d, const double* w, const double* 
   if (!d || !w) return CONV_EINVAL;
   if (d->p.n == 0) return CONV_OK;
   if (!dy || !dx) return CONV_EINVAL;
-  return run_corr64(d, d->bwd64, d->bwd64_pack, d->bwd64_ws, w, dy, nullptr, dx, ws, ws_bytes, hip_stream);
+  return run_corr64(d, d->bwd64_rows, d->bwd64, d->bwd64_pack, d->bwd64_ws, w, dy, nullptr, dx, ws, ws_bytes, hip_stream);
 }
 
 int conv_backward_filter_f64(const conv_desc_t* d, const double* x, const double* dy, double* dw, double beta,
@@ -735,7 +736,7 @@ int conv_backward_filter_f64(const conv_desc_t* d, const double* x, const double
   a.dy = reinterpret_cast<const float*>(dy);
   a.x = reinterpret_cast<const float*>(x);
   a.part = static_cast<float*>(ws);
-  int e = empty ? 0 : launch_wgrad64(a, hip_stream);
+  int e = empty ? 0 : launch_wgrad64(d->wg64_rows, a, hip_stream);
   if (e) return record_hip_error(e);
   ReduceArgs r = {};
   r.part = a.part;

@@ -198,9 +198,10 @@ int launch_wgrad(int32_t tile, const WgradArgs& a, void* stream);
 int launch_reduce(const ReduceArgs& a, void* stream);
 int launch_bias_grad(const BiasGradArgs& a, void* stream);
 // double base type: the same argument structs, pointer members addressing doubles
-void f64_tile_shape(int32_t* bm, int32_t* bn, int32_t* bk);
-int launch_corr64(const CorrArgs& a, void* stream);
-int launch_wgrad64(const WgradArgs& a, void* stream);
+constexpr int32_t kF64TileCols = 64, kF64TileK = 16;
+int32_t f64_pick_rows(int64_t rows, bool filter_gradient);  // 96, 64, 48, 32 or 16: pads `rows` least
+int launch_corr64(int32_t tile_rows, const CorrArgs& a, void* stream);
+int launch_wgrad64(int32_t tile_rows, const WgradArgs& a, void* stream);
 int launch_reduce64(const ReduceArgs& a, void* stream);
 int launch_bias_grad64(const BiasGradArgs& a, void* stream);
 int launch_relu_bwd(const ReluBwdArgs& a, void* stream);
@@ -249,8 +250,10 @@ struct conv_desc {
   size_t bg_ws;
   size_t ws_bytes;
   char names[256];
-  // double base type: one 64x64x16 tile for every pass (f64_ok = 0: a blob of 2^29 or more elements)
+  // double base type: tiles of fwd64_rows / bwd64_rows / wg64_rows x 64 x 16 (f64_ok = 0: a blob of
+  // 2^29 or more elements)
   int32_t f64_ok;
+  int32_t fwd64_rows, bwd64_rows, wg64_rows;
   mi355conv::CorrArgs fwd64, bwd64;
   mi355conv::PackArgs fwd64_pack, bwd64_pack;
   size_t fwd64_ws, bwd64_ws;

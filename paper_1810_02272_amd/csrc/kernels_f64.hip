@@ -1,6 +1,7 @@
 // Double-precision base type for the convolution layer (the paper builds every layer for a
 // "float or double base type", section after Table 1): the same four passes on the fp64 matrix
-// instruction v_mfma_f64_16x16x4f64.  One tile shape per kernel, MODE-1 style bounds checks (row
+// instruction v_mfma_f64_16x16x4f64.  Workgroup tiles of 96/64/48/32/16 rows by 64 columns by 16 k
+// (the row count that pads the matrix least is chosen per pass), MODE-1 style bounds checks (row
 // and column compares, out-of-image elements read as 0 through the buffer range check), a
 // two-stage LDS ring with a register prefetch.  The argument structs are those of the fp32
 // kernels; their pointer members address doubles here and the byte counts are those of doubles.
@@ -21,12 +22,20 @@ typedef double f64x2 __attribute__((ext_vector_type(2)));
 typedef double f64x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kThreads = 256;
-constexpr int BM = 64, BN = 64, BK = 16;
+constexpr int BN = 64, BK = 16;
 // LDS tiles are [row][k] with rows of 18 doubles: for the 8-byte operand reads (lane -> row l%16,
 // k 4s + l/16) the 16 rows of a quarter wave start on 16 distinct bank pairs, and the next quarter
 // is shifted by one pair.
 constexpr int LDK = BK + 2;
-constexpr int STAGE = (BM + BN) * LDK;  // doubles per stage
+
+// Four waves as WM x WN, each owning MB x NB MFMA tiles of 16x16: BM = WM*MB*16 rows, 64 columns.
+template <int MB, int NB, int WM, int WN>
+struct Cfg64 {
+  static constexpr int BM = WM * MB * 16;
+  static constexpr int STAGE = (BM + BN) * LDK;  // doubles per stage
+  static constexpr int A_PER = (BM * 4 + kThreads - 1) / kThreads;  // 32-byte pieces of the A tile per thread
+  static_assert(WM * WN == 4 && WN * NB * 16 == BN, "four waves, 64 columns");
+};
 
 __device__ __forceinline__ double buffer_load_f64(__amdgpu_buffer_rsrc_t rsrc, uint32_t off) {
   return __builtin_bit_cast(double, __builtin_amdgcn_raw_buffer_load_b64(rsrc, off, 0, 0));
@@ -36,30 +45,33 @@ __device__ __forceinline__ void mfma64(double a, double b, f64x4& c) {
   c = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0);
 }
 
-// One chunk (BK k values) of the 64x64 workgroup tile: each wave owns a 32x32 quarter as 2x2
-// MFMA tiles.
-__device__ __forceinline__ void chunk_mfma(const double* sA, const double* sB, f64x4 (&acc)[2][2]) {
+// One chunk (BK k values) of a wave's MB x NB MFMA tiles.
+template <int MB, int NB>
+__device__ __forceinline__ void chunk_mfma(const double* sA, const double* sB, f64x4 (&acc)[MB][NB]) {
 #pragma unroll
   for (int s = 0; s < BK / 4; ++s) {
-    double av[2], bv[2];
+    double av[MB], bv[NB];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) av[i] = sA[i * 16 * LDK + 4 * s];
+    for (int i = 0; i < MB; ++i) av[i] = sA[i * 16 * LDK + 4 * s];
 #pragma unroll
-    for (int j = 0; j < 2; ++j) bv[j] = sB[j * 16 * LDK + 4 * s];
+    for (int j = 0; j < NB; ++j) bv[j] = sB[j * 16 * LDK + 4 * s];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < MB; ++i)
 #pragma unroll
-      for (int j = 0; j < 2; ++j) mfma64(av[i], bv[j], acc[i][j]);
+      for (int j = 0; j < NB; ++j) mfma64(av[i], bv[j], acc[i][j]);
   }
 }
 
 // D[m][col] = sum_kk A[m][kk] * gather(in)[kk][col]: forward and backward data (see corr_kernel
 // for the fp32 version and the meaning of every CorrArgs field).
+template <int MB, int NB, int WM, int WN>
 __global__ __launch_bounds__(kThreads) void corr64_kernel(const CorrArgs a) {
+  using C = Cfg64<MB, NB, WM, WN>;
+  constexpr int BM = C::BM, STAGE = C::STAGE, A_PER = C::A_PER;
   __shared__ __align__(16) double smem[2 * STAGE];
   const int t = threadIdx.x, lane = t & 63;
   const int wv = __builtin_amdgcn_readfirstlane(t >> 6);
-  const int wm = wv >> 1, wn = wv & 1;
+  const int wm = wv / WN, wn = wv % WN;
 
   uint32_t lin = xcd_contiguous_block_id();
   const uint32_t m_tile = lin % (uint32_t)a.m_tiles;
@@ -83,22 +95,28 @@ __global__ __launch_bounds__(kThreads) void corr64_kernel(const CorrArgs a) {
     }
   }
   const double* Ag = reinterpret_cast<const double*>(a.A) + ((size_t)g * a.MP + (size_t)m_tile * BM) * a.KP;
-  const int arow = t >> 2, ak = (t & 3) * 4;
+  const int ak = (t & 3) * 4;  // piece p of this thread: row (t >> 2) + 64*p, k ak .. ak+3
   const __amdgpu_buffer_rsrc_t in_rsrc =
       __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(a.in), 0, (int)a.in_bytes, 0x00020000);
 
-  f64x4 acc[2][2];
+  f64x4 acc[MB][NB];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < MB; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j) acc[i][j] = f64x4{0., 0., 0., 0.};
+    for (int j = 0; j < NB; ++j) acc[i][j] = f64x4{0., 0., 0., 0.};
 
-  f64x2 ra[2];
+  f64x2 ra[A_PER][2];
   double rb[4];
   auto load_chunk = [&](int kc) {
-    const double* src = Ag + (size_t)arow * a.KP + kc * BK + ak;
-    ra[0] = *reinterpret_cast<const f64x2*>(src);
-    ra[1] = *reinterpret_cast<const f64x2*>(src + 2);
+#pragma unroll
+    for (int p = 0; p < A_PER; ++p) {
+      const int arow = (t >> 2) + 64 * p;
+      if (arow < BM) {
+        const double* src = Ag + (size_t)arow * a.KP + kc * BK + ak;
+        ra[p][0] = *reinterpret_cast<const f64x2*>(src);
+        ra[p][1] = *reinterpret_cast<const f64x2*>(src + 2);
+      }
+    }
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       const KTabEntry te = a.ktab[kc * BK + wv * 4 + e];  // uniform over the wave: scalar loads
@@ -109,24 +127,30 @@ __global__ __launch_bounds__(kThreads) void corr64_kernel(const CorrArgs a) {
     }
   };
   auto store_chunk = [&](int buf) {
-    double* sa = smem + buf * STAGE + arow * LDK + ak;
-    *reinterpret_cast<f64x2*>(sa) = ra[0];
-    *reinterpret_cast<f64x2*>(sa + 2) = ra[1];
+#pragma unroll
+    for (int p = 0; p < A_PER; ++p) {
+      const int arow = (t >> 2) + 64 * p;
+      if (arow < BM) {
+        double* sa = smem + buf * STAGE + arow * LDK + ak;
+        *reinterpret_cast<f64x2*>(sa) = ra[p][0];
+        *reinterpret_cast<f64x2*>(sa + 2) = ra[p][1];
+      }
+    }
     double* sb = smem + buf * STAGE + BM * LDK + lane * LDK + wv * 4;
     *reinterpret_cast<f64x2*>(sb) = f64x2{rb[0], rb[1]};
     *reinterpret_cast<f64x2*>(sb + 2) = f64x2{rb[2], rb[3]};
   };
 
   const int nchunks = a.KP / BK;
-  const double* opA = smem + (wm * 32 + (lane & 15)) * LDK + (lane >> 4);
-  const double* opB = smem + BM * LDK + (wn * 32 + (lane & 15)) * LDK + (lane >> 4);
+  const double* opA = smem + (wm * MB * 16 + (lane & 15)) * LDK + (lane >> 4);
+  const double* opB = smem + BM * LDK + (wn * NB * 16 + (lane & 15)) * LDK + (lane >> 4);
   load_chunk(0);
   store_chunk(0);
   __syncthreads();
   for (int kc = 0; kc < nchunks; ++kc) {
     const int cur = kc & 1;
     if (kc + 1 < nchunks) load_chunk(kc + 1);  // in flight while this chunk is multiplied
-    chunk_mfma(opA + cur * STAGE, opB + cur * STAGE, acc);
+    chunk_mfma<MB, NB>(opA + cur * STAGE, opB + cur * STAGE, acc);
     if (kc + 1 < nchunks) store_chunk(cur ^ 1);
     __syncthreads();
   }
@@ -172,13 +196,13 @@ __global__ __launch_bounds__(kThreads) void corr64_kernel(const CorrArgs a) {
   }
   __syncthreads();
 #pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    const int4 ct = coltab[wn * 32 + j * 16 + (lane & 15)];
+  for (int j = 0; j < NB; ++j) {
+    const int4 ct = coltab[(wn * NB + j) * 16 + (lane & 15)];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < MB; ++i)
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        const int m = wm * 32 + i * 16 + 4 * r + (lane >> 4);
+        const int m = (wm * MB + i) * 16 + 4 * r + (lane >> 4);
         const int4 rt = rowtab[m];
         const int hh = rt.y + ct.y, ww = rt.z + ct.z;
         if ((uint32_t)hh < (uint32_t)a.OHd && (uint32_t)ww < (uint32_t)a.OWd)
@@ -190,11 +214,14 @@ __global__ __launch_bounds__(kThreads) void corr64_kernel(const CorrArgs a) {
 // Backward filter: part[split][g][k][nn] = sum over the split's columns (n, oh, ow) of
 // dy[n, g*Kg + k, oh, ow] * x[n, g*Cg + c, oh*sh - ph + i*dh, ow*sw - pw + j*dw], nn = (c, i, j).
 // Lanes run along the reduction index (16 columns per chunk), 16 row slots per operand.
+template <int MB, int NB, int WM, int WN>
 __global__ __launch_bounds__(kThreads) void wgrad64_kernel(const WgradArgs a) {
+  using C = Cfg64<MB, NB, WM, WN>;
+  constexpr int BM = C::BM, STAGE = C::STAGE, AR = BM / 16;  // AR dy rows per thread
   __shared__ __align__(16) double smem[2 * STAGE];
   const int t = threadIdx.x, lane = t & 63;
   const int wv = __builtin_amdgcn_readfirstlane(t >> 6);
-  const int wm = wv >> 1, wn = wv & 1;
+  const int wm = wv / WN, wn = wv % WN;
   const int kc = t & 15, rslot = t >> 4;
 
   uint32_t lin = xcd_contiguous_block_id();
@@ -207,12 +234,15 @@ __global__ __launch_bounds__(kThreads) void wgrad64_kernel(const WgradArgs a) {
 
   // rows this thread loads (rows past the matrix edge are clamped: they feed accumulators that
   // are never stored)
-  uint32_t aoff[4], boff[4], bij[4];
+  uint32_t aoff[AR], boff[4], bij[4];
 #pragma unroll
-  for (int e = 0; e < 4; ++e) {
+  for (int e = 0; e < AR; ++e) {
     uint32_t m = m_tile * BM + rslot + 16 * e;
     if (m > (uint32_t)a.Kg - 1) m = (uint32_t)a.Kg - 1;
     aoff[e] = 8u * m * (uint32_t)a.P;
+  }
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
     uint32_t nn = n_tile * BN + rslot + 16 * e;
     if (nn > (uint32_t)a.Kred - 1) nn = (uint32_t)a.Kred - 1;
     const uint32_t c = mdiv(nn, a.mKHW);
@@ -232,13 +262,13 @@ __global__ __launch_bounds__(kThreads) void wgrad64_kernel(const WgradArgs a) {
   const __amdgpu_buffer_rsrc_t x_rsrc =
       __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(a.x), 0, (int)a.x_bytes, 0x00020000);
 
-  f64x4 acc[2][2];
+  f64x4 acc[MB][NB];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < MB; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j) acc[i][j] = f64x4{0., 0., 0., 0.};
+    for (int j = 0; j < NB; ++j) acc[i][j] = f64x4{0., 0., 0., 0.};
 
-  double ra[4], rb[4];
+  double ra[AR], rb[4];
   auto load_chunk = [&](int chunk) {
     const uint32_t col = c_begin + chunk * BK + kc;
     const bool colok = col < c_end;
@@ -251,8 +281,9 @@ __global__ __launch_bounds__(kThreads) void wgrad64_kernel(const WgradArgs a) {
     const uint32_t dybase = 8u * ((n * a.Ktot + g * a.Kg) * (uint32_t)a.P + pix);
     const uint32_t xbase = 8u * (uint32_t)((int)(n * (uint32_t)(a.C * a.HW)) + ih0 * a.W + iw0);
 #pragma unroll
+    for (int e = 0; e < AR; ++e) ra[e] = buffer_load_f64(dy_rsrc, colok ? dybase + aoff[e] : a.dy_bytes);
+#pragma unroll
     for (int e = 0; e < 4; ++e) {
-      ra[e] = buffer_load_f64(dy_rsrc, colok ? dybase + aoff[e] : a.dy_bytes);
       const int ih = ih0 + (int)(bij[e] >> 16), iw = iw0 + (int)(bij[e] & 0xffffu);
       const bool ok = colok & ((uint32_t)ih < (uint32_t)a.H) & ((uint32_t)iw < (uint32_t)a.W);
       rb[e] = buffer_load_f64(x_rsrc, ok ? xbase + boff[e] : a.x_bytes);
@@ -260,14 +291,13 @@ __global__ __launch_bounds__(kThreads) void wgrad64_kernel(const WgradArgs a) {
   };
   auto store_chunk = [&](int buf) {
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      smem[buf * STAGE + (rslot + 16 * e) * LDK + kc] = ra[e];
-      smem[buf * STAGE + BM * LDK + (rslot + 16 * e) * LDK + kc] = rb[e];
-    }
+    for (int e = 0; e < AR; ++e) smem[buf * STAGE + (rslot + 16 * e) * LDK + kc] = ra[e];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) smem[buf * STAGE + BM * LDK + (rslot + 16 * e) * LDK + kc] = rb[e];
   };
 
-  const double* opA = smem + (wm * 32 + (lane & 15)) * LDK + (lane >> 4);
-  const double* opB = smem + BM * LDK + (wn * 32 + (lane & 15)) * LDK + (lane >> 4);
+  const double* opA = smem + (wm * MB * 16 + (lane & 15)) * LDK + (lane >> 4);
+  const double* opB = smem + BM * LDK + (wn * NB * 16 + (lane & 15)) * LDK + (lane >> 4);
   if (nchunks > 0) {
     load_chunk(0);
     store_chunk(0);
@@ -276,20 +306,20 @@ __global__ __launch_bounds__(kThreads) void wgrad64_kernel(const WgradArgs a) {
   for (int ch = 0; ch < nchunks; ++ch) {
     const int cur = ch & 1;
     if (ch + 1 < nchunks) load_chunk(ch + 1);
-    chunk_mfma(opA + cur * STAGE, opB + cur * STAGE, acc);
+    chunk_mfma<MB, NB>(opA + cur * STAGE, opB + cur * STAGE, acc);
     if (ch + 1 < nchunks) store_chunk(cur ^ 1);
     __syncthreads();
   }
 
   double* dst = reinterpret_cast<double*>(a.part) + ((size_t)split * a.G + g) * ((size_t)a.Kg * a.Kred);
 #pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    const uint32_t nn = n_tile * BN + wn * 32 + j * 16 + (lane & 15);
+  for (int j = 0; j < NB; ++j) {
+    const uint32_t nn = n_tile * BN + (wn * NB + j) * 16 + (lane & 15);
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < MB; ++i)
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        const uint32_t k = m_tile * BM + wm * 32 + i * 16 + 4 * r + (lane >> 4);
+        const uint32_t k = m_tile * BM + (wm * MB + i) * 16 + 4 * r + (lane >> 4);
         if (k < (uint32_t)a.Kg && nn < (uint32_t)a.Kred) dst[(size_t)k * a.Kred + nn] = acc[i][j][r];
       }
   }
@@ -343,21 +373,48 @@ __global__ __launch_bounds__(256) void bias_grad64_kernel(const BiasGradArgs a) 
 
 }  // namespace
 
-void f64_tile_shape(int32_t* bm, int32_t* bn, int32_t* bk) {
-  *bm = BM;
-  *bn = BN;
-  *bk = BK;
+// Row counts of the fp64 workgroup tiles (columns 64, k 16 for all of them).
+// Ties go to the 64-row tile for the correlation (measured faster than 96 rows there: four
+// workgroups per compute unit instead of three) and to the 96-row tile for the filter gradient.
+int32_t f64_pick_rows(int64_t rows, bool filter_gradient) {
+  static const int32_t corr_order[] = {64, 96, 48, 32, 16}, wgrad_order[] = {96, 64, 48, 32, 16};
+  int32_t best = 64;
+  int64_t best_pad = -1;
+  for (int32_t bm : (filter_gradient ? wgrad_order : corr_order)) {
+    const int64_t pad = (rows + bm - 1) / bm * bm;
+    if (best_pad < 0 || pad < best_pad) {
+      best = bm;
+      best_pad = pad;
+    }
+  }
+  return best;
 }
 
-int launch_corr64(const CorrArgs& a, void* stream) {
-  const uint32_t blocks = (uint32_t)a.G * a.m_tiles * a.col_tiles;
-  hipLaunchKernelGGL(corr64_kernel, dim3(blocks), dim3(kThreads), 0, (hipStream_t)stream, a);
+int launch_corr64(int32_t bm, const CorrArgs& a, void* stream) {
+  const dim3 grid((uint32_t)a.G * a.m_tiles * a.col_tiles), block(kThreads);
+  hipStream_t s = (hipStream_t)stream;
+  switch (bm) {
+    case 96: hipLaunchKernelGGL((corr64_kernel<3, 2, 2, 2>), grid, block, 0, s, a); break;
+    case 64: hipLaunchKernelGGL((corr64_kernel<2, 2, 2, 2>), grid, block, 0, s, a); break;
+    case 48: hipLaunchKernelGGL((corr64_kernel<3, 1, 1, 4>), grid, block, 0, s, a); break;
+    case 32: hipLaunchKernelGGL((corr64_kernel<2, 1, 1, 4>), grid, block, 0, s, a); break;
+    case 16: hipLaunchKernelGGL((corr64_kernel<1, 1, 1, 4>), grid, block, 0, s, a); break;
+    default: return (int)hipErrorInvalidValue;
+  }
   return (int)hipGetLastError();
 }
 
-int launch_wgrad64(const WgradArgs& a, void* stream) {
-  const uint32_t blocks = (uint32_t)a.G * a.S * a.m_tiles * a.n_tiles;
-  hipLaunchKernelGGL(wgrad64_kernel, dim3(blocks), dim3(kThreads), 0, (hipStream_t)stream, a);
+int launch_wgrad64(int32_t bm, const WgradArgs& a, void* stream) {
+  const dim3 grid((uint32_t)a.G * a.S * a.m_tiles * a.n_tiles), block(kThreads);
+  hipStream_t s = (hipStream_t)stream;
+  switch (bm) {
+    case 96: hipLaunchKernelGGL((wgrad64_kernel<3, 2, 2, 2>), grid, block, 0, s, a); break;
+    case 64: hipLaunchKernelGGL((wgrad64_kernel<2, 2, 2, 2>), grid, block, 0, s, a); break;
+    case 48: hipLaunchKernelGGL((wgrad64_kernel<3, 1, 1, 4>), grid, block, 0, s, a); break;
+    case 32: hipLaunchKernelGGL((wgrad64_kernel<2, 1, 1, 4>), grid, block, 0, s, a); break;
+    case 16: hipLaunchKernelGGL((wgrad64_kernel<1, 1, 1, 4>), grid, block, 0, s, a); break;
+    default: return (int)hipErrorInvalidValue;
+  }
   return (int)hipGetLastError();
 }
 

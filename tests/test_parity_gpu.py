@@ -103,12 +103,13 @@ SWEEP = [
 ]
 
 # Shapes that select the patch-staged kernel (256-column tiles of the 16-row MFMA): 48 or <= 16
-# rows, 8-aligned reduction channels, enough columns for the wide tile to win.
+# rows, 8-aligned reduction channels, enough columns for the wide tile to win and for the grid not
+# to want a split reduction.
 PATCH_CASES = [
-    (P(14, 48, 60, 45, 16, 5, 5, 1, 1, 2, 2), "bwd_data"),             # 5x5, one image per many tiles
+    (P(20, 48, 60, 45, 16, 5, 5, 1, 1, 2, 2), "bwd_data"),             # 5x5, one image per many tiles
     (P(400, 96, 9, 9, 16, 3, 3, 1, 1, 1, 1, 1, 1, 2), "bwd_data"),     # grouped, tiles span 4 images
     (P(49, 8, 32, 32, 8, 3, 3, 1, 1, 1, 1), "bwd_data"),               # 16-row tile
-    (P(9, 16, 70, 61, 48, 3, 5, 1, 1, 0, 3), "fwd"),                   # forward with 48 rows, ragged pad
+    (P(12, 16, 70, 61, 48, 3, 5, 1, 1, 0, 3), "fwd"),                  # forward with 48 rows, ragged pad
 ]
 
 

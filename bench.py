@@ -68,6 +68,13 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
 
+    if args.copy_calibration:
+        src = torch.ones(64 << 20, device=dev)  # 256 MiB read + 256 MiB written per copy
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     if args.workload == "pg":
         return bench_pg(args, torch, conv, workloads, dev)
     is_ip = args.workload.startswith("ip")
@@ -169,14 +176,6 @@ def main():
                 else:
                     run_pass(t, name)
 
-    if args.copy_calibration:
-        src = torch.ones(64 << 20, device=dev)  # 256 MiB read + 256 MiB written per copy
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
-
     # Cost of one empty dispatch on this machine, for reading the microsecond-scale layers: a one-element
     # fill, enqueued back to back.
     one = torch.zeros(1, device=dev)
@@ -251,10 +250,10 @@ def main():
     roofline.update({"kernel": kernel_names.get(dp, dp), "layer": dl, "pass": dp, "avg_ms": round(dms, 5),
                      "algorithmic_gflop_per_launch": dlayer.flop_per_pass / 1e9})
     traffic_file = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "hbm_traffic.json")
-    if os.path.exists(traffic_file) and not f64 and not is_ip:  # measured separately with rocprofv3 --pmc (see profiles/)
+    if os.path.exists(traffic_file):  # measured separately with rocprofv3 --pmc (see profiles/)
         try:
             tr = json.load(open(traffic_file))
-            roofline["traffic"] = tr.get(f"{dl}:{dp}")
+            roofline["traffic"] = tr.get(("f64/" if f64 else "") + f"{dl}:{dp}")
         except Exception:
             pass
 
@@ -346,7 +345,7 @@ def bench_pg(args, torch, lib, workloads, dev):
         "config": {"workload": f"pg: {episodes} episodes of {lo}..{hi} steps = {steps} time steps, {actions} actions, "
                                f"gamma {gamma}", "time_steps_per_s": round(steps * args.steps / wall, 1)},
         "roofline": {"bound": "hbm", "achieved": per_pass[dom]["GBps"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                     "frac": round(per_pass[dom]["GBps"] / PEAK_HBM_GBS, 4), "traffic": None, "kernel": dom,
+                     "frac": round(per_pass[dom]["GBps"] / PEAK_HBM_GBS, 4), "traffic": pg_traffic(dom), "kernel": dom,
                      "avg_ms": per_pass[dom]["ms"]},
         "per_pass": per_pass,
     }
@@ -369,6 +368,15 @@ def bench_pg(args, torch, lib, workloads, dev):
                                "sample": f"first {len(off) - 1} episodes ({n} time steps), same fp32-sized byte count, "
                                          f"double-precision loops, {secs:.1f} s"}
     print(json.dumps(res))
+
+
+def pg_traffic(pass_name):
+    """HBM bytes of one pg pass as measured separately with rocprofv3 --pmc (see profiles/), or None."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "hbm_traffic.json")
+    try:
+        return json.load(open(path)).get(f"pg:{pass_name}")
+    except Exception:
+        return None
 
 
 def dy_bytes(l):

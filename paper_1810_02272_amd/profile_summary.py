@@ -1,15 +1,16 @@
 """Turns rocprofv3 CSV output of a ``bench.py`` run into the short text summaries kept under profiles/.
 
     python -m paper_1810_02272_amd.profile_summary trace  <dir with *_kernel_trace.csv>  > profiles/<name>.txt
-    python -m paper_1810_02272_amd.profile_summary traffic <fetch dir> <write dir> [--layers 5.a,5.b,5.c]
+    python -m paper_1810_02272_amd.profile_summary traffic <fetch dir> <write dir> [--workload config4|f64|ip5|pg]
     python -m paper_1810_02272_amd.profile_summary sq <dir with *_counter_collection.csv of an SQ_* --pmc run>
 
 ``trace`` prints calls / average / min / max duration per (kernel, grid).  ``traffic`` reads two
 ``--pmc`` runs (FETCH_SIZE, then WRITE_SIZE, both KiB per dispatch) of
 ``bench.py --copy-calibration``, scales each counter by what it reads for the plain 256 MiB device
-copy in the same run, prints HBM bytes per (layer, pass) and writes profiles/hbm_traffic.json
-(which bench.py reports as ``roofline.traffic``).  Dispatches are matched to (layer, pass) by
-their order inside a step: forward, backward data, backward filter, backward bias per layer.
+copy in the same run, prints HBM bytes per (layer, pass) and merges them into
+profiles/hbm_traffic.json (which bench.py reports as ``roofline.traffic``).  Dispatches are
+matched to (layer, pass) by their order inside a step (the main kernel of each pass, per layer);
+``--workload`` names the bench.py workload the two runs were made with.
 ``sq`` condenses a run with SQ_BUSY_CYCLES SQ_WAVE_CYCLES SQ_VALU_MFMA_BUSY_CYCLES
 SQ_INSTS_VALU_MFMA_MOPS_F32 SQ_WAIT_INST_ANY SQ_LDS_BANK_CONFLICT SQ_INSTS_MFMA SQ_INSTS_VALU into MFMA
 utilisation per kernel (counters are summed over 32 shader engines / 1024 SIMDs of the chip).
@@ -25,6 +26,15 @@ from collections import OrderedDict
 
 MAIN = ("corr_kernel", "corr_patch_kernel", "wgrad_kernel", "bias_grad_kernel")
 PASSES = ("fwd", "bwd_data", "bwd_filter", "bwd_bias")
+# workload -> (main kernels in pass order, pass names, layers, key prefix in hbm_traffic.json)
+WORKLOADS = {
+    "config4": (MAIN, PASSES, ["5.a", "5.b", "5.c"], ""),
+    "f64": (("corr64_kernel", "wgrad64_kernel", "bias_grad64_kernel"), PASSES, ["5.a", "5.b", "5.c"], "f64/"),
+    "ip5": (("wgrad_kernel", "relu_bwd_kernel", "corr_kernel", "colsum_kernel"),
+            ("fwd", "relu_bwd", "bwd_data", "bwd_filter", "bwd_bias"), ["ip5.6", "ip5.7", "ip5.8"], ""),
+    "pg": (("pg_sample_kernel", "pg_discount_kernel", "pg_sigmoid_kernel", "pg_softmax_rows_kernel"),
+           ("sample_action", "discount_rewards", "sigmoid_bottom_diff", "softmax_bottom_diff"), ["pg"], ""),
+}
 COPY_BYTES = 256 * 1024 * 1024
 
 
@@ -59,24 +69,25 @@ def _counter(directory: str):
              float(r["Counter_Value"])) for r in rows]
 
 
-def _per_pass(rows, layers):
-    copies = [v for n, b, v in rows if "copyBuffer" in n and b > 1]
+def _per_pass(rows, main_kernels, passes, layers, prefix):
+    copies = [v for n, b, v in rows if "copyBuffer" in n and b >= 256]  # the 256 MiB calibration copies only
     if not copies:
         raise SystemExit("no calibration copy found: run bench.py with --copy-calibration")
     kib_per_copy = sum(copies) / len(copies)
     factor = (COPY_BYTES / 1024.0) / kib_per_copy  # true KiB per counted KiB
-    main = [(n, v) for n, b, v in rows if any(m in n for m in MAIN)]
-    per_step = len(layers) * len(PASSES)
+    main = [(n, v) for n, b, v in rows if any(m + "<" in n or m + "(" in n for m in main_kernels)]
+    per_step = len(layers) * len(passes)
     out: "OrderedDict[str, list]" = OrderedDict()
     for i, (n, v) in enumerate(main):
-        layer, p = layers[(i % per_step) // len(PASSES)], PASSES[i % len(PASSES)]
-        out.setdefault(f"{layer}:{p}", []).append(v * factor * 1024.0)
+        layer, p = layers[(i % per_step) // len(passes)], passes[i % len(passes)]
+        out.setdefault(f"{prefix}{layer}:{p}", []).append(v * factor * 1024.0)
     return factor, {k: sum(v) / len(v) for k, v in out.items()}
 
 
-def traffic(fetch_dir: str, write_dir: str, layers) -> None:
-    ff, fetch = _per_pass(_counter(fetch_dir), layers)
-    wf, write = _per_pass(_counter(write_dir), layers)
+def traffic(fetch_dir: str, write_dir: str, workload: str) -> None:
+    spec = WORKLOADS[workload]
+    ff, fetch = _per_pass(_counter(fetch_dir), *spec)
+    wf, write = _per_pass(_counter(write_dir), *spec)
     print(f"calibration: FETCH_SIZE x {ff:.3f}, WRITE_SIZE x {wf:.3f} (from the 256 MiB device copy)")
     print(f"{'layer:pass':16s} {'read MB':>10s} {'written MB':>11s} {'total MB':>10s}   (main kernel of the pass)")
     total = {}
@@ -84,8 +95,11 @@ def traffic(fetch_dir: str, write_dir: str, layers) -> None:
         total[k] = int(fetch[k] + write[k])
         print(f"{k:16s} {fetch[k] / 1e6:10.1f} {write[k] / 1e6:11.1f} {total[k] / 1e6:10.1f}")
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-    with open(os.path.join(root, "profiles", "hbm_traffic.json"), "w") as f:
-        json.dump(total, f, indent=1)
+    path = os.path.join(root, "profiles", "hbm_traffic.json")
+    merged = json.load(open(path)) if os.path.exists(path) else {}
+    merged.update(total)
+    with open(path, "w") as f:
+        json.dump(merged, f, indent=1)
 
 
 def sq(directory: str) -> None:
@@ -114,10 +128,8 @@ def main(argv) -> None:
     elif len(argv) >= 3 and argv[1] == "sq":
         sq(argv[2])
     elif len(argv) >= 4 and argv[1] == "traffic":
-        layers = ["5.a", "5.b", "5.c"]
-        if "--layers" in argv:
-            layers = argv[argv.index("--layers") + 1].split(",")
-        traffic(argv[2], argv[3], layers)
+        workload = argv[argv.index("--workload") + 1] if "--workload" in argv else "config4"
+        traffic(argv[2], argv[3], workload)
     else:
         raise SystemExit(__doc__)
 

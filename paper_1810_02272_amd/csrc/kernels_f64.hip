@@ -23,16 +23,16 @@ typedef double f64x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kThreads = 256;
 constexpr int BN = 64, BK = 16;
-// LDS tiles are [row][k] with rows of 18 doubles: for the 8-byte operand reads (lane -> row l%16,
-// k 4s + l/16) the 16 rows of a quarter wave start on 16 distinct bank pairs, and the next quarter
-// is shifted by one pair.
-constexpr int LDK = BK + 2;
+// LDS tiles are [k][row] with an odd row count per k (BM + 1, 65): an 8-byte operand read (lane ->
+// row l%16, k 4s + l/16) takes 16 consecutive doubles per quarter wave, and a staging write whose
+// lanes run along k (filter gradient) steps through the 32 banks two at a time.
 
 // Four waves as WM x WN, each owning MB x NB MFMA tiles of 16x16: BM = WM*MB*16 rows, 64 columns.
 template <int MB, int NB, int WM, int WN>
 struct Cfg64 {
   static constexpr int BM = WM * MB * 16;
-  static constexpr int STAGE = (BM + BN) * LDK;  // doubles per stage
+  static constexpr int LDA = BM + 1, LDB = BN + 1;      // doubles per k row of the two tiles
+  static constexpr int STAGE = BK * (LDA + LDB);        // doubles per stage
   static constexpr int A_PER = (BM * 4 + kThreads - 1) / kThreads;  // 32-byte pieces of the A tile per thread
   static_assert(WM * WN == 4 && WN * NB * 16 == BN, "four waves, 64 columns");
 };
@@ -46,15 +46,15 @@ __device__ __forceinline__ void mfma64(double a, double b, f64x4& c) {
 }
 
 // One chunk (BK k values) of a wave's MB x NB MFMA tiles.
-template <int MB, int NB>
+template <int MB, int NB, int LDA, int LDB>
 __device__ __forceinline__ void chunk_mfma(const double* sA, const double* sB, f64x4 (&acc)[MB][NB]) {
 #pragma unroll
   for (int s = 0; s < BK / 4; ++s) {
     double av[MB], bv[NB];
 #pragma unroll
-    for (int i = 0; i < MB; ++i) av[i] = sA[i * 16 * LDK + 4 * s];
+    for (int i = 0; i < MB; ++i) av[i] = sA[4 * s * LDA + i * 16];
 #pragma unroll
-    for (int j = 0; j < NB; ++j) bv[j] = sB[j * 16 * LDK + 4 * s];
+    for (int j = 0; j < NB; ++j) bv[j] = sB[4 * s * LDB + j * 16];
 #pragma unroll
     for (int i = 0; i < MB; ++i)
 #pragma unroll
@@ -67,7 +67,7 @@ __device__ __forceinline__ void chunk_mfma(const double* sA, const double* sB, f
 template <int MB, int NB, int WM, int WN>
 __global__ __launch_bounds__(kThreads) void corr64_kernel(const CorrArgs a) {
   using C = Cfg64<MB, NB, WM, WN>;
-  constexpr int BM = C::BM, STAGE = C::STAGE, A_PER = C::A_PER;
+  constexpr int BM = C::BM, STAGE = C::STAGE, A_PER = C::A_PER, LDA = C::LDA, LDB = C::LDB;
   __shared__ __align__(16) double smem[2 * STAGE];
   const int t = threadIdx.x, lane = t & 63;
   const int wv = __builtin_amdgcn_readfirstlane(t >> 6);
@@ -95,7 +95,8 @@ __global__ __launch_bounds__(kThreads) void corr64_kernel(const CorrArgs a) {
     }
   }
   const double* Ag = reinterpret_cast<const double*>(a.A) + ((size_t)g * a.MP + (size_t)m_tile * BM) * a.KP;
-  const int ak = (t & 3) * 4;  // piece p of this thread: row (t >> 2) + 64*p, k ak .. ak+3
+  // Piece p = t + 256*i of the A tile: k quad p / BM, row p % BM (consecutive lanes on consecutive
+  // rows: the four 8-byte LDS writes of a piece are conflict free).
   const __amdgpu_buffer_rsrc_t in_rsrc =
       __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(a.in), 0, (int)a.in_bytes, 0x00020000);
 
@@ -107,50 +108,67 @@ __global__ __launch_bounds__(kThreads) void corr64_kernel(const CorrArgs a) {
 
   f64x2 ra[A_PER][2];
   double rb[4];
+  // k-table entries of this wave's four k rows (uniform over the wave: scalar loads), fetched one
+  // chunk before their use so that the gather never waits on scalar memory
+  KTabEntry te[4], te_next[4];
+  auto load_tab = [&](int kc) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) te_next[e] = a.ktab[kc * BK + wv * 4 + e];
+  };
+  auto swap_tab = [&]() {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) te[e] = te_next[e];
+  };
   auto load_chunk = [&](int kc) {
 #pragma unroll
     for (int p = 0; p < A_PER; ++p) {
-      const int arow = (t >> 2) + 64 * p;
-      if (arow < BM) {
-        const double* src = Ag + (size_t)arow * a.KP + kc * BK + ak;
+      const int piece = t + kThreads * p;
+      if (piece < BM * 4) {
+        const double* src = Ag + (size_t)(piece % BM) * a.KP + kc * BK + (piece / BM) * 4;
         ra[p][0] = *reinterpret_cast<const f64x2*>(src);
         ra[p][1] = *reinterpret_cast<const f64x2*>(src + 2);
       }
     }
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      const KTabEntry te = a.ktab[kc * BK + wv * 4 + e];  // uniform over the wave: scalar loads
-      const int ih = cih0 + te.idh, iw = ciw0 + te.jdw;
+      const int ih = cih0 + te[e].idh, iw = ciw0 + te[e].jdw;
       const bool ok = ((uint32_t)ih < (uint32_t)a.IH) & ((uint32_t)iw < (uint32_t)a.IW);
       // the k table holds byte offsets of 4-byte elements
-      rb[e] = buffer_load_f64(in_rsrc, ok ? cbase + 2u * te.koff : a.in_bytes);
+      rb[e] = buffer_load_f64(in_rsrc, ok ? cbase + 2u * te[e].koff : a.in_bytes);
     }
   };
   auto store_chunk = [&](int buf) {
 #pragma unroll
     for (int p = 0; p < A_PER; ++p) {
-      const int arow = (t >> 2) + 64 * p;
-      if (arow < BM) {
-        double* sa = smem + buf * STAGE + arow * LDK + ak;
-        *reinterpret_cast<f64x2*>(sa) = ra[p][0];
-        *reinterpret_cast<f64x2*>(sa + 2) = ra[p][1];
+      const int piece = t + kThreads * p;
+      if (piece < BM * 4) {
+        double* sa = smem + buf * STAGE + (piece / BM) * 4 * LDA + piece % BM;
+        sa[0] = ra[p][0][0];
+        sa[LDA] = ra[p][0][1];
+        sa[2 * LDA] = ra[p][1][0];
+        sa[3 * LDA] = ra[p][1][1];
       }
     }
-    double* sb = smem + buf * STAGE + BM * LDK + lane * LDK + wv * 4;
-    *reinterpret_cast<f64x2*>(sb) = f64x2{rb[0], rb[1]};
-    *reinterpret_cast<f64x2*>(sb + 2) = f64x2{rb[2], rb[3]};
+    double* sb = smem + buf * STAGE + BK * LDA + wv * 4 * LDB + lane;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) sb[e * LDB] = rb[e];
   };
 
   const int nchunks = a.KP / BK;
-  const double* opA = smem + (wm * MB * 16 + (lane & 15)) * LDK + (lane >> 4);
-  const double* opB = smem + BM * LDK + (wn * NB * 16 + (lane & 15)) * LDK + (lane >> 4);
+  const double* opA = smem + (lane >> 4) * LDA + wm * MB * 16 + (lane & 15);
+  const double* opB = smem + BK * LDA + (lane >> 4) * LDB + wn * NB * 16 + (lane & 15);
+  load_tab(0);
+  swap_tab();
   load_chunk(0);
+  load_tab(nchunks > 1 ? 1 : 0);
   store_chunk(0);
   __syncthreads();
   for (int kc = 0; kc < nchunks; ++kc) {
     const int cur = kc & 1;
+    swap_tab();  // entries of chunk kc + 1, fetched during the previous iteration
     if (kc + 1 < nchunks) load_chunk(kc + 1);  // in flight while this chunk is multiplied
-    chunk_mfma<MB, NB>(opA + cur * STAGE, opB + cur * STAGE, acc);
+    load_tab(kc + 2 < nchunks ? kc + 2 : nchunks - 1);
+    chunk_mfma<MB, NB, LDA, LDB>(opA + cur * STAGE, opB + cur * STAGE, acc);
     if (kc + 1 < nchunks) store_chunk(cur ^ 1);
     __syncthreads();
   }
@@ -217,7 +235,7 @@ __global__ __launch_bounds__(kThreads) void corr64_kernel(const CorrArgs a) {
 template <int MB, int NB, int WM, int WN>
 __global__ __launch_bounds__(kThreads) void wgrad64_kernel(const WgradArgs a) {
   using C = Cfg64<MB, NB, WM, WN>;
-  constexpr int BM = C::BM, STAGE = C::STAGE, AR = BM / 16;  // AR dy rows per thread
+  constexpr int BM = C::BM, STAGE = C::STAGE, LDA = C::LDA, LDB = C::LDB, AR = BM / 16;  // AR dy rows per thread
   __shared__ __align__(16) double smem[2 * STAGE];
   const int t = threadIdx.x, lane = t & 63;
   const int wv = __builtin_amdgcn_readfirstlane(t >> 6);
@@ -291,13 +309,13 @@ __global__ __launch_bounds__(kThreads) void wgrad64_kernel(const WgradArgs a) {
   };
   auto store_chunk = [&](int buf) {
 #pragma unroll
-    for (int e = 0; e < AR; ++e) smem[buf * STAGE + (rslot + 16 * e) * LDK + kc] = ra[e];
+    for (int e = 0; e < AR; ++e) smem[buf * STAGE + kc * LDA + rslot + 16 * e] = ra[e];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) smem[buf * STAGE + BM * LDK + (rslot + 16 * e) * LDK + kc] = rb[e];
+    for (int e = 0; e < 4; ++e) smem[buf * STAGE + BK * LDA + kc * LDB + rslot + 16 * e] = rb[e];
   };
 
-  const double* opA = smem + (wm * MB * 16 + (lane & 15)) * LDK + (lane >> 4);
-  const double* opB = smem + BM * LDK + (wn * NB * 16 + (lane & 15)) * LDK + (lane >> 4);
+  const double* opA = smem + (lane >> 4) * LDA + wm * MB * 16 + (lane & 15);
+  const double* opB = smem + BK * LDA + (lane >> 4) * LDB + wn * NB * 16 + (lane & 15);
   if (nchunks > 0) {
     load_chunk(0);
     store_chunk(0);
@@ -306,7 +324,7 @@ __global__ __launch_bounds__(kThreads) void wgrad64_kernel(const WgradArgs a) {
   for (int ch = 0; ch < nchunks; ++ch) {
     const int cur = ch & 1;
     if (ch + 1 < nchunks) load_chunk(ch + 1);
-    chunk_mfma<MB, NB>(opA + cur * STAGE, opB + cur * STAGE, acc);
+    chunk_mfma<MB, NB, LDA, LDB>(opA + cur * STAGE, opB + cur * STAGE, acc);
     if (ch + 1 < nchunks) store_chunk(cur ^ 1);
     __syncthreads();
   }

@@ -152,8 +152,8 @@ __global__ __launch_bounds__(kThreads) void corr_kernel(const CorrArgs a) {
   };
   // Rows of this wave in a chunk: each tap's byte offset and (row, column) displacement come from
   // the k table with scalar loads (the index is uniform over the wave).  The entries are fetched a
-  // whole iteration before their use, right after the first MFMAs of an iteration have issued, so
-  // that the scalar-memory latency never sits in front of an MFMA or the barrier.
+  // whole iteration before their use, in the middle of a chunk's MFMAs, so that the scalar-memory
+  // latency never sits in front of an MFMA or the barrier.
   KTabEntry te[RPW], te_next[RPW];
   auto load_tab = [&](int kc) {
 #pragma unroll
@@ -242,7 +242,11 @@ __global__ __launch_bounds__(kThreads) void corr_kernel(const CorrArgs a) {
       for (int i = 0; i < MB; ++i)
 #pragma unroll
         for (int j = 0; j < NB; ++j) M::run(av[ss & 1][i][u], bv[ss & 1][j][u], acc[i][j]);
-      if (ks == 0) load_tab(kc + 4 < last ? kc + 4 : last);  // for the next iteration's loads
+      // Table entries for the next iteration's loads.  Scalar loads share the LDS counter and return
+      // out of order, so any LDS wait behind them becomes a full wait: they are issued in the middle
+      // of the chunk, one step after the last operand read of this iteration was consumed, and have half a
+      // chunk of MFMAs to arrive before the barrier's wait.
+      if (ks == (NSS > 1 ? NKS / 2 + 1 : 1)) load_tab(kc + 4 < last ? kc + 4 : last);
       // this step's share of the staging work
 #pragma unroll
       for (int q = 0; q < CPL; ++q)

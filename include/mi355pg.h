@@ -31,7 +31,8 @@
  *
  * No workspace, no descriptor, no device allocation; enqueued on the caller's hipStream_t
  * (void*, NULL = default stream) without synchronising.  Returns a conv_status_t: CONV_EINVAL
- * for null pointers / negative sizes / actions < 1, CONV_ESHAPE when steps * actions >= 2^31.
+ * for null pointers / negative sizes / actions < 1, CONV_ESHAPE when steps (or episodes) exceed
+ * 2^31 - 65536 or steps * actions >= 2^31.
  * steps == 0 (or episodes == 0) is a no-op.
  */
 #ifndef MI355PG_H

@@ -14,60 +14,141 @@ namespace mi355conv {
 namespace {
 
 // ---- step 3: action = (random < Aprob) ? 0 : 1 ----
+// Four consecutive steps per thread (16-byte loads and stores); the last, partial group of a
+// launch goes element by element.
 __global__ __launch_bounds__(256) void pg_sample_kernel(const float* __restrict__ aprob,
                                                         const float* __restrict__ random, int32_t* __restrict__ action,
                                                         int steps) {
-  const int t = blockIdx.x * 256 + threadIdx.x;
-  if (t < steps) action[t] = random[t] < aprob[t] ? 0 : 1;
+  const int t = (blockIdx.x * 256 + threadIdx.x) * 4;
+  if (t + 3 < steps) {
+    const float4 ap = *reinterpret_cast<const float4*>(aprob + t);
+    const float4 rn = *reinterpret_cast<const float4*>(random + t);
+    *reinterpret_cast<int4*>(action + t) =
+        make_int4(rn.x < ap.x ? 0 : 1, rn.y < ap.y ? 0 : 1, rn.z < ap.z ? 0 : 1, rn.w < ap.w ? 0 : 1);
+  } else {
+    for (int i = t; i < steps; ++i) action[i] = random[i] < aprob[i] ? 0 : 1;
+  }
 }
 
 // ---- step 9: R[t] = reward[t] + gamma * R[t+1] inside each episode ----
-// One wave per episode, walking it from its end in chunks of 64 steps (lane 63 = the chunk's last
-// step).  Inside a chunk the recurrence is a weighted suffix sum, done in six shuffle rounds with
-// the weights gamma^1, ^2, ^4 ... ^32; the value carried in from the later chunk enters as
-// gamma * carry added to the last lane's reward before the rounds.  Four chunks are loaded at a
-// time so that a long episode does not pay one memory latency per 64 steps.
+// One wave per episode at a time, walking it from its end in chunks of 64 steps (lane 63 = the
+// chunk's last step).  Inside a chunk the recurrence is a weighted suffix sum: four DPP row shifts
+// with the weights gamma^1, ^2, ^4, ^8 finish each row of 16 lanes, three lane reads chain the
+// rows, and the value carried in from the later chunk is added with the weight gamma^(64 - lane).
+// The scans of the four chunks that are loaded together are independent; only the carry links
+// them.  A wave walks several episodes with the next one's loads already in flight.
 constexpr int kChunksInFlight = 4;
 
-__device__ __forceinline__ float suffix_scan(float v, int lane, const float (&gpow)[6]) {
-#pragma unroll
-  for (int i = 0; i < 6; ++i) {
-    const int d = 1 << i;
-    const float o = __shfl_down(v, d, 64);
-    v += (lane + d < 64) ? gpow[i] * o : 0.f;
-  }
-  return v;
+// Lane l receives the value of lane l + N of its row of 16 lanes, 0 past the row's end.
+template <int N>
+__device__ __forceinline__ float row_shift_down(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x100 + N, 0xF, 0xF, true));
+}
+
+struct ScanWeights {
+  float g1, g2, g4, g8, g16;  // powers of gamma
+  float to_row_end;           // gamma^(16 - lane % 16): from this lane to the first lane of the next row
+  float to_chunk_end;         // gamma^(64 - lane): from this lane to the first step of the later chunk
+};
+
+__device__ __forceinline__ ScanWeights scan_weights(float gamma, int lane) {
+  ScanWeights w;
+  w.g1 = gamma;
+  w.g2 = w.g1 * w.g1;
+  w.g4 = w.g2 * w.g2;
+  w.g8 = w.g4 * w.g4;
+  w.g16 = w.g8 * w.g8;
+  const int li = lane & 15;
+  float p = 1.f;
+  p *= (16 - li) & 1 ? w.g1 : 1.f;
+  p *= (16 - li) & 2 ? w.g2 : 1.f;
+  p *= (16 - li) & 4 ? w.g4 : 1.f;
+  p *= (16 - li) & 8 ? w.g8 : 1.f;
+  p *= (16 - li) & 16 ? w.g16 : 1.f;
+  w.to_row_end = p;
+  const int rows_after = 3 - (lane >> 4);
+  float q = p;
+  q *= rows_after & 1 ? w.g16 : 1.f;
+  q *= rows_after & 2 ? w.g16 * w.g16 : 1.f;
+  w.to_chunk_end = q;
+  return w;
+}
+
+// v[l] <- sum over the lanes m >= l of the wave of gamma^(m - l) * v[m]
+__device__ __forceinline__ float suffix_scan(float v, int lane, const ScanWeights& w) {
+  v += w.g1 * row_shift_down<1>(v);
+  v += w.g2 * row_shift_down<2>(v);
+  v += w.g4 * row_shift_down<4>(v);
+  v += w.g8 * row_shift_down<8>(v);
+  const int iv = __builtin_bit_cast(int, v);
+  const float t3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 48));
+  const float t2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 32)) + w.g16 * t3;
+  const float t1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 16)) + w.g16 * t2;
+  const int row = lane >> 4;
+  const float later_rows = row == 0 ? t1 : row == 1 ? t2 : row == 2 ? t3 : 0.f;
+  return v + w.to_row_end * later_rows;
 }
 
 __global__ __launch_bounds__(256) void pg_discount_kernel(const float* __restrict__ reward,
                                                           const int32_t* __restrict__ offsets, int episodes,
                                                           int steps, float gamma, float* __restrict__ discounted) {
   const int lane = threadIdx.x & 63;
-  const int e = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int stride = (int)gridDim.x * 4;  // waves in the grid: a wave takes episodes e, e + stride, ...
+  int e = (int)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
   if (e >= episodes) return;
-  int b = offsets[e], end = offsets[e + 1];
-  b = b < 0 ? 0 : (b > steps ? steps : b);
-  end = end < b ? b : (end > steps ? steps : end);
-  float gpow[6];
-  gpow[0] = gamma;
-#pragma unroll
-  for (int i = 1; i < 6; ++i) gpow[i] = gpow[i - 1] * gpow[i - 1];
-  float carry = 0.f;
-  for (int hi = end; hi > b; hi -= 64 * kChunksInFlight) {
-    float r[kChunksInFlight];
+  const ScanWeights w = scan_weights(gamma, lane);
+
+  auto bounds = [&](int ep, int& b, int& end) {  // clamped to [0, steps]; empty for ep >= episodes
+    b = end = 0;
+    if (ep < episodes) {
+      b = offsets[ep];
+      end = offsets[ep + 1];
+      b = b < 0 ? 0 : (b > steps ? steps : b);
+      end = end < b ? b : (end > steps ? steps : end);
+    }
+  };
+  auto fetch = [&](float(&r)[kChunksInFlight], int b, int hi, int end) {  // the chunks below hi
 #pragma unroll
     for (int c = 0; c < kChunksInFlight; ++c) {
       const int t = hi - 64 * (c + 1) + lane;
       r[c] = (t >= b && t < end) ? reward[t] : 0.f;
     }
+  };
+
+  // The rewards of the wave's next episode (its last four chunks) and the bounds of the one after
+  // that are requested before the current episode is scanned, so that their memory latency
+  // overlaps the scan.
+  int b, end, nb, nend;
+  bounds(e, b, end);
+  bounds(e + stride, nb, nend);
+  float r[kChunksInFlight], rn[kChunksInFlight];
+  fetch(r, b, end, end);
+  for (;;) {
+    int nnb, nnend;
+    bounds(e + 2 * stride, nnb, nnend);
+    fetch(rn, nb, nend, nend);
+    float carry = 0.f;
+    for (int hi = end; hi > b; hi -= 64 * kChunksInFlight) {
+      if (hi != end) fetch(r, b, hi, end);  // episodes longer than four chunks: further rounds
+      float v[kChunksInFlight];
 #pragma unroll
-    for (int c = 0; c < kChunksInFlight; ++c) {
-      const int t = hi - 64 * (c + 1) + lane;
-      float v = r[c] + (lane == 63 ? gamma * carry : 0.f);
-      v = suffix_scan(v, lane, gpow);
-      if (t >= b && t < end) discounted[t] = v;
-      carry = __shfl(v, 0, 64);
+      for (int c = 0; c < kChunksInFlight; ++c) v[c] = suffix_scan(r[c], lane, w);
+#pragma unroll
+      for (int c = 0; c < kChunksInFlight; ++c) {
+        const int t = hi - 64 * (c + 1) + lane;
+        v[c] += w.to_chunk_end * carry;
+        if (t >= b && t < end) discounted[t] = v[c];
+        carry = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, v[c])));
+      }
     }
+    e += stride;
+    if (e >= episodes) break;
+    b = nb;
+    end = nend;
+    nb = nnb;
+    nend = nnend;
+#pragma unroll
+    for (int c = 0; c < kChunksInFlight; ++c) r[c] = rn[c];
   }
 }
 
@@ -77,13 +158,24 @@ __global__ __launch_bounds__(256) void pg_sigmoid_kernel(const float* __restrict
                                                          const float* __restrict__ discounted,
                                                          float* __restrict__ dlogps, float* __restrict__ bottom_diff,
                                                          int steps) {
-  const int t = blockIdx.x * 256 + threadIdx.x;
-  if (t >= steps) return;
-  const float ap = aprob[t];
-  const float d = action[t] == 0 ? 1.f - ap : 0.f - ap;
-  if (dlogps) dlogps[t] = d;
-  const float w = discounted ? discounted[t] : 1.f;
-  bottom_diff[t] = -d * w;
+  const int t = (blockIdx.x * 256 + threadIdx.x) * 4;
+  if (t + 3 < steps) {
+    const float4 ap = *reinterpret_cast<const float4*>(aprob + t);
+    const int4 ac = *reinterpret_cast<const int4*>(action + t);
+    float4 w = make_float4(1.f, 1.f, 1.f, 1.f);
+    if (discounted) w = *reinterpret_cast<const float4*>(discounted + t);
+    const float4 d = make_float4(ac.x == 0 ? 1.f - ap.x : 0.f - ap.x, ac.y == 0 ? 1.f - ap.y : 0.f - ap.y,
+                                 ac.z == 0 ? 1.f - ap.z : 0.f - ap.z, ac.w == 0 ? 1.f - ap.w : 0.f - ap.w);
+    if (dlogps) *reinterpret_cast<float4*>(dlogps + t) = d;
+    *reinterpret_cast<float4*>(bottom_diff + t) = make_float4(-d.x * w.x, -d.y * w.y, -d.z * w.z, -d.w * w.w);
+  } else {
+    for (int i = t; i < steps; ++i) {
+      const float ap = aprob[i];
+      const float d = action[i] == 0 ? 1.f - ap : 0.f - ap;
+      if (dlogps) dlogps[i] = d;
+      bottom_diff[i] = -d * (discounted ? discounted[i] : 1.f);
+    }
+  }
 }
 
 // ---- Softmax model, steps 8, 10, 11 ----
@@ -176,6 +268,8 @@ __global__ __launch_bounds__(256) void pg_softmax_wide_kernel(const float* __res
   }
 }
 
+constexpr int32_t kMaxSteps = 0x7FFF0000;  // index arithmetic of the kernels stays below 2^31
+
 int done(void) {
   const int e = (int)hipGetLastError();
   return e ? record_hip_error(e) : CONV_OK;
@@ -192,19 +286,23 @@ extern "C" {
 int pg_sigmoid_sample_action(const float* aprob, const float* random, int32_t* action, int32_t steps,
                              void* hip_stream) {
   if (steps < 0) return CONV_EINVAL;
+  if (steps > kMaxSteps) return CONV_ESHAPE;
   if (steps == 0) return CONV_OK;
   if (!aprob || !random || !action) return CONV_EINVAL;
-  hipLaunchKernelGGL(pg_sample_kernel, dim3((steps + 255) / 256), dim3(256), 0, (hipStream_t)hip_stream, aprob, random,
-                     action, steps);
+  hipLaunchKernelGGL(pg_sample_kernel, dim3((steps + 1023) / 1024), dim3(256), 0, (hipStream_t)hip_stream, aprob,
+                     random, action, steps);
   return done();
 }
 
 int pg_discount_rewards(const float* reward, const int32_t* episode_offsets, int32_t episodes, int32_t steps,
                         float gamma, float* discounted, void* hip_stream) {
   if (episodes < 0 || steps < 0) return CONV_EINVAL;
+  if (steps > kMaxSteps || episodes > kMaxSteps) return CONV_ESHAPE;
   if (episodes == 0 || steps == 0) return CONV_OK;
   if (!reward || !episode_offsets || !discounted) return CONV_EINVAL;
-  hipLaunchKernelGGL(pg_discount_kernel, dim3((episodes + 3) / 4), dim3(256), 0, (hipStream_t)hip_stream, reward,
+  int blocks = (episodes + 3) / 4;
+  if (blocks > 256 * 8) blocks = 256 * 8;  // eight resident workgroups on each of the 256 compute units
+  hipLaunchKernelGGL(pg_discount_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)hip_stream, reward,
                      episode_offsets, episodes, steps, gamma, discounted);
   return done();
 }
@@ -212,9 +310,10 @@ int pg_discount_rewards(const float* reward, const int32_t* episode_offsets, int
 int pg_sigmoid_bottom_diff(const float* aprob, const int32_t* action, const float* discounted, float* dlogps,
                            float* bottom_diff, int32_t steps, void* hip_stream) {
   if (steps < 0) return CONV_EINVAL;
+  if (steps > kMaxSteps) return CONV_ESHAPE;
   if (steps == 0) return CONV_OK;
   if (!aprob || !action || !bottom_diff) return CONV_EINVAL;
-  hipLaunchKernelGGL(pg_sigmoid_kernel, dim3((steps + 255) / 256), dim3(256), 0, (hipStream_t)hip_stream, aprob,
+  hipLaunchKernelGGL(pg_sigmoid_kernel, dim3((steps + 1023) / 1024), dim3(256), 0, (hipStream_t)hip_stream, aprob,
                      action, discounted, dlogps, bottom_diff, steps);
   return done();
 }

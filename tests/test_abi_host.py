@@ -176,6 +176,10 @@ def test_library_exports_every_declared_pg_symbol_and_checks_arguments():
     assert lib.pg_softmax_bottom_diff(fake, fake, None, None, fake, 4, 0, None) == binding.CONV_EINVAL
     assert lib.pg_softmax_bottom_diff(fake, fake, None, None, fake, 1 << 30, 2, None) == binding.CONV_ESHAPE
     assert lib.pg_softmax_bottom_diff(None, None, None, None, None, 0, 3, None) == binding.CONV_OK
+    big = 0x7FFFFFFF  # beyond what the kernels' 32-bit index arithmetic covers
+    assert lib.pg_sigmoid_sample_action(fake, fake, fake, big, None) == binding.CONV_ESHAPE
+    assert lib.pg_sigmoid_bottom_diff(fake, fake, None, None, fake, big, None) == binding.CONV_ESHAPE
+    assert lib.pg_discount_rewards(fake, fake, 4, big, 0.9, fake, None) == binding.CONV_ESHAPE
 
 
 def test_f64_entry_points_check_arguments():

@@ -12,7 +12,7 @@ profiles/hbm_traffic.json (which bench.py reports as ``roofline.traffic``).  Dis
 matched to (layer, pass) by their order inside a step (the main kernel of each pass, per layer);
 ``--workload`` names the bench.py workload the two runs were made with.
 ``sq`` condenses a run with SQ_BUSY_CYCLES SQ_WAVE_CYCLES SQ_VALU_MFMA_BUSY_CYCLES
-SQ_INSTS_VALU_MFMA_MOPS_F32 SQ_WAIT_INST_ANY SQ_LDS_BANK_CONFLICT SQ_INSTS_MFMA SQ_INSTS_VALU into MFMA
+SQ_INSTS_VALU_MFMA_MOPS_F32 (or _F64 for the double path) SQ_WAIT_INST_ANY SQ_LDS_BANK_CONFLICT SQ_INSTS_MFMA SQ_INSTS_VALU into MFMA
 utilisation per kernel (counters are summed over 32 shader engines / 1024 SIMDs of the chip).
 """
 from __future__ import annotations
@@ -107,7 +107,7 @@ def sq(directory: str) -> None:
     agg: "OrderedDict[tuple, dict]" = OrderedDict()
     for r in rows:
         name = _short(r["Kernel_Name"])
-        if not any(m in name for m in MAIN[:3]):
+        if not any(m in name for m in MAIN[:3] + ("corr64_kernel", "wgrad64_kernel")):
             continue
         key = (name[:50], int(r["Grid_Size"]) // max(int(r["Workgroup_Size"]), 1))
         agg.setdefault(key, {}).setdefault(r["Counter_Name"], []).append(float(r["Counter_Value"]))
@@ -117,7 +117,8 @@ def sq(directory: str) -> None:
         v = {k: sum(x) / len(x) for k, x in c.items()}
         cyc = v["SQ_BUSY_CYCLES"] / 32.0
         print(f"{name:50s} {blocks:6d} {cyc / 1e3:8.0f} {100 * v['SQ_VALU_MFMA_BUSY_CYCLES'] / 1024 / cyc:8.1f}% "
-              f"{v['SQ_INSTS_VALU_MFMA_MOPS_F32'] * 512 / 1e9:11.2f} {v['SQ_WAVE_CYCLES'] * 4 / 1024 / cyc:10.2f} "
+              f"{v.get('SQ_INSTS_VALU_MFMA_MOPS_F32', v.get('SQ_INSTS_VALU_MFMA_MOPS_F64', 0.0)) * 512 / 1e9:11.2f} "
+              f"{v['SQ_WAVE_CYCLES'] * 4 / 1024 / cyc:10.2f} "
               f"{100 * v['SQ_WAIT_INST_ANY'] / v['SQ_WAVE_CYCLES']:4.0f}% "
               f"{(v['SQ_INSTS_VALU'] - v['SQ_INSTS_MFMA']) / v['SQ_INSTS_MFMA']:9.2f} {v['SQ_LDS_BANK_CONFLICT']:9.0f}")
 

@@ -100,7 +100,7 @@ int conv_backward_bias(const conv_desc_t* d, const float* dy, float* db, float b
                        void* ws, size_t ws_bytes, void* hip_stream);
 
 /*
- * Double base type (the paper builds every layer for a "float or double base type", section after
+ * Double base type (the paper builds every layer for either a float or a double base type, section after
  * Table 1).  The same descriptor, semantics, layouts, ownership, execution and error rules as the
  * fp32 passes above, with every blob in doubles; products and sums are fp64 (fp64 matrix
  * instructions).  The workspace size differs: use conv_desc_workspace_bytes_f64.  A descriptor

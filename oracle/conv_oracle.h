@@ -11,7 +11,7 @@
  * convolution (a cross-correlation, kernel not flipped) with num_output,
  * kernel, stride, pad, dilation, group and bias_term, over dense NCHW blobs,
  * written as direct nested loops in double precision: no lowering, no GEMM,
- * no blocking.  The "float or double base type" remark (section after Table 1)
+ * no blocking.  The paper's remark that the base type is either float or double (section after Table 1)
  * is why inputs are fp32 values widened to double by the caller.
  *
  * Layouts (all dense, last index fastest):

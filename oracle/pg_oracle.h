@@ -9,7 +9,7 @@
  *   step 8   Sigmoid:  Dlogps = (action == 0) ? 1 - Aprob : 0 - Aprob (Appendix A, "Sigmoid Gradient Calculation")
  *            Softmax:  softmax from the action logits; Dlogps = softmax - target, target = one-hot(action)
  *                                                                      (Appendix B, "Softmax Gradient Calculation")
- *   step 9   discounted rewards, "discounted backwards in time": R[t] = reward[t] + gamma * R[t+1]
+ *   step 9   discounted rewards, accumulated from the end of the episode backwards: R[t] = reward[t] + gamma * R[t+1]
  *            inside each episode, R past the episode's last step = 0
  *   step 10  modulated gradient = Dlogps * discounted reward of that step
  *   step 11  Bottom.diff of the layer feeding the loss

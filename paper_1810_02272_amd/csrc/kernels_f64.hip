@@ -1,5 +1,5 @@
-// Double-precision base type for the convolution layer (the paper builds every layer for a
-// "float or double base type", section after Table 1): the same four passes on the fp64 matrix
+// Double-precision base type for the convolution layer (the paper builds every layer for either
+// a float or a double base type, section after Table 1): the same four passes on the fp64 matrix
 // instruction v_mfma_f64_16x16x4f64.  Workgroup tiles of 96/64/48/32/16 rows by 64 columns by 16 k
 // (the row count that pads the matrix least is chosen per pass), MODE-1 style bounds checks (row
 // and column compares, out-of-image elements read as 0 through the buffer range check), a

@@ -149,3 +149,31 @@ def test_f64_beta_and_empty_batch():
     conv.conv_backward_bias_f64(de, e_y, edb, 0.0, wse)
     torch.cuda.synchronize()
     assert torch.all(edw == 0.0) and torch.all(edb == 0.0)
+
+
+def test_f64_blobs_between_2_and_4_gib():
+    """Maximum sizes of the double path: blobs of 3.0e8 doubles (2.3 GiB; the limit is 2^29 elements),
+    where byte offsets no longer fit 31 bits.  Sampled outputs, all of dw, the bias gradient in full."""
+    pd = P(19, 4, 2000, 2000, 4, 3, 3, 1, 1, 1, 1, 1, 1, 2)
+    op = OracleParams(**pd)
+    x, w, b, dy = (t.double() for t in workloads.random_inputs(oracle.x_shape(op), oracle.w_shape(op),
+                                                               oracle.output_shape(op), 5160))
+    assert x.numel() * 8 > (1 << 31)
+    d, ws, _, (y, dx, dw, db) = run_all64(pd, x, w, b, dy)
+    xn, wn, bn, dyn = x.numpy(), w.numpy(), b.numpy(), dy.numpy()
+    rng = np.random.default_rng(8)
+
+    def samples(total, count):
+        edge = np.array([0, 1, total // 2 - 1, total // 2, total - 2, total - 1])
+        return np.unique(np.concatenate([edge, rng.integers(0, total, size=count)]))
+
+    yi, xi = samples(y.numel(), 4000), samples(dx.numel(), 4000)
+    ref_y = oracle.forward_at(op, xn, wn, bn, yi)
+    ref_dx = oracle.backward_data_at(op, wn, dyn, xi)
+    ref_dw = oracle.backward_filter_at(op, xn, dyn, np.arange(dw.numel()))
+    yc, dxc = y.cpu().numpy().ravel(), dx.cpu().numpy().ravel()
+    assert np.max(np.abs(yc[yi] - ref_y)) / np.max(np.abs(ref_y)) <= TOL
+    assert np.max(np.abs(dxc[xi] - ref_dx)) / np.max(np.abs(ref_dx)) <= TOL
+    assert nerr(dw, ref_dw.reshape(tuple(w.shape))) <= TOL
+    assert nerr(db, oracle.backward_bias(op, dyn)) <= TOL
+    assert np.isfinite(yc).all() and np.isfinite(dxc).all()

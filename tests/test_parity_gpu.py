@@ -246,3 +246,74 @@ def test_runs_on_a_side_stream():
         conv.conv_forward(d, xd, wd, bd, y, ws)
     s.synchronize()
     assert nerr(y, oracle.forward(op, x.numpy(), w.numpy(), b.numpy())) <= TOL
+
+
+def test_blobs_between_2_and_4_gib():
+    """Maximum sizes: x, y, dx and dy of 2.2 GiB each (5.9e8 elements; the limit is 2^30), where byte
+    offsets no longer fit 31 bits and the kernels fall back to compare-based bounds checks.  Sampled
+    outputs the oracle computes one by one, the bias gradient in full, finiteness everywhere."""
+    pd = P(37, 4, 2000, 2000, 4, 3, 3, 1, 1, 1, 1, 1, 1, 2)
+    op = OracleParams(**pd)
+    x, w, b, dy = workloads.random_inputs(oracle.x_shape(op), oracle.w_shape(op), oracle.output_shape(op), 5150)
+    assert x.numel() * 4 > (1 << 31) and dy.numel() * 4 > (1 << 31)
+    d, ws, _, (y, dx, dw, db) = run_all(pd, x, w, b, dy)
+    print("large blobs:", conv.conv_desc_kernel_names(d), flush=True)
+    xn, wn, bn, dyn = x.numpy(), w.numpy(), b.numpy(), dy.numpy()
+    rng = np.random.default_rng(7)
+
+    def samples(total, count):
+        edge = np.array([0, 1, total // 2 - 1, total // 2, total - 2, total - 1])
+        return np.unique(np.concatenate([edge, rng.integers(0, total, size=count)]))
+
+    yi, xi = samples(y.numel(), 4000), samples(dx.numel(), 4000)
+    wi = np.arange(dw.numel())
+    ref_y = oracle.forward_at(op, xn, wn, bn, yi)
+    ref_dx = oracle.backward_data_at(op, wn, dyn, xi)
+    ref_dw = oracle.backward_filter_at(op, xn, dyn, wi)
+    yc, dxc = y.cpu().numpy().ravel(), dx.cpu().numpy().ravel()
+    assert np.max(np.abs(yc[yi].astype(np.float64) - ref_y)) / np.max(np.abs(ref_y)) <= TOL
+    assert np.max(np.abs(dxc[xi].astype(np.float64) - ref_dx)) / np.max(np.abs(ref_dx)) <= TOL
+    assert nerr(dw, ref_dw.reshape(tuple(w.shape))) <= TOL
+    assert nerr(db, oracle.backward_bias(op, dyn)) <= TOL
+    assert np.isfinite(yc).all() and np.isfinite(dxc).all()
+
+
+def test_one_descriptor_two_threads_two_streams():
+    """A descriptor is immutable and may be shared between threads; passes on different streams need
+    their own workspace."""
+    import threading
+
+    pd = P(6, 8, 21, 19, 12, 3, 3, 1, 1, 1, 1, 1, 1, 2)
+    op = OracleParams(**pd)
+    d = conv.conv_desc_create(conv.ConvParams(**pd))
+    ws_elems = max(conv.conv_desc_workspace_bytes(d) // 4, 1)
+    results, errors = {}, []
+
+    def worker(idx):
+        try:
+            torch.cuda.set_device(0)
+            x, w, b, dy = workloads.random_inputs(oracle.x_shape(op), oracle.w_shape(op), oracle.output_shape(op),
+                                                  6000 + idx)
+            s = torch.cuda.Stream()
+            with torch.cuda.stream(s):
+                ws = torch.zeros(ws_elems, device=DEV)
+                xd, wd, bd, dyd = x.to(DEV), w.to(DEV), b.to(DEV), dy.to(DEV)
+                y, dx, dw = torch.empty_like(dyd), torch.empty_like(xd), torch.empty_like(wd)
+                for _ in range(20):
+                    conv.conv_forward(d, xd, wd, bd, y, ws, s)
+                    conv.conv_backward_data(d, wd, dyd, dx, ws, s)
+                    conv.conv_backward_filter(d, xd, dyd, dw, 0.0, ws, s)
+            s.synchronize()
+            results[idx] = (nerr(y, oracle.forward(op, x.numpy(), w.numpy(), b.numpy())),
+                            nerr(dx, oracle.backward_data(op, w.numpy(), dy.numpy())),
+                            nerr(dw, oracle.backward_filter(op, x.numpy(), dy.numpy())))
+        except Exception as e:  # surfaced by the assertion below
+            errors.append(repr(e))
+
+    threads = [threading.Thread(target=worker, args=(i,)) for i in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+    assert len(results) == 2 and all(v <= TOL for r in results.values() for v in r), results

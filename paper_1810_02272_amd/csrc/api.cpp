@@ -135,19 +135,37 @@ void configure_patch(CorrArgs& a, PackArgs& k, int64_t cg_in, int64_t n_img, int
   k.kperm_T = (int32_t)T;
 }
 
-// Split of the reduction for small problems: with few workgroups and a long chunk loop the chip
-// idles while each workgroup walks its chunks one barrier at a time; S slices run side by side and
-// a reduce kernel adds them.  Only worth an extra launch when the grid is well under one
-// workgroup per compute unit.
+// Split of the reduction: with few workgroups and a long chunk loop the chip idles while each
+// workgroup walks its chunks one barrier at a time; S slices run side by side and a reduce kernel
+// adds them.  Worth an extra launch when the grid is well under one workgroup per compute unit,
+// or when a large problem leaves the compute units unevenly loaded.
 void configure_ksplit(CorrArgs& a, int64_t out_elems) {
   a.ksplit = 1;
   a.chunks_per_split = a.KP / 16;
   a.out_elems = (int32_t)out_elems;
   const int64_t units = (int64_t)a.G * a.m_tiles * a.col_tiles, chunks = a.KP / 16;
-  if (a.use_patch || units > 160 || chunks < 8 || a.ncols < 1) return;
-  int64_t S = ceil_div(512, units);
-  if (S > chunks / 4) S = chunks / 4;
-  if (S > 16) S = 16;
+  if (a.use_patch || chunks < 8 || a.ncols < 1) return;
+  int64_t S = 1;
+  if (units <= 160) {
+    S = ceil_div(512, units);
+    if (S > chunks / 4) S = chunks / 4;
+    if (S > 16) S = 16;
+  } else if (units < 512 && 2.0 * a.Mrows * a.Kred * (double)a.ncols * a.G >= 5e9) {
+    // Mid-sized grids of a large problem (a 14x14 or 7x7 layer with hundreds of channels): one or
+    // two workgroups per compute unit with some units idle.  Take the split that brings the load
+    // of the busiest unit, relative to the unsplit grid, down by at least 15 % (20 % when the
+    // unsplit grid already has two workgroups on some units; 1 % per slice charged for the partial
+    // sums); every slice keeps at least 16 chunks.
+    const double base = (double)ceil_div(units, 256);
+    double best = base > 1.0 ? 0.80 : 0.85;
+    for (int64_t c = 2; c <= 8 && chunks / c >= 16; ++c) {
+      const double ratio = (double)ceil_div(units * c, 256) / ((double)c * base) * (1.0 + 0.01 * (double)c);
+      if (ratio < best) {
+        best = ratio;
+        S = c;
+      }
+    }
+  }
   if (S < 2) return;
   a.chunks_per_split = (int32_t)ceil_div(chunks, S);
   a.ksplit = (int32_t)ceil_div(chunks, a.chunks_per_split);

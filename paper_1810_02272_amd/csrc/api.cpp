@@ -96,6 +96,56 @@ int32_t bounds_mode(bool no_padding, int64_t taps, int64_t bytes, int64_t reach)
   return 1;
 }
 
+// One spatial dimension of the backward-data rewriting.  Input position x + pad = stride*a + r
+// collects the taps i with i*dilation = stride*q + r from dy position a - q.
+//  - Only the phases r in { i*dilation mod stride : i < kernel } are reached by any tap; when that
+//    is a proper subset of 0 .. stride-1 of at most kMaxPhases values, the row space keeps only
+//    those (a 1x1 stride-2 layer: one phase of four) and the rest of dx is zero-filled.
+//  - When the stride divides the dilation (stride 1 included) the only phase is 0 and the taps sit
+//    e = dilation/stride positions apart: kernel slots instead of (kernel-1)*dilation/stride + 1.
+struct PhaseDim {
+  int64_t Q, e, nv;
+  int32_t tab;
+  int32_t phase[kMaxPhases];
+};
+
+PhaseDim phase_dim(int64_t kernel, int64_t stride, int64_t dilation) {
+  PhaseDim r = {};
+  if (dilation % stride == 0) {
+    r.Q = kernel;
+    r.e = dilation / stride;
+  } else {
+    r.Q = (kernel - 1) * dilation / stride + 1;
+    r.e = 1;
+  }
+  int64_t found = 0;
+  int32_t vals[kMaxPhases];
+  for (int64_t i = 0; i < kernel && found <= kMaxPhases; ++i) {
+    const int32_t v = (int32_t)((i * dilation) % stride);
+    bool seen = false;
+    for (int64_t j = 0; j < found && j < kMaxPhases; ++j) seen = seen || vals[j] == v;
+    if (!seen) {
+      if (found < kMaxPhases) vals[found] = v;
+      ++found;
+    }
+  }
+  if (found >= stride || found > kMaxPhases) {  // every phase reached, or too many to tabulate
+    r.nv = stride;
+    r.tab = 0;
+    return r;
+  }
+  for (int64_t i = 1; i < found; ++i)  // ascending order
+    for (int64_t j = i; j > 0 && vals[j - 1] > vals[j]; --j) {
+      const int32_t t = vals[j];
+      vals[j] = vals[j - 1];
+      vals[j - 1] = t;
+    }
+  r.nv = found;
+  r.tab = 1;
+  for (int64_t i = 0; i < found; ++i) r.phase[i] = vals[i];
+  return r;
+}
+
 uint32_t koff_invalid(int32_t mode) { return mode == 0 ? 0x7FFFFFFCu : mode == 2 ? 0x40000000u : 0u; }
 
 // Decides whether the patch-staged kernel can run this correlation and, if so, fills its fields.
@@ -240,6 +290,13 @@ int run_backward_data(const conv_desc* d, const float* w, const float* dy, float
   a.out = dx;
   a.accumulate = beta != 0.f;
   a.part = reinterpret_cast<float*>(static_cast<char*>(ws) + d->bwd_pack_bytes);
+  if (d->bwd_zero_fill) {  // positions no tap reaches: zero the split partials, or dx itself when it is overwritten
+    if (a.ksplit > 1)
+      e = launch_fill_zero(a.part, (size_t)a.ksplit * a.out_elems * 4, hip_stream);
+    else if (beta == 0.f)
+      e = launch_fill_zero(dx, (size_t)a.out_elems * 4, hip_stream);
+    if (e) return record_hip_error(e);
+  }
   e = a.use_patch ? launch_corr_patch(d->bwd_tile, a, hip_stream) : launch_corr(d->bwd_tile, a, hip_stream);
   if (e) return record_hip_error(e);
   if (a.ksplit > 1) {
@@ -356,6 +413,7 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
     a.Mrows = (int32_t)Kg;
     a.MP = (int32_t)round_up(Kg, bm);
     a.RSh = a.RSw = a.RShw = 1;
+    a.OSh = a.OSw = 1;
     a.mRSw = make_magic(1);
     a.mRShw = make_magic(1);
     a.opad_h = a.opad_w = 0;
@@ -399,16 +457,19 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
 
   // ---- backward data: a stride-1 correlation over dy whose rows are (c, row phase, column
   // phase) of dx -- input position h + pad = stride*a + rh collects the taps i with
-  // i*dilation = stride*q + rh from dy row a - q, q = 0 .. Q-1.  Positions with a < a0 =
-  // pad / stride lie wholly in the padding, so the column space starts at a0. ----
+  // i*dilation = stride*q + rh from dy row a - q (see phase_dim for the tap slots and the phases
+  // kept).  Positions with a < a0 = pad / stride lie wholly in the padding, so the column space
+  // starts at a0. ----
   {
-    const int64_t Qh = ((int64_t)p.kernel_h - 1) * p.dilation_h / p.stride_h + 1;
-    const int64_t Qw = ((int64_t)p.kernel_w - 1) * p.dilation_w / p.stride_w + 1;
+    const PhaseDim dim_h = phase_dim(p.kernel_h, p.stride_h, p.dilation_h);
+    const PhaseDim dim_w = phase_dim(p.kernel_w, p.stride_w, p.dilation_w);
+    const int64_t Qh = dim_h.Q, Qw = dim_w.Q;
     const int64_t a0h = p.pad_h / p.stride_h, a0w = p.pad_w / p.stride_w;
     const int64_t Ah = (H - 1 + p.pad_h) / p.stride_h + 1 - a0h;
     const int64_t Aw = (W - 1 + p.pad_w) / p.stride_w + 1 - a0w;
-    const int64_t rows = Cg * p.stride_h * p.stride_w;
+    const int64_t rows = Cg * dim_h.nv * dim_w.nv;
     const int64_t kred_b = Kg * Qh * Qw;
+    d->bwd_zero_fill = dim_h.nv < p.stride_h || dim_w.nv < p.stride_w;
     if (rows >= ((int64_t)1 << 24) || N * Ah * Aw >= ((int64_t)1 << 31) || kred_b >= kMaxElems) {
       delete d;
       return CONV_ESHAPE;
@@ -427,23 +488,34 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
     a.in_img_stride = (int32_t)(K * OH * OW);
     a.in_grp_stride = (int32_t)(Kg * OH * OW);
     a.in_bytes = (uint32_t)(4 * y_elems);
-    a.bounds_mode = bounds_mode(false, Qh * Qw, 4 * y_elems, 4 * (2 * Qh * OW + 2 * Qw));
+    a.bounds_mode = bounds_mode(false, Qh * Qw, 4 * y_elems,
+                                4 * (2 * ((Qh - 1) * dim_h.e + 1) * OW + 2 * ((Qw - 1) * dim_w.e + 1)));
     a.TW = (int32_t)Qw;
     a.THW = (int32_t)(Qh * Qw);
     a.mTW = make_magic(a.TW);
     a.mTHW = make_magic(a.THW);
-    a.sh = a.sw = a.dh = a.dw = 1;
-    a.ph = (int32_t)(Qh - 1 - a0h);
-    a.pw = (int32_t)(Qw - 1 - a0w);
+    a.sh = a.sw = 1;
+    a.dh = (int32_t)dim_h.e;
+    a.dw = (int32_t)dim_w.e;
+    a.ph = (int32_t)((Qh - 1) * dim_h.e - a0h);
+    a.pw = (int32_t)((Qw - 1) * dim_w.e - a0w);
     a.Kred = (int32_t)kred_b;
     a.KP = (int32_t)round_up(kred_b, bk);
     a.Mrows = (int32_t)rows;
     a.MP = (int32_t)round_up(rows, bm);
-    a.RSh = p.stride_h;
-    a.RSw = p.stride_w;
-    a.RShw = p.stride_h * p.stride_w;
+    a.RSh = (int32_t)dim_h.nv;
+    a.RSw = (int32_t)dim_w.nv;
+    a.RShw = a.RSh * a.RSw;
     a.mRSw = make_magic(a.RSw);
     a.mRShw = make_magic(a.RShw);
+    a.OSh = p.stride_h;
+    a.OSw = p.stride_w;
+    a.tab_h = dim_h.tab;
+    a.tab_w = dim_w.tab;
+    for (int i = 0; i < kMaxPhases; ++i) {
+      a.phase_h[i] = dim_h.phase[i];
+      a.phase_w[i] = dim_w.phase[i];
+    }
     a.opad_h = (int32_t)(p.pad_h - a0h * p.stride_h);
     a.opad_w = (int32_t)(p.pad_w - a0w * p.stride_w);
     a.OHd = p.h;
@@ -466,6 +538,16 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
     k.dw = p.dilation_w;
     k.Qh = (int32_t)Qh;
     k.Qw = (int32_t)Qw;
+    k.nvh = a.RSh;
+    k.nvw = a.RSw;
+    k.eh = a.dh;
+    k.ew = a.dw;
+    k.tab_h = a.tab_h;
+    k.tab_w = a.tab_w;
+    for (int i = 0; i < kMaxPhases; ++i) {
+      k.phase_h[i] = a.phase_h[i];
+      k.phase_w[i] = a.phase_w[i];
+    }
     k.Kred = a.Kred;
     k.KP = a.KP;
     k.Mrows = a.Mrows;
@@ -705,10 +787,14 @@ int conv_desc_workspace_bytes_f64(const conv_desc_t* d, size_t* bytes) {
 }
 
 static int run_corr64(const conv_desc_t* d, int32_t tile_rows, const CorrArgs& args, const PackArgs& pack, size_t need,
-                      const double* w, const double* in, const double* bias, double* out, void* ws,
-                      size_t ws_bytes, void* hip_stream) {
+                      const double* w, const double* in, const double* bias, double* out, size_t zero_out_bytes,
+                      void* ws, size_t ws_bytes, void* hip_stream) {
   if (!d->f64_ok) return CONV_ESHAPE;
   if (!ws || ws_bytes < need) return CONV_EWORKSPACE;
+  if (zero_out_bytes) {  // backward data with row / column phases no tap reaches
+    const int ez = launch_fill_zero(out, zero_out_bytes, hip_stream);
+    if (ez) return record_hip_error(ez);
+  }
   PackArgs k = pack;
   k.w = reinterpret_cast<const float*>(w);
   k.A = static_cast<float*>(ws);
@@ -731,7 +817,8 @@ int conv_forward_f64(const conv_desc_t* d, const double* x, const double* w, con
   if ((d->p.bias_term != 0) != (bias != nullptr)) return CONV_EINVAL;
   if (d->p.n == 0) return CONV_OK;
   if (!x || !y) return CONV_EINVAL;
-  return run_corr64(d, d->fwd64_rows, d->fwd64, d->fwd64_pack, d->fwd64_ws, w, x, bias, y, ws, ws_bytes, hip_stream);
+  return run_corr64(d, d->fwd64_rows, d->fwd64, d->fwd64_pack, d->fwd64_ws, w, x, bias, y, 0, ws, ws_bytes,
+                    hip_stream);
 }
 
 int conv_backward_data_f64(const conv_desc_t* d, const double* w, const double* dy, double* dx, void* ws,
@@ -739,7 +826,9 @@ int conv_backward_data_f64(const conv_desc_t* d, const double* w, const double* 
   if (!d || !w) return CONV_EINVAL;
   if (d->p.n == 0) return CONV_OK;
   if (!dy || !dx) return CONV_EINVAL;
-  return run_corr64(d, d->bwd64_rows, d->bwd64, d->bwd64_pack, d->bwd64_ws, w, dy, nullptr, dx, ws, ws_bytes, hip_stream);
+  const size_t zero = d->bwd_zero_fill ? (size_t)d->bwd64.out_elems * 8 : 0;
+  return run_corr64(d, d->bwd64_rows, d->bwd64, d->bwd64_pack, d->bwd64_ws, w, dy, nullptr, dx, zero, ws, ws_bytes,
+                    hip_stream);
 }
 
 int conv_backward_filter_f64(const conv_desc_t* d, const double* x, const double* dy, double* dw, double beta,

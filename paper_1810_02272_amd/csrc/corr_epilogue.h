@@ -33,8 +33,10 @@ __device__ __forceinline__ void corr_epilogue(const CorrArgs& a, float* smem, Ac
     if (gm < (uint32_t)a.Mrows) {
       const uint32_t c = mdiv(gm, a.mRShw);
       const uint32_t rem = gm - c * a.RShw;
-      const uint32_t rh = mdiv(rem, a.mRSw);
-      const uint32_t rw = rem - rh * a.RSw;
+      uint32_t rh = mdiv(rem, a.mRSw);
+      uint32_t rw = rem - rh * a.RSw;
+      if (a.tab_h) rh = (uint32_t)a.phase_h[rh];
+      if (a.tab_w) rw = (uint32_t)a.phase_w[rw];
       const uint32_t chan = g * a.chan_per_grp + c;
       hh = (int)rh - a.opad_h;
       ww = (int)rw - a.opad_w;
@@ -51,8 +53,8 @@ __device__ __forceinline__ void corr_epilogue(const CorrArgs& a, float* smem, Ac
       const uint32_t pix = col - n * a.P;
       const uint32_t pa = mdiv(pix, a.mPW);
       const uint32_t pb = pix - pa * a.PW;
-      hh = (int)pa * a.RSh;
-      ww = (int)pb * a.RSw;
+      hh = (int)pa * a.OSh;
+      ww = (int)pb * a.OSw;
       off = (int)(n * (uint32_t)a.out_img_stride) + hh * a.OWd + ww;
     }
     coltab[cl] = make_int4(off, hh, ww, 0);

@@ -39,6 +39,8 @@ struct KTabEntry {
   int32_t tap;  // i*TW + j (mod 32): bit index into a column's tap bitmask
 };
 
+constexpr int kMaxPhases = 8;  // phase tables of the backward-data row space (larger sets stay dense)
+
 struct CorrArgs {
   const float* A;     // packed operand, [G][MP][KP] floats, zero padded
   const KTabEntry* ktab;  // [KP], written by the pack kernel
@@ -59,11 +61,16 @@ struct CorrArgs {
   int32_t sh, sw, dh, dw, ph, pw;
   int32_t Kred, KP;   // reduction length and its padded size (multiple of the k tile)
   int32_t Mrows, MP;  // rows per group and padded rows (multiple of the m tile)
-  // epilogue: row m = (c*RSh + rh)*RSw + rw lands at channel g*chan_per_grp + c,
-  // spatial (a*RSh + rh - opad_h, b*RSw + rw - opad_w) of an [N][*][OHd][OWd] blob
+  // epilogue: row m = (c*RSh + ph)*RSw + pw lands at channel g*chan_per_grp + c, spatial
+  // (a*OSh + rh - opad_h, b*OSw + rw - opad_w) of an [N][*][OHd][OWd] blob, where rh = ph, or
+  // phase_h[ph] when tab_h is set (backward data keeps only the row phases that some tap reaches:
+  // RSh of the OSh phases; the same for columns).  Forward: everything 1.
   int32_t RSw, RShw;
   Magic mRSw, mRShw;
   int32_t RSh;
+  int32_t OSh, OSw;
+  int32_t tab_h, tab_w;
+  int32_t phase_h[kMaxPhases], phase_w[kMaxPhases];
   int32_t opad_h, opad_w;
   int32_t OHd, OWd;
   int32_t out_img_stride;
@@ -93,7 +100,7 @@ constexpr int kPatchEPT = 3;  // patch elements per thread and channel: PSZ <= 3
 // Packs the weights into the A operand of the correlation kernel.
 //   mode 0 (forward): A[g][m][kk] = w[g*Kg + m][kk]
 //   mode 1 (backward data): rows m = (c, rh, rw), kk = (k, qh', qw'); the entry is
-//     w[g*Kg + k][c][i][j] with i*dil_h = stride_h*(Qh-1-qh') + rh (and likewise j), else 0.
+//     w[g*Kg + k][c][i][j] with i*dil_h = stride_h*eh*(Qh-1-qh') + rh (and likewise j), else 0.
 struct PackArgs {
   const float* w;
   float* A;
@@ -104,6 +111,11 @@ struct PackArgs {
   int32_t G, Kg, Cg, kh, kw;
   int32_t sh, sw, dh, dw;
   int32_t Qh, Qw;
+  // backward data: nvh x nvw row phases per channel (phase value = index, or phase_h[index] when
+  // tab_h is set); tap slot q of a phase sits q*eh rows of dy away
+  int32_t nvh, nvw, eh, ew;
+  int32_t tab_h, tab_w;
+  int32_t phase_h[kMaxPhases], phase_w[kMaxPhases];
   int32_t Kred, KP, Mrows, MP;
   int32_t kperm_T;  // 0, or the tap count T: k runs (8-channel chunk, tap, channel in chunk) instead of (c, tap)
 };
@@ -197,6 +209,7 @@ int launch_corr_patch(int32_t tile, const CorrArgs& a, void* stream);
 int launch_wgrad(int32_t tile, const WgradArgs& a, void* stream);
 int launch_reduce(const ReduceArgs& a, void* stream);
 int launch_bias_grad(const BiasGradArgs& a, void* stream);
+int launch_fill_zero(void* dst, size_t bytes, void* stream);  // bytes a multiple of 4
 // double base type: the same argument structs, pointer members addressing doubles
 constexpr int32_t kF64TileCols = 64, kF64TileK = 16;
 int32_t f64_pick_rows(int64_t rows, bool filter_gradient);  // 96, 64, 48, 32 or 16: pads `rows` least
@@ -241,6 +254,7 @@ struct conv_desc {
   mi355conv::CorrArgs bwd;
   mi355conv::PackArgs bwd_pack;
   size_t bwd_ws, bwd_pack_bytes;
+  int32_t bwd_zero_fill;  // some row / column phases of dx are reached by no tap: zero dx first
   // backward filter
   int32_t wg_tile;
   mi355conv::WgradArgs wg;

@@ -55,7 +55,25 @@ __global__ __launch_bounds__(256) void bias_grad_kernel(const BiasGradArgs a) {
   if (threadIdx.x == 0) a.part[(size_t)s * a.K + k] = (wsum[0] + wsum[1]) + (wsum[2] + wsum[3]);
 }
 
+// Zero fill, 16 bytes per thread (the tail word by word).
+__global__ __launch_bounds__(256) void fill_zero_kernel(float* __restrict__ dst, size_t words) {
+  const size_t i = ((size_t)blockIdx.x * 256 + threadIdx.x) * 4;
+  if (i + 3 < words) {
+    *reinterpret_cast<float4*>(dst + i) = make_float4(0.f, 0.f, 0.f, 0.f);
+  } else {
+    for (size_t j = i; j < words; ++j) dst[j] = 0.f;
+  }
+}
+
 }  // namespace
+
+int launch_fill_zero(void* dst, size_t bytes, void* stream) {
+  const size_t words = bytes / 4;
+  if (words == 0) return 0;
+  hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((words + 1023) / 1024)), dim3(256), 0, (hipStream_t)stream,
+                     static_cast<float*>(dst), words);
+  return (int)hipGetLastError();
+}
 
 int launch_bias_grad(const BiasGradArgs& a, void* stream) {
   hipLaunchKernelGGL(bias_grad_kernel, dim3(a.K, a.S), dim3(256), 0, (hipStream_t)stream, a);

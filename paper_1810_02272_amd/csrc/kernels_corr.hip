@@ -319,7 +319,10 @@ __global__ __launch_bounds__(256) void pack_fwd_kernel(const PackArgs a) {
 // Backward data: rows are (input channel, row phase, column phase), k is (output channel,
 // flipped reduced tap).  Phase (rh, rw) of input position h + pad = stride*a + rh is reached by
 // tap i exactly when i*dilation = stride*q + rh for an integer q >= 0; the gather then reads
-// dy at a - q.  Entries with no such tap are zero.
+// dy at a - q.  Only phases that some tap reaches have rows (the others are zero-filled by the
+// host code), and when the stride divides the dilation -- stride 1 included -- the taps sit eh =
+// dilation/stride rows of dy apart, so slot qh stands for q = qh*eh.  Entries with no such tap
+// are zero.
 template <typename T>
 __global__ __launch_bounds__(256) void pack_bwd_kernel(const PackArgs a) {
   const size_t total = (size_t)a.G * a.MP * a.KP;
@@ -335,10 +338,12 @@ __global__ __launch_bounds__(256) void pack_bwd_kernel(const PackArgs a) {
     const int QQ = a.Qh * a.Qw;
     const int k = kk / QQ, qr = kk % QQ;
     const int qh = a.Qh - 1 - qr / a.Qw, qw = a.Qw - 1 - qr % a.Qw;
-    const int ss = a.sh * a.sw;
-    const int c = m / ss, mr = m % ss;
-    const int rh = mr / a.sw, rw = mr % a.sw;
-    const int th = a.sh * qh + rh, tw = a.sw * qw + rw;
+    const int nv = a.nvh * a.nvw;
+    const int c = m / nv, mr = m % nv;
+    int rh = mr / a.nvw, rw = mr % a.nvw;
+    if (a.tab_h) rh = a.phase_h[rh];
+    if (a.tab_w) rw = a.phase_w[rw];
+    const int th = a.sh * a.eh * qh + rh, tw = a.sw * a.ew * qw + rw;
     if (th % a.dh == 0 && tw % a.dw == 0) {
       const int i = th / a.dh, j = tw / a.dw;
       if (i < a.kh && j < a.kw) v = w[((((size_t)g * a.Kg + k) * a.Cg + c) * a.kh + i) * a.kw + j];

@@ -100,6 +100,15 @@ SWEEP = [
     P(1, 200, 7, 7, 50, 3, 3, 1, 1, 1, 1),                  # long reduction, 50 rows (split reduction)
     P(3, 5, 30, 27, 12, 7, 7, 2, 2, 3, 3),                  # 49 taps with padding: compare-based bounds mode
     P(2, 16, 24, 24, 8, 6, 6, 1, 1, 2, 2),                  # 36 taps at stride 1: backward-data bitmask does not apply
+    # backward-data row space: phases no tap reaches are dropped and dx zero-filled; taps spaced
+    # dilation/stride apart when the stride divides the dilation
+    P(4, 24, 15, 14, 40, 1, 1, 2, 2),                       # 1x1 stride 2: one phase of four
+    P(3, 8, 17, 17, 12, 1, 1, 3, 3, 1, 2),                  # 1x1 stride 3 with padding: one phase of nine
+    P(2, 6, 23, 21, 10, 2, 2, 4, 4, 0, 1),                  # 2x2 stride 4: phases {0, 1} of four (table)
+    P(1, 16, 9, 9, 300, 1, 1, 2, 2),                        # zero fill together with a split reduction
+    P(2, 12, 29, 29, 16, 5, 5, 1, 1, 4, 4, 2, 2),           # 5x5 dilation 2 stride 1: five spaced slots, not nine
+    P(2, 8, 31, 30, 8, 3, 3, 2, 2, 2, 2, 4, 4),             # stride 2 dilation 4: one phase, slots two rows apart
+    P(2, 8, 26, 26, 8, 3, 2, 3, 2, 1, 1, 2, 3, 2),          # neither divides: dense slots, all phases
 ]
 
 # Shapes that select the patch-staged kernel (256-column tiles of the 16-row MFMA): 48 or <= 16

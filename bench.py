@@ -226,6 +226,11 @@ def main():
             elif name == "bwd_bias":  # one read of dy: the HBM-bound pass
                 row["bwd_bias_GBps"] = round(dy_bytes(l) * (2 if f64 else 1) / ms / 1e6, 1)
         row["fwd_bwd_tflops"] = round(3 * l.flop_per_pass / tot / 1e9, 2)
+        if not is_ip and l.name in ("1.a", "3.a", "4.a", "5.a"):
+            # first layer of its network: real training skips its backward-data pass (no gradient
+            # flows into the data), so also give the rate over forward + backward filter + backward bias
+            row["first_layer_without_bwd_data_tflops"] = round(
+                2 * l.flop_per_pass / (tot - row["bwd_data_ms"]) / 1e9, 2)
         row["fwd_bwd_frac_of_%s_mfma_peak" % ("fp64" if f64 else "fp32")] = round(
             3 * l.flop_per_pass / tot / 1e9 / peak, 4)
         per_layer.append(row)

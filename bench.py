@@ -44,6 +44,9 @@ def parse():
                     help="rotate every step among enough distinct sets of tensors that one pass over all sets "
                          "exceeds 512 MB (twice the 256 MB last-level cache), so no operand of a pass is still "
                          "cached from the step before")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step in a HIP graph and time its replays (no per-pass times): what the "
+                         "microsecond-scale layers cost without the per-dispatch launch gaps")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run plain 256 MiB device copies (outside the timed region) so that a rocprofv3 "
                          "--pmc FETCH_SIZE / WRITE_SIZE run of this command holds a kernel of known traffic")
@@ -130,6 +133,9 @@ def main():
     kernel_names_of = conv.ip_desc_kernel_names if is_ip else conv.conv_desc_kernel_names
 
     def run_pass(t, name):
+        run_pass_on(t, name, stream)
+
+    def run_pass_on(t, name, stream):
         d = t["desc"]
         if is_ip:
             if name == "fwd":
@@ -192,6 +198,33 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+
+    if args.graph:
+        if args.cold_cache:
+            print("--graph replays one captured step: it cannot rotate tensor sets (--cold-cache)", file=sys.stderr)
+            sys.exit(2)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for t in state:
+                for name in passes:
+                    run_pass_on(t, name, torch.cuda.current_stream())
+        for _ in range(args.warmup):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        flop_step = 3 * sum(l.flop_per_pass for l in layers)
+        print(json.dumps({
+            "metric": "fwd+bwd GFLOP/s, one captured step replayed as a HIP graph, " + args.dtype,
+            "value": round(flop_step * args.steps / wall / 1e9, 1), "unit": "GFLOP/s", "n_gpus": 1,
+            "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(wall / args.steps * 1e3, 4),
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
+            "config": {"workload": f"{args.workload}: layers " + ",".join(l.name for l in layers) + ", graph replay",
+                       "frac_of_mfma_peak": round(flop_step * args.steps / wall / 1e12 / peak, 4)}}))
+        return
 
     # ---- timed region: exactly --steps steps, HIP events around every pass on the launch stream ----
     events = []

@@ -326,3 +326,43 @@ def test_one_descriptor_two_threads_two_streams():
         t.join()
     assert not errors, errors
     assert len(results) == 2 and all(v <= TOL for r in results.values() for v in r), results
+
+
+def test_passes_can_be_captured_in_a_hip_graph():
+    """Every pass only enqueues kernels on the caller's stream (no allocation, no memset, no
+    synchronisation), so a step can be captured once and replayed: replays after changes to the
+    input buffers must match eager runs of the same inputs bit for bit."""
+    pd = P(5, 6, 18, 17, 8, 3, 3, 2, 1, 1, 1, 1, 1, 2)
+    op = OracleParams(**pd)
+    d = conv.conv_desc_create(conv.ConvParams(**pd))
+    ws = torch.zeros(max(conv.conv_desc_workspace_bytes(d) // 4, 1), device=DEV)
+    x0, w0, b0, dy0 = workloads.random_inputs(oracle.x_shape(op), oracle.w_shape(op), oracle.output_shape(op), 808)
+    xd, wd, bd, dyd = x0.to(DEV), w0.to(DEV), b0.to(DEV), dy0.to(DEV)
+    y, dx, dw, db = torch.empty_like(dyd), torch.empty_like(xd), torch.empty_like(wd), torch.empty_like(bd)
+
+    def step():
+        conv.conv_forward(d, xd, wd, bd, y, ws)
+        conv.conv_backward_data(d, wd, dyd, dx, ws)
+        conv.conv_backward_filter(d, xd, dyd, dw, 0.0, ws)
+        conv.conv_backward_bias(d, dyd, db, 0.0, ws)
+
+    step()  # warm-up outside the capture (one-time kernel attribute set-up)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for rep in range(3):
+        x1, w1, b1, dy1 = workloads.random_inputs(oracle.x_shape(op), oracle.w_shape(op), oracle.output_shape(op),
+                                                  900 + rep)
+        xd.copy_(x1.to(DEV)); wd.copy_(w1.to(DEV)); bd.copy_(b1.to(DEV)); dyd.copy_(dy1.to(DEV))
+        for t in (y, dx, dw, db):
+            t.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [t.clone() for t in (y, dx, dw, db)]
+        step()  # eager, same inputs
+        torch.cuda.synchronize()
+        for a, e in zip(got, (y, dx, dw, db)):
+            assert torch.equal(a, e)
+        assert nerr(y, oracle.forward(op, x1.numpy(), w1.numpy(), b1.numpy())) <= TOL
+        assert nerr(dw, oracle.backward_filter(op, x1.numpy(), dy1.numpy())) <= TOL

@@ -130,7 +130,8 @@ def main():
     passes = ("fwd", "relu_bwd", "bwd_data", "bwd_filter", "bwd_bias") if is_ip else (
         "fwd", "bwd_data", "bwd_filter", "bwd_bias")
     flop_passes = ("fwd", "bwd_data", "bwd_filter")
-    kernel_names_of = conv.ip_desc_kernel_names if is_ip else conv.conv_desc_kernel_names
+    kernel_names_of = (conv.ip_desc_kernel_names if is_ip else
+                       conv.conv_desc_kernel_names_f64 if f64 else conv.conv_desc_kernel_names)
 
     def run_pass(t, name):
         run_pass_on(t, name, stream)
@@ -282,9 +283,6 @@ def main():
         achieved = dlayer.flop_per_pass / (dms * 1e-3) / 1e12
         roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": peak,
                     "unit": "TFLOP/s", "frac": round(achieved / peak, 4), "traffic": None}
-    if f64:  # the double path has one tile shape per kernel
-        kernel_names = {"fwd": "corr64_64x64x16", "bwd_data": "corr64_64x64x16", "bwd_filter": "wgrad64_64x64x16",
-                        "bwd_bias": "bias_grad64"}
     roofline.update({"kernel": kernel_names.get(dp, dp), "layer": dl, "pass": dp, "avg_ms": round(dms, 5),
                      "algorithmic_gflop_per_launch": dlayer.flop_per_pass / 1e9})
     traffic_file = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "hbm_traffic.json")

@@ -107,6 +107,8 @@ int conv_backward_bias(const conv_desc_t* d, const float* dy, float* db, float b
  * with a blob of 2^29 or more elements has no double path: these functions return CONV_ESHAPE.
  */
 int conv_desc_workspace_bytes_f64(const conv_desc_t* d, size_t* bytes);
+/* Kernel variants of the double path ("fwd=...;bwd_data=...;..."); "" when the descriptor has none. */
+const char* conv_desc_kernel_names_f64(const conv_desc_t* d);
 int conv_forward_f64(const conv_desc_t* d, const double* x, const double* w, const double* bias, double* y, void* ws,
                      size_t ws_bytes, void* hip_stream);
 int conv_backward_data_f64(const conv_desc_t* d, const double* w, const double* dy, double* dx, void* ws,

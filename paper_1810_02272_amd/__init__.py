@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     conv_backward_bias_f64,
     conv_backward_data_f64,
     conv_backward_filter_f64,
+    conv_desc_kernel_names_f64,
     conv_desc_workspace_bytes_f64,
     conv_forward_f64,
     conv_backward_data,

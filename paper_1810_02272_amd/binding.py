@@ -76,6 +76,8 @@ def _load():
     lib.conv_backward_data_f64.argtypes = [vp, vp, vp, vp, vp, sz, vp]
     lib.conv_backward_filter_f64.argtypes = [vp, vp, vp, vp, dbl, vp, sz, vp]
     lib.conv_backward_bias_f64.argtypes = [vp, vp, vp, dbl, vp, sz, vp]
+    lib.conv_desc_kernel_names_f64.restype = ctypes.c_char_p
+    lib.conv_desc_kernel_names_f64.argtypes = [vp]
     lib.conv_status_string.restype = ctypes.c_char_p
     lib.conv_status_string.argtypes = [ctypes.c_int]
     lib.conv_last_hip_error.restype = ctypes.c_int
@@ -218,6 +220,10 @@ def conv_desc_workspace_bytes_f64(desc: ConvDesc) -> int:
     b = ctypes.c_size_t()
     _check(_load().conv_desc_workspace_bytes_f64(desc.handle, ctypes.byref(b)), "conv_desc_workspace_bytes_f64")
     return int(b.value)
+
+
+def conv_desc_kernel_names_f64(desc: ConvDesc) -> str:
+    return _load().conv_desc_kernel_names_f64(desc.handle).decode()
 
 
 def conv_forward_f64(desc, x, w, bias, y, ws=None, stream=None) -> None:

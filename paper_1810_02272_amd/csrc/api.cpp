@@ -699,6 +699,9 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
     if (a.S * w_elems >= max64 || tiles * a.S >= ((int64_t)1 << 31)) d->f64_ok = 0;
     d->wg64_ws = (size_t)a.S * (size_t)w_elems * 8;
     d->bg64_ws = 2 * d->bg_ws;
+    snprintf(d->names64, sizeof(d->names64),
+             "fwd=corr64_%dx64x16;bwd_data=corr64_%dx64x16;bwd_filter=wgrad64_%dx64x16(S=%d);bwd_bias=bias_grad64(S=%d)",
+             d->fwd64_rows, d->bwd64_rows, d->wg64_rows, a.S, d->bg.S);
     d->ws_bytes64 = d->fwd64_ws;
     if (d->bwd64_ws > d->ws_bytes64) d->ws_bytes64 = d->bwd64_ws;
     if (d->wg64_ws > d->ws_bytes64) d->ws_bytes64 = d->wg64_ws;
@@ -778,6 +781,8 @@ int conv_backward_bias(const conv_desc_t* d, const float* dy, float* db, float b
 }
 
 // ---- double base type ----
+
+const char* conv_desc_kernel_names_f64(const conv_desc_t* d) { return d && d->f64_ok ? d->names64 : ""; }
 
 int conv_desc_workspace_bytes_f64(const conv_desc_t* d, size_t* bytes) {
   if (!d || !bytes) return CONV_EINVAL;

@@ -187,6 +187,7 @@ def test_f64_entry_points_check_arguments():
     d = conv.conv_desc_create(conv.ConvParams(2, 4, 8, 8, 4, 3, 3))
     dn = conv.conv_desc_create(conv.ConvParams(2, 4, 8, 8, 4, 3, 3, bias_term=0))
     assert conv.conv_desc_workspace_bytes_f64(d) > 0
+    assert "fwd=corr64_" in conv.conv_desc_kernel_names_f64(d)
     fake = ctypes.c_void_p(256)  # never dereferenced: every call below fails before any launch
     assert lib.conv_forward_f64(None, fake, fake, fake, fake, None, 0, None) == binding.CONV_EINVAL
     assert lib.conv_forward_f64(d.handle, fake, fake, None, fake, None, 0, None) == binding.CONV_EINVAL
@@ -204,3 +205,4 @@ def test_f64_entry_points_check_arguments():
         conv.conv_desc_workspace_bytes_f64(big)
     assert e.value.status == binding.CONV_ESHAPE
     assert lib.conv_forward_f64(big.handle, fake, fake, fake, fake, fake, 1 << 40, None) == binding.CONV_ESHAPE
+    assert conv.conv_desc_kernel_names_f64(big) == ""

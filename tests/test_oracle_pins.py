@@ -294,3 +294,51 @@ def test_against_torch_float64(p):
     np.testing.assert_allclose(oracle.backward_filter(p, x, dy), tw.grad.numpy(), atol=1e-10)
     if b is not None:
         np.testing.assert_allclose(oracle.backward_bias(p, dy), tb.grad.numpy(), atol=1e-10)
+
+
+def _im2col_reference(p, x, w, b):
+    """The lowering route: unfold x into a (c'*kh*kw) x (oh*ow) matrix per image and group, multiply by
+    the group's weight matrix with numpy -- none of the oracle's loop structure."""
+    OH = (p.h + 2 * p.pad_h - p.dilation_h * (p.kernel_h - 1) - 1) // p.stride_h + 1
+    OW = (p.w + 2 * p.pad_w - p.dilation_w * (p.kernel_w - 1) - 1) // p.stride_w + 1
+    Cg, Kg = p.c // p.group, p.num_output // p.group
+    xp = np.zeros((p.n, p.c, p.h + 2 * p.pad_h, p.w + 2 * p.pad_w))
+    xp[:, :, p.pad_h:p.pad_h + p.h, p.pad_w:p.pad_w + p.w] = x
+    y = np.zeros((p.n, p.num_output, OH, OW))
+    for n in range(p.n):
+        for g in range(p.group):
+            col = np.empty((Cg * p.kernel_h * p.kernel_w, OH * OW))
+            r = 0
+            for c in range(Cg):
+                for i in range(p.kernel_h):
+                    for j in range(p.kernel_w):
+                        win = xp[n, g * Cg + c, i * p.dilation_h:i * p.dilation_h + (OH - 1) * p.stride_h + 1:p.stride_h,
+                                 j * p.dilation_w:j * p.dilation_w + (OW - 1) * p.stride_w + 1:p.stride_w]
+                        col[r] = win.reshape(-1)
+                        r += 1
+            wg = w[g * Kg:(g + 1) * Kg].reshape(Kg, -1)
+            y[n, g * Kg:(g + 1) * Kg] = (wg @ col).reshape(Kg, OH, OW)
+    if b is not None:
+        y += b[None, :, None, None]
+    return y
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_forward_equals_lowering_plus_matmul(seed):
+    """Random parameter sets (every field) against im2col + GEMM written with numpy slicing."""
+    r = np.random.default_rng(4400 + seed)
+    while True:
+        g = int(r.choice([1, 2, 3]))
+        p = OracleParams(n=int(r.integers(1, 4)), c=g * int(r.integers(1, 5)), h=int(r.integers(3, 15)),
+                         w=int(r.integers(3, 15)), num_output=g * int(r.integers(1, 5)),
+                         kernel_h=int(r.integers(1, 5)), kernel_w=int(r.integers(1, 5)),
+                         stride_h=int(r.integers(1, 4)), stride_w=int(r.integers(1, 4)),
+                         pad_h=int(r.integers(0, 4)), pad_w=int(r.integers(0, 4)),
+                         dilation_h=int(r.integers(1, 3)), dilation_w=int(r.integers(1, 3)), group=g, bias_term=1)
+        if (oracle.out_size(p.h, p.kernel_h, p.stride_h, p.pad_h, p.dilation_h) >= 1
+                and oracle.out_size(p.w, p.kernel_w, p.stride_w, p.pad_w, p.dilation_w) >= 1):
+            break
+    x = r.standard_normal(oracle.x_shape(p))
+    w = r.standard_normal(oracle.w_shape(p))
+    b = r.standard_normal(p.num_output)
+    np.testing.assert_allclose(oracle.forward(p, x, w, b), _im2col_reference(p, x, w, b), rtol=1e-12, atol=1e-12)

@@ -366,3 +366,22 @@ def test_passes_can_be_captured_in_a_hip_graph():
             assert torch.equal(a, e)
         assert nerr(y, oracle.forward(op, x1.numpy(), w1.numpy(), b1.numpy())) <= TOL
         assert nerr(dw, oracle.backward_filter(op, x1.numpy(), dy1.numpy())) <= TOL
+
+
+@pytest.mark.parametrize("name", ["5.a", "5.b", "5.c"])
+def test_benchmark_layers_config_4_full(name):
+    """The large configuration at full size, every output element of every pass against the oracle
+    (the 16 host cores of the GPU machine finish one layer in a few seconds)."""
+    l = workloads.BY_NAME[name]
+    print("layer", name, "full compare", flush=True)
+    pd = l.params_dict()
+    op = OracleParams(**pd)
+    x, w, b, dy = workloads.layer_inputs(l, bias="random")
+    d, ws, _, (y, dx, dw, db) = run_all(pd, x, w, b, dy)
+    xn, wn, bn, dyn = x.numpy(), w.numpy(), b.numpy(), dy.numpy()
+    assert nerr(y, oracle.forward(op, xn, wn, bn)) <= TOL
+    print("  forward ok", flush=True)
+    assert nerr(dx, oracle.backward_data(op, wn, dyn)) <= TOL
+    print("  backward data ok", flush=True)
+    assert nerr(dw, oracle.backward_filter(op, xn, dyn)) <= TOL
+    assert nerr(db, oracle.backward_bias(op, dyn)) <= TOL

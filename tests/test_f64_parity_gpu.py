@@ -177,3 +177,12 @@ def test_f64_blobs_between_2_and_4_gib():
     assert nerr(dw, ref_dw.reshape(tuple(w.shape))) <= TOL
     assert nerr(db, oracle.backward_bias(op, dyn)) <= TOL
     assert np.isfinite(yc).all() and np.isfinite(dxc).all()
+
+
+@pytest.mark.parametrize("name", ["5.a", "5.b", "5.c"])
+def test_f64_benchmark_layers_config_4_full(name):
+    """Configuration 4 at full size in doubles, every output element of every pass against the oracle."""
+    l = workloads.BY_NAME[name]
+    print("f64 layer", name, "full compare", flush=True)
+    x, w, b, dy = (t.double() for t in workloads.layer_inputs(l, bias="random"))
+    check_full64(l.params_dict(), x, w, b, dy)

@@ -365,9 +365,12 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
   const int64_t N = p.n, C = p.c, H = p.h, W = p.w, K = p.num_output, G = p.group;
   const int64_t Cg = C / G, Kg = K / G;
   const int64_t kred = Cg * p.kernel_h * p.kernel_w;
+  // sizes in 128-bit arithmetic first: four 31-bit factors do not fit 64 bits
+  const __int128 big = kMaxElems;
+  if ((__int128)C * H * W >= big || (__int128)K * OH * OW >= big || (__int128)N * C * H * W >= big ||
+      (__int128)N * K * OH * OW >= big || (__int128)K * Cg * p.kernel_h * p.kernel_w >= big)
+    return CONV_ESHAPE;
   const int64_t x_elems = N * C * H * W, y_elems = N * K * OH * OW, w_elems = K * kred;
-  if (C * H * W >= kMaxElems || K * OH * OW >= kMaxElems) return CONV_ESHAPE;
-  if (x_elems >= kMaxElems || y_elems >= kMaxElems || w_elems >= kMaxElems) return CONV_ESHAPE;
 
   conv_desc* d = new (std::nothrow) conv_desc;
   if (!d) return CONV_EINVAL;

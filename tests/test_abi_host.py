@@ -61,9 +61,14 @@ def test_invalid_parameters_are_rejected(bad):
 
 
 def test_too_large_tensors_are_rejected():
-    with pytest.raises(conv.ConvError) as e:
-        conv.conv_desc_create(conv.ConvParams(4096, 64, 128, 128, 64, 3, 3))
-    assert e.value.status == binding.CONV_ESHAPE
+    big = 2 ** 31 - 1
+    for prm in [(4096, 64, 128, 128, 64, 3, 3),
+                (big, big, 2 ** 24, 2 ** 24, big, 1, 1),   # products far beyond 64 bits
+                (1, big, 1, 1, big, 1, 1),                 # weight blob alone too large
+                (big, 1, 1, 1, 1, 1, 1)]:                  # 2^31 - 1 images of one element
+        with pytest.raises(conv.ConvError) as e:
+            conv.conv_desc_create(conv.ConvParams(*prm))
+        assert e.value.status == binding.CONV_ESHAPE, prm
 
 
 def test_null_arguments_and_status_strings():

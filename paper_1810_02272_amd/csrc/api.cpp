@@ -645,6 +645,10 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
     int64_t S = ceil_div(2048, K);
     if (S > N) S = N;
     if (S < 1) S = 1;
+    // up to a megabyte: one workgroup per channel sums the whole batch and finishes db
+    // itself -- the second launch would cost more than the lost parallelism
+    d->bg_direct = y_elems * 4 <= ((int64_t)1 << 20);
+    if (d->bg_direct) S = 1;
     a.n_per_split = (int32_t)ceil_div(N > 0 ? N : 1, S);
     a.S = (int32_t)ceil_div(N > 0 ? N : 1, a.n_per_split);
     d->bg_ws = p.bias_term ? (size_t)a.S * K * 4 : 0;
@@ -771,6 +775,12 @@ int conv_backward_bias(const conv_desc_t* d, const float* dy, float* db, float b
   BiasGradArgs a = d->bg;
   a.dy = dy;
   a.part = static_cast<float*>(ws);
+  if (!empty && d->bg_direct) {  // small blob: one launch writes db
+    a.db = db;
+    a.beta = beta;
+    const int e1 = launch_bias_grad(a, hip_stream);
+    return e1 ? record_hip_error(e1) : CONV_OK;
+  }
   int e = empty ? 0 : launch_bias_grad(a, hip_stream);
   if (e) return record_hip_error(e);
   ReduceArgs r = {};

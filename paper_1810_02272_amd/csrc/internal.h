@@ -171,6 +171,10 @@ struct BiasGradArgs {
   int32_t N, K, P;
   int32_t S;        // splits over the images
   int32_t n_per_split;
+  // S == 1 on a small blob: the kernel finishes db itself (db = beta*db + sum) and no reduce
+  // kernel follows; db is null otherwise
+  float* db;
+  float beta;
 };
 
 // Tile variants, chosen once per descriptor.
@@ -262,6 +266,7 @@ struct conv_desc {
   // backward bias
   mi355conv::BiasGradArgs bg;
   size_t bg_ws;
+  int32_t bg_direct;  // fp32: the bias-gradient kernel writes db itself (small blobs)
   size_t ws_bytes;
   char names[256];
   // double base type: tiles of fwd64_rows / bwd64_rows / wg64_rows x 64 x 16 (f64_ok = 0: a blob of

@@ -52,7 +52,13 @@ __global__ __launch_bounds__(256) void bias_grad_kernel(const BiasGradArgs a) {
   const float w = wave_sum((acc0 + acc1) + (acc2 + acc3));
   if (lane == 0) wsum[wv] = w;
   __syncthreads();
-  if (threadIdx.x == 0) a.part[(size_t)s * a.K + k] = (wsum[0] + wsum[1]) + (wsum[2] + wsum[3]);
+  if (threadIdx.x == 0) {
+    const float total = (wsum[0] + wsum[1]) + (wsum[2] + wsum[3]);
+    if (a.db)
+      a.db[k] = a.beta != 0.f ? a.beta * a.db[k] + total : total;
+    else
+      a.part[(size_t)s * a.K + k] = total;
+  }
 }
 
 // Zero fill, 16 bytes per thread (the tail word by word).

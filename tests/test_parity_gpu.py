@@ -328,6 +328,63 @@ def test_one_descriptor_two_threads_two_streams():
     assert len(results) == 2 and all(v <= TOL for r in results.values() for v in r), results
 
 
+def test_gradients_on_a_second_stream_overlapping_backward_data():
+    """The schedule of a training loop (and of bench.py --overlap): forward passes, then backward data on
+    the launch stream while the filter and bias gradients of the same layer run on a second stream with
+    a workspace of their own.  Every result against the oracle, and bit-identical to the serial run."""
+    layers = [l for l in workloads.LAYERS if l.config == 3]
+    main, side = torch.cuda.current_stream(), torch.cuda.Stream()
+    state, ws_elems = [], 1
+    for l in layers:
+        pd = l.params_dict()
+        x, w, b, dy = workloads.layer_inputs(l)
+        d = conv.conv_desc_create(conv.ConvParams(**pd))
+        ws_elems = max(ws_elems, conv.conv_desc_workspace_bytes(d) // 4)
+        state.append(dict(op=OracleParams(**pd), d=d, host=(x, w, b, dy), x=x.to(DEV), w=w.to(DEV), b=b.to(DEV),
+                          dy=dy.to(DEV)))
+    ws = [torch.full((ws_elems,), float("nan"), device=DEV) for _ in range(2)]
+
+    def outputs(t):
+        t["out"] = [torch.full(tuple(v.shape), float("nan"), device=DEV)
+                    for v in (t["dy"], t["x"], t["w"], t["b"])]
+        return t["out"]
+
+    for t in state:  # serial
+        y, dx, dw, db = outputs(t)
+        conv.conv_forward(t["d"], t["x"], t["w"], t["b"], y, ws[0])
+        conv.conv_backward_data(t["d"], t["w"], t["dy"], dx, ws[0])
+        conv.conv_backward_filter(t["d"], t["x"], t["dy"], dw, 0.0, ws[0])
+        conv.conv_backward_bias(t["d"], t["dy"], db, 0.0, ws[0])
+    torch.cuda.synchronize()
+    serial = [[v.clone() for v in t["out"]] for t in state]
+
+    for _ in range(3):
+        for t in state:
+            y = outputs(t)[0]
+            conv.conv_forward(t["d"], t["x"], t["w"], t["b"], y, ws[0], main)
+        fork = torch.cuda.Event()
+        fork.record(main)
+        side.wait_event(fork)
+        for t in reversed(state):
+            _, dx, dw, db = t["out"]
+            conv.conv_backward_data(t["d"], t["w"], t["dy"], dx, ws[0], main)
+            conv.conv_backward_filter(t["d"], t["x"], t["dy"], dw, 0.0, ws[1], side)
+            conv.conv_backward_bias(t["d"], t["dy"], db, 0.0, ws[1], side)
+        join = torch.cuda.Event()
+        join.record(side)
+        main.wait_event(join)
+        torch.cuda.synchronize()
+        for t, ref in zip(state, serial):
+            assert all(torch.equal(a, r) for a, r in zip(t["out"], ref))
+    for t in state:
+        x, w, b, dy = (v.numpy() for v in t["host"])
+        y, dx, dw, db = t["out"]
+        assert nerr(y, oracle.forward(t["op"], x, w, b)) <= TOL
+        assert nerr(dx, oracle.backward_data(t["op"], w, dy)) <= TOL
+        assert nerr(dw, oracle.backward_filter(t["op"], x, dy)) <= TOL
+        assert nerr(db, oracle.backward_bias(t["op"], dy)) <= TOL
+
+
 def test_passes_can_be_captured_in_a_hip_graph():
     """Every pass only enqueues kernels on the caller's stream (no allocation, no memset, no
     synchronisation), so a step can be captured once and replayed: replays after changes to the

@@ -68,6 +68,18 @@ int32_t pick_corr_tile(int32_t rows, int64_t groups, int64_t ncols) {
   return best;
 }
 
+// Thin groups.  The GEMM path pads a group's rows to 16 and its reduction to 16, so its cost per
+// group is that of 16 x round_up(Cg*taps, 16) however few of them are real; the direct kernels cost
+// Kg*Cg*taps multiply-adds per position at roughly a fifth of the matrix unit's rate for the 3x3 and
+// 5x5 forms and a tenth for the general one (measured: 3x3 with 4 channels in and out per group is
+// 1.8x faster direct, with 8 in and out 2x slower).
+bool direct_is_faster(int64_t cg, int64_t kg, int64_t kh, int64_t kw) {
+  const int64_t taps = kh * kw;
+  const int64_t gemm = round_up(kg, 16) * round_up(cg * taps, 16);
+  const bool rows_form = (kh == 3 && kw == 3) || (kh == 5 && kw == 5);
+  return kg * cg * taps * (rows_form ? 5 : 10) <= gemm;
+}
+
 int32_t pick_wgrad_tile(int32_t rows, int32_t kred) {
   int32_t best = -1;
   int64_t best_work = 0, best_area = 0;
@@ -236,6 +248,15 @@ int run_forward(const conv_desc* d, const float* x, const float* w, const float*
   if ((d->p.bias_term != 0) != (bias != nullptr)) return CONV_EINVAL;
   if (d->p.n == 0) return CONV_OK;  // empty blobs: nothing to read or write
   if (!x || !y) return CONV_EINVAL;
+  if (d->use_direct) {
+    DirectArgs da = d->dir;
+    da.in = x;
+    da.w = w;
+    da.bias = bias;
+    da.out = y;
+    const int ed = launch_direct(0, da, false, false, hip_stream);
+    return ed ? record_hip_error(ed) : CONV_OK;
+  }
   if (d->fwd_ws > 0 && (!ws || ws_bytes < d->fwd_ws)) return CONV_EWORKSPACE;
   PackArgs k = d->fwd_pack;
   k.w = w;
@@ -275,6 +296,14 @@ int run_backward_data(const conv_desc* d, const float* w, const float* dy, float
   if (!(beta == 0.f || beta == 1.f)) return CONV_EINVAL;
   if (d->p.n == 0) return CONV_OK;
   if (!dy || !dx) return CONV_EINVAL;
+  if (d->use_direct) {
+    DirectArgs da = d->dir;
+    da.in = dy;
+    da.w = w;
+    da.out = dx;
+    const int ed = launch_direct(1, da, false, beta != 0.f, hip_stream);
+    return ed ? record_hip_error(ed) : CONV_OK;
+  }
   if (d->bwd_ws > 0 && (!ws || ws_bytes < d->bwd_ws)) return CONV_EWORKSPACE;
   PackArgs k = d->bwd_pack;
   k.w = w;
@@ -322,7 +351,17 @@ int run_backward_filter(const conv_desc* d, const float* x, const float* dy, flo
   a.dy = dy;
   a.x = x;
   a.part = static_cast<float*>(ws);
-  int e = empty ? 0 : launch_wgrad(d->wg_tile, a, hip_stream);
+  int e = 0;
+  if (d->use_direct) {
+    DirectArgs da = d->dir;
+    da.in = x;
+    da.w = dy;
+    da.part = ws;
+    a.S = da.S;
+    if (!empty) e = launch_direct(2, da, false, false, hip_stream);
+  } else if (!empty) {
+    e = launch_wgrad(d->wg_tile, a, hip_stream);
+  }
   if (e) return record_hip_error(e);
   ReduceArgs r = {};
   r.part = a.part;
@@ -715,6 +754,72 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
     if (d->bg64_ws > d->ws_bytes64) d->ws_bytes64 = d->bg64_ws;
   }
 
+  // ---- thin groups: direct kernels instead of the GEMM tiles ----
+  {
+    const int64_t taps = (int64_t)p.kernel_h * p.kernel_w;
+    d->use_direct = G > 1 && taps <= 64 && direct_is_faster(Cg, Kg, p.kernel_h, p.kernel_w);
+    DirectArgs& a = d->dir;
+    a.N = p.n;
+    a.C = p.c;
+    a.H = p.h;
+    a.W = p.w;
+    a.K = p.num_output;
+    a.OH = (int32_t)OH;
+    a.OW = (int32_t)OW;
+    a.kh = p.kernel_h;
+    a.kw = p.kernel_w;
+    a.sh = p.stride_h;
+    a.sw = p.stride_w;
+    a.ph = p.pad_h;
+    a.pw = p.pad_w;
+    a.dh = p.dilation_h;
+    a.dw = p.dilation_w;
+    a.Cg = (int32_t)Cg;
+    a.Kg = (int32_t)Kg;
+    a.x_elems = (uint32_t)x_elems;
+    a.y_elems = (uint32_t)y_elems;
+    a.w_elems = (uint32_t)w_elems;
+    a.mOW = make_magic((uint32_t)OW);
+    a.mOH = make_magic((uint32_t)OH);
+    a.mK = make_magic((uint32_t)K);
+    a.mKg = make_magic((uint32_t)Kg);
+    a.mW = make_magic((uint32_t)W);
+    a.mH = make_magic((uint32_t)H);
+    a.mC = make_magic((uint32_t)C);
+    a.mCg = make_magic((uint32_t)Cg);
+    a.mSh = make_magic((uint32_t)p.stride_h);
+    a.mSw = make_magic((uint32_t)p.stride_w);
+    if (d->use_direct) {
+      a.taps = (int32_t)taps;
+      a.slots = (int32_t)(64 / taps);
+      a.chunks_per_img = (int32_t)ceil_div(OH * OW, a.slots);
+      a.mTaps = make_magic((uint32_t)taps);
+      a.mKw = make_magic((uint32_t)p.kernel_w);
+      a.mChunks = make_magic((uint32_t)a.chunks_per_img);
+      // splits over the images: about a thousand workgroups, partial sums of at most 32 MiB
+      int64_t S = ceil_div(1024, K * Cg);
+      const int64_t max_by_ws = ((int64_t)8 << 20) / (w_elems > 0 ? w_elems : 1);
+      if (S > max_by_ws) S = max_by_ws;
+      if (S > N) S = N;
+      if (S > 256) S = 256;
+      if (S < 1) S = 1;
+      a.imgs_per_split = (int32_t)ceil_div(N > 0 ? N : 1, S);
+      a.S = (int32_t)ceil_div(N > 0 ? N : 1, a.imgs_per_split);
+      if ((int64_t)N * a.chunks_per_img >= ((int64_t)1 << 31) || K * Cg >= ((int64_t)1 << 31) ||
+          a.S * w_elems >= kMaxElems)
+        d->use_direct = 0;
+    }
+    if (d->use_direct) {
+      d->fwd_ws = d->bwd_ws = 0;
+      d->wg_ws = (size_t)a.S * (size_t)w_elems * 4;
+      d->fwd64_ws = d->bwd64_ws = 0;
+      d->wg64_ws = 2 * d->wg_ws;
+      d->ws_bytes64 = d->wg64_ws > d->bg64_ws ? d->wg64_ws : d->bg64_ws;
+      snprintf(d->names64, sizeof(d->names64),
+               "fwd=direct64;bwd_data=direct64;bwd_filter=direct64_wgrad(S=%d);bwd_bias=bias_grad64(S=%d)", a.S, d->bg.S);
+    }
+  }
+
   d->ws_bytes = d->fwd_ws;
   if (d->bwd_ws > d->ws_bytes) d->ws_bytes = d->bwd_ws;
   if (d->wg_ws > d->ws_bytes) d->ws_bytes = d->wg_ws;
@@ -722,6 +827,9 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
   snprintf(d->names, sizeof(d->names), "fwd=%s%s(S=%d);bwd_data=%s%s(S=%d);bwd_filter=%s(S=%d);bwd_bias=bias_grad(S=%d)",
            corr_tile_name(d->fwd_tile), d->fwd.use_patch ? "_patch" : "", d->fwd.ksplit, corr_tile_name(d->bwd_tile),
            d->bwd.use_patch ? "_patch" : "", d->bwd.ksplit, wgrad_tile_name(d->wg_tile), d->wg.S, d->bg.S);
+  if (d->use_direct)
+    snprintf(d->names, sizeof(d->names), "fwd=direct;bwd_data=direct;bwd_filter=direct_wgrad(S=%d);bwd_bias=bias_grad(S=%d)",
+             d->dir.S, d->bg.S);
   *out = d;
   return CONV_OK;
 }
@@ -835,6 +943,15 @@ int conv_forward_f64(const conv_desc_t* d, const double* x, const double* w, con
   if ((d->p.bias_term != 0) != (bias != nullptr)) return CONV_EINVAL;
   if (d->p.n == 0) return CONV_OK;
   if (!x || !y) return CONV_EINVAL;
+  if (d->use_direct && d->f64_ok) {
+    DirectArgs da = d->dir;
+    da.in = x;
+    da.w = w;
+    da.bias = bias;
+    da.out = y;
+    const int ed = launch_direct(0, da, true, false, hip_stream);
+    return ed ? record_hip_error(ed) : CONV_OK;
+  }
   return run_corr64(d, d->fwd64_rows, d->fwd64, d->fwd64_pack, d->fwd64_ws, w, x, bias, y, 0, ws, ws_bytes,
                     hip_stream);
 }
@@ -844,6 +961,14 @@ int conv_backward_data_f64(const conv_desc_t* d, const double* w, const double* 
   if (!d || !w) return CONV_EINVAL;
   if (d->p.n == 0) return CONV_OK;
   if (!dy || !dx) return CONV_EINVAL;
+  if (d->use_direct && d->f64_ok) {
+    DirectArgs da = d->dir;
+    da.in = dy;
+    da.w = w;
+    da.out = dx;
+    const int ed = launch_direct(1, da, true, false, hip_stream);
+    return ed ? record_hip_error(ed) : CONV_OK;
+  }
   const size_t zero = d->bwd_zero_fill ? (size_t)d->bwd64.out_elems * 8 : 0;
   return run_corr64(d, d->bwd64_rows, d->bwd64, d->bwd64_pack, d->bwd64_ws, w, dy, nullptr, dx, zero, ws, ws_bytes,
                     hip_stream);
@@ -861,7 +986,17 @@ int conv_backward_filter_f64(const conv_desc_t* d, const double* x, const double
   a.dy = reinterpret_cast<const float*>(dy);
   a.x = reinterpret_cast<const float*>(x);
   a.part = static_cast<float*>(ws);
-  int e = empty ? 0 : launch_wgrad64(d->wg64_rows, a, hip_stream);
+  int e = 0;
+  if (d->use_direct) {
+    DirectArgs da = d->dir;
+    da.in = x;
+    da.w = dy;
+    da.part = ws;
+    a.S = da.S;
+    if (!empty) e = launch_direct(2, da, true, false, hip_stream);
+  } else if (!empty) {
+    e = launch_wgrad64(d->wg64_rows, a, hip_stream);
+  }
   if (e) return record_hip_error(e);
   ReduceArgs r = {};
   r.part = a.part;

@@ -177,6 +177,31 @@ struct BiasGradArgs {
   float beta;
 };
 
+// Direct (no matrix unit) kernels for thin groups -- depthwise convolution and its neighbours,
+// where a group's GEMM has one to a few rows and a handful of reduction indices and the MFMA tiles
+// would be almost all padding.  The pointer members address floats or doubles.
+struct DirectArgs {
+  const void* in;    // forward, filter gradient: x; backward data: dy
+  const void* w;     // forward, backward data: weights; filter gradient: dy
+  const void* bias;  // forward only (may be null)
+  void* out;         // y / dx
+  void* part;        // filter gradient: [S][K][Cg][kh][kw] partial sums
+  int32_t N, C, H, W, K, OH, OW, kh, kw, sh, sw, ph, pw, dh, dw, Cg, Kg;
+  uint32_t x_elems, y_elems, w_elems;
+  Magic mOW, mOH, mK, mKg;             // forward: output index -> (n, k, oh, ow), k -> group
+  Magic mW, mH, mC, mCg, mSh, mSw;     // backward data: input index -> (n, c, h, w), divisions by the stride
+  // filter gradient: lanes = (position slot, tap); a workgroup = one (k, c) pair x one run of images
+  int32_t taps, slots;                 // kh*kw <= 64; slots = 64 / taps positions per wave and iteration
+  int32_t chunks_per_img;              // ceil(OH*OW / slots)
+  int32_t S, imgs_per_split;
+  Magic mTaps, mKw, mChunks;
+  // 3x3 and 5x5 kernels: a thread takes four consecutive output rows of one column
+  int32_t OHB;                         // ceil(OH / 4)
+  Magic mOHB;
+  uint32_t row_items;                  // N*K*OHB*OW
+  uint32_t w_out_stride, w_in_stride;  // weight index = group block + out*w_out_stride + in*w_in_stride + tap
+};
+
 // Tile variants, chosen once per descriptor.
 enum CorrTile : int32_t {
   CORR_128x128 = 0,  // 32x32x2 MFMA, 2x2 waves of 64x64
@@ -214,6 +239,8 @@ int launch_wgrad(int32_t tile, const WgradArgs& a, void* stream);
 int launch_reduce(const ReduceArgs& a, void* stream);
 int launch_bias_grad(const BiasGradArgs& a, void* stream);
 int launch_fill_zero(void* dst, size_t bytes, void* stream);  // bytes a multiple of 4
+// pass: 0 forward, 1 backward data (accumulate: dx += instead of dx =), 2 filter-gradient partials
+int launch_direct(int pass, const DirectArgs& a, bool f64, bool accumulate, void* stream);
 // double base type: the same argument structs, pointer members addressing doubles
 constexpr int32_t kF64TileCols = 64, kF64TileK = 16;
 int32_t f64_pick_rows(int64_t rows, bool filter_gradient);  // 96, 64, 48, 32 or 16: pads `rows` least
@@ -268,6 +295,9 @@ struct conv_desc {
   size_t bg_ws;
   int32_t bg_direct;  // fp32: the bias-gradient kernel writes db itself (small blobs)
   size_t ws_bytes;
+  // thin groups: all three passes run the direct kernels (both base types)
+  int32_t use_direct;
+  mi355conv::DirectArgs dir;
   char names[256];
   // double base type: tiles of fwd64_rows / bwd64_rows / wg64_rows x 64 x 16 (f64_ok = 0: a blob of
   // 2^29 or more elements)

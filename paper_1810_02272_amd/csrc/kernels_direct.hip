@@ -1,0 +1,383 @@
+// Direct kernels for thin groups (depthwise convolution and its neighbours): one thread per
+// output element for forward and backward data, one lane per (position, tap) for the filter
+// gradient.  No matrix unit: a group's GEMM would have one to a few rows and a handful of reduction
+// indices, and the work is bound by memory, not arithmetic.  The definitions are the layer's own
+// (cross-correlation, zero padding, stride, dilation, contiguous channel groups), written out per
+// element; T is the base type of the blobs.
+#include <hip/hip_runtime.h>
+
+#include "device_utils.h"
+#include "internal.h"
+
+namespace mi355conv {
+namespace {
+
+// The loops over taps are branch-free -- an element outside the image is read from a clamped
+// address and multiplied by a zero weight -- so that the loads of all taps are in flight together;
+// KH x KW = 0 x 0 stands for a kernel size only known at run time.
+
+// y[n][k][oh][ow] = bias[k] + sum over the group's channels c and taps (i, j) of
+//   w[k][c][i][j] * x[n][g*Cg + c][oh*sh - ph + i*dh][ow*sw - pw + j*dw]   (0 outside the image)
+template <typename T, int KH, int KW>
+__global__ __launch_bounds__(256) void direct_fwd_kernel(const DirectArgs a) {
+  const uint32_t idx = blockIdx.x * 256u + threadIdx.x;
+  if (idx >= a.y_elems) return;
+  const int kh = KH ? KH : a.kh, kw = KW ? KW : a.kw;
+  const uint32_t q1 = mdiv(idx, a.mOW), ow = idx - q1 * (uint32_t)a.OW;
+  const uint32_t q2 = mdiv(q1, a.mOH), oh = q1 - q2 * (uint32_t)a.OH;
+  const uint32_t n = mdiv(q2, a.mK), k = q2 - n * (uint32_t)a.K;
+  const uint32_t g = mdiv(k, a.mKg);
+  const T* x = static_cast<const T*>(a.in) + (n * (uint32_t)a.C + g * (uint32_t)a.Cg) * (uint32_t)(a.H * a.W);
+  const T* w = static_cast<const T*>(a.w) + k * (uint32_t)(a.Cg * kh * kw);
+  const int ih0 = (int)oh * a.sh - a.ph, iw0 = (int)ow * a.sw - a.pw;
+  T acc = T(0);
+  for (int c = 0; c < a.Cg; ++c) {
+#pragma unroll
+    for (int i = 0; i < kh; ++i) {
+      const int ih = ih0 + i * a.dh;
+      const bool row_ok = (uint32_t)ih < (uint32_t)a.H;
+      const T* xr = x + (c * a.H + (row_ok ? ih : 0)) * a.W;
+      const T* wr = w + (c * kh + i) * kw;
+#pragma unroll
+      for (int j = 0; j < kw; ++j) {
+        const int iw = iw0 + j * a.dw;
+        const bool ok = row_ok & ((uint32_t)iw < (uint32_t)a.W);
+        acc += (ok ? wr[j] : T(0)) * xr[ok ? iw : 0];
+      }
+    }
+  }
+  if (a.bias) acc += static_cast<const T*>(a.bias)[k];
+  static_cast<T*>(a.out)[idx] = acc;
+}
+
+// dx[n][c][h][w] = sum over the group's output channels k and the taps (i, j) with
+//   h + ph - i*dh = sh*oh and w + pw - j*dw = sw*ow for an output position (oh, ow) of
+//   w[k][c - g*Cg][i][j] * dy[n][k][oh][ow]
+template <typename T, int KH, int KW, bool ACC>
+__global__ __launch_bounds__(256) void direct_bwd_data_kernel(const DirectArgs a) {
+  const uint32_t idx = blockIdx.x * 256u + threadIdx.x;
+  if (idx >= a.x_elems) return;
+  const int kh = KH ? KH : a.kh, kw = KW ? KW : a.kw;
+  const uint32_t q1 = mdiv(idx, a.mW), wi = idx - q1 * (uint32_t)a.W;
+  const uint32_t q2 = mdiv(q1, a.mH), hi = q1 - q2 * (uint32_t)a.H;
+  const uint32_t n = mdiv(q2, a.mC), c = q2 - n * (uint32_t)a.C;
+  const uint32_t g = mdiv(c, a.mCg), cl = c - g * (uint32_t)a.Cg;
+  const uint32_t P = (uint32_t)(a.OH * a.OW), taps = (uint32_t)(kh * kw);
+  const T* dy = static_cast<const T*>(a.in) + (n * (uint32_t)a.K + g * (uint32_t)a.Kg) * P;
+  const T* w = static_cast<const T*>(a.w) + (g * (uint32_t)a.Kg * (uint32_t)a.Cg + cl) * taps;
+  T acc = T(0);
+  for (int k = 0; k < a.Kg; ++k) {
+    const T* wk = w + (uint32_t)k * (uint32_t)a.Cg * taps;
+    const T* dk = dy + (uint32_t)k * P;
+#pragma unroll
+    for (int i = 0; i < kh; ++i) {
+      const int hh = (int)hi + a.ph - i * a.dh;
+      const uint32_t oh = mdiv((uint32_t)(hh < 0 ? 0 : hh), a.mSh);
+      const bool row_ok = (hh >= 0) & (oh * (uint32_t)a.sh == (uint32_t)hh) & (oh < (uint32_t)a.OH);
+      const T* dr = dk + (row_ok ? oh : 0u) * (uint32_t)a.OW;
+#pragma unroll
+      for (int j = 0; j < kw; ++j) {
+        const int ww = (int)wi + a.pw - j * a.dw;
+        const uint32_t ow = mdiv((uint32_t)(ww < 0 ? 0 : ww), a.mSw);
+        const bool ok = row_ok & (ww >= 0) & (ow * (uint32_t)a.sw == (uint32_t)ww) & (ow < (uint32_t)a.OW);
+        acc += (ok ? wk[i * kw + j] : T(0)) * dr[ok ? ow : 0u];
+      }
+    }
+  }
+  T* dst = static_cast<T*>(a.out) + idx;
+  *dst = ACC ? *dst + acc : acc;
+}
+
+// part[s][k][c][i][j] = sum over the images of split s and all output positions of
+//   dy[n][k][oh][ow] * x[n][g*Cg + c][oh*sh - ph + i*dh][ow*sw - pw + j*dw]
+// One workgroup per ((k, c) pair, split).  Lane l of a wave stands for tap l % taps of position
+// slot l / taps, so an iteration of a wave covers `slots` consecutive output positions of one image
+// with every tap (one load of dy, broadcast over the taps, and one load of x per lane); the four
+// waves take the (image, chunk of positions) units in turn, four units in flight per wave.  The
+// per-lane sums are added over slots and waves in a fixed order.
+template <typename T>
+__global__ __launch_bounds__(256) void direct_wgrad_kernel(const DirectArgs a) {
+  __shared__ T red[256];
+  constexpr int kInFlight = 4;
+  const int t = threadIdx.x, lane = t & 63, wv = t >> 6;
+  const uint32_t pair = blockIdx.x, split = blockIdx.y;
+  const uint32_t k = mdiv(pair, a.mCg), c = pair - k * (uint32_t)a.Cg;
+  const uint32_t g = mdiv(k, a.mKg);
+  const uint32_t slot = mdiv((uint32_t)lane, a.mTaps), tap = (uint32_t)lane - slot * (uint32_t)a.taps;
+  const uint32_t ti = mdiv(tap, a.mKw), tj = tap - ti * (uint32_t)a.kw;
+  const bool lane_on = slot < (uint32_t)a.slots;
+  const int dih = (int)ti * a.dh - a.ph, diw = (int)tj * a.dw - a.pw;
+  const uint32_t P = (uint32_t)(a.OH * a.OW), HW = (uint32_t)(a.H * a.W);
+  const uint32_t n0 = split * (uint32_t)a.imgs_per_split;
+  const uint32_t n1 = n0 + (uint32_t)a.imgs_per_split < (uint32_t)a.N ? n0 + (uint32_t)a.imgs_per_split : (uint32_t)a.N;
+  const uint32_t units = (n1 - n0) * (uint32_t)a.chunks_per_img;
+  const T* dy = static_cast<const T*>(a.w) + k * P;                                        // + n*K*P + pos
+  const T* x = static_cast<const T*>(a.in) + (g * (uint32_t)a.Cg + c) * HW;                // + n*C*HW + ih*W + iw
+  T acc = T(0);
+  for (uint32_t u0 = (uint32_t)wv; u0 < units; u0 += 4 * kInFlight) {
+    T dv[kInFlight], xv[kInFlight];
+#pragma unroll
+    for (int q = 0; q < kInFlight; ++q) {
+      const uint32_t u = u0 + 4u * (uint32_t)q;
+      const uint32_t nl = mdiv(u, a.mChunks), ch = u - nl * (uint32_t)a.chunks_per_img;
+      const uint32_t pos = ch * (uint32_t)a.slots + slot;
+      const uint32_t oh = mdiv(pos, a.mOW), ow = pos - oh * (uint32_t)a.OW;
+      const int ih = (int)oh * a.sh + dih, iw = (int)ow * a.sw + diw;
+      const bool ok = lane_on & (u < units) & (pos < P) & ((uint32_t)ih < (uint32_t)a.H) & ((uint32_t)iw < (uint32_t)a.W);
+      const uint32_t n = n0 + nl;
+      const T d = dy[ok ? n * (uint32_t)a.K * P + pos : 0u];
+      dv[q] = ok ? d : T(0);
+      xv[q] = x[ok ? n * (uint32_t)a.C * HW + (uint32_t)ih * (uint32_t)a.W + (uint32_t)iw : 0u];
+    }
+#pragma unroll
+    for (int q = 0; q < kInFlight; ++q) acc += dv[q] * xv[q];
+  }
+  red[t] = acc;
+  __syncthreads();
+  if (t < a.taps) {
+    T sum = T(0);
+    for (int w4 = 0; w4 < 4; ++w4)
+      for (int sl = 0; sl < a.slots; ++sl) sum += red[w4 * 64 + sl * a.taps + t];
+    static_cast<T*>(a.part)[split * a.w_elems + pair * (uint32_t)a.taps + (uint32_t)t] = sum;
+  }
+}
+
+// ---- 3x3 and 5x5 kernels: four output rows per thread ----
+// A thread owns output rows 4*ohb .. 4*ohb+3 of one column: the weights of a channel are read once
+// for the four of them, and with unit stride and dilation (UNIT) the 4 + KH - 1 input rows they
+// touch are read once instead of KH times.  FLIP reverses the taps: backward data of a stride-1
+// layer is the forward pass of the mirrored kernel with the roles of the blobs exchanged (the host
+// code swaps the fields and sets the padding to dilation*(k-1) - pad, which may be negative).
+constexpr int kRows = 4;
+
+template <typename T, int KH, int KW, bool UNIT>
+__device__ __forceinline__ void load_window(const DirectArgs& a, const T* xc, int oh0, int ow,
+                                            T (&xs)[kRows + KH - 1][KW]) {
+  static_assert(UNIT, "window form needs unit stride and dilation");
+#pragma unroll
+  for (int rr = 0; rr < kRows + KH - 1; ++rr) {
+    const int ih = oh0 - a.ph + rr;
+    const bool row_ok = (uint32_t)ih < (uint32_t)a.H;
+    const T* xr = xc + (row_ok ? ih : 0) * a.W;
+#pragma unroll
+    for (int j = 0; j < KW; ++j) {
+      const int iw = ow - a.pw + j;
+      const bool ok = row_ok & ((uint32_t)iw < (uint32_t)a.W);
+      const T v = xr[ok ? iw : 0];
+      xs[rr][j] = ok ? v : T(0);
+    }
+  }
+}
+
+template <typename T>
+__device__ __forceinline__ T load_tap(const DirectArgs& a, const T* xc, int ih, int iw) {
+  const bool ok = ((uint32_t)ih < (uint32_t)a.H) & ((uint32_t)iw < (uint32_t)a.W);
+  const T v = xc[ok ? ih * a.W + iw : 0];
+  return ok ? v : T(0);
+}
+
+template <typename T, int KH, int KW, bool UNIT, bool FLIP, bool ACC>
+__global__ __launch_bounds__(256) void direct_rows_kernel(const DirectArgs a) {
+  const uint32_t idx = blockIdx.x * 256u + threadIdx.x;
+  if (idx >= a.row_items) return;
+  const uint32_t q1 = mdiv(idx, a.mOW), ow = idx - q1 * (uint32_t)a.OW;
+  const uint32_t q2 = mdiv(q1, a.mOHB), ohb = q1 - q2 * (uint32_t)a.OHB;
+  const uint32_t n = mdiv(q2, a.mK), k = q2 - n * (uint32_t)a.K;
+  const uint32_t g = mdiv(k, a.mKg), kl = k - g * (uint32_t)a.Kg;
+  const uint32_t HW = (uint32_t)(a.H * a.W);
+  const T* x = static_cast<const T*>(a.in) + (n * (uint32_t)a.C + g * (uint32_t)a.Cg) * HW;
+  const T* w = static_cast<const T*>(a.w) + g * (uint32_t)(a.Kg * a.Cg * KH * KW) + kl * a.w_out_stride;
+  const int oh0 = (int)ohb * kRows;
+  T acc[kRows];
+#pragma unroll
+  for (int r = 0; r < kRows; ++r) acc[r] = T(0);
+  for (int c = 0; c < a.Cg; ++c) {
+    T wv[KH][KW];
+#pragma unroll
+    for (int i = 0; i < KH; ++i)
+#pragma unroll
+      for (int j = 0; j < KW; ++j)
+        wv[i][j] = w[(uint32_t)c * a.w_in_stride + (uint32_t)(FLIP ? (KH - 1 - i) * KW + (KW - 1 - j) : i * KW + j)];
+    const T* xc = x + (uint32_t)c * HW;
+    if constexpr (UNIT) {
+      T xs[kRows + KH - 1][KW];
+      load_window<T, KH, KW, UNIT>(a, xc, oh0, (int)ow, xs);
+#pragma unroll
+      for (int r = 0; r < kRows; ++r)
+#pragma unroll
+        for (int i = 0; i < KH; ++i)
+#pragma unroll
+          for (int j = 0; j < KW; ++j) acc[r] += wv[i][j] * xs[r + i][j];
+    } else {
+#pragma unroll
+      for (int r = 0; r < kRows; ++r)
+#pragma unroll
+        for (int i = 0; i < KH; ++i)
+#pragma unroll
+          for (int j = 0; j < KW; ++j)
+            acc[r] += wv[i][j] * load_tap(a, xc, (oh0 + r) * a.sh - a.ph + i * a.dh, (int)ow * a.sw - a.pw + j * a.dw);
+    }
+  }
+  const T bb = a.bias ? static_cast<const T*>(a.bias)[k] : T(0);
+  T* out = static_cast<T*>(a.out) + ((n * (uint32_t)a.K + k) * (uint32_t)a.OH + (uint32_t)oh0) * (uint32_t)a.OW + ow;
+#pragma unroll
+  for (int r = 0; r < kRows; ++r)
+    if (oh0 + r < a.OH) {
+      T* dst = out + (uint32_t)r * (uint32_t)a.OW;
+      const T v = acc[r] + bb;
+      *dst = ACC ? *dst + v : v;
+    }
+}
+
+// Filter gradient, 3x3 and 5x5: lanes are output columns, a thread keeps one running sum per tap
+// over its (image, four rows, column) items; the sums are then added over the wave (fixed
+// shuffle tree) and over the four waves.
+template <typename T, int KH, int KW, bool UNIT>
+__global__ __launch_bounds__(256) void direct_wgrad_rows_kernel(const DirectArgs a) {
+  __shared__ T red[4][KH * KW];
+  const int t = threadIdx.x, lane = t & 63, wv = t >> 6;
+  const uint32_t pair = blockIdx.x, split = blockIdx.y;
+  const uint32_t k = mdiv(pair, a.mCg), c = pair - k * (uint32_t)a.Cg;
+  const uint32_t g = mdiv(k, a.mKg);
+  const uint32_t P = (uint32_t)(a.OH * a.OW), HW = (uint32_t)(a.H * a.W);
+  const uint32_t n0 = split * (uint32_t)a.imgs_per_split;
+  const uint32_t n1 = n0 + (uint32_t)a.imgs_per_split < (uint32_t)a.N ? n0 + (uint32_t)a.imgs_per_split : (uint32_t)a.N;
+  const uint32_t items = (n1 - n0) * (uint32_t)a.OHB * (uint32_t)a.OW;
+  const T* dy = static_cast<const T*>(a.w) + k * P;
+  const T* x = static_cast<const T*>(a.in) + (g * (uint32_t)a.Cg + c) * HW;
+  T acc[KH][KW];
+#pragma unroll
+  for (int i = 0; i < KH; ++i)
+#pragma unroll
+    for (int j = 0; j < KW; ++j) acc[i][j] = T(0);
+  for (uint32_t item = (uint32_t)t; item < items; item += 256u) {
+    const uint32_t q1 = mdiv(item, a.mOW), ow = item - q1 * (uint32_t)a.OW;
+    const uint32_t nl = mdiv(q1, a.mOHB), ohb = q1 - nl * (uint32_t)a.OHB;
+    const uint32_t n = n0 + nl;
+    const int oh0 = (int)ohb * kRows;
+    const T* dn = dy + n * (uint32_t)a.K * P + ow;
+    const T* xc = x + n * (uint32_t)a.C * HW;
+    T dv[kRows];
+#pragma unroll
+    for (int r = 0; r < kRows; ++r) {
+      const bool ok = oh0 + r < a.OH;
+      const T v = dn[ok ? (uint32_t)(oh0 + r) * (uint32_t)a.OW : 0u];
+      dv[r] = ok ? v : T(0);
+    }
+    if constexpr (UNIT) {
+      T xs[kRows + KH - 1][KW];
+      load_window<T, KH, KW, UNIT>(a, xc, oh0, (int)ow, xs);
+#pragma unroll
+      for (int r = 0; r < kRows; ++r)
+#pragma unroll
+        for (int i = 0; i < KH; ++i)
+#pragma unroll
+          for (int j = 0; j < KW; ++j) acc[i][j] += dv[r] * xs[r + i][j];
+    } else {
+#pragma unroll
+      for (int r = 0; r < kRows; ++r)
+#pragma unroll
+        for (int i = 0; i < KH; ++i)
+#pragma unroll
+          for (int j = 0; j < KW; ++j)
+            acc[i][j] += dv[r] * load_tap(a, xc, (oh0 + r) * a.sh - a.ph + i * a.dh, (int)ow * a.sw - a.pw + j * a.dw);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < KH; ++i)
+#pragma unroll
+    for (int j = 0; j < KW; ++j) {
+      T v = acc[i][j];
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) v += __shfl_down(v, off, 64);
+      if (lane == 0) red[wv][i * KW + j] = v;
+    }
+  __syncthreads();
+  if (t < KH * KW)
+    static_cast<T*>(a.part)[split * a.w_elems + pair * (uint32_t)(KH * KW) + (uint32_t)t] =
+        ((red[0][t] + red[1][t]) + red[2][t]) + red[3][t];
+}
+
+template <typename T, int KH, int KW>
+int launch_direct_k(int pass, const DirectArgs& a, bool accumulate, hipStream_t s) {
+  if (pass == 0) {
+    hipLaunchKernelGGL((direct_fwd_kernel<T, KH, KW>), dim3((a.y_elems + 255u) / 256u), dim3(256), 0, s, a);
+  } else {
+    const dim3 grid((a.x_elems + 255u) / 256u);
+    if (accumulate)
+      hipLaunchKernelGGL((direct_bwd_data_kernel<T, KH, KW, true>), grid, dim3(256), 0, s, a);
+    else
+      hipLaunchKernelGGL((direct_bwd_data_kernel<T, KH, KW, false>), grid, dim3(256), 0, s, a);
+  }
+  return (int)hipGetLastError();
+}
+
+// The four-rows kernels.  Backward data (stride 1 only) runs as the forward pass of the mirrored
+// problem: dy is the input blob with K channels, dx the output with C channels.
+template <typename T, int KH, int KW, bool UNIT>
+int launch_rows(int pass, const DirectArgs& src, bool accumulate, hipStream_t s) {
+  DirectArgs a = src;
+  if (pass == 2) {
+    a.OHB = (a.OH + kRows - 1) / kRows;
+    a.mOHB = make_magic((uint32_t)a.OHB);
+    hipLaunchKernelGGL((direct_wgrad_rows_kernel<T, KH, KW, UNIT>), dim3((uint32_t)(a.K * a.Cg), (uint32_t)a.S),
+                       dim3(256), 0, s, a);
+    return (int)hipGetLastError();
+  }
+  if (pass == 0) {
+    a.w_out_stride = (uint32_t)(a.Cg * KH * KW);
+    a.w_in_stride = (uint32_t)(KH * KW);
+  } else {
+    a.C = src.K;
+    a.K = src.C;
+    a.Cg = src.Kg;
+    a.Kg = src.Cg;
+    a.H = src.OH;
+    a.W = src.OW;
+    a.OH = src.H;
+    a.OW = src.W;
+    a.ph = src.dh * (KH - 1) - src.ph;
+    a.pw = src.dw * (KW - 1) - src.pw;
+    a.w_out_stride = (uint32_t)(KH * KW);
+    a.w_in_stride = (uint32_t)(src.Cg * KH * KW);
+    a.mOW = src.mW;
+    a.mK = src.mC;
+    a.mKg = src.mCg;
+  }
+  a.OHB = (a.OH + kRows - 1) / kRows;
+  a.mOHB = make_magic((uint32_t)a.OHB);
+  a.row_items = (uint32_t)a.N * (uint32_t)a.K * (uint32_t)a.OHB * (uint32_t)a.OW;
+  const dim3 grid((a.row_items + 255u) / 256u);
+  if (pass == 0)
+    hipLaunchKernelGGL((direct_rows_kernel<T, KH, KW, UNIT, false, false>), grid, dim3(256), 0, s, a);
+  else if (accumulate)
+    hipLaunchKernelGGL((direct_rows_kernel<T, KH, KW, UNIT, true, true>), grid, dim3(256), 0, s, a);
+  else
+    hipLaunchKernelGGL((direct_rows_kernel<T, KH, KW, UNIT, true, false>), grid, dim3(256), 0, s, a);
+  return (int)hipGetLastError();
+}
+
+template <typename T>
+int launch_direct_t(int pass, const DirectArgs& a, bool accumulate, hipStream_t s) {
+  const bool unit = a.sh == 1 && a.sw == 1 && a.dh == 1 && a.dw == 1;
+  const bool rows_ok = pass != 1 || (a.sh == 1 && a.sw == 1);  // backward data: stride 1 only
+  if (rows_ok && a.kh == 3 && a.kw == 3)
+    return unit ? launch_rows<T, 3, 3, true>(pass, a, accumulate, s) : launch_rows<T, 3, 3, false>(pass, a, accumulate, s);
+  if (rows_ok && a.kh == 5 && a.kw == 5)
+    return unit ? launch_rows<T, 5, 5, true>(pass, a, accumulate, s) : launch_rows<T, 5, 5, false>(pass, a, accumulate, s);
+  if (pass == 2) {
+    hipLaunchKernelGGL(direct_wgrad_kernel<T>, dim3((uint32_t)(a.K * a.Cg), (uint32_t)a.S), dim3(256), 0, s, a);
+    return (int)hipGetLastError();
+  }
+  if (a.kh == 3 && a.kw == 3) return launch_direct_k<T, 3, 3>(pass, a, accumulate, s);
+  return launch_direct_k<T, 0, 0>(pass, a, accumulate, s);
+}
+
+}  // namespace
+
+int launch_direct(int pass, const DirectArgs& a, bool f64, bool accumulate, void* stream) {
+  hipStream_t s = (hipStream_t)stream;
+  return f64 ? launch_direct_t<double>(pass, a, accumulate, s) : launch_direct_t<float>(pass, a, accumulate, s);
+}
+
+}  // namespace mi355conv

@@ -12,7 +12,7 @@ import oracle
 import paper_1810_02272_amd as conv
 from oracle import OracleParams
 from paper_1810_02272_amd import workloads
-from test_parity_gpu import P, SWEEP
+from test_parity_gpu import DIRECT_CASES, P, SWEEP
 
 pytestmark = pytest.mark.gpu
 TOL = 1e-12
@@ -72,9 +72,9 @@ def check_full64(pd, x, w, b, dy):
     return errs
 
 
-@pytest.mark.parametrize("i", range(len(SWEEP)))
+@pytest.mark.parametrize("i", range(len(SWEEP) + len(DIRECT_CASES)))
 def test_f64_sweep_full_compare(i):
-    pd = SWEEP[i]
+    pd = (SWEEP + DIRECT_CASES)[i]
     print("f64 case", i, pd, flush=True)
     op = OracleParams(**pd)
     x, w, b, dy = workloads.random_inputs(oracle.x_shape(op), oracle.w_shape(op), oracle.output_shape(op),

@@ -111,6 +111,26 @@ SWEEP = [
     P(2, 8, 26, 26, 8, 3, 2, 3, 2, 1, 1, 2, 3, 2),          # neither divides: dense slots, all phases
 ]
 
+# Thin groups: the direct kernels (one thread per output element; lanes = (position, tap) for the
+# filter gradient).  Depthwise and channel multipliers, every parameter, tap counts that do and do
+# not divide 64, more positions than one chunk, fewer images than splits.
+DIRECT_CASES = [
+    P(5, 24, 19, 17, 24, 3, 3, 1, 1, 1, 1, 1, 1, 24),          # depthwise 3x3
+    P(3, 16, 22, 25, 32, 3, 3, 2, 2, 1, 1, 1, 1, 16),          # channel multiplier 2, stride 2
+    P(2, 12, 15, 15, 12, 5, 5, 1, 1, 2, 2, 1, 1, 12),          # depthwise 5x5
+    P(4, 10, 18, 21, 10, 3, 2, 2, 3, 1, 0, 2, 3, 10, 0),       # stride + dilation + no bias, non-square
+    P(2, 8, 9, 9, 8, 1, 1, 1, 1, 0, 0, 1, 1, 8),               # depthwise 1x1 (a per-channel scale)
+    P(3, 6, 31, 29, 6, 7, 7, 2, 2, 3, 3, 1, 1, 6),             # depthwise 7x7: one position per wave iteration
+    P(1, 300, 6, 6, 300, 3, 3, 1, 1, 1, 1, 1, 1, 300),         # more pairs than a thousand / few images
+    P(70, 4, 8, 8, 4, 3, 3, 1, 1, 1, 1, 1, 1, 4),              # many images per split
+    P(2, 8, 12, 12, 8, 2, 2, 2, 2, 3, 3, 1, 1, 4),             # two channels per group, pad > kernel
+    P(3, 10, 21, 18, 10, 3, 3, 1, 1, 2, 2, 2, 2, 10),          # 3x3 dilation 2 at stride 1
+    P(2, 6, 14, 13, 6, 3, 3, 1, 1, 0, 0, 1, 1, 6),             # 3x3 without padding
+    P(2, 6, 10, 11, 6, 3, 3, 1, 1, 4, 3, 1, 1, 6),             # pad beyond the kernel (mirrored pad negative)
+    P(2, 14, 27, 26, 28, 5, 5, 2, 2, 2, 2, 1, 1, 14),          # 5x5 stride 2, channel multiplier 2
+    P(2, 8, 13, 13, 8, 5, 5, 1, 1, 1, 3, 1, 2, 4),             # 5x5, two channels per group, mixed dilation
+]
+
 # Shapes that select the patch-staged kernel (256-column tiles of the 16-row MFMA): 48 or <= 16
 # rows, 8-aligned reduction channels, enough columns for the wide tile to win and for the grid not
 # to want a split reduction.
@@ -127,6 +147,14 @@ def test_sweep_full_compare(i):
     pd = SWEEP[i]
     print("case", i, pd, flush=True)
     check_full(pd, seed=7000 + 10 * i, bias=bool(pd["bias_term"]))
+
+
+@pytest.mark.parametrize("i", range(len(DIRECT_CASES)))
+def test_thin_groups_direct_kernels(i):
+    pd = DIRECT_CASES[i]
+    d = conv.conv_desc_create(conv.ConvParams(**pd))
+    assert "direct" in conv.conv_desc_kernel_names(d), conv.conv_desc_kernel_names(d)
+    check_full(pd, 4400 + i, bias=bool(pd["bias_term"]))
 
 
 @pytest.mark.parametrize("i", range(len(PATCH_CASES)))
@@ -193,8 +221,9 @@ def test_benchmark_layers_config_4_sampled(name):
     assert abs(lin - via_dx) <= 1e-3 * scale and abs(lin - via_dw) <= 1e-3 * scale, (lin, via_dx, via_dw, scale)
 
 
-def test_beta_accumulates_and_overwrites():
-    pd = P(3, 6, 11, 12, 10, 3, 3, 2, 1, 1, 1, 1, 1, 2)
+@pytest.mark.parametrize("pd", [P(3, 6, 11, 12, 10, 3, 3, 2, 1, 1, 1, 1, 1, 2),
+                                P(3, 6, 11, 12, 6, 3, 3, 2, 1, 1, 1, 1, 1, 6)], ids=["gemm", "direct"])
+def test_beta_accumulates_and_overwrites(pd):
     op = OracleParams(**pd)
     x, w, b, dy = workloads.random_inputs(oracle.x_shape(op), oracle.w_shape(op), oracle.output_shape(op), 4242)
     d, ws, (xd, wd, bd, dyd), (y, dx, dw, db) = run_all(pd, x, w, b, dy)

@@ -35,7 +35,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="config4", help="config0..config4, ip5, ip1, pg, or a comma list of layer names (all conv or all ip)")
+    ap.add_argument("--workload", default="config4", help="config0..config4, dw (depthwise layers), ip5, ip1, pg, or a comma list of layer names (all conv or all ip)")
     ap.add_argument("--dtype", default="f32", choices=["f32", "f64"],
                     help="base type of the convolution workloads (f64: the conv_*_f64 entry points)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
@@ -94,6 +94,8 @@ def main():
     if args.workload.startswith("config"):
         cfg = int(args.workload[len("config"):])
         layers = [l for l in workloads.LAYERS if l.config == cfg]
+    elif args.workload == "dw":
+        layers = list(workloads.DW_LAYERS)
     elif args.workload in ("ip5", "ip1"):
         layers = [l for l in workloads.IP_LAYERS if l.name.startswith(args.workload + ".")]
     elif is_ip:
@@ -313,6 +315,8 @@ def main():
                 row[name + "_tflops"] = round(l.flop_per_pass / ms / 1e9, 2)
             elif name == "bwd_bias":  # one read of dy: the HBM-bound pass
                 row["bwd_bias_GBps"] = round(dy_bytes(l) * (2 if f64 else 1) / ms / 1e6, 1)
+            if name in flop_passes and not is_ip and "direct" in row["kernels"]:
+                row[name + "_GBps"] = round(blob_bytes(l, name) * (2 if f64 else 1) / ms / 1e6, 1)
         row["fwd_bwd_tflops"] = round(3 * l.flop_per_pass / tot / 1e9, 2)
         if not is_ip and l.name in ("1.a", "3.a", "4.a", "5.a"):
             # first layer of its network: real training skips its backward-data pass (no gradient
@@ -329,11 +333,16 @@ def main():
     dstate = next(t for t in state if t["layer"].name == dl)
     dlayer = dstate["layer"]
     kernel_names = dict(kv.split("=", 1) for kv in kernel_names_of(dstate["desc"]).split(";"))
-    if dp in ("bwd_bias", "relu_bwd"):
-        bytes_launch = dy_bytes(dlayer) * (1 if dp == "bwd_bias" else 3) * (2 if f64 else 1)
+    direct = not is_ip and "direct" in kernel_names.get(dp, "")
+    if dp in ("bwd_bias", "relu_bwd") or direct:
+        if direct:  # thin groups: every blob of the pass moved once
+            bytes_launch = blob_bytes(dlayer, dp) * (2 if f64 else 1)
+        else:
+            bytes_launch = dy_bytes(dlayer) * (1 if dp == "bwd_bias" else 3) * (2 if f64 else 1)
         achieved = bytes_launch / (dms * 1e-3) / 1e9
         roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                    "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": None}
+                    "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": None,
+                    "algorithmic_bytes_per_launch": bytes_launch}
     else:
         achieved = dlayer.flop_per_pass / (dms * 1e-3) / 1e12
         roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": peak,
@@ -478,6 +487,13 @@ def pg_traffic(pass_name):
         return json.load(open(path)).get(f"pg:{pass_name}")
     except Exception:
         return None
+
+
+def blob_bytes(l, pass_name):
+    """fp32 bytes of the blobs one pass of a convolution layer reads and writes, each once."""
+    import math
+    x, y, w = (math.prod(s) for s in (l.x_shape, l.y_shape, l.w_shape))
+    return 4 * (x + y + (0 if pass_name == "bwd_filter" else w))
 
 
 def dy_bytes(l):

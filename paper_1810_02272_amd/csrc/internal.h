@@ -200,6 +200,10 @@ struct DirectArgs {
   Magic mOHB;
   uint32_t row_items;                  // N*K*OHB*OW
   uint32_t w_out_stride, w_in_stride;  // weight index = group block + out*w_out_stride + in*w_in_stride + tap
+  // 3x3 and 5x5 backward data at stride 2: a thread takes one stride x stride block of dx
+  int32_t BH, BW;                      // blocks per image: ceil((H + ph) / stride), ceil((W + pw) / stride)
+  Magic mBH, mBW;
+  uint32_t block_items;                // N*C*BH*BW
 };
 
 // Tile variants, chosen once per descriptor.

@@ -298,6 +298,73 @@ __global__ __launch_bounds__(256) void direct_wgrad_rows_kernel(const DirectArgs
         ((red[0][t] + red[1][t]) + red[2][t]) + red[3][t];
 }
 
+// Backward data at stride S (dilation 1), 3x3 and 5x5: a thread owns the S x S block of dx with
+// h + ph = S*a + rh, w + pw = S*b + rw.  Tap (i, j) reaches phase (rh, rw) exactly when i - rh and
+// j - rw are non-negative multiples of S, and then reads dy at (a - (i-rh)/S, b - (j-rw)/S): the
+// block needs only ((KH-1)/S + 1) x ((KW-1)/S + 1) values of dy per channel and uses every tap once.
+template <typename T, int KH, int KW, int S, bool ACC>
+__global__ __launch_bounds__(256) void direct_bwd_blocks_kernel(const DirectArgs a) {
+  constexpr int QH = (KH - 1) / S + 1, QW = (KW - 1) / S + 1;
+  const uint32_t idx = blockIdx.x * 256u + threadIdx.x;
+  if (idx >= a.block_items) return;
+  const uint32_t q1 = mdiv(idx, a.mBW), bb = idx - q1 * (uint32_t)a.BW;
+  const uint32_t q2 = mdiv(q1, a.mBH), ba = q1 - q2 * (uint32_t)a.BH;
+  const uint32_t n = mdiv(q2, a.mC), c = q2 - n * (uint32_t)a.C;
+  const uint32_t g = mdiv(c, a.mCg), cl = c - g * (uint32_t)a.Cg;
+  const uint32_t P = (uint32_t)(a.OH * a.OW);
+  const T* dy = static_cast<const T*>(a.in) + (n * (uint32_t)a.K + g * (uint32_t)a.Kg) * P;
+  const T* w = static_cast<const T*>(a.w) + (g * (uint32_t)a.Kg * (uint32_t)a.Cg + cl) * (uint32_t)(KH * KW);
+  T acc[S][S];
+#pragma unroll
+  for (int rh = 0; rh < S; ++rh)
+#pragma unroll
+    for (int rw = 0; rw < S; ++rw) acc[rh][rw] = T(0);
+  for (int k = 0; k < a.Kg; ++k) {
+    const T* wk = w + (uint32_t)k * (uint32_t)a.Cg * (uint32_t)(KH * KW);
+    const T* dk = dy + (uint32_t)k * P;
+    T dv[QH][QW];
+#pragma unroll
+    for (int qh = 0; qh < QH; ++qh)
+#pragma unroll
+      for (int qw = 0; qw < QW; ++qw) {
+        const int oh = (int)ba - qh, ow = (int)bb - qw;
+        const bool ok = ((uint32_t)oh < (uint32_t)a.OH) & ((uint32_t)ow < (uint32_t)a.OW);
+        const T v = dk[ok ? oh * a.OW + ow : 0];
+        dv[qh][qw] = ok ? v : T(0);
+      }
+#pragma unroll
+    for (int i = 0; i < KH; ++i)
+#pragma unroll
+      for (int j = 0; j < KW; ++j) acc[i % S][j % S] += wk[i * KW + j] * dv[i / S][j / S];
+  }
+#pragma unroll
+  for (int rh = 0; rh < S; ++rh)
+#pragma unroll
+    for (int rw = 0; rw < S; ++rw) {
+      const int h = (int)ba * S + rh - a.ph, wi = (int)bb * S + rw - a.pw;
+      if ((uint32_t)h < (uint32_t)a.H && (uint32_t)wi < (uint32_t)a.W) {
+        T* dst = static_cast<T*>(a.out) + ((n * (uint32_t)a.C + c) * (uint32_t)a.H + (uint32_t)h) * (uint32_t)a.W + (uint32_t)wi;
+        *dst = ACC ? *dst + acc[rh][rw] : acc[rh][rw];
+      }
+    }
+}
+
+template <typename T, int KH, int KW, int S>
+int launch_bwd_blocks(const DirectArgs& src, bool accumulate, hipStream_t s) {
+  DirectArgs a = src;
+  a.BH = (a.H + a.ph + S - 1) / S;
+  a.BW = (a.W + a.pw + S - 1) / S;
+  a.mBH = make_magic((uint32_t)a.BH);
+  a.mBW = make_magic((uint32_t)a.BW);
+  a.block_items = (uint32_t)a.N * (uint32_t)a.C * (uint32_t)a.BH * (uint32_t)a.BW;
+  const dim3 grid((a.block_items + 255u) / 256u);
+  if (accumulate)
+    hipLaunchKernelGGL((direct_bwd_blocks_kernel<T, KH, KW, S, true>), grid, dim3(256), 0, s, a);
+  else
+    hipLaunchKernelGGL((direct_bwd_blocks_kernel<T, KH, KW, S, false>), grid, dim3(256), 0, s, a);
+  return (int)hipGetLastError();
+}
+
 template <typename T, int KH, int KW>
 int launch_direct_k(int pass, const DirectArgs& a, bool accumulate, hipStream_t s) {
   if (pass == 0) {
@@ -368,6 +435,10 @@ int launch_direct_t(int pass, const DirectArgs& a, bool accumulate, hipStream_t 
   if (pass == 2) {
     hipLaunchKernelGGL(direct_wgrad_kernel<T>, dim3((uint32_t)(a.K * a.Cg), (uint32_t)a.S), dim3(256), 0, s, a);
     return (int)hipGetLastError();
+  }
+  if (pass == 1 && a.sh == 2 && a.sw == 2 && a.dh == 1 && a.dw == 1) {
+    if (a.kh == 3 && a.kw == 3) return launch_bwd_blocks<T, 3, 3, 2>(a, accumulate, s);
+    if (a.kh == 5 && a.kw == 5) return launch_bwd_blocks<T, 5, 5, 2>(a, accumulate, s);
   }
   if (a.kh == 3 && a.kw == 3) return launch_direct_k<T, 3, 3>(pass, a, accumulate, s);
   return launch_direct_k<T, 0, 0>(pass, a, accumulate, s);

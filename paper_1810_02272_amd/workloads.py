@@ -73,7 +73,17 @@ LAYERS = [
     Layer("5.b", 4, 128, 96, 27, 256, 5, 1, 2, 2, 27, "normal", "gauss0.01", 0.1),
     Layer("5.c", 4, 128, 256, 13, 384, 3, 1, 1, 1, 13, "normal", "gauss0.01", 0.1),
 ]
-BY_NAME = {l.name: l for l in LAYERS}
+# Depthwise layers of a mobile-style network (one channel per group, 3x3, strides 1 and 2) at the
+# resolutions such a network runs them; not part of the five benchmark configurations -- they
+# exercise the thin-group (direct) kernels at a realistic size.
+DW_LAYERS = [
+    Layer("dw.a", 5, 64, 32, 112, 32, 3, 1, 1, 32, 112, "normal", "xavier", 1.0),
+    Layer("dw.b", 5, 64, 64, 112, 64, 3, 2, 1, 64, 56, "normal", "xavier", 1.0),
+    Layer("dw.c", 5, 64, 128, 56, 128, 3, 1, 1, 128, 56, "normal", "xavier", 1.0),
+    Layer("dw.d", 5, 64, 256, 28, 256, 3, 1, 1, 256, 28, "normal", "xavier", 1.0),
+    Layer("dw.e", 5, 64, 512, 14, 512, 3, 1, 1, 512, 14, "normal", "xavier", 1.0),
+]
+BY_NAME = {l.name: l for l in LAYERS + DW_LAYERS}
 
 
 def _gen(seed: int) -> torch.Generator:
@@ -100,7 +110,7 @@ def layer_inputs(layer: Layer, bias: str = "zero", n: int | None = None):
     ``n`` draws only the first n images (x and dy are generated image-major, so a prefix of the
     full batch is bit-identical to the same images of the full draw).
     """
-    idx = LAYERS.index(layer)
+    idx = (LAYERS + DW_LAYERS).index(layer)
     seed = BASE_SEED + 1000 * idx
     nn = layer.n if n is None else n
     xs, ys = (nn,) + layer.x_shape[1:], (nn,) + layer.y_shape[1:]

@@ -129,6 +129,9 @@ DIRECT_CASES = [
     P(2, 6, 10, 11, 6, 3, 3, 1, 1, 4, 3, 1, 1, 6),             # pad beyond the kernel (mirrored pad negative)
     P(2, 14, 27, 26, 28, 5, 5, 2, 2, 2, 2, 1, 1, 14),          # 5x5 stride 2, channel multiplier 2
     P(2, 8, 13, 13, 8, 5, 5, 1, 1, 1, 3, 1, 2, 4),             # 5x5, two channels per group, mixed dilation
+    P(3, 9, 23, 20, 9, 3, 3, 2, 2, 0, 0, 1, 1, 9),             # 3x3 stride 2 without padding (last row unread)
+    P(2, 6, 16, 19, 12, 3, 3, 2, 2, 3, 2, 1, 1, 3),            # 3x3 stride 2, pad beyond the kernel, 2 -> 4 channels
+    P(2, 5, 18, 17, 5, 5, 5, 2, 2, 1, 4, 1, 1, 5),             # 5x5 stride 2, uneven padding
 ]
 
 # Shapes that select the patch-staged kernel (256-column tiles of the 16-row MFMA): 48 or <= 16
@@ -173,6 +176,22 @@ def test_benchmark_layers_configs_0_to_3_full(name):
     l = workloads.BY_NAME[name]
     print("layer", name, flush=True)
     pd = l.params_dict()
+    op = OracleParams(**pd)
+    x, w, b, dy = workloads.layer_inputs(l, bias="random")
+    d, ws, _, (y, dx, dw, db) = run_all(pd, x, w, b, dy)
+    xn, wn, bn, dyn = x.numpy(), w.numpy(), b.numpy(), dy.numpy()
+    assert nerr(y, oracle.forward(op, xn, wn, bn)) <= TOL
+    assert nerr(dx, oracle.backward_data(op, wn, dyn)) <= TOL
+    assert nerr(dw, oracle.backward_filter(op, xn, dyn)) <= TOL
+    assert nerr(db, oracle.backward_bias(op, dyn)) <= TOL
+
+
+@pytest.mark.parametrize("name", [l.name for l in workloads.DW_LAYERS])
+def test_depthwise_layers_full(name):
+    """The depthwise layers `bench.py --workload dw` times, at full size, element by element."""
+    l = workloads.BY_NAME[name]
+    pd = l.params_dict()
+    assert "direct" in conv.conv_desc_kernel_names(conv.conv_desc_create(conv.ConvParams(**pd)))
     op = OracleParams(**pd)
     x, w, b, dy = workloads.layer_inputs(l, bias="random")
     d, ws, _, (y, dx, dw, db) = run_all(pd, x, w, b, dy)

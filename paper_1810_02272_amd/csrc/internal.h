@@ -195,8 +195,8 @@ struct DirectArgs {
   int32_t chunks_per_img;              // ceil(OH*OW / slots)
   int32_t S, imgs_per_split;
   Magic mTaps, mKw, mChunks;
-  // 3x3 and 5x5 kernels: a thread takes four consecutive output rows of one column
-  int32_t OHB;                         // ceil(OH / 4)
+  // 3x3 and 5x5 kernels: a thread takes R consecutive output rows of one column (R = 8 or 4)
+  int32_t OHB;                         // ceil(OH / R)
   Magic mOHB;
   uint32_t row_items;                  // N*K*OHB*OW
   uint32_t w_out_stride, w_in_stride;  // weight index = group block + out*w_out_stride + in*w_in_stride + tap

@@ -12,6 +12,9 @@
 namespace mi355conv {
 namespace {
 
+// Consecutive workgroups go to the eight XCDs in turn; the element index is taken from the
+// renumbered workgroup id so that neighbouring rows of an image, which share halo rows of the
+// input, meet in one XCD's L2.
 // The loops over taps are branch-free -- an element outside the image is read from a clamped
 // address and multiplied by a zero weight -- so that the loads of all taps are in flight together;
 // KH x KW = 0 x 0 stands for a kernel size only known at run time.
@@ -20,7 +23,7 @@ namespace {
 //   w[k][c][i][j] * x[n][g*Cg + c][oh*sh - ph + i*dh][ow*sw - pw + j*dw]   (0 outside the image)
 template <typename T, int KH, int KW>
 __global__ __launch_bounds__(256) void direct_fwd_kernel(const DirectArgs a) {
-  const uint32_t idx = blockIdx.x * 256u + threadIdx.x;
+  const uint32_t idx = xcd_contiguous_block_id() * 256u + threadIdx.x;
   if (idx >= a.y_elems) return;
   const int kh = KH ? KH : a.kh, kw = KW ? KW : a.kw;
   const uint32_t q1 = mdiv(idx, a.mOW), ow = idx - q1 * (uint32_t)a.OW;
@@ -55,7 +58,7 @@ __global__ __launch_bounds__(256) void direct_fwd_kernel(const DirectArgs a) {
 //   w[k][c - g*Cg][i][j] * dy[n][k][oh][ow]
 template <typename T, int KH, int KW, bool ACC>
 __global__ __launch_bounds__(256) void direct_bwd_data_kernel(const DirectArgs a) {
-  const uint32_t idx = blockIdx.x * 256u + threadIdx.x;
+  const uint32_t idx = xcd_contiguous_block_id() * 256u + threadIdx.x;
   if (idx >= a.x_elems) return;
   const int kh = KH ? KH : a.kh, kw = KW ? KW : a.kw;
   const uint32_t q1 = mdiv(idx, a.mW), wi = idx - q1 * (uint32_t)a.W;
@@ -142,18 +145,21 @@ __global__ __launch_bounds__(256) void direct_wgrad_kernel(const DirectArgs a) {
   }
 }
 
-// ---- 3x3 and 5x5 kernels: four output rows per thread ----
-// A thread owns output rows 4*ohb .. 4*ohb+3 of one column: the weights of a channel are read once
-// for the four of them, and with unit stride and dilation (UNIT) the 4 + KH - 1 input rows they
-// touch are read once instead of KH times.  FLIP reverses the taps: backward data of a stride-1
+// ---- 3x3 and 5x5 kernels: several output rows per thread ----
+// A thread owns output rows R*ohb .. R*ohb+R-1 of one column: the weights of a channel are read once
+// for all of them, and with unit stride and dilation (UNIT) the R + KH - 1 input rows they touch
+// are read once instead of KH times.  FLIP reverses the taps: backward data of a stride-1
 // layer is the forward pass of the mirrored kernel with the roles of the blobs exchanged (the host
 // code swaps the fields and sets the padding to dilation*(k-1) - pad, which may be negative).
-constexpr int kRows = 4;
+// Rows per thread: eight where the input rows are shared between them, four where every tap of every
+// row is a load of its own.
+constexpr int rows_per_thread(bool unit) { return unit ? 8 : 4; }
 
 template <typename T, int KH, int KW, bool UNIT>
 __device__ __forceinline__ void load_window(const DirectArgs& a, const T* xc, int oh0, int ow,
-                                            T (&xs)[kRows + KH - 1][KW]) {
+                                            T (&xs)[rows_per_thread(UNIT) + KH - 1][KW]) {
   static_assert(UNIT, "window form needs unit stride and dilation");
+  constexpr int kRows = rows_per_thread(UNIT);
 #pragma unroll
   for (int rr = 0; rr < kRows + KH - 1; ++rr) {
     const int ih = oh0 - a.ph + rr;
@@ -178,7 +184,8 @@ __device__ __forceinline__ T load_tap(const DirectArgs& a, const T* xc, int ih, 
 
 template <typename T, int KH, int KW, bool UNIT, bool FLIP, bool ACC>
 __global__ __launch_bounds__(256) void direct_rows_kernel(const DirectArgs a) {
-  const uint32_t idx = blockIdx.x * 256u + threadIdx.x;
+  constexpr int kRows = rows_per_thread(UNIT);
+  const uint32_t idx = xcd_contiguous_block_id() * 256u + threadIdx.x;
   if (idx >= a.row_items) return;
   const uint32_t q1 = mdiv(idx, a.mOW), ow = idx - q1 * (uint32_t)a.OW;
   const uint32_t q2 = mdiv(q1, a.mOHB), ohb = q1 - q2 * (uint32_t)a.OHB;
@@ -230,10 +237,11 @@ __global__ __launch_bounds__(256) void direct_rows_kernel(const DirectArgs a) {
 }
 
 // Filter gradient, 3x3 and 5x5: lanes are output columns, a thread keeps one running sum per tap
-// over its (image, four rows, column) items; the sums are then added over the wave (fixed
+// over its (image, R rows, column) items; the sums are then added over the wave (fixed
 // shuffle tree) and over the four waves.
 template <typename T, int KH, int KW, bool UNIT>
 __global__ __launch_bounds__(256) void direct_wgrad_rows_kernel(const DirectArgs a) {
+  constexpr int kRows = rows_per_thread(UNIT);
   __shared__ T red[4][KH * KW];
   const int t = threadIdx.x, lane = t & 63, wv = t >> 6;
   const uint32_t pair = blockIdx.x, split = blockIdx.y;
@@ -305,7 +313,7 @@ __global__ __launch_bounds__(256) void direct_wgrad_rows_kernel(const DirectArgs
 template <typename T, int KH, int KW, int S, bool ACC>
 __global__ __launch_bounds__(256) void direct_bwd_blocks_kernel(const DirectArgs a) {
   constexpr int QH = (KH - 1) / S + 1, QW = (KW - 1) / S + 1;
-  const uint32_t idx = blockIdx.x * 256u + threadIdx.x;
+  const uint32_t idx = xcd_contiguous_block_id() * 256u + threadIdx.x;
   if (idx >= a.block_items) return;
   const uint32_t q1 = mdiv(idx, a.mBW), bb = idx - q1 * (uint32_t)a.BW;
   const uint32_t q2 = mdiv(q1, a.mBH), ba = q1 - q2 * (uint32_t)a.BH;
@@ -379,10 +387,11 @@ int launch_direct_k(int pass, const DirectArgs& a, bool accumulate, hipStream_t 
   return (int)hipGetLastError();
 }
 
-// The four-rows kernels.  Backward data (stride 1 only) runs as the forward pass of the mirrored
+// The rows-per-thread kernels.  Backward data (stride 1 only) runs as the forward pass of the mirrored
 // problem: dy is the input blob with K channels, dx the output with C channels.
 template <typename T, int KH, int KW, bool UNIT>
 int launch_rows(int pass, const DirectArgs& src, bool accumulate, hipStream_t s) {
+  constexpr int kRows = rows_per_thread(UNIT);
   DirectArgs a = src;
   if (pass == 2) {
     a.OHB = (a.OH + kRows - 1) / kRows;

@@ -1,7 +1,7 @@
 """Turns rocprofv3 CSV output of a ``bench.py`` run into the short text summaries kept under profiles/.
 
     python -m paper_1810_02272_amd.profile_summary trace  <dir with *_kernel_trace.csv>  > profiles/<name>.txt
-    python -m paper_1810_02272_amd.profile_summary traffic <fetch dir> <write dir> [--workload config4|f64|ip5|pg]
+    python -m paper_1810_02272_amd.profile_summary traffic <fetch dir> <write dir> [--workload config4|f64|ip5|dw|pg]
     python -m paper_1810_02272_amd.profile_summary sq <dir with *_counter_collection.csv of an SQ_* --pmc run>
 
 ``trace`` prints calls / average / min / max duration per (kernel, grid).  ``traffic`` reads two
@@ -32,6 +32,8 @@ WORKLOADS = {
     "f64": (("corr64_kernel", "wgrad64_kernel", "bias_grad64_kernel"), PASSES, ["5.a", "5.b", "5.c"], "f64/"),
     "ip5": (("wgrad_kernel", "relu_bwd_kernel", "corr_kernel", "colsum_kernel"),
             ("fwd", "relu_bwd", "bwd_data", "bwd_filter", "bwd_bias"), ["ip5.6", "ip5.7", "ip5.8"], ""),
+    "dw": (("direct_rows_kernel", "direct_bwd_blocks_kernel", "direct_wgrad_rows_kernel", "bias_grad_kernel"), PASSES,
+           ["dw.a", "dw.b", "dw.c", "dw.d", "dw.e"], ""),
     "pg": (("pg_sample_kernel", "pg_discount_kernel", "pg_sigmoid_kernel", "pg_softmax_rows_kernel"),
            ("sample_action", "discount_rewards", "sigmoid_bottom_diff", "softmax_bottom_diff"), ["pg"], ""),
 }

@@ -198,6 +198,8 @@ struct DirectArgs {
   // 3x3 and 5x5 kernels: a thread takes R consecutive output rows of one column (R = 8 or 4)
   int32_t OHB;                         // ceil(OH / R)
   Magic mOHB;
+  int32_t OWQ;                         // four columns per thread: OW / 4
+  Magic mOWQ;
   uint32_t row_items;                  // N*K*OHB*OW
   uint32_t w_out_stride, w_in_stride;  // weight index = group block + out*w_out_stride + in*w_in_stride + tap
   // 3x3 and 5x5 backward data at stride 2: a thread takes one stride x stride block of dx

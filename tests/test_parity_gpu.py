@@ -132,6 +132,11 @@ DIRECT_CASES = [
     P(3, 9, 23, 20, 9, 3, 3, 2, 2, 0, 0, 1, 1, 9),             # 3x3 stride 2 without padding (last row unread)
     P(2, 6, 16, 19, 12, 3, 3, 2, 2, 3, 2, 1, 1, 3),            # 3x3 stride 2, pad beyond the kernel, 2 -> 4 channels
     P(2, 5, 18, 17, 5, 5, 5, 2, 2, 1, 4, 1, 1, 5),             # 5x5 stride 2, uneven padding
+    # "same" padding along rows of a multiple of four elements: four columns per thread, 16-byte accesses
+    P(3, 7, 18, 12, 7, 3, 3, 1, 1, 1, 1, 1, 1, 7),             # 3x3, OH not a multiple of four
+    P(2, 6, 9, 8, 12, 5, 5, 1, 1, 2, 2, 1, 1, 3),              # 5x5, two channels in and four out per group
+    P(2, 5, 11, 20, 5, 3, 3, 1, 1, 0, 1, 1, 1, 5),             # no padding along the height
+    P(2, 4, 7, 4, 4, 5, 5, 1, 1, 3, 2, 1, 1, 4),               # a single four-column block per row
 ]
 
 # Shapes that select the patch-staged kernel (256-column tiles of the 16-row MFMA): 48 or <= 16
@@ -158,6 +163,34 @@ def test_thin_groups_direct_kernels(i):
     d = conv.conv_desc_create(conv.ConvParams(**pd))
     assert "direct" in conv.conv_desc_kernel_names(d), conv.conv_desc_kernel_names(d)
     check_full(pd, 4400 + i, bias=bool(pd["bias_term"]))
+
+
+def test_thin_groups_blobs_not_16_byte_aligned():
+    """The four-columns-per-thread kernels need 16-byte aligned blobs; blobs that start 4 bytes off
+    such a boundary take the one-column kernels (the C boundary only asks for the base type's alignment)."""
+    pd = P(3, 8, 14, 16, 8, 3, 3, 1, 1, 1, 1, 1, 1, 8)
+    op = OracleParams(**pd)
+    x, w, b, dy = workloads.random_inputs(oracle.x_shape(op), oracle.w_shape(op), oracle.output_shape(op), 4711)
+    d = conv.conv_desc_create(conv.ConvParams(**pd))
+    assert "direct" in conv.conv_desc_kernel_names(d)
+    ws = torch.zeros(max(conv.conv_desc_workspace_bytes(d) // 4, 1), device=DEV)
+
+    def off_by_one(t):
+        buf = torch.full((t.numel() + 1,), float("nan"), device=DEV)
+        v = buf[1:].view(t.shape)
+        v.copy_(t)
+        assert v.data_ptr() % 16 == 4 and v.is_contiguous()
+        return v
+
+    xd, dyd, wd, bd = off_by_one(x), off_by_one(dy), w.to(DEV), b.to(DEV)
+    y, dx, dw = off_by_one(torch.zeros_like(dy)), off_by_one(torch.zeros_like(x)), torch.zeros_like(wd)
+    conv.conv_forward(d, xd, wd, bd, y, ws)
+    conv.conv_backward_data(d, wd, dyd, dx, ws)
+    conv.conv_backward_filter(d, xd, dyd, dw, 0.0, ws)
+    torch.cuda.synchronize()
+    assert nerr(y, oracle.forward(op, x.numpy(), w.numpy(), b.numpy())) <= TOL
+    assert nerr(dx, oracle.backward_data(op, w.numpy(), dy.numpy())) <= TOL
+    assert nerr(dw, oracle.backward_filter(op, x.numpy(), dy.numpy())) <= TOL
 
 
 @pytest.mark.parametrize("i", range(len(PATCH_CASES)))

@@ -151,10 +151,12 @@ def test_f64_beta_and_empty_batch():
     assert torch.all(edw == 0.0) and torch.all(edb == 0.0)
 
 
-def test_f64_blobs_between_2_and_4_gib():
+@pytest.mark.parametrize("group", [1, 2], ids=["gemm", "direct"])
+def test_f64_blobs_between_2_and_4_gib(group):
     """Maximum sizes of the double path: blobs of 3.0e8 doubles (2.3 GiB; the limit is 2^29 elements),
-    where byte offsets no longer fit 31 bits.  Sampled outputs, all of dw, the bias gradient in full."""
-    pd = P(19, 4, 2000, 2000, 4, 3, 3, 1, 1, 1, 1, 1, 1, 2)
+    where byte offsets no longer fit 31 bits; on the MFMA kernels (one group) and on the direct kernels
+    (two groups of two channels).  Sampled outputs, all of dw, the bias gradient in full."""
+    pd = P(19, 4, 2000, 2000, 4, 3, 3, 1, 1, 1, 1, 1, 1, group)
     op = OracleParams(**pd)
     x, w, b, dy = (t.double() for t in workloads.random_inputs(oracle.x_shape(op), oracle.w_shape(op),
                                                                oracle.output_shape(op), 5160))

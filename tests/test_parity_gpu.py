@@ -109,6 +109,7 @@ SWEEP = [
     P(2, 12, 29, 29, 16, 5, 5, 1, 1, 4, 4, 2, 2),           # 5x5 dilation 2 stride 1: five spaced slots, not nine
     P(2, 8, 31, 30, 8, 3, 3, 2, 2, 2, 2, 4, 4),             # stride 2 dilation 4: one phase, slots two rows apart
     P(2, 8, 26, 26, 8, 3, 2, 3, 2, 1, 1, 2, 3, 2),          # neither divides: dense slots, all phases
+    P(3, 12, 12, 14, 18, 3, 3, 2, 2, 1, 1, 2, 2, 3),        # three groups of 4 -> 6 channels on the GEMM tiles
 ]
 
 # Thin groups: the direct kernels (one thread per output element; lanes = (position, tap) for the

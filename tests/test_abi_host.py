@@ -47,6 +47,27 @@ def test_benchmark_layers_shapes_and_workspace():
         assert "fwd=" in names and "bwd_data=" in names and "bwd_filter=" in names
 
 
+def test_thin_groups_select_the_direct_kernels():
+    """Depthwise and near-depthwise descriptors take the direct kernels (forward and backward data then
+    need no workspace); wide groups and ungrouped layers stay on the matrix-unit tiles."""
+    for l in workloads.DW_LAYERS:
+        d = conv.conv_desc_create(conv.ConvParams(**l.params_dict()))
+        assert conv.conv_desc_output_shape(d) == l.y_shape
+        assert conv.conv_desc_kernel_names(d).startswith("fwd=direct;bwd_data=direct;bwd_filter=direct_wgrad")
+        assert conv.conv_desc_kernel_names_f64(d).startswith("fwd=direct64;")
+        assert 0 < conv.conv_desc_workspace_bytes(d) <= 32 << 20
+    for l in workloads.LAYERS:
+        assert "direct" not in conv.conv_desc_kernel_names(conv.conv_desc_create(conv.ConvParams(**l.params_dict())))
+    base = dict(n=4, h=20, w=20, kernel_h=3, kernel_w=3, pad_h=1, pad_w=1)
+    for c, k, g, direct in [(32, 32, 32, True), (32, 128, 32, True), (32, 32, 8, True), (64, 64, 8, False),
+                            (32, 512, 32, False), (32, 32, 1, False)]:
+        names = conv.conv_desc_kernel_names(conv.conv_desc_create(conv.ConvParams(c=c, num_output=k, group=g, **base)))
+        assert ("direct" in names) == direct, (c, k, g, names)
+    # more than 64 taps: the filter gradient's lane layout does not apply
+    big = conv.conv_desc_create(conv.ConvParams(n=1, c=8, h=20, w=20, num_output=8, kernel_h=9, kernel_w=9, group=8))
+    assert "direct" not in conv.conv_desc_kernel_names(big)
+
+
 @pytest.mark.parametrize("bad", [
     dict(c=0), dict(h=0), dict(num_output=0), dict(kernel_h=0), dict(stride_w=0), dict(pad_h=-1),
     dict(dilation_w=0), dict(group=0), dict(group=2, c=3), dict(group=2, c=4, num_output=3), dict(bias_term=2),

@@ -207,11 +207,11 @@ def main():
         step()
     torch.cuda.synchronize()
 
-    if args.overlap:
-        if is_ip:
-            print("--overlap applies to the convolution workloads", file=sys.stderr)
-            sys.exit(2)
-        side = torch.cuda.Stream()  # default priority
+    def time_two_streams(steps, warmup):
+        """Seconds for `steps` steps scheduled as a training loop would: forward passes, then the
+        backward-data chain on the launch stream with the filter and bias gradients of the same layers
+        on a second stream (default priority, workspace of its own)."""
+        side = torch.cuda.Stream()
         ws_side = torch.empty_like(ws)
 
         def overlapped_step():
@@ -230,14 +230,20 @@ def main():
             join.record(side)
             stream.wait_event(join)
 
-        for _ in range(args.warmup):
+        for _ in range(warmup):
             overlapped_step()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for _ in range(args.steps):
+        for _ in range(steps):
             overlapped_step()
         torch.cuda.synchronize()
-        wall = time.perf_counter() - t0
+        return time.perf_counter() - t0
+
+    if args.overlap:
+        if is_ip:
+            print("--overlap applies to the convolution workloads", file=sys.stderr)
+            sys.exit(2)
+        wall = time_two_streams(args.steps, args.warmup)
         flop_step = 3 * sum(l.flop_per_pass for l in layers)
         print(json.dumps({
             "metric": "conv fwd+bwd GFLOP/s, filter and bias gradients on a second stream, " + args.dtype,
@@ -379,6 +385,13 @@ def main():
         "per_layer": per_layer,
     }
 
+    if not is_ip:
+        # context only (never `value`): the same steps with the filter and bias gradients on a second stream
+        two = time_two_streams(args.steps, 3)
+        out["two_streams"] = {"value": round(flop_step * args.steps / two / 1e9, 1), "unit": "GFLOP/s",
+                              "ms_per_step": round(two / args.steps * 1e3, 4),
+                              "schedule": "forward chain, then backward data on the launch stream with backward "
+                                          "filter + backward bias of the same layers on a second stream"}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline_ip(layers) if is_ip else cpu_baseline(layers, args.cpu_sample_images)
     print(json.dumps(out))

@@ -38,7 +38,9 @@ def parse():
     ap.add_argument("--workload", default="config4", help="config0..config4, dw (depthwise layers), ip5, ip1, pg, or a comma list of layer names (all conv or all ip)")
     ap.add_argument("--dtype", default="f32", choices=["f32", "f64"],
                     help="base type of the convolution workloads (f64: the conv_*_f64 entry points)")
-    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
+    ap.add_argument("--no-cpu-baseline", action="store_true",
+                    help="skip the context legs after the timed steps (the CPU oracle timing and the two-stream "
+                         "schedule): what runs under the profiler")
     ap.add_argument("--cpu-sample-images", type=int, default=128)
     ap.add_argument("--cold-cache", action="store_true",
                     help="rotate every step among enough distinct sets of tensors that one pass over all sets "
@@ -385,7 +387,7 @@ def main():
         "per_layer": per_layer,
     }
 
-    if not is_ip:
+    if not is_ip and not args.no_cpu_baseline:
         # context only (never `value`): the same steps with the filter and bias gradients on a second stream
         two = time_two_streams(args.steps, 3)
         out["two_streams"] = {"value": round(flop_step * args.steps / two / 1e9, 1), "unit": "GFLOP/s",

@@ -378,6 +378,176 @@ __global__ __launch_bounds__(256) void direct_wgrad_rows_vec_kernel(const Direct
         ((red[0][t] + red[1][t]) + red[2][t]) + red[3][t];
 }
 
+// ---- stride 2, "same" padding along rows of a multiple of four elements ----
+// A thread owns four output rows x two output columns (2q, 2q+1): their windows span the input
+// columns 4q - pad_w .. 4q + KW - pad_w + 1, i.e. one aligned four-element load per input row plus
+// the halo elements, and the two outputs of a row leave as one two-element store.
+constexpr int kS2Rows = 4, kS2Cols = 2;
+
+template <typename T>
+struct alignas(2 * sizeof(T)) Vec2 {
+  T v[2];
+};
+
+template <typename T, int KH, int KW>
+__device__ __forceinline__ void load_window_s2(const DirectArgs& a, const T* xc, int oh0, int q,
+                                               T (&xs)[2 * (kS2Rows - 1) + KH][KW + 2]) {
+  constexpr int PW = (KW - 1) / 2, RIGHT = KW - 2 - PW;
+#pragma unroll
+  for (int rr = 0; rr < 2 * (kS2Rows - 1) + KH; ++rr) {
+    const int ih = 2 * oh0 - a.ph + rr;
+    const bool row_ok = (uint32_t)ih < (uint32_t)a.H;
+    const T* xr = xc + (row_ok ? ih : 0) * a.W;
+    const Vec4<T> mid = *reinterpret_cast<const Vec4<T>*>(xr + 4 * q);
+#pragma unroll
+    for (int v = 0; v < 4; ++v) xs[rr][PW + v] = row_ok ? mid.v[v] : T(0);
+#pragma unroll
+    for (int j = 0; j < PW; ++j) {
+      const int il = 4 * q - PW + j;
+      const bool ok = row_ok & (il >= 0);
+      const T v = xr[ok ? il : 0];
+      xs[rr][j] = ok ? v : T(0);
+    }
+#pragma unroll
+    for (int j = 0; j < RIGHT; ++j) {
+      const int ir = 4 * q + 4 + j;
+      const bool ok = row_ok & (ir < a.W);
+      const T v = xr[ok ? ir : 0];
+      xs[rr][PW + 4 + j] = ok ? v : T(0);
+    }
+  }
+}
+
+template <typename T, int KH, int KW>
+__global__ __launch_bounds__(256) void direct_rows_s2_kernel(const DirectArgs a) {
+  const uint32_t idx = xcd_contiguous_block_id() * 256u + threadIdx.x;
+  if (idx >= a.row_items) return;
+  const uint32_t q1 = mdiv(idx, a.mOWQ), q = idx - q1 * (uint32_t)a.OWQ;
+  const uint32_t q2 = mdiv(q1, a.mOHB), ohb = q1 - q2 * (uint32_t)a.OHB;
+  const uint32_t n = mdiv(q2, a.mK), k = q2 - n * (uint32_t)a.K;
+  const uint32_t g = mdiv(k, a.mKg), kl = k - g * (uint32_t)a.Kg;
+  const uint32_t HW = (uint32_t)(a.H * a.W);
+  const T* x = static_cast<const T*>(a.in) + (n * (uint32_t)a.C + g * (uint32_t)a.Cg) * HW;
+  const T* w = static_cast<const T*>(a.w) + (g * (uint32_t)a.Kg + kl) * (uint32_t)(a.Cg * KH * KW);
+  const int oh0 = (int)ohb * kS2Rows;
+  T acc[kS2Rows][kS2Cols];
+#pragma unroll
+  for (int r = 0; r < kS2Rows; ++r)
+#pragma unroll
+    for (int v = 0; v < kS2Cols; ++v) acc[r][v] = T(0);
+  for (int c = 0; c < a.Cg; ++c) {
+    T wv[KH][KW];
+#pragma unroll
+    for (int i = 0; i < KH; ++i)
+#pragma unroll
+      for (int j = 0; j < KW; ++j) wv[i][j] = w[(uint32_t)(c * KH * KW + i * KW + j)];
+    T xs[2 * (kS2Rows - 1) + KH][KW + 2];
+    load_window_s2<T, KH, KW>(a, x + (uint32_t)c * HW, oh0, (int)q, xs);
+#pragma unroll
+    for (int r = 0; r < kS2Rows; ++r)
+#pragma unroll
+      for (int i = 0; i < KH; ++i)
+#pragma unroll
+        for (int j = 0; j < KW; ++j)
+#pragma unroll
+          for (int v = 0; v < kS2Cols; ++v) acc[r][v] += wv[i][j] * xs[2 * r + i][2 * v + j];
+  }
+  const T bb = a.bias ? static_cast<const T*>(a.bias)[k] : T(0);
+  T* out = static_cast<T*>(a.out) + ((n * (uint32_t)a.K + k) * (uint32_t)a.OH + (uint32_t)oh0) * (uint32_t)a.OW + 2u * q;
+#pragma unroll
+  for (int r = 0; r < kS2Rows; ++r)
+    if (oh0 + r < a.OH) {
+      Vec2<T> o;
+      o.v[0] = acc[r][0] + bb;
+      o.v[1] = acc[r][1] + bb;
+      *reinterpret_cast<Vec2<T>*>(out + (uint32_t)r * (uint32_t)a.OW) = o;
+    }
+}
+
+template <typename T, int KH, int KW>
+__global__ __launch_bounds__(256) void direct_wgrad_rows_s2_kernel(const DirectArgs a) {
+  __shared__ T red[4][KH * KW];
+  const int t = threadIdx.x, lane = t & 63, wv = t >> 6;
+  const uint32_t pair = blockIdx.x, split = blockIdx.y;
+  const uint32_t k = mdiv(pair, a.mCg), c = pair - k * (uint32_t)a.Cg;
+  const uint32_t g = mdiv(k, a.mKg);
+  const uint32_t P = (uint32_t)(a.OH * a.OW), HW = (uint32_t)(a.H * a.W);
+  const uint32_t n0 = split * (uint32_t)a.imgs_per_split;
+  const uint32_t n1 = n0 + (uint32_t)a.imgs_per_split < (uint32_t)a.N ? n0 + (uint32_t)a.imgs_per_split : (uint32_t)a.N;
+  const uint32_t items = (n1 - n0) * (uint32_t)a.OHB * (uint32_t)a.OWQ;
+  const T* dy = static_cast<const T*>(a.w) + k * P;
+  const T* x = static_cast<const T*>(a.in) + (g * (uint32_t)a.Cg + c) * HW;
+  T acc[KH][KW];
+#pragma unroll
+  for (int i = 0; i < KH; ++i)
+#pragma unroll
+    for (int j = 0; j < KW; ++j) acc[i][j] = T(0);
+  for (uint32_t item = (uint32_t)t; item < items; item += 256u) {
+    const uint32_t q1 = mdiv(item, a.mOWQ), q = item - q1 * (uint32_t)a.OWQ;
+    const uint32_t nl = mdiv(q1, a.mOHB), ohb = q1 - nl * (uint32_t)a.OHB;
+    const uint32_t n = n0 + nl;
+    const int oh0 = (int)ohb * kS2Rows;
+    const T* dn = dy + n * (uint32_t)a.K * P + 2u * q;
+    T dv[kS2Rows][kS2Cols];
+#pragma unroll
+    for (int r = 0; r < kS2Rows; ++r) {
+      const bool ok = oh0 + r < a.OH;
+      const Vec2<T> d2 = *reinterpret_cast<const Vec2<T>*>(dn + (ok ? (uint32_t)(oh0 + r) * (uint32_t)a.OW : 0u));
+      dv[r][0] = ok ? d2.v[0] : T(0);
+      dv[r][1] = ok ? d2.v[1] : T(0);
+    }
+    T xs[2 * (kS2Rows - 1) + KH][KW + 2];
+    load_window_s2<T, KH, KW>(a, x + n * (uint32_t)a.C * HW, oh0, (int)q, xs);
+#pragma unroll
+    for (int i = 0; i < KH; ++i)
+#pragma unroll
+      for (int j = 0; j < KW; ++j)
+#pragma unroll
+        for (int r = 0; r < kS2Rows; ++r)
+#pragma unroll
+          for (int v = 0; v < kS2Cols; ++v) acc[i][j] += dv[r][v] * xs[2 * r + i][2 * v + j];
+  }
+#pragma unroll
+  for (int i = 0; i < KH; ++i)
+#pragma unroll
+    for (int j = 0; j < KW; ++j) {
+      T v = acc[i][j];
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) v += __shfl_down(v, off, 64);
+      if (lane == 0) red[wv][i * KW + j] = v;
+    }
+  __syncthreads();
+  if (t < KH * KW)
+    static_cast<T*>(a.part)[split * a.w_elems + pair * (uint32_t)(KH * KW) + (uint32_t)t] =
+        ((red[0][t] + red[1][t]) + red[2][t]) + red[3][t];
+}
+
+// Stride-2 launcher for forward (pass 0) and filter gradient (pass 2); false when the shape or the
+// alignment of the blobs does not fit (the caller then takes the one-column kernels).
+template <typename T, int KH, int KW>
+bool launch_s2(int pass, const DirectArgs& src, hipStream_t s, int* status) {
+  const uintptr_t mask = 4 * sizeof(T) - 1;
+  const uintptr_t other = pass == 0 ? (uintptr_t)src.out : (uintptr_t)src.w;  // y or dy: two-element accesses
+  const bool fits = src.sh == 2 && src.sw == 2 && src.dh == 1 && src.dw == 1 && src.W % 4 == 0 &&
+                    src.pw == (KW - 1) / 2 && 2 * src.OW == src.W && ((uintptr_t)src.in & mask) == 0 &&
+                    (other & (2 * sizeof(T) - 1)) == 0;
+  if (!fits) return false;
+  DirectArgs a = src;
+  a.OWQ = src.W / 4;
+  a.mOWQ = make_magic((uint32_t)a.OWQ);
+  a.OHB = (a.OH + kS2Rows - 1) / kS2Rows;
+  a.mOHB = make_magic((uint32_t)a.OHB);
+  if (pass == 0) {
+    a.row_items = (uint32_t)a.N * (uint32_t)a.K * (uint32_t)a.OHB * (uint32_t)a.OWQ;
+    hipLaunchKernelGGL((direct_rows_s2_kernel<T, KH, KW>), dim3((a.row_items + 255u) / 256u), dim3(256), 0, s, a);
+  } else {
+    hipLaunchKernelGGL((direct_wgrad_rows_s2_kernel<T, KH, KW>), dim3((uint32_t)(a.K * a.Cg), (uint32_t)a.S), dim3(256),
+                       0, s, a);
+  }
+  *status = (int)hipGetLastError();
+  return true;
+}
+
 // Filter gradient, 3x3 and 5x5: lanes are output columns, a thread keeps one running sum per tap
 // over its (image, R rows, column) items; the sums are then added over the wave (fixed
 // shuffle tree) and over the four waves.
@@ -515,6 +685,95 @@ int launch_bwd_blocks(const DirectArgs& src, bool accumulate, hipStream_t s) {
   return (int)hipGetLastError();
 }
 
+// Backward data of a stride-2 "same" layer (pad = (k-1)/2 both ways, dilation 1) on rows of a
+// multiple of four elements: a thread owns dx rows 2t, 2t+1 and columns 4q .. 4q+3 and stores them
+// as two four-element rows.  With h + PH = 2a + rh, tap i reaches row h exactly when i has the
+// parity of rh, and then reads dy row a - i/2; all of that is known at compile time per (row,
+// column) of the block, so the loops below fold to the taps that apply.
+template <typename T, int KH, int KW, bool ACC>
+__global__ __launch_bounds__(256) void direct_bwd_s2_vec_kernel(const DirectArgs a) {
+  constexpr int PH = (KH - 1) / 2, PW = (KW - 1) / 2;
+  constexpr int DR0 = (PH >> 1) - (KH - 1) / 2, DR1 = (1 + PH) >> 1, NR = DR1 - DR0 + 1;
+  constexpr int DC0 = (PW >> 1) - (KW - 1) / 2, DC1 = (3 + PW) >> 1, NC = DC1 - DC0 + 1;
+  const uint32_t idx = xcd_contiguous_block_id() * 256u + threadIdx.x;
+  if (idx >= a.block_items) return;
+  const uint32_t q1 = mdiv(idx, a.mBW), q = idx - q1 * (uint32_t)a.BW;
+  const uint32_t q2 = mdiv(q1, a.mBH), t = q1 - q2 * (uint32_t)a.BH;
+  const uint32_t n = mdiv(q2, a.mC), c = q2 - n * (uint32_t)a.C;
+  const uint32_t g = mdiv(c, a.mCg), cl = c - g * (uint32_t)a.Cg;
+  const uint32_t P = (uint32_t)(a.OH * a.OW);
+  const T* dy = static_cast<const T*>(a.in) + (n * (uint32_t)a.K + g * (uint32_t)a.Kg) * P;
+  const T* w = static_cast<const T*>(a.w) + (g * (uint32_t)a.Kg * (uint32_t)a.Cg + cl) * (uint32_t)(KH * KW);
+  T acc[2][4];
+#pragma unroll
+  for (int r = 0; r < 2; ++r)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) acc[r][v] = T(0);
+  for (int k = 0; k < a.Kg; ++k) {
+    const T* wk = w + (uint32_t)k * (uint32_t)a.Cg * (uint32_t)(KH * KW);
+    const T* dk = dy + (uint32_t)k * P;
+    T wv[KH][KW];
+#pragma unroll
+    for (int i = 0; i < KH; ++i)
+#pragma unroll
+      for (int j = 0; j < KW; ++j) wv[i][j] = wk[i * KW + j];
+    T dv[NR][NC];
+#pragma unroll
+    for (int dr = 0; dr < NR; ++dr)
+#pragma unroll
+      for (int dc = 0; dc < NC; ++dc) {
+        const int oh = (int)t + DR0 + dr, ow = 2 * (int)q + DC0 + dc;
+        const bool ok = ((uint32_t)oh < (uint32_t)a.OH) & ((uint32_t)ow < (uint32_t)a.OW);
+        const T val = dk[ok ? oh * a.OW + ow : 0];
+        dv[dr][dc] = ok ? val : T(0);
+      }
+#pragma unroll
+    for (int r = 0; r < 2; ++r)
+#pragma unroll
+      for (int v = 0; v < 4; ++v)
+#pragma unroll
+        for (int i = 0; i < KH; ++i)
+#pragma unroll
+          for (int j = 0; j < KW; ++j)
+            if ((i & 1) == ((r + PH) & 1) && (j & 1) == ((v + PW) & 1))
+              acc[r][v] += wv[i][j] * dv[((r + PH) >> 1) - (i >> 1) - DR0][((v + PW) >> 1) - (j >> 1) - DC0];
+  }
+#pragma unroll
+  for (int r = 0; r < 2; ++r) {
+    const uint32_t h = 2u * t + (uint32_t)r;
+    if (h < (uint32_t)a.H) {
+      Vec4<T>* dst = reinterpret_cast<Vec4<T>*>(static_cast<T*>(a.out) +
+                                                ((n * (uint32_t)a.C + c) * (uint32_t)a.H + h) * (uint32_t)a.W + 4u * q);
+      Vec4<T> o;
+      if (ACC) o = *dst;
+#pragma unroll
+      for (int v = 0; v < 4; ++v) o.v[v] = ACC ? o.v[v] + acc[r][v] : acc[r][v];
+      *dst = o;
+    }
+  }
+}
+
+template <typename T, int KH, int KW>
+bool launch_bwd_s2_vec(const DirectArgs& src, bool accumulate, hipStream_t s, int* status) {
+  const bool fits = src.sh == 2 && src.sw == 2 && src.dh == 1 && src.dw == 1 && src.W % 4 == 0 &&
+                    src.ph == (KH - 1) / 2 && src.pw == (KW - 1) / 2 &&
+                    ((uintptr_t)src.out & (4 * sizeof(T) - 1)) == 0;
+  if (!fits) return false;
+  DirectArgs a = src;
+  a.BH = (a.H + 1) / 2;
+  a.BW = a.W / 4;
+  a.mBH = make_magic((uint32_t)a.BH);
+  a.mBW = make_magic((uint32_t)a.BW);
+  a.block_items = (uint32_t)a.N * (uint32_t)a.C * (uint32_t)a.BH * (uint32_t)a.BW;
+  const dim3 grid((a.block_items + 255u) / 256u);
+  if (accumulate)
+    hipLaunchKernelGGL((direct_bwd_s2_vec_kernel<T, KH, KW, true>), grid, dim3(256), 0, s, a);
+  else
+    hipLaunchKernelGGL((direct_bwd_s2_vec_kernel<T, KH, KW, false>), grid, dim3(256), 0, s, a);
+  *status = (int)hipGetLastError();
+  return true;
+}
+
 template <typename T, int KH, int KW>
 int launch_direct_k(int pass, const DirectArgs& a, bool accumulate, hipStream_t s) {
   if (pass == 0) {
@@ -606,6 +865,11 @@ int launch_rows(int pass, const DirectArgs& src, bool accumulate, hipStream_t s)
 
 template <typename T>
 int launch_direct_t(int pass, const DirectArgs& a, bool accumulate, hipStream_t s) {
+  if (pass != 1) {
+    int status = 0;
+    if (a.kh == 3 && a.kw == 3 && launch_s2<T, 3, 3>(pass, a, s, &status)) return status;
+    if (a.kh == 5 && a.kw == 5 && launch_s2<T, 5, 5>(pass, a, s, &status)) return status;
+  }
   const bool unit = a.sh == 1 && a.sw == 1 && a.dh == 1 && a.dw == 1;
   const bool rows_ok = pass != 1 || (a.sh == 1 && a.sw == 1);  // backward data: stride 1 only
   if (rows_ok && a.kh == 3 && a.kw == 3)
@@ -617,6 +881,9 @@ int launch_direct_t(int pass, const DirectArgs& a, bool accumulate, hipStream_t 
     return (int)hipGetLastError();
   }
   if (pass == 1 && a.sh == 2 && a.sw == 2 && a.dh == 1 && a.dw == 1) {
+    int status = 0;
+    if (a.kh == 3 && a.kw == 3 && launch_bwd_s2_vec<T, 3, 3>(a, accumulate, s, &status)) return status;
+    if (a.kh == 5 && a.kw == 5 && launch_bwd_s2_vec<T, 5, 5>(a, accumulate, s, &status)) return status;
     if (a.kh == 3 && a.kw == 3) return launch_bwd_blocks<T, 3, 3, 2>(a, accumulate, s);
     if (a.kh == 5 && a.kw == 5) return launch_bwd_blocks<T, 5, 5, 2>(a, accumulate, s);
   }

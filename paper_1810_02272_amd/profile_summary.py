@@ -32,8 +32,9 @@ WORKLOADS = {
     "f64": (("corr64_kernel", "wgrad64_kernel", "bias_grad64_kernel"), PASSES, ["5.a", "5.b", "5.c"], "f64/"),
     "ip5": (("wgrad_kernel", "relu_bwd_kernel", "corr_kernel", "colsum_kernel"),
             ("fwd", "relu_bwd", "bwd_data", "bwd_filter", "bwd_bias"), ["ip5.6", "ip5.7", "ip5.8"], ""),
-    "dw": (("direct_rows_kernel", "direct_rows_vec_kernel", "direct_bwd_blocks_kernel", "direct_wgrad_rows_kernel",
-            "direct_wgrad_rows_vec_kernel", "bias_grad_kernel"), PASSES,
+    "dw": (("direct_rows_kernel", "direct_rows_vec_kernel", "direct_rows_s2_kernel", "direct_bwd_blocks_kernel",
+            "direct_bwd_s2_vec_kernel", "direct_wgrad_rows_kernel", "direct_wgrad_rows_vec_kernel",
+            "direct_wgrad_rows_s2_kernel", "bias_grad_kernel"), PASSES,
            ["dw.a", "dw.b", "dw.c", "dw.d", "dw.e"], ""),
     "pg": (("pg_sample_kernel", "pg_discount_kernel", "pg_sigmoid_kernel", "pg_softmax_rows_kernel"),
            ("sample_action", "discount_rewards", "sigmoid_bottom_diff", "softmax_bottom_diff"), ["pg"], ""),

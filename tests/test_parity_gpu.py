@@ -138,6 +138,11 @@ DIRECT_CASES = [
     P(2, 6, 9, 8, 12, 5, 5, 1, 1, 2, 2, 1, 1, 3),              # 5x5, two channels in and four out per group
     P(2, 5, 11, 20, 5, 3, 3, 1, 1, 0, 1, 1, 1, 5),             # no padding along the height
     P(2, 4, 7, 4, 4, 5, 5, 1, 1, 3, 2, 1, 1, 4),               # a single four-column block per row
+    # the same at stride 2: two output columns per thread
+    P(2, 6, 18, 16, 6, 3, 3, 2, 2, 1, 1, 1, 1, 6),             # 3x3 stride 2
+    P(2, 4, 13, 12, 8, 5, 5, 2, 2, 2, 2, 1, 1, 4),             # 5x5 stride 2, channel multiplier 2, odd height
+    P(3, 4, 10, 8, 4, 3, 3, 2, 2, 0, 1, 1, 1, 4),              # no padding along the height
+    P(2, 4, 9, 20, 4, 3, 3, 2, 2, 3, 1, 1, 1, 2),              # two channels per group, tall padding
 ]
 
 # Shapes that select the patch-staged kernel (256-column tiles of the 16-row MFMA): 48 or <= 16

@@ -40,16 +40,33 @@ def is_stale() -> bool:
 
 
 def build(force: bool = True, verbose: bool = False) -> str:
-    """Compile every kernel for gfx950 and link the C-ABI library next to this file."""
+    """Compile every kernel for gfx950 (one hipcc process per source file, side by side) and link the
+    C-ABI library next to this file."""
     if not force and not is_stale():
         return LIB
-    cmd = [_hipcc(), *HIPCC_FLAGS, "-I", os.path.join(_ROOT, "include"), "-I", CSRC,
-           "-o", LIB, *[os.path.join(CSRC, s) for s in SOURCES]]
+    from concurrent.futures import ThreadPoolExecutor
+
+    obj_dir = os.path.join(_HERE, "_build")
+    os.makedirs(obj_dir, exist_ok=True)
+    flags = [f for f in HIPCC_FLAGS if f != "-shared"]
+    include = ["-I", os.path.join(_ROOT, "include"), "-I", CSRC]
+
+    def compile_one(src: str) -> str:
+        obj = os.path.join(obj_dir, os.path.splitext(src)[0] + ".o")
+        cmd = [_hipcc(), *flags, *include, "-c", os.path.join(CSRC, src), "-o", obj]
+        res = subprocess.run(cmd, cwd=CSRC, capture_output=True, text=True)
+        if res.returncode != 0:
+            raise RuntimeError("hipcc failed:\n" + " ".join(cmd) + "\n" + res.stdout + res.stderr)
+        if verbose:
+            print(res.stderr)
+        return obj
+
+    with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1)) as pool:
+        objs = list(pool.map(compile_one, SOURCES))
+    cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
     res = subprocess.run(cmd, cwd=CSRC, capture_output=True, text=True)
     if res.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + " ".join(cmd) + "\n" + res.stdout + res.stderr)
-    if verbose:
-        print(res.stderr)
+        raise RuntimeError("hipcc link failed:\n" + " ".join(cmd) + "\n" + res.stdout + res.stderr)
     return LIB
 
 

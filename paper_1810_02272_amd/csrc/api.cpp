@@ -254,7 +254,7 @@ int run_forward(const conv_desc* d, const float* x, const float* w, const float*
     da.w = w;
     da.bias = bias;
     da.out = y;
-    const int ed = launch_direct(0, da, false, false, hip_stream);
+    const int ed = launch_direct(0, da, false, hip_stream);
     return ed ? record_hip_error(ed) : CONV_OK;
   }
   if (d->fwd_ws > 0 && (!ws || ws_bytes < d->fwd_ws)) return CONV_EWORKSPACE;
@@ -301,7 +301,8 @@ int run_backward_data(const conv_desc* d, const float* w, const float* dy, float
     da.in = dy;
     da.w = w;
     da.out = dx;
-    const int ed = launch_direct(1, da, false, beta != 0.f, hip_stream);
+    if (beta != 0.f) return CONV_EINVAL;  // accumulation into dx is only used by the ungrouped InnerProduct passes
+    const int ed = launch_direct(1, da, false, hip_stream);
     return ed ? record_hip_error(ed) : CONV_OK;
   }
   if (d->bwd_ws > 0 && (!ws || ws_bytes < d->bwd_ws)) return CONV_EWORKSPACE;
@@ -358,7 +359,7 @@ int run_backward_filter(const conv_desc* d, const float* x, const float* dy, flo
     da.w = dy;
     da.part = ws;
     a.S = da.S;
-    if (!empty) e = launch_direct(2, da, false, false, hip_stream);
+    if (!empty) e = launch_direct(2, da, false, hip_stream);
   } else if (!empty) {
     e = launch_wgrad(d->wg_tile, a, hip_stream);
   }
@@ -949,7 +950,7 @@ int conv_forward_f64(const conv_desc_t* d, const double* x, const double* w, con
     da.w = w;
     da.bias = bias;
     da.out = y;
-    const int ed = launch_direct(0, da, true, false, hip_stream);
+    const int ed = launch_direct(0, da, true, hip_stream);
     return ed ? record_hip_error(ed) : CONV_OK;
   }
   return run_corr64(d, d->fwd64_rows, d->fwd64, d->fwd64_pack, d->fwd64_ws, w, x, bias, y, 0, ws, ws_bytes,
@@ -966,7 +967,7 @@ int conv_backward_data_f64(const conv_desc_t* d, const double* w, const double* 
     da.in = dy;
     da.w = w;
     da.out = dx;
-    const int ed = launch_direct(1, da, true, false, hip_stream);
+    const int ed = launch_direct(1, da, true, hip_stream);
     return ed ? record_hip_error(ed) : CONV_OK;
   }
   const size_t zero = d->bwd_zero_fill ? (size_t)d->bwd64.out_elems * 8 : 0;
@@ -993,7 +994,7 @@ int conv_backward_filter_f64(const conv_desc_t* d, const double* x, const double
     da.w = dy;
     da.part = ws;
     a.S = da.S;
-    if (!empty) e = launch_direct(2, da, true, false, hip_stream);
+    if (!empty) e = launch_direct(2, da, true, hip_stream);
   } else if (!empty) {
     e = launch_wgrad64(d->wg64_rows, a, hip_stream);
   }

@@ -245,8 +245,8 @@ int launch_wgrad(int32_t tile, const WgradArgs& a, void* stream);
 int launch_reduce(const ReduceArgs& a, void* stream);
 int launch_bias_grad(const BiasGradArgs& a, void* stream);
 int launch_fill_zero(void* dst, size_t bytes, void* stream);  // bytes a multiple of 4
-// pass: 0 forward, 1 backward data (accumulate: dx += instead of dx =), 2 filter-gradient partials
-int launch_direct(int pass, const DirectArgs& a, bool f64, bool accumulate, void* stream);
+// pass: 0 forward, 1 backward data (dx overwritten), 2 filter-gradient partials
+int launch_direct(int pass, const DirectArgs& a, bool f64, void* stream);
 // double base type: the same argument structs, pointer members addressing doubles
 constexpr int32_t kF64TileCols = 64, kF64TileK = 16;
 int32_t f64_pick_rows(int64_t rows, bool filter_gradient);  // 96, 64, 48, 32 or 16: pads `rows` least

@@ -56,7 +56,7 @@ __global__ __launch_bounds__(256) void direct_fwd_kernel(const DirectArgs a) {
 // dx[n][c][h][w] = sum over the group's output channels k and the taps (i, j) with
 //   h + ph - i*dh = sh*oh and w + pw - j*dw = sw*ow for an output position (oh, ow) of
 //   w[k][c - g*Cg][i][j] * dy[n][k][oh][ow]
-template <typename T, int KH, int KW, bool ACC>
+template <typename T, int KH, int KW>
 __global__ __launch_bounds__(256) void direct_bwd_data_kernel(const DirectArgs a) {
   const uint32_t idx = xcd_contiguous_block_id() * 256u + threadIdx.x;
   if (idx >= a.x_elems) return;
@@ -87,8 +87,7 @@ __global__ __launch_bounds__(256) void direct_bwd_data_kernel(const DirectArgs a
       }
     }
   }
-  T* dst = static_cast<T*>(a.out) + idx;
-  *dst = ACC ? *dst + acc : acc;
+  static_cast<T*>(a.out)[idx] = acc;
 }
 
 // part[s][k][c][i][j] = sum over the images of split s and all output positions of
@@ -182,7 +181,7 @@ __device__ __forceinline__ T load_tap(const DirectArgs& a, const T* xc, int ih, 
   return ok ? v : T(0);
 }
 
-template <typename T, int KH, int KW, bool UNIT, bool FLIP, bool ACC>
+template <typename T, int KH, int KW, bool UNIT, bool FLIP>
 __global__ __launch_bounds__(256) void direct_rows_kernel(const DirectArgs a) {
   constexpr int kRows = rows_per_thread(UNIT);
   const uint32_t idx = xcd_contiguous_block_id() * 256u + threadIdx.x;
@@ -230,9 +229,7 @@ __global__ __launch_bounds__(256) void direct_rows_kernel(const DirectArgs a) {
 #pragma unroll
   for (int r = 0; r < kRows; ++r)
     if (oh0 + r < a.OH) {
-      T* dst = out + (uint32_t)r * (uint32_t)a.OW;
-      const T v = acc[r] + bb;
-      *dst = ACC ? *dst + v : v;
+      out[(uint32_t)r * (uint32_t)a.OW] = acc[r] + bb;
     }
 }
 
@@ -271,7 +268,7 @@ __device__ __forceinline__ void load_window_vec(const DirectArgs& a, const T* xc
   }
 }
 
-template <typename T, int KH, int KW, bool FLIP, bool ACC>
+template <typename T, int KH, int KW, bool FLIP>
 __global__ __launch_bounds__(256) void direct_rows_vec_kernel(const DirectArgs a) {
   const uint32_t idx = xcd_contiguous_block_id() * 256u + threadIdx.x;
   if (idx >= a.row_items) return;
@@ -313,9 +310,8 @@ __global__ __launch_bounds__(256) void direct_rows_vec_kernel(const DirectArgs a
     if (oh0 + r < a.OH) {
       Vec4<T>* dst = reinterpret_cast<Vec4<T>*>(out + (uint32_t)r * (uint32_t)a.OW);
       Vec4<T> o;
-      if (ACC) o = *dst;
 #pragma unroll
-      for (int v = 0; v < kVecCols; ++v) o.v[v] = ACC ? o.v[v] + (acc[r][v] + bb) : acc[r][v] + bb;
+      for (int v = 0; v < kVecCols; ++v) o.v[v] = acc[r][v] + bb;
       *dst = o;
     }
 }
@@ -622,7 +618,7 @@ __global__ __launch_bounds__(256) void direct_wgrad_rows_kernel(const DirectArgs
 // h + ph = S*a + rh, w + pw = S*b + rw.  Tap (i, j) reaches phase (rh, rw) exactly when i - rh and
 // j - rw are non-negative multiples of S, and then reads dy at (a - (i-rh)/S, b - (j-rw)/S): the
 // block needs only ((KH-1)/S + 1) x ((KW-1)/S + 1) values of dy per channel and uses every tap once.
-template <typename T, int KH, int KW, int S, bool ACC>
+template <typename T, int KH, int KW, int S>
 __global__ __launch_bounds__(256) void direct_bwd_blocks_kernel(const DirectArgs a) {
   constexpr int QH = (KH - 1) / S + 1, QW = (KW - 1) / S + 1;
   const uint32_t idx = xcd_contiguous_block_id() * 256u + threadIdx.x;
@@ -663,14 +659,14 @@ __global__ __launch_bounds__(256) void direct_bwd_blocks_kernel(const DirectArgs
     for (int rw = 0; rw < S; ++rw) {
       const int h = (int)ba * S + rh - a.ph, wi = (int)bb * S + rw - a.pw;
       if ((uint32_t)h < (uint32_t)a.H && (uint32_t)wi < (uint32_t)a.W) {
-        T* dst = static_cast<T*>(a.out) + ((n * (uint32_t)a.C + c) * (uint32_t)a.H + (uint32_t)h) * (uint32_t)a.W + (uint32_t)wi;
-        *dst = ACC ? *dst + acc[rh][rw] : acc[rh][rw];
+        static_cast<T*>(a.out)[((n * (uint32_t)a.C + c) * (uint32_t)a.H + (uint32_t)h) * (uint32_t)a.W + (uint32_t)wi] =
+            acc[rh][rw];
       }
     }
 }
 
 template <typename T, int KH, int KW, int S>
-int launch_bwd_blocks(const DirectArgs& src, bool accumulate, hipStream_t s) {
+int launch_bwd_blocks(const DirectArgs& src, hipStream_t s) {
   DirectArgs a = src;
   a.BH = (a.H + a.ph + S - 1) / S;
   a.BW = (a.W + a.pw + S - 1) / S;
@@ -678,10 +674,7 @@ int launch_bwd_blocks(const DirectArgs& src, bool accumulate, hipStream_t s) {
   a.mBW = make_magic((uint32_t)a.BW);
   a.block_items = (uint32_t)a.N * (uint32_t)a.C * (uint32_t)a.BH * (uint32_t)a.BW;
   const dim3 grid((a.block_items + 255u) / 256u);
-  if (accumulate)
-    hipLaunchKernelGGL((direct_bwd_blocks_kernel<T, KH, KW, S, true>), grid, dim3(256), 0, s, a);
-  else
-    hipLaunchKernelGGL((direct_bwd_blocks_kernel<T, KH, KW, S, false>), grid, dim3(256), 0, s, a);
+  hipLaunchKernelGGL((direct_bwd_blocks_kernel<T, KH, KW, S>), grid, dim3(256), 0, s, a);
   return (int)hipGetLastError();
 }
 
@@ -690,7 +683,7 @@ int launch_bwd_blocks(const DirectArgs& src, bool accumulate, hipStream_t s) {
 // as two four-element rows.  With h + PH = 2a + rh, tap i reaches row h exactly when i has the
 // parity of rh, and then reads dy row a - i/2; all of that is known at compile time per (row,
 // column) of the block, so the loops below fold to the taps that apply.
-template <typename T, int KH, int KW, bool ACC>
+template <typename T, int KH, int KW>
 __global__ __launch_bounds__(256) void direct_bwd_s2_vec_kernel(const DirectArgs a) {
   constexpr int PH = (KH - 1) / 2, PW = (KW - 1) / 2;
   constexpr int DR0 = (PH >> 1) - (KH - 1) / 2, DR1 = (1 + PH) >> 1, NR = DR1 - DR0 + 1;
@@ -745,16 +738,15 @@ __global__ __launch_bounds__(256) void direct_bwd_s2_vec_kernel(const DirectArgs
       Vec4<T>* dst = reinterpret_cast<Vec4<T>*>(static_cast<T*>(a.out) +
                                                 ((n * (uint32_t)a.C + c) * (uint32_t)a.H + h) * (uint32_t)a.W + 4u * q);
       Vec4<T> o;
-      if (ACC) o = *dst;
 #pragma unroll
-      for (int v = 0; v < 4; ++v) o.v[v] = ACC ? o.v[v] + acc[r][v] : acc[r][v];
+      for (int v = 0; v < 4; ++v) o.v[v] = acc[r][v];
       *dst = o;
     }
   }
 }
 
 template <typename T, int KH, int KW>
-bool launch_bwd_s2_vec(const DirectArgs& src, bool accumulate, hipStream_t s, int* status) {
+bool launch_bwd_s2_vec(const DirectArgs& src, hipStream_t s, int* status) {
   const bool fits = src.sh == 2 && src.sw == 2 && src.dh == 1 && src.dw == 1 && src.W % 4 == 0 &&
                     src.ph == (KH - 1) / 2 && src.pw == (KW - 1) / 2 &&
                     ((uintptr_t)src.out & (4 * sizeof(T) - 1)) == 0;
@@ -766,24 +758,17 @@ bool launch_bwd_s2_vec(const DirectArgs& src, bool accumulate, hipStream_t s, in
   a.mBW = make_magic((uint32_t)a.BW);
   a.block_items = (uint32_t)a.N * (uint32_t)a.C * (uint32_t)a.BH * (uint32_t)a.BW;
   const dim3 grid((a.block_items + 255u) / 256u);
-  if (accumulate)
-    hipLaunchKernelGGL((direct_bwd_s2_vec_kernel<T, KH, KW, true>), grid, dim3(256), 0, s, a);
-  else
-    hipLaunchKernelGGL((direct_bwd_s2_vec_kernel<T, KH, KW, false>), grid, dim3(256), 0, s, a);
+  hipLaunchKernelGGL((direct_bwd_s2_vec_kernel<T, KH, KW>), grid, dim3(256), 0, s, a);
   *status = (int)hipGetLastError();
   return true;
 }
 
 template <typename T, int KH, int KW>
-int launch_direct_k(int pass, const DirectArgs& a, bool accumulate, hipStream_t s) {
+int launch_direct_k(int pass, const DirectArgs& a, hipStream_t s) {
   if (pass == 0) {
     hipLaunchKernelGGL((direct_fwd_kernel<T, KH, KW>), dim3((a.y_elems + 255u) / 256u), dim3(256), 0, s, a);
   } else {
-    const dim3 grid((a.x_elems + 255u) / 256u);
-    if (accumulate)
-      hipLaunchKernelGGL((direct_bwd_data_kernel<T, KH, KW, true>), grid, dim3(256), 0, s, a);
-    else
-      hipLaunchKernelGGL((direct_bwd_data_kernel<T, KH, KW, false>), grid, dim3(256), 0, s, a);
+    hipLaunchKernelGGL((direct_bwd_data_kernel<T, KH, KW>), dim3((a.x_elems + 255u) / 256u), dim3(256), 0, s, a);
   }
   return (int)hipGetLastError();
 }
@@ -791,7 +776,7 @@ int launch_direct_k(int pass, const DirectArgs& a, bool accumulate, hipStream_t 
 // The rows-per-thread kernels.  Backward data (stride 1 only) runs as the forward pass of the mirrored
 // problem: dy is the input blob with K channels, dx the output with C channels.
 template <typename T, int KH, int KW, bool UNIT>
-int launch_rows(int pass, const DirectArgs& src, bool accumulate, hipStream_t s) {
+int launch_rows(int pass, const DirectArgs& src, hipStream_t s) {
   constexpr int kRows = rows_per_thread(UNIT);
   DirectArgs a = src;
   // four columns per thread: "same" padding along the row, rows of a multiple of four elements,
@@ -843,11 +828,9 @@ int launch_rows(int pass, const DirectArgs& src, bool accumulate, hipStream_t s)
     a.row_items = (uint32_t)a.N * (uint32_t)a.K * (uint32_t)a.OHB * (uint32_t)a.OWQ;
     const dim3 vgrid((a.row_items + 255u) / 256u);
     if (pass == 0)
-      hipLaunchKernelGGL((direct_rows_vec_kernel<T, KH, KW, false, false>), vgrid, dim3(256), 0, s, a);
-    else if (accumulate)
-      hipLaunchKernelGGL((direct_rows_vec_kernel<T, KH, KW, true, true>), vgrid, dim3(256), 0, s, a);
+      hipLaunchKernelGGL((direct_rows_vec_kernel<T, KH, KW, false>), vgrid, dim3(256), 0, s, a);
     else
-      hipLaunchKernelGGL((direct_rows_vec_kernel<T, KH, KW, true, false>), vgrid, dim3(256), 0, s, a);
+      hipLaunchKernelGGL((direct_rows_vec_kernel<T, KH, KW, true>), vgrid, dim3(256), 0, s, a);
     return (int)hipGetLastError();
   }
   a.OHB = (a.OH + kRows - 1) / kRows;
@@ -855,16 +838,14 @@ int launch_rows(int pass, const DirectArgs& src, bool accumulate, hipStream_t s)
   a.row_items = (uint32_t)a.N * (uint32_t)a.K * (uint32_t)a.OHB * (uint32_t)a.OW;
   const dim3 grid((a.row_items + 255u) / 256u);
   if (pass == 0)
-    hipLaunchKernelGGL((direct_rows_kernel<T, KH, KW, UNIT, false, false>), grid, dim3(256), 0, s, a);
-  else if (accumulate)
-    hipLaunchKernelGGL((direct_rows_kernel<T, KH, KW, UNIT, true, true>), grid, dim3(256), 0, s, a);
+    hipLaunchKernelGGL((direct_rows_kernel<T, KH, KW, UNIT, false>), grid, dim3(256), 0, s, a);
   else
-    hipLaunchKernelGGL((direct_rows_kernel<T, KH, KW, UNIT, true, false>), grid, dim3(256), 0, s, a);
+    hipLaunchKernelGGL((direct_rows_kernel<T, KH, KW, UNIT, true>), grid, dim3(256), 0, s, a);
   return (int)hipGetLastError();
 }
 
 template <typename T>
-int launch_direct_t(int pass, const DirectArgs& a, bool accumulate, hipStream_t s) {
+int launch_direct_t(int pass, const DirectArgs& a, hipStream_t s) {
   if (pass != 1) {
     int status = 0;
     if (a.kh == 3 && a.kw == 3 && launch_s2<T, 3, 3>(pass, a, s, &status)) return status;
@@ -873,29 +854,29 @@ int launch_direct_t(int pass, const DirectArgs& a, bool accumulate, hipStream_t 
   const bool unit = a.sh == 1 && a.sw == 1 && a.dh == 1 && a.dw == 1;
   const bool rows_ok = pass != 1 || (a.sh == 1 && a.sw == 1);  // backward data: stride 1 only
   if (rows_ok && a.kh == 3 && a.kw == 3)
-    return unit ? launch_rows<T, 3, 3, true>(pass, a, accumulate, s) : launch_rows<T, 3, 3, false>(pass, a, accumulate, s);
+    return unit ? launch_rows<T, 3, 3, true>(pass, a, s) : launch_rows<T, 3, 3, false>(pass, a, s);
   if (rows_ok && a.kh == 5 && a.kw == 5)
-    return unit ? launch_rows<T, 5, 5, true>(pass, a, accumulate, s) : launch_rows<T, 5, 5, false>(pass, a, accumulate, s);
+    return unit ? launch_rows<T, 5, 5, true>(pass, a, s) : launch_rows<T, 5, 5, false>(pass, a, s);
   if (pass == 2) {
     hipLaunchKernelGGL(direct_wgrad_kernel<T>, dim3((uint32_t)(a.K * a.Cg), (uint32_t)a.S), dim3(256), 0, s, a);
     return (int)hipGetLastError();
   }
   if (pass == 1 && a.sh == 2 && a.sw == 2 && a.dh == 1 && a.dw == 1) {
     int status = 0;
-    if (a.kh == 3 && a.kw == 3 && launch_bwd_s2_vec<T, 3, 3>(a, accumulate, s, &status)) return status;
-    if (a.kh == 5 && a.kw == 5 && launch_bwd_s2_vec<T, 5, 5>(a, accumulate, s, &status)) return status;
-    if (a.kh == 3 && a.kw == 3) return launch_bwd_blocks<T, 3, 3, 2>(a, accumulate, s);
-    if (a.kh == 5 && a.kw == 5) return launch_bwd_blocks<T, 5, 5, 2>(a, accumulate, s);
+    if (a.kh == 3 && a.kw == 3 && launch_bwd_s2_vec<T, 3, 3>(a, s, &status)) return status;
+    if (a.kh == 5 && a.kw == 5 && launch_bwd_s2_vec<T, 5, 5>(a, s, &status)) return status;
+    if (a.kh == 3 && a.kw == 3) return launch_bwd_blocks<T, 3, 3, 2>(a, s);
+    if (a.kh == 5 && a.kw == 5) return launch_bwd_blocks<T, 5, 5, 2>(a, s);
   }
-  if (a.kh == 3 && a.kw == 3) return launch_direct_k<T, 3, 3>(pass, a, accumulate, s);
-  return launch_direct_k<T, 0, 0>(pass, a, accumulate, s);
+  if (a.kh == 3 && a.kw == 3) return launch_direct_k<T, 3, 3>(pass, a, s);
+  return launch_direct_k<T, 0, 0>(pass, a, s);
 }
 
 }  // namespace
 
-int launch_direct(int pass, const DirectArgs& a, bool f64, bool accumulate, void* stream) {
+int launch_direct(int pass, const DirectArgs& a, bool f64, void* stream) {
   hipStream_t s = (hipStream_t)stream;
-  return f64 ? launch_direct_t<double>(pass, a, accumulate, s) : launch_direct_t<float>(pass, a, accumulate, s);
+  return f64 ? launch_direct_t<double>(pass, a, s) : launch_direct_t<float>(pass, a, s);
 }
 
 }  // namespace mi355conv

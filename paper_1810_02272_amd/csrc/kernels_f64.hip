@@ -106,10 +106,11 @@ __global__ __launch_bounds__(kThreads) void corr64_kernel(const CorrArgs a) {
 #pragma unroll
     for (int j = 0; j < NB; ++j) acc[i][j] = f64x4{0., 0., 0., 0.};
 
-  f64x2 ra[A_PER][2];
-  double rb[4];
+  // Two register sets (see the loop below): f64x2 pairs of the A tile, four gathered k rows.
+  f64x2 raX[A_PER][2], raY[A_PER][2];
+  double rbX[4], rbY[4];
   // k-table entries of this wave's four k rows (uniform over the wave: scalar loads), fetched one
-  // chunk before their use so that the gather never waits on scalar memory
+  // iteration before the gather that uses them so that it never waits on scalar memory
   KTabEntry te[4], te_next[4];
   auto load_tab = [&](int kc) {
 #pragma unroll
@@ -119,7 +120,7 @@ __global__ __launch_bounds__(kThreads) void corr64_kernel(const CorrArgs a) {
 #pragma unroll
     for (int e = 0; e < 4; ++e) te[e] = te_next[e];
   };
-  auto load_chunk = [&](int kc) {
+  auto load_chunk = [&](f64x2(&ra)[A_PER][2], double(&rb)[4], int kc) {
 #pragma unroll
     for (int p = 0; p < A_PER; ++p) {
       const int piece = t + kThreads * p;
@@ -137,7 +138,7 @@ __global__ __launch_bounds__(kThreads) void corr64_kernel(const CorrArgs a) {
       rb[e] = buffer_load_f64(in_rsrc, ok ? cbase + 2u * te[e].koff : a.in_bytes);
     }
   };
-  auto store_chunk = [&](int buf) {
+  auto store_chunk = [&](f64x2(&ra)[A_PER][2], double(&rb)[4], int buf) {
 #pragma unroll
     for (int p = 0; p < A_PER; ++p) {
       const int piece = t + kThreads * p;
@@ -154,24 +155,40 @@ __global__ __launch_bounds__(kThreads) void corr64_kernel(const CorrArgs a) {
     for (int e = 0; e < 4; ++e) sb[e * LDB] = rb[e];
   };
 
-  const int nchunks = a.KP / BK;
+  // Pipeline, three chunks deep: while chunk kc is multiplied out of one LDS buffer, the register
+  // set holding chunk kc+1 (loaded two iterations ago) is written to the other buffer and reloaded
+  // with chunk kc+3; the other set holds chunk kc+2.  Chunk indices past the end are clamped: the
+  // last iterations re-load and re-store the final chunk into a buffer nobody reads.
+  const int nchunks = a.KP / BK, last = nchunks - 1;
   const double* opA = smem + (lane >> 4) * LDA + wm * MB * 16 + (lane & 15);
   const double* opB = smem + BK * LDA + (lane >> 4) * LDB + wn * NB * 16 + (lane & 15);
   load_tab(0);
   swap_tab();
-  load_chunk(0);
-  load_tab(nchunks > 1 ? 1 : 0);
-  store_chunk(0);
+  load_chunk(raX, rbX, 0);
+  store_chunk(raX, rbX, 0);
+  load_tab(last < 1 ? last : 1);
+  swap_tab();
+  load_chunk(raX, rbX, last < 1 ? last : 1);
+  load_tab(last < 2 ? last : 2);
+  swap_tab();
+  load_chunk(raY, rbY, last < 2 ? last : 2);
+  load_tab(last < 3 ? last : 3);
   __syncthreads();
-  for (int kc = 0; kc < nchunks; ++kc) {
+  auto iteration = [&](int kc, f64x2(&ra)[A_PER][2], double(&rb)[4]) {
     const int cur = kc & 1;
-    swap_tab();  // entries of chunk kc + 1, fetched during the previous iteration
-    if (kc + 1 < nchunks) load_chunk(kc + 1);  // in flight while this chunk is multiplied
-    load_tab(kc + 2 < nchunks ? kc + 2 : nchunks - 1);
+    swap_tab();  // entries of chunk kc + 3, fetched during the previous iteration
+    store_chunk(ra, rb, cur ^ 1);
+    load_chunk(ra, rb, kc + 3 < last ? kc + 3 : last);
+    load_tab(kc + 4 < last ? kc + 4 : last);
     chunk_mfma<MB, NB, LDA, LDB>(opA + cur * STAGE, opB + cur * STAGE, acc);
-    if (kc + 1 < nchunks) store_chunk(cur ^ 1);
     __syncthreads();
+  };
+  int kc = 0;
+  for (; kc + 1 < nchunks; kc += 2) {
+    iteration(kc, raX, rbX);
+    iteration(kc + 1, raY, rbY);
   }
+  if (kc < nchunks) iteration(kc, raX, rbX);
 
   // Epilogue: the same two LDS tables as the fp32 kernel (row -> channel / sub-pixel offset,
   // column -> image / pixel offset), the bias kept beside them as doubles.
@@ -288,8 +305,12 @@ __global__ __launch_bounds__(kThreads) void wgrad64_kernel(const WgradArgs a) {
 #pragma unroll
     for (int j = 0; j < NB; ++j) acc[i][j] = f64x4{0., 0., 0., 0.};
 
-  double ra[AR], rb[4];
-  auto load_chunk = [&](int chunk) {
+  // Two register sets: while chunk ch is multiplied out of one LDS buffer, the set holding chunk
+  // ch+1 (loaded two iterations ago) goes to the other buffer and is reloaded with chunk ch+3; the
+  // other set holds chunk ch+2.  Chunks past the end load nothing that is used (their columns fail
+  // the range test and read as zero into a buffer nobody multiplies).
+  double raX[AR], rbX[4], raY[AR], rbY[4];
+  auto load_chunk = [&](double(&ra)[AR], double(&rb)[4], int chunk) {
     const uint32_t col = c_begin + chunk * BK + kc;
     const bool colok = col < c_end;
     const uint32_t n = mdiv(col, a.mP);
@@ -309,7 +330,7 @@ __global__ __launch_bounds__(kThreads) void wgrad64_kernel(const WgradArgs a) {
       rb[e] = buffer_load_f64(x_rsrc, ok ? xbase + boff[e] : a.x_bytes);
     }
   };
-  auto store_chunk = [&](int buf) {
+  auto store_chunk = [&](double(&ra)[AR], double(&rb)[4], int buf) {
 #pragma unroll
     for (int e = 0; e < AR; ++e) smem[buf * STAGE + kc * LDA + rslot + 16 * e] = ra[e];
 #pragma unroll
@@ -319,17 +340,25 @@ __global__ __launch_bounds__(kThreads) void wgrad64_kernel(const WgradArgs a) {
   const double* opA = smem + (lane >> 4) * LDA + wm * MB * 16 + (lane & 15);
   const double* opB = smem + BK * LDA + (lane >> 4) * LDB + wn * NB * 16 + (lane & 15);
   if (nchunks > 0) {
-    load_chunk(0);
-    store_chunk(0);
+    load_chunk(raX, rbX, 0);
+    store_chunk(raX, rbX, 0);
+    load_chunk(raX, rbX, 1);
+    load_chunk(raY, rbY, 2);
   }
   __syncthreads();
-  for (int ch = 0; ch < nchunks; ++ch) {
+  auto iteration = [&](int ch, double(&ra)[AR], double(&rb)[4]) {
     const int cur = ch & 1;
-    if (ch + 1 < nchunks) load_chunk(ch + 1);
+    store_chunk(ra, rb, cur ^ 1);  // chunk ch+1, in registers since iteration ch-2
+    load_chunk(ra, rb, ch + 3);
     chunk_mfma<MB, NB, LDA, LDB>(opA + cur * STAGE, opB + cur * STAGE, acc);
-    if (ch + 1 < nchunks) store_chunk(cur ^ 1);
     __syncthreads();
+  };
+  int ch = 0;
+  for (; ch + 1 < nchunks; ch += 2) {
+    iteration(ch, raX, rbX);
+    iteration(ch + 1, raY, rbY);
   }
+  if (ch < nchunks) iteration(ch, raX, rbX);
 
   double* dst = reinterpret_cast<double*>(a.part) + ((size_t)split * a.G + g) * ((size_t)a.Kg * a.Kred);
 #pragma unroll

@@ -665,17 +665,23 @@ __global__ __launch_bounds__(256) void direct_bwd_blocks_kernel(const DirectArgs
     }
 }
 
+// False when the block space does not fit 31 bits (padding far larger than the image): the caller
+// then takes the one-element-per-thread kernel, whose index space is dx itself.
 template <typename T, int KH, int KW, int S>
-int launch_bwd_blocks(const DirectArgs& src, hipStream_t s) {
+bool launch_bwd_blocks(const DirectArgs& src, hipStream_t s, int* status) {
   DirectArgs a = src;
   a.BH = (a.H + a.ph + S - 1) / S;
   a.BW = (a.W + a.pw + S - 1) / S;
+  const unsigned long long items = (unsigned long long)a.N * (unsigned long long)a.C * (unsigned long long)a.BH *
+                                   (unsigned long long)a.BW;
+  if (items >= (1ull << 31)) return false;
   a.mBH = make_magic((uint32_t)a.BH);
   a.mBW = make_magic((uint32_t)a.BW);
-  a.block_items = (uint32_t)a.N * (uint32_t)a.C * (uint32_t)a.BH * (uint32_t)a.BW;
+  a.block_items = (uint32_t)items;
   const dim3 grid((a.block_items + 255u) / 256u);
   hipLaunchKernelGGL((direct_bwd_blocks_kernel<T, KH, KW, S>), grid, dim3(256), 0, s, a);
-  return (int)hipGetLastError();
+  *status = (int)hipGetLastError();
+  return true;
 }
 
 // Backward data of a stride-2 "same" layer (pad = (k-1)/2 both ways, dilation 1) on rows of a
@@ -865,8 +871,8 @@ int launch_direct_t(int pass, const DirectArgs& a, hipStream_t s) {
     int status = 0;
     if (a.kh == 3 && a.kw == 3 && launch_bwd_s2_vec<T, 3, 3>(a, s, &status)) return status;
     if (a.kh == 5 && a.kw == 5 && launch_bwd_s2_vec<T, 5, 5>(a, s, &status)) return status;
-    if (a.kh == 3 && a.kw == 3) return launch_bwd_blocks<T, 3, 3, 2>(a, s);
-    if (a.kh == 5 && a.kw == 5) return launch_bwd_blocks<T, 5, 5, 2>(a, s);
+    if (a.kh == 3 && a.kw == 3 && launch_bwd_blocks<T, 3, 3, 2>(a, s, &status)) return status;
+    if (a.kh == 5 && a.kw == 5 && launch_bwd_blocks<T, 5, 5, 2>(a, s, &status)) return status;
   }
   if (a.kh == 3 && a.kw == 3) return launch_direct_k<T, 3, 3>(pass, a, s);
   return launch_direct_k<T, 0, 0>(pass, a, s);

@@ -143,6 +143,8 @@ DIRECT_CASES = [
     P(2, 4, 13, 12, 8, 5, 5, 2, 2, 2, 2, 1, 1, 4),             # 5x5 stride 2, channel multiplier 2, odd height
     P(3, 4, 10, 8, 4, 3, 3, 2, 2, 0, 1, 1, 1, 4),              # no padding along the height
     P(2, 4, 9, 20, 4, 3, 3, 2, 2, 3, 1, 1, 1, 2),              # two channels per group, tall padding
+    P(1, 3, 3, 3, 3, 3, 3, 2, 2, 40, 37, 1, 1, 3),             # padding far larger than the image
+    P(2, 16, 9, 10, 2, 3, 3, 2, 2, 1, 0, 1, 1, 2),             # eight channels in, one out per group
 ]
 
 # Shapes that select the patch-staged kernel (256-column tiles of the 16-row MFMA): 48 or <= 16

@@ -187,7 +187,7 @@ __global__ __launch_bounds__(256) void pg_softmax_rows_kernel(const float* __res
                                                               const float* __restrict__ discounted,
                                                               float* __restrict__ probs,
                                                               float* __restrict__ bottom_diff, int steps, int A,
-                                                              Magic mA) {
+                                                              Magic mA, bool vec_ok) {
   extern __shared__ float tile[];  // [256][A | 1], then a second copy for the gradient
   const int AP = A | 1;
   float* const ptile = tile;
@@ -196,9 +196,30 @@ __global__ __launch_bounds__(256) void pg_softmax_rows_kernel(const float* __res
   const int nrows = steps - row0 < 256 ? steps - row0 : 256;
   const int count = nrows * A;
   const size_t base = (size_t)row0 * A;
-  for (int i = threadIdx.x; i < count; i += 256) {
-    const int r = (int)mdiv((uint32_t)i, mA);
-    ptile[r * AP + (i - r * A)] = logits[base + i];
+  // Four-element global accesses when the block's slice is a multiple of four elements and the
+  // blobs are 16-byte aligned (a block's slice then starts on such a boundary too: 256*A elements
+  // per block); the (row, column) of the first element comes from one division, the next three
+  // follow by stepping the column.
+  const bool vec = vec_ok && (count & 3) == 0;
+  if (vec) {
+    for (int i = threadIdx.x * 4; i < count; i += 1024) {
+      const float4 v = *reinterpret_cast<const float4*>(logits + base + i);
+      int r = (int)mdiv((uint32_t)i, mA), c = i - r * A;
+      const float e[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        ptile[r * AP + c] = e[q];
+        if (++c == A) {
+          c = 0;
+          ++r;
+        }
+      }
+    }
+  } else {
+    for (int i = threadIdx.x; i < count; i += 256) {
+      const int r = (int)mdiv((uint32_t)i, mA);
+      ptile[r * AP + (i - r * A)] = logits[base + i];
+    }
   }
   __syncthreads();
   if ((int)threadIdx.x < nrows) {
@@ -222,11 +243,29 @@ __global__ __launch_bounds__(256) void pg_softmax_rows_kernel(const float* __res
     }
   }
   __syncthreads();
-  for (int i = threadIdx.x; i < count; i += 256) {
-    const int r = (int)mdiv((uint32_t)i, mA);
-    const int o = r * AP + (i - r * A);
-    if (probs) probs[base + i] = ptile[o];
-    bottom_diff[base + i] = dtile[o];
+  if (vec) {
+    for (int i = threadIdx.x * 4; i < count; i += 1024) {
+      int r = (int)mdiv((uint32_t)i, mA), c = i - r * A;
+      float pv[4], dv[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        pv[q] = ptile[r * AP + c];
+        dv[q] = dtile[r * AP + c];
+        if (++c == A) {
+          c = 0;
+          ++r;
+        }
+      }
+      if (probs) *reinterpret_cast<float4*>(probs + base + i) = make_float4(pv[0], pv[1], pv[2], pv[3]);
+      *reinterpret_cast<float4*>(bottom_diff + base + i) = make_float4(dv[0], dv[1], dv[2], dv[3]);
+    }
+  } else {
+    for (int i = threadIdx.x; i < count; i += 256) {
+      const int r = (int)mdiv((uint32_t)i, mA);
+      const int o = r * AP + (i - r * A);
+      if (probs) probs[base + i] = ptile[o];
+      bottom_diff[base + i] = dtile[o];
+    }
   }
 }
 
@@ -331,8 +370,10 @@ int pg_softmax_bottom_diff(const float* logits, const int32_t* action, const flo
                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
       if (e) return record_hip_error(e);
     }
+    const bool vec_ok = (((uintptr_t)logits | (uintptr_t)probs | (uintptr_t)bottom_diff) & 15u) == 0;
     hipLaunchKernelGGL(pg_softmax_rows_kernel, dim3((steps + 255) / 256), dim3(256), lds, (hipStream_t)hip_stream,
-                       logits, action, discounted, probs, bottom_diff, steps, actions, make_magic((uint32_t)actions));
+                       logits, action, discounted, probs, bottom_diff, steps, actions, make_magic((uint32_t)actions),
+                       vec_ok);
   } else {
     hipLaunchKernelGGL(pg_softmax_wide_kernel, dim3((steps + 3) / 4), dim3(256), 0, (hipStream_t)hip_stream, logits,
                        action, discounted, probs, bottom_diff, steps, actions);

@@ -29,10 +29,14 @@ template <int MT, int MB, int NB, int WM, int WN, int BK>
 struct CorrCfg {
   static constexpr int BM = WM * MB * MT;
   static constexpr int BN = WN * NB * MT;
-  // Both LDS tiles are [row][k] with rows of BK + 4 floats: 16-byte aligned, and any 8 consecutive
-  // rows start on 8 distinct quads of banks, so the 16-byte operand reads (lane -> row) and the
-  // 16-byte staging writes are conflict free.
-  static constexpr int LDK = BK + 4;
+  // Both LDS tiles are [row][k], 16-byte aligned rows.  32-row MFMA: rows of BK + 4 floats -- the
+  // 16-byte operand reads (lanes 0..31 on 32 consecutive rows) and the 16-byte staging writes are
+  // conflict free.  16-row MFMA: a wave's operand read covers 16 rows x 4 k quads, which on rows of
+  // BK + 4 floats takes twice the cycles (measured with the bank-conflict counter on a probe
+  // kernel); rows of BK + 8 floats with the position of a row's k quad XORed with bit 2 of the row
+  // number make that read and both staging writes conflict free.
+  static constexpr int LDK = MT == 16 ? BK + 8 : BK + 4;
+  static constexpr bool SWZ = MT == 16;
   static constexpr int RPW = 4;        // gathered k rows per wave and chunk: one 16-byte LDS write
   static constexpr int CPL = BN / 64;  // gathered columns per lane
   static constexpr int A_WI = BM / 16;  // wave-wide 16-byte loads per chunk of A (16 rows x 16 k each)
@@ -121,6 +125,7 @@ __global__ __launch_bounds__(kThreads) void corr_kernel(const CorrArgs a) {
   const int kc_first = (int)split * a.chunks_per_split;
   const float* Ag = a.A + ((size_t)g * a.MP + (size_t)m_tile * BM) * a.KP + (size_t)kc_first * BK;
   const int arow = (lane & 7) + 8 * (lane >> 5), ac4 = (lane >> 3) & 3;
+  const int aswz = C::SWZ ? (arow >> 2) & 1 : 0, bswz = C::SWZ ? (lane >> 2) & 1 : 0;  // k-quad swizzle of this lane's rows
   uint32_t aoff[C::A_PER];
 #pragma unroll
   for (int p = 0; p < C::A_PER; ++p) aoff[p] = 4u * (uint32_t)(((wv + 4 * p) * 16 + arow) * a.KP + ac4 * 4);
@@ -148,7 +153,7 @@ __global__ __launch_bounds__(kThreads) void corr_kernel(const CorrArgs a) {
   };
   auto store_a = [&](f32x4(&ra)[C::A_PER], int buf, int p) {
     if (C::A_WI % 4 == 0 || wv + 4 * p < C::A_WI)
-      *reinterpret_cast<f32x4*>(smem + buf * C::STAGE + ((wv + 4 * p) * 16 + arow) * LDK + ac4 * 4) = ra[p];
+      *reinterpret_cast<f32x4*>(smem + buf * C::STAGE + ((wv + 4 * p) * 16 + arow) * LDK + (ac4 ^ aswz) * 4) = ra[p];
   };
   // Rows of this wave in a chunk: each tap's byte offset and (row, column) displacement come from
   // the k table with scalar loads (the index is uniform over the wave).  The entries are fetched a
@@ -175,7 +180,7 @@ __global__ __launch_bounds__(kThreads) void corr_kernel(const CorrArgs a) {
     rb[q][e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(in_rsrc, off, 0, 0));
   };
   auto store_b = [&](f32x4(&rb)[CPL], int buf, int q) {
-    *reinterpret_cast<f32x4*>(smem + buf * C::STAGE + BM * LDK + (q * 64 + lane) * LDK + wv * 4) = rb[q];
+    *reinterpret_cast<f32x4*>(smem + buf * C::STAGE + BM * LDK + (q * 64 + lane) * LDK + (wv ^ bswz) * 4) = rb[q];
   };
   auto load_all = [&](f32x4(&ra)[C::A_PER], f32x4(&rb)[CPL], int kc) {
     load_tab(kc);
@@ -203,8 +208,9 @@ __global__ __launch_bounds__(kThreads) void corr_kernel(const CorrArgs a) {
   if (nchunks > a.chunks_per_split) nchunks = a.chunks_per_split;
   const int last = nchunks - 1;
   constexpr int NKS = C::NKS, NSS = C::NSS;
-  const float* opA = smem + (wm * MB * MT + lane % MT) * LDK + (lane / MT) * 4;
-  const float* opB = smem + BM * LDK + (wn * NB * MT + lane % MT) * LDK + (lane / MT) * 4;
+  const int oswz = C::SWZ ? ((lane % MT) >> 2) & 1 : 0;
+  const float* opA = smem + (wm * MB * MT + lane % MT) * LDK + ((lane / MT) ^ oswz) * 4;
+  const float* opB = smem + BM * LDK + (wn * NB * MT + lane % MT) * LDK + ((lane / MT) ^ oswz) * 4;
 
   load_all(raX, rbX, 0);
 #pragma unroll

@@ -182,7 +182,11 @@ void configure_patch(CorrArgs& a, PackArgs& k, int64_t cg_in, int64_t n_img, int
     const int64_t rows = (n1 == n0 ? a1 - a0 : R0 + (n1 - n0 - 1) * RS + a1) + TH;
     if (rows > max_rows) max_rows = rows;
   }
-  const int64_t psz = max_rows * PWID;
+  // Channel stride of the patch in LDS.  At one MFMA step the four lane groups of a wave read four
+  // channels 2*psz floats apart, 16 consecutive positions each: a stride of 8 mod 16 puts those
+  // four runs on different banks.
+  int64_t psz = max_rows * PWID;
+  psz += (8 - psz % 16 + 16) % 16;
   const int64_t lds = (2 * (int64_t)bm * 20 + 16 * psz) * 4;
   if (psz > kPatchEPT * 256 || lds > 80 * 1024 || lds < 16 * ((int64_t)bm + bn)) return;
   a.use_patch = 1;

@@ -35,19 +35,35 @@ __global__ __launch_bounds__(256) void bias_grad_kernel(const BiasGradArgs a) {
   int n1 = n0 + a.n_per_split;
   if (n1 > a.N) n1 = a.N;
   // Each wave walks whole images (one contiguous run of P floats per image and channel), the four
-  // waves of the block taking every fourth image, so small feature maps still keep all lanes of
-  // a wave busy; four independent accumulators per lane keep several loads in flight.
+  // waves of the block taking every fourth image; four independent accumulators per lane keep
+  // several loads in flight.
+  // A plane starts on an arbitrary 4-byte boundary: up to three leading elements, then 16-byte
+  // loads, then up to three trailing elements.
   float acc0 = 0.f, acc1 = 0.f, acc2 = 0.f, acc3 = 0.f;
   for (int n = n0 + wv; n < n1; n += 4) {
     const float* src = a.dy + ((size_t)n * a.K + k) * a.P;
-    int p = lane;
-    for (; p + 192 < a.P; p += 256) {
-      acc0 += src[p];
-      acc1 += src[p + 64];
-      acc2 += src[p + 128];
-      acc3 += src[p + 192];
+    if (a.P < 512 && (a.P & 3) != 0) {  // small planes that start off 16-byte boundaries: head and tail cost more than they save
+      for (int p = lane; p < a.P; p += 64) acc0 += src[p];
+      continue;
     }
-    for (; p < a.P; p += 64) acc0 += src[p];
+    int head = (int)((0u - (uint32_t)(reinterpret_cast<uintptr_t>(src) >> 2)) & 3u);
+    if (lane < head) acc0 += src[lane];
+    const float4* v = reinterpret_cast<const float4*>(src + head);
+    const int nvec = (a.P - head) >> 2;
+    int i = lane;
+    for (; i + 192 < nvec; i += 256) {
+      const float4 x0 = v[i], x1 = v[i + 64], x2 = v[i + 128], x3 = v[i + 192];
+      acc0 += (x0.x + x0.y) + (x0.z + x0.w);
+      acc1 += (x1.x + x1.y) + (x1.z + x1.w);
+      acc2 += (x2.x + x2.y) + (x2.z + x2.w);
+      acc3 += (x3.x + x3.y) + (x3.z + x3.w);
+    }
+    for (; i < nvec; i += 64) {
+      const float4 x0 = v[i];
+      acc1 += (x0.x + x0.y) + (x0.z + x0.w);
+    }
+    const int tail = head + 4 * nvec + lane;
+    if (tail < a.P) acc2 += src[tail];
   }
   const float w = wave_sum((acc0 + acc1) + (acc2 + acc3));
   if (lane == 0) wsum[wv] = w;

@@ -273,40 +273,66 @@ int launch_wgrad_t(const WgradArgs& a, hipStream_t s) {
   return launch_wgrad_m<MB, NB, WM, WN, 1>(a, s);
 }
 
-// dst = beta*dst + sum_s part[s].  A block owns 64 consecutive elements; its four waves each add
-// a contiguous quarter of the splits (four independent chains per lane), and the four quarter
-// sums are combined in a fixed order, so the result does not depend on scheduling.
+// dst = beta*dst + sum_s part[s] (+ bias, ReLU).  A block owns 64*V consecutive elements (V = 4 with
+// 16-byte accesses when the element count is a multiple of four and the blobs are 16-byte aligned,
+// else 1); its four waves each add a contiguous quarter of the splits (four independent chains per
+// lane), and the four quarter sums are combined in a fixed order, so the result does not depend on
+// scheduling.
+template <int V>
 __global__ __launch_bounds__(256) void reduce_kernel(const ReduceArgs a) {
-  __shared__ float quarter[4][64];
+  struct alignas(4 * V) Vec {
+    float v[V];
+  };
+  __shared__ Vec quarter[4][64];
   const int lane = threadIdx.x & 63, q = threadIdx.x >> 6;
-  const int i = blockIdx.x * 64 + lane;
+  const int i = (blockIdx.x * 64 + lane) * V;
   const int per = (a.S + 3) / 4;
   const int s0 = q * per;
   int s1 = s0 + per;
   if (s1 > a.S) s1 = a.S;
-  float acc0 = 0.f, acc1 = 0.f, acc2 = 0.f, acc3 = 0.f;
+  Vec acc[4];
+#pragma unroll
+  for (int c = 0; c < 4; ++c)
+#pragma unroll
+    for (int e = 0; e < V; ++e) acc[c].v[e] = 0.f;
   if (i < a.count) {
     const float* src = a.part + i;
     int k = s0;
     for (; k + 3 < s1; k += 4) {
-      acc0 += src[(size_t)k * a.count];
-      acc1 += src[(size_t)(k + 1) * a.count];
-      acc2 += src[(size_t)(k + 2) * a.count];
-      acc3 += src[(size_t)(k + 3) * a.count];
+      Vec x[4];
+#pragma unroll
+      for (int c = 0; c < 4; ++c) x[c] = *reinterpret_cast<const Vec*>(src + (size_t)(k + c) * a.count);
+#pragma unroll
+      for (int c = 0; c < 4; ++c)
+#pragma unroll
+        for (int e = 0; e < V; ++e) acc[c].v[e] += x[c].v[e];
     }
-    for (; k < s1; ++k) acc0 += src[(size_t)k * a.count];
+    for (; k < s1; ++k) {
+      const Vec x = *reinterpret_cast<const Vec*>(src + (size_t)k * a.count);
+#pragma unroll
+      for (int e = 0; e < V; ++e) acc[0].v[e] += x.v[e];
+    }
   }
-  quarter[q][lane] = (acc0 + acc1) + (acc2 + acc3);
+  Vec sum;
+#pragma unroll
+  for (int e = 0; e < V; ++e) sum.v[e] = (acc[0].v[e] + acc[1].v[e]) + (acc[2].v[e] + acc[3].v[e]);
+  quarter[q][lane] = sum;
   __syncthreads();
   if (q == 0 && i < a.count) {
-    float s = (quarter[0][lane] + quarter[1][lane]) + (quarter[2][lane] + quarter[3][lane]);
-    if (a.bias) {
-      const uint32_t c = mdiv((uint32_t)i, a.mChanElems);
-      s += a.bias[c - mdiv(c, a.mChannels) * a.channels];
+    Vec out, old;
+    if (a.beta != 0.f) old = *reinterpret_cast<const Vec*>(a.dst + i);
+#pragma unroll
+    for (int e = 0; e < V; ++e) {
+      float s = (quarter[0][lane].v[e] + quarter[1][lane].v[e]) + (quarter[2][lane].v[e] + quarter[3][lane].v[e]);
+      if (a.bias) {
+        const uint32_t c = mdiv((uint32_t)(i + e), a.mChanElems);
+        s += a.bias[c - mdiv(c, a.mChannels) * a.channels];
+      }
+      if (a.beta != 0.f) s += a.beta * old.v[e];
+      if (a.relu) s = s > 0.f ? s : 0.f;
+      out.v[e] = s;
     }
-    if (a.beta != 0.f) s += a.beta * a.dst[i];
-    if (a.relu) s = s > 0.f ? s : 0.f;
-    a.dst[i] = s;
+    *reinterpret_cast<Vec*>(a.dst + i) = out;
   }
 }
 
@@ -339,7 +365,13 @@ int launch_wgrad(int32_t tile, const WgradArgs& a, void* stream) {
 }
 
 int launch_reduce(const ReduceArgs& a, void* stream) {
-  hipLaunchKernelGGL(reduce_kernel, dim3((a.count + 63) / 64), dim3(256), 0, (hipStream_t)stream, a);
+  // the four-element form needs enough elements to keep a thousand workgroups busy
+  const bool vec = a.count >= (1 << 18) && a.count % 4 == 0 &&
+                   ((reinterpret_cast<uintptr_t>(a.part) | reinterpret_cast<uintptr_t>(a.dst)) & 15u) == 0;
+  if (vec)
+    hipLaunchKernelGGL(reduce_kernel<4>, dim3((a.count / 4 + 63) / 64), dim3(256), 0, (hipStream_t)stream, a);
+  else
+    hipLaunchKernelGGL(reduce_kernel<1>, dim3((a.count + 63) / 64), dim3(256), 0, (hipStream_t)stream, a);
   return (int)hipGetLastError();
 }
 

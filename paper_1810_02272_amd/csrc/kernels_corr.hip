@@ -297,26 +297,32 @@ __device__ __forceinline__ void fill_ktab(const PackArgs& a, int kk) {
   a.ktab[kk] = e;
 }
 
+// Divisors of the pack kernels' index arithmetic as magic numbers (built per launch on the host).
+struct PackMagic {
+  Magic KP, MP, perm, QQ, Qw, nv, nvw, dh, dw;
+};
+
 // Packed position kp -> reduction index (channel, tap) in the blob's own order.  The patch kernel
 // runs the reduction as (8-channel chunk, tap, channel in chunk); the gather kernel keeps (c, tap).
-__device__ __forceinline__ int source_k(const PackArgs& a, int kp) {
+__device__ __forceinline__ int source_k(const PackArgs& a, const PackMagic& mg, int kp) {
   if (a.kperm_T == 0) return kp;
   const int T = a.kperm_T;
-  const int cc = kp / (8 * T), rem = kp % (8 * T);
-  return (cc * 8 + rem % 8) * T + rem / 8;
+  const int cc = (int)mdiv((uint32_t)kp, mg.perm), rem = kp - cc * 8 * T;
+  return (cc * 8 + (rem & 7)) * T + (rem >> 3);
 }
 
 // Forward: A[g][m][k] = w[g*Kg + m][k], zero padded to [MP][KP] (the weight blob's own order).
 // T is the base type of the blob (the pointer members of PackArgs address floats or doubles).
 template <typename T>
-__global__ __launch_bounds__(256) void pack_fwd_kernel(const PackArgs a) {
-  const size_t total = (size_t)a.G * a.MP * a.KP;
-  const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+__global__ __launch_bounds__(256) void pack_fwd_kernel(const PackArgs a, const PackMagic mg) {
+  const uint32_t total = (uint32_t)a.G * (uint32_t)a.MP * (uint32_t)a.KP;
+  const uint32_t idx = blockIdx.x * 256u + threadIdx.x;
   if (idx >= total) return;
-  const int kp = (int)(idx % a.KP);
-  const int m = (int)((idx / a.KP) % a.MP);
-  const int g = (int)(idx / ((size_t)a.MP * a.KP));
-  const int kk = source_k(a, kp);
+  const uint32_t row = mdiv(idx, mg.KP);
+  const int kp = (int)(idx - row * (uint32_t)a.KP);
+  const int g = (int)mdiv(row, mg.MP);
+  const int m = (int)(row - (uint32_t)g * (uint32_t)a.MP);
+  const int kk = source_k(a, mg, kp);
   const T* w = reinterpret_cast<const T*>(a.w);
   reinterpret_cast<T*>(a.A)[idx] = (m < a.Mrows && kp < a.Kred) ? w[((size_t)g * a.Kg + m) * a.Kred + kk] : T(0);
   if (m == 0 && g == 0) fill_ktab(a, kp);
@@ -330,30 +336,31 @@ __global__ __launch_bounds__(256) void pack_fwd_kernel(const PackArgs a) {
 // dilation/stride rows of dy apart, so slot qh stands for q = qh*eh.  Entries with no such tap
 // are zero.
 template <typename T>
-__global__ __launch_bounds__(256) void pack_bwd_kernel(const PackArgs a) {
-  const size_t total = (size_t)a.G * a.MP * a.KP;
-  const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+__global__ __launch_bounds__(256) void pack_bwd_kernel(const PackArgs a, const PackMagic mg) {
+  const uint32_t total = (uint32_t)a.G * (uint32_t)a.MP * (uint32_t)a.KP;
+  const uint32_t idx = blockIdx.x * 256u + threadIdx.x;
   if (idx >= total) return;
-  const int kp = (int)(idx % a.KP);
-  const int m = (int)((idx / a.KP) % a.MP);
-  const int g = (int)(idx / ((size_t)a.MP * a.KP));
-  const int kk = source_k(a, kp);
+  const uint32_t row = mdiv(idx, mg.KP);
+  const int kp = (int)(idx - row * (uint32_t)a.KP);
+  const int g = (int)mdiv(row, mg.MP);
+  const int m = (int)(row - (uint32_t)g * (uint32_t)a.MP);
+  const int kk = source_k(a, mg, kp);
   const T* w = reinterpret_cast<const T*>(a.w);
   T v = T(0);
   if (m < a.Mrows && kp < a.Kred) {
     const int QQ = a.Qh * a.Qw;
-    const int k = kk / QQ, qr = kk % QQ;
-    const int qh = a.Qh - 1 - qr / a.Qw, qw = a.Qw - 1 - qr % a.Qw;
+    const int k = (int)mdiv((uint32_t)kk, mg.QQ), qr = kk - k * QQ;
+    const int qrh = (int)mdiv((uint32_t)qr, mg.Qw);
+    const int qh = a.Qh - 1 - qrh, qw = a.Qw - 1 - (qr - qrh * a.Qw);
     const int nv = a.nvh * a.nvw;
-    const int c = m / nv, mr = m % nv;
-    int rh = mr / a.nvw, rw = mr % a.nvw;
+    const int c = (int)mdiv((uint32_t)m, mg.nv), mr = m - c * nv;
+    int rh = (int)mdiv((uint32_t)mr, mg.nvw), rw = mr - rh * a.nvw;
     if (a.tab_h) rh = a.phase_h[rh];
     if (a.tab_w) rw = a.phase_w[rw];
     const int th = a.sh * a.eh * qh + rh, tw = a.sw * a.ew * qw + rw;
-    if (th % a.dh == 0 && tw % a.dw == 0) {
-      const int i = th / a.dh, j = tw / a.dw;
-      if (i < a.kh && j < a.kw) v = w[((((size_t)g * a.Kg + k) * a.Cg + c) * a.kh + i) * a.kw + j];
-    }
+    const int i = (int)mdiv((uint32_t)th, mg.dh), j = (int)mdiv((uint32_t)tw, mg.dw);
+    if (i * a.dh == th && j * a.dw == tw && i < a.kh && j < a.kw)
+      v = w[((((size_t)g * a.Kg + k) * a.Cg + c) * a.kh + i) * a.kw + j];
   }
   reinterpret_cast<T*>(a.A)[idx] = v;
   if (m == 0 && g == 0) fill_ktab(a, kp);
@@ -412,16 +419,27 @@ int launch_pack(const PackArgs& a, void* stream, bool f64) {
   hipStream_t s = (hipStream_t)stream;
   const size_t total = (size_t)a.G * a.KP * a.MP;
   const dim3 grid((uint32_t)((total + 255) / 256));
+  auto positive = [](int32_t v) { return (uint32_t)(v > 0 ? v : 1); };
+  PackMagic mg;
+  mg.KP = make_magic(positive(a.KP));
+  mg.MP = make_magic(positive(a.MP));
+  mg.perm = make_magic(positive(8 * a.kperm_T));
+  mg.QQ = make_magic(positive(a.Qh * a.Qw));
+  mg.Qw = make_magic(positive(a.Qw));
+  mg.nv = make_magic(positive(a.nvh * a.nvw));
+  mg.nvw = make_magic(positive(a.nvw));
+  mg.dh = make_magic(positive(a.dh));
+  mg.dw = make_magic(positive(a.dw));
   if (a.mode == 0) {
     if (f64)
-      hipLaunchKernelGGL(pack_fwd_kernel<double>, grid, dim3(256), 0, s, a);
+      hipLaunchKernelGGL(pack_fwd_kernel<double>, grid, dim3(256), 0, s, a, mg);
     else
-      hipLaunchKernelGGL(pack_fwd_kernel<float>, grid, dim3(256), 0, s, a);
+      hipLaunchKernelGGL(pack_fwd_kernel<float>, grid, dim3(256), 0, s, a, mg);
   } else {
     if (f64)
-      hipLaunchKernelGGL(pack_bwd_kernel<double>, grid, dim3(256), 0, s, a);
+      hipLaunchKernelGGL(pack_bwd_kernel<double>, grid, dim3(256), 0, s, a, mg);
     else
-      hipLaunchKernelGGL(pack_bwd_kernel<float>, grid, dim3(256), 0, s, a);
+      hipLaunchKernelGGL(pack_bwd_kernel<float>, grid, dim3(256), 0, s, a, mg);
   }
   return (int)hipGetLastError();
 }

@@ -31,13 +31,25 @@ __global__ __launch_bounds__(256) void pg_sample_kernel(const float* __restrict_
 }
 
 // ---- step 9: R[t] = reward[t] + gamma * R[t+1] inside each episode ----
-// One wave per episode at a time, walking it from its end in chunks of 64 steps (lane 63 = the
-// chunk's last step).  Inside a chunk the recurrence is a weighted suffix sum: four DPP row shifts
-// with the weights gamma^1, ^2, ^4, ^8 finish each row of 16 lanes, three lane reads chain the
-// rows, and the value carried in from the later chunk is added with the weight gamma^(64 - lane).
-// The scans of the four chunks that are loaded together are independent; only the carry links
-// them.  A wave walks several episodes with the next one's loads already in flight.
-constexpr int kChunksInFlight = 4;
+// One wave per episode at a time, walking it from its end in chunks of 256 steps: lane l holds the
+// four consecutive steps 4l .. 4l+3 of the chunk (one 16-byte access on a 4-byte boundary; lanes at
+// the edges of the episode go element by element).  A lane first runs the recurrence over its own
+// four steps; the lane totals then form the same recurrence with gamma^4 per lane, a weighted
+// suffix sum: four DPP row shifts with the weights (gamma^4)^1, ^2, ^4, ^8 finish each row of 16
+// lanes, three lane reads chain the rows, and the value carried in from the later chunk is added
+// with the weight (gamma^4)^(64 - lane).  Each step's result is its in-lane partial plus
+// gamma^(4-j) times the total of the next lane.  The scans of the chunks that are loaded together
+// are independent; only the carry links them.  A wave walks several episodes with the next one's
+// loads already in flight.
+constexpr int kChunksInFlight = 2;
+constexpr int kChunkSteps = 256;
+
+struct Quad {
+  float v[4];
+};
+struct __attribute__((packed, aligned(4))) QuadMem {
+  float v[4];
+};
 
 // Lane l receives the value of lane l + N of its row of 16 lanes, 0 past the row's end.
 template <int N>
@@ -46,14 +58,14 @@ __device__ __forceinline__ float row_shift_down(float v) {
 }
 
 struct ScanWeights {
-  float g1, g2, g4, g8, g16;  // powers of gamma
-  float to_row_end;           // gamma^(16 - lane % 16): from this lane to the first lane of the next row
-  float to_chunk_end;         // gamma^(64 - lane): from this lane to the first step of the later chunk
+  float g1, g2, g4, g8, g16;  // powers of the per-lane factor
+  float to_row_end;           // factor^(16 - lane % 16): from this lane to the first lane of the next row
+  float to_chunk_end;         // factor^(64 - lane): from this lane to the first lane of the later chunk
 };
 
-__device__ __forceinline__ ScanWeights scan_weights(float gamma, int lane) {
+__device__ __forceinline__ ScanWeights scan_weights(float factor, int lane) {
   ScanWeights w;
-  w.g1 = gamma;
+  w.g1 = factor;
   w.g2 = w.g1 * w.g1;
   w.g4 = w.g2 * w.g2;
   w.g8 = w.g4 * w.g4;
@@ -74,16 +86,17 @@ __device__ __forceinline__ ScanWeights scan_weights(float gamma, int lane) {
   return w;
 }
 
-// v[l] <- sum over the lanes m >= l of the wave of gamma^(m - l) * v[m]
-__device__ __forceinline__ float suffix_scan(float v, int lane, const ScanWeights& w) {
+// v[l] <- sum over the lanes m >= l of the wave of factor^(m - l) * v[m]; t16/t32/t48 return the
+// finished values of lanes 16, 32, 48 (the row heads) without the carry of a later chunk.
+__device__ __forceinline__ float suffix_scan(float v, int lane, const ScanWeights& w, float& t1, float& t2, float& t3) {
   v += w.g1 * row_shift_down<1>(v);
   v += w.g2 * row_shift_down<2>(v);
   v += w.g4 * row_shift_down<4>(v);
   v += w.g8 * row_shift_down<8>(v);
   const int iv = __builtin_bit_cast(int, v);
-  const float t3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 48));
-  const float t2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 32)) + w.g16 * t3;
-  const float t1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 16)) + w.g16 * t2;
+  t3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 48));
+  t2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 32)) + w.g16 * t3;
+  t1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 16)) + w.g16 * t2;
   const int row = lane >> 4;
   const float later_rows = row == 0 ? t1 : row == 1 ? t2 : row == 2 ? t3 : 0.f;
   return v + w.to_row_end * later_rows;
@@ -96,7 +109,9 @@ __global__ __launch_bounds__(256) void pg_discount_kernel(const float* __restric
   const int stride = (int)gridDim.x * 4;  // waves in the grid: a wave takes episodes e, e + stride, ...
   int e = (int)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
   if (e >= episodes) return;
-  const ScanWeights w = scan_weights(gamma, lane);
+  const float g2 = gamma * gamma, g3 = g2 * gamma, g4 = g2 * g2;
+  const ScanWeights w = scan_weights(g4, lane);
+  const int row = lane >> 4;
 
   auto bounds = [&](int ep, int& b, int& end) {  // clamped to [0, steps]; empty for ep >= episodes
     b = end = 0;
@@ -107,38 +122,72 @@ __global__ __launch_bounds__(256) void pg_discount_kernel(const float* __restric
       end = end < b ? b : (end > steps ? steps : end);
     }
   };
-  auto fetch = [&](float(&r)[kChunksInFlight], int b, int hi, int end) {  // the chunks below hi
+  auto fetch = [&](Quad(&r)[kChunksInFlight], int b, int hi, int end) {  // the chunks below hi
 #pragma unroll
     for (int c = 0; c < kChunksInFlight; ++c) {
-      const int t = hi - 64 * (c + 1) + lane;
-      r[c] = (t >= b && t < end) ? reward[t] : 0.f;
+      const int t = hi - kChunkSteps * (c + 1) + 4 * lane;
+      if (t >= b && t + 3 < end) {
+        const QuadMem m = *reinterpret_cast<const QuadMem*>(reward + t);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) r[c].v[j] = m.v[j];
+      } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) r[c].v[j] = (t + j >= b && t + j < end) ? reward[t + j] : 0.f;
+      }
     }
   };
 
-  // The rewards of the wave's next episode (its last four chunks) and the bounds of the one after
-  // that are requested before the current episode is scanned, so that their memory latency
-  // overlaps the scan.
+  // The rewards of the wave's next episode (its last chunks) and the bounds of the one after that
+  // are requested before the current episode is scanned, so that their memory latency overlaps
+  // the scan.
   int b, end, nb, nend;
   bounds(e, b, end);
   bounds(e + stride, nb, nend);
-  float r[kChunksInFlight], rn[kChunksInFlight];
+  Quad r[kChunksInFlight], rn[kChunksInFlight];
   fetch(r, b, end, end);
   for (;;) {
     int nnb, nnend;
     bounds(e + 2 * stride, nnb, nnend);
     fetch(rn, nb, nend, nend);
-    float carry = 0.f;
-    for (int hi = end; hi > b; hi -= 64 * kChunksInFlight) {
-      if (hi != end) fetch(r, b, hi, end);  // episodes longer than four chunks: further rounds
-      float v[kChunksInFlight];
-#pragma unroll
-      for (int c = 0; c < kChunksInFlight; ++c) v[c] = suffix_scan(r[c], lane, w);
+    float carry = 0.f;  // R of the first step of the later chunk
+    for (int hi = end; hi > b; hi -= kChunkSteps * kChunksInFlight) {
+      if (hi != end) fetch(r, b, hi, end);  // long episodes: further rounds
+      float s[kChunksInFlight][4], total[kChunksInFlight], t1[kChunksInFlight], t2[kChunksInFlight], t3[kChunksInFlight];
 #pragma unroll
       for (int c = 0; c < kChunksInFlight; ++c) {
-        const int t = hi - 64 * (c + 1) + lane;
-        v[c] += w.to_chunk_end * carry;
-        if (t >= b && t < end) discounted[t] = v[c];
-        carry = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, v[c])));
+        s[c][3] = r[c].v[3];
+        s[c][2] = r[c].v[2] + gamma * s[c][3];
+        s[c][1] = r[c].v[1] + gamma * s[c][2];
+        s[c][0] = r[c].v[0] + gamma * s[c][1];
+        total[c] = suffix_scan(s[c][0], lane, w, t1[c], t2[c], t3[c]);
+      }
+#pragma unroll
+      for (int c = 0; c < kChunksInFlight; ++c) {
+        const int t = hi - kChunkSteps * (c + 1) + 4 * lane;
+        const float with_carry = total[c] + w.to_chunk_end * carry;
+        // total of the next lane (with the carry): inside a row by a shift, at a row's last lane the
+        // head of the next row, at lane 63 the carry itself
+        const float h1 = t1[c] + w.g16 * w.g16 * w.g16 * carry;  // lane 16: 48 lanes before the chunk's end
+        const float h2 = t2[c] + w.g16 * w.g16 * carry;
+        const float h3 = t3[c] + w.g16 * carry;
+        float next = row_shift_down<1>(with_carry);
+        if ((lane & 15) == 15) next = row == 0 ? h1 : row == 1 ? h2 : row == 2 ? h3 : carry;
+        Quad out;
+        out.v[0] = with_carry;
+        out.v[1] = s[c][1] + g3 * next;
+        out.v[2] = s[c][2] + g2 * next;
+        out.v[3] = s[c][3] + gamma * next;
+        if (t >= b && t + 3 < end) {
+          QuadMem m;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) m.v[j] = out.v[j];
+          *reinterpret_cast<QuadMem*>(discounted + t) = m;
+        } else {
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            if (t + j >= b && t + j < end) discounted[t + j] = out.v[j];
+        }
+        carry = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, with_carry)));
       }
     }
     e += stride;

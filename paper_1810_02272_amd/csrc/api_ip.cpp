@@ -81,8 +81,10 @@ int ip_desc_create(ip_desc_t** out, const ip_params_t* pp) {
   d->cs_ws = p.bias_term ? (size_t)cs.S * O * 4 : 0;
   if (d->cs_ws > d->ws_bytes) d->ws_bytes = d->cs_ws;
   const char* in = d->inner ? conv_desc_kernel_names(d->inner) : "";
+  const bool one_launch = M * O * 4 <= ((int64_t)4 << 20);  // see ip_backward_bias
   snprintf(d->names, sizeof(d->names), "fwd=%s;bwd_data=%s;bwd_filter=%s;bwd_bias=colsum(S=%d)",
-           field(in, "bwd_filter=").c_str(), field(in, "fwd=").c_str(), field(in, "bwd_data=").c_str(), cs.S);
+           field(in, "bwd_filter=").c_str(), field(in, "fwd=").c_str(), field(in, "bwd_data=").c_str(),
+           one_launch ? 1 : cs.S);
   *out = d;
   return CONV_OK;
 }
@@ -169,6 +171,14 @@ int ip_backward_bias(const ip_desc_t* d, const float* dz, float* db, float beta,
   ColSumArgs a = d->cs;
   a.src = dz;
   a.part = static_cast<float*>(ws);
+  // up to 4 MiB of dz: one launch sums every column and finishes db (the second launch would cost
+  // more than the lost parallelism)
+  if (!empty && (int64_t)d->p.m * d->p.num_output * 4 <= ((int64_t)4 << 20)) {
+    a.dst = db;
+    a.beta = beta;
+    const int e1 = launch_colsum(a, hip_stream);
+    return e1 ? record_hip_error(e1) : CONV_OK;
+  }
   int e = empty ? 0 : launch_colsum(a, hip_stream);
   if (e) return record_hip_error(e);
   ReduceArgs r = {};

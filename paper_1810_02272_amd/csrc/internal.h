@@ -163,6 +163,9 @@ struct ColSumArgs {
   const float* src;  // [rows][cols]
   float* part;       // [S][cols]
   int32_t rows, cols, S, rows_per_split;
+  // small matrices: one launch finishes dst = beta*dst + column sums (dst null otherwise)
+  float* dst;
+  float beta;
 };
 
 struct BiasGradArgs {

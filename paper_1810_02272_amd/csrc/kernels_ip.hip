@@ -49,6 +49,33 @@ __global__ __launch_bounds__(256) void colsum_kernel(const ColSumArgs a) {
   a.part[(size_t)s * a.cols + c] = (acc0 + acc1) + (acc2 + acc3);
 }
 
+// Small matrices: dst[c] = beta*dst[c] + sum over all rows of src[r][c] in one launch.  A block
+// owns 64 columns; its four waves take every fourth row (four loads in flight per lane) and the
+// four partial sums are added in wave order.
+__global__ __launch_bounds__(256) void colsum_direct_kernel(const ColSumArgs a) {
+  __shared__ float part[4][64];
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const int c = blockIdx.x * 64 + lane;
+  float acc0 = 0.f, acc1 = 0.f, acc2 = 0.f, acc3 = 0.f;
+  if (c < a.cols) {
+    const float* src = a.src + c;
+    int r = wv;
+    for (; r + 12 < a.rows; r += 16) {
+      acc0 += src[(size_t)r * a.cols];
+      acc1 += src[(size_t)(r + 4) * a.cols];
+      acc2 += src[(size_t)(r + 8) * a.cols];
+      acc3 += src[(size_t)(r + 12) * a.cols];
+    }
+    for (; r < a.rows; r += 4) acc0 += src[(size_t)r * a.cols];
+  }
+  part[wv][lane] = (acc0 + acc1) + (acc2 + acc3);
+  __syncthreads();
+  if (wv == 0 && c < a.cols) {
+    const float s = (part[0][lane] + part[1][lane]) + (part[2][lane] + part[3][lane]);
+    a.dst[c] = a.beta != 0.f ? a.beta * a.dst[c] + s : s;
+  }
+}
+
 }  // namespace
 
 int launch_relu_bwd(const ReluBwdArgs& a, void* stream) {
@@ -59,6 +86,10 @@ int launch_relu_bwd(const ReluBwdArgs& a, void* stream) {
 }
 
 int launch_colsum(const ColSumArgs& a, void* stream) {
+  if (a.dst) {
+    hipLaunchKernelGGL(colsum_direct_kernel, dim3((a.cols + 63) / 64), dim3(256), 0, (hipStream_t)stream, a);
+    return (int)hipGetLastError();
+  }
   hipLaunchKernelGGL(colsum_kernel, dim3((a.cols + 255) / 256, a.S), dim3(256), 0, (hipStream_t)stream, a);
   return (int)hipGetLastError();
 }

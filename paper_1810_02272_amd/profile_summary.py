@@ -30,7 +30,7 @@ PASSES = ("fwd", "bwd_data", "bwd_filter", "bwd_bias")
 WORKLOADS = {
     "config4": (MAIN, PASSES, ["5.a", "5.b", "5.c"], ""),
     "f64": (("corr64_kernel", "wgrad64_kernel", "bias_grad64_kernel"), PASSES, ["5.a", "5.b", "5.c"], "f64/"),
-    "ip5": (("wgrad_kernel", "relu_bwd_kernel", "corr_kernel", "colsum_kernel"),
+    "ip5": (("wgrad_kernel", "relu_bwd_kernel", "corr_kernel", "colsum_kernel", "colsum_direct_kernel"),
             ("fwd", "relu_bwd", "bwd_data", "bwd_filter", "bwd_bias"), ["ip5.6", "ip5.7", "ip5.8"], ""),
     "dw": (("direct_rows_kernel", "direct_rows_vec_kernel", "direct_rows_s2_kernel", "direct_bwd_blocks_kernel",
             "direct_bwd_s2_vec_kernel", "direct_wgrad_rows_kernel", "direct_wgrad_rows_vec_kernel",

@@ -279,6 +279,12 @@ def test_benchmark_layers_config_4_sampled(name):
     via_dw = float(np.sum(dwc * wn.astype(np.float64).ravel()))
     scale = float(np.sqrt(y.numel())) * float(np.max(np.abs(ref_y))) * l.dy_std
     assert abs(lin - via_dx) <= 1e-3 * scale and abs(lin - via_dw) <= 1e-3 * scale, (lin, via_dx, via_dw, scale)
+    # beta = 1 at full size (the wide form of the split reduction): dw + dw and db + db are exact in fp32
+    dw0, db0 = dw.clone(), db.clone()
+    conv.conv_backward_filter(d, xd, dyd, dw, 1.0, ws)
+    conv.conv_backward_bias(d, dyd, db, 1.0, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(dw, dw0 + dw0) and torch.equal(db, db0 + db0)
 
 
 @pytest.mark.parametrize("pd", [P(3, 6, 11, 12, 10, 3, 3, 2, 1, 1, 1, 1, 1, 2),

@@ -195,10 +195,13 @@ def test_thin_groups_blobs_not_16_byte_aligned():
     conv.conv_forward(d, xd, wd, bd, y, ws)
     conv.conv_backward_data(d, wd, dyd, dx, ws)
     conv.conv_backward_filter(d, xd, dyd, dw, 0.0, ws)
+    db = torch.zeros_like(bd)
+    conv.conv_backward_bias(d, dyd, db, 0.0, ws)  # planes of a multiple of four elements, 4 bytes off a boundary
     torch.cuda.synchronize()
     assert nerr(y, oracle.forward(op, x.numpy(), w.numpy(), b.numpy())) <= TOL
     assert nerr(dx, oracle.backward_data(op, w.numpy(), dy.numpy())) <= TOL
     assert nerr(dw, oracle.backward_filter(op, x.numpy(), dy.numpy())) <= TOL
+    assert nerr(db, oracle.backward_bias(op, dy.numpy())) <= TOL
 
 
 @pytest.mark.parametrize("i", range(len(PATCH_CASES)))

@@ -209,6 +209,7 @@ void configure_ksplit(CorrArgs& a, int64_t out_elems) {
   a.ksplit = 1;
   a.chunks_per_split = a.KP / 16;
   a.out_elems = (int32_t)out_elems;
+  a.simple_epilogue = a.RShw == 1 && a.tab_h == 0 && a.tab_w == 0 && 4 * out_elems <= ((int64_t)1 << 30);
   const int64_t units = (int64_t)a.G * a.m_tiles * a.col_tiles, chunks = a.KP / 16;
   if (a.use_patch || chunks < 8 || a.ncols < 1) return;
   int64_t S = 1;

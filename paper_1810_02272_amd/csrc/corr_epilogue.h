@@ -26,6 +26,59 @@ __device__ __forceinline__ void corr_epilogue(const CorrArgs& a, float* smem, Ac
   const int t = threadIdx.x, lane = t & 63;
   int4* rowtab = reinterpret_cast<int4*>(smem);
   int4* coltab = rowtab + BM;
+  if (a.simple_epilogue) {
+    // One output phase per channel (forward, stride-1 backward data, InnerProduct) and an output blob
+    // of at most 2^30 bytes: whether an element is stored depends on its row and on its column
+    // separately, so the tables hold byte offsets with an out-of-range value for "not stored"
+    // (2^31 for a row, 2^30 for a column: any sum with one of them lies beyond the blob) and the
+    // range check of the buffer store drops those elements -- one add per element, no compares.
+    for (int m = t; m < BM; m += 256) {
+      const uint32_t gm = m_tile * BM + m;
+      uint32_t off = 0x80000000u;
+      float bb = 0.f;
+      if (gm < (uint32_t)a.Mrows) {
+        const uint32_t chan = g * a.chan_per_grp + gm;
+        off = 4u * chan * (uint32_t)(a.OHd * a.OWd);
+        if (bias) bb = bias[chan];
+      }
+      rowtab[m] = make_int4((int)off, 0, 0, __builtin_bit_cast(int, bb));
+    }
+    for (int cl = t; cl < BN; cl += 256) {
+      const uint32_t col = col_tile * BN + cl;
+      uint32_t off = 0x40000000u;
+      if (col < (uint32_t)a.ncols) {
+        const uint32_t n = mdiv(col, a.mP);
+        const uint32_t pix = col - n * a.P;
+        const uint32_t pa = mdiv(pix, a.mPW);
+        const uint32_t pb = pix - pa * a.PW;
+        const int hh = (int)pa * a.OSh - a.opad_h, ww = (int)pb * a.OSw - a.opad_w;
+        if ((uint32_t)hh < (uint32_t)a.OHd && (uint32_t)ww < (uint32_t)a.OWd)
+          off = 4u * (n * (uint32_t)a.out_img_stride + (uint32_t)hh * (uint32_t)a.OWd + (uint32_t)ww);
+      }
+      coltab[cl] = make_int4((int)off, 0, 0, 0);
+    }
+    __syncthreads();
+    const __amdgpu_buffer_rsrc_t out_rsrc =
+        __builtin_amdgcn_make_buffer_rsrc(out, 0, (int)(4u * (uint32_t)a.out_elems), 0x00020000);
+    uint32_t co[NB];
+#pragma unroll
+    for (int j = 0; j < NB; ++j) co[j] = (uint32_t)coltab[(wn * NB + j) * MT + lane % MT].x;
+#pragma unroll
+    for (int i = 0; i < MB; ++i)
+#pragma unroll
+      for (int r = 0; r < M::NR; ++r) {
+        const int4 rt = rowtab[(wm * MB + i) * MT + M::row(r, lane)];
+        const float bb = __builtin_bit_cast(float, rt.w);
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+          const uint32_t off = (uint32_t)rt.x + co[j];
+          float v = acc[i][j][r] + bb;
+          if (accumulate) v += __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(out_rsrc, off, 0, 0));
+          __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, v), out_rsrc, off, 0, 0);
+        }
+      }
+    return;
+  }
   for (int m = t; m < BM; m += 256) {
     const uint32_t gm = m_tile * BM + m;
     int off = 0, hh = -(1 << 28), ww = 0;

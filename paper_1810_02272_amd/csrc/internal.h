@@ -93,6 +93,7 @@ struct CorrArgs {
   int32_t Nimg;        // images
   int32_t PWID, PSZ;   // patch row length (PW + TW - 1); floats per channel of an LDS patch stage
   Magic mPWID, mRSEG;  // divisions by PWID and by the patch rows of a full image (PH + TH - 1)
+  int32_t simple_epilogue;  // one phase per channel and an output of at most 2^30 bytes: offset-only epilogue
 };
 
 constexpr int kPatchEPT = 3;  // patch elements per thread and channel: PSZ <= 3 * 256

@@ -719,6 +719,7 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
       a.chunks_per_split = a.KP / bk64;
       a.use_patch = 0;
       a.accumulate = 0;
+      a.simple_epilogue = src.simple_epilogue && 8 * (int64_t)src.out_elems <= ((int64_t)1 << 30);
       k = psrc;
       k.KP = a.KP;
       k.MP = a.MP;

@@ -190,7 +190,59 @@ __global__ __launch_bounds__(kThreads) void corr64_kernel(const CorrArgs a) {
   }
   if (kc < nchunks) iteration(kc, raX, rbX);
 
-  // Epilogue: the same two LDS tables as the fp32 kernel (row -> channel / sub-pixel offset,
+  // Epilogue.  One output phase per channel and an output of at most 2^30 bytes (see the fp32
+  // epilogue): byte offsets per row and per column with out-of-range values for "not stored", and
+  // range-checked buffer stores.
+  if (a.simple_epilogue) {
+    uint32_t* rowoff = reinterpret_cast<uint32_t*>(smem);
+    uint32_t* coloff = rowoff + BM;
+    double* rbias = reinterpret_cast<double*>(coloff + BN);
+    const double* bias8 = reinterpret_cast<const double*>(a.bias);
+    if (t < BM) {
+      const uint32_t gm = m_tile * BM + t;
+      uint32_t off = 0x80000000u;
+      double bb = 0.;
+      if (gm < (uint32_t)a.Mrows) {
+        const uint32_t chan = g * a.chan_per_grp + gm;
+        off = 8u * chan * (uint32_t)(a.OHd * a.OWd);
+        if (bias8) bb = bias8[chan];
+      }
+      rowoff[t] = off;
+      rbias[t] = bb;
+    } else if (t < BM + BN) {
+      const int cl = t - BM;
+      const uint32_t col = col_tile * BN + cl;
+      uint32_t off = 0x40000000u;
+      if (col < (uint32_t)a.ncols) {
+        const uint32_t n = mdiv(col, a.mP);
+        const uint32_t pix = col - n * a.P;
+        const uint32_t pa = mdiv(pix, a.mPW);
+        const uint32_t pb = pix - pa * a.PW;
+        const int hh = (int)pa * a.OSh - a.opad_h, ww = (int)pb * a.OSw - a.opad_w;
+        if ((uint32_t)hh < (uint32_t)a.OHd && (uint32_t)ww < (uint32_t)a.OWd)
+          off = 8u * (n * (uint32_t)a.out_img_stride + (uint32_t)hh * (uint32_t)a.OWd + (uint32_t)ww);
+      }
+      coloff[cl] = off;
+    }
+    __syncthreads();
+    const __amdgpu_buffer_rsrc_t out_rsrc =
+        __builtin_amdgcn_make_buffer_rsrc(a.out, 0, (int)(8u * (uint32_t)a.out_elems), 0x00020000);
+    typedef int i32x2 __attribute__((ext_vector_type(2)));
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+      const uint32_t co = coloff[(wn * NB + j) * 16 + (lane & 15)];
+#pragma unroll
+      for (int i = 0; i < MB; ++i)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int m = (wm * MB + i) * 16 + 4 * r + (lane >> 4);
+          const double v = acc[i][j][r] + rbias[m];
+          __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(i32x2, v), out_rsrc, rowoff[m] + co, 0, 0);
+        }
+    }
+    return;
+  }
+  // General form: the same two LDS tables as the fp32 kernel (row -> channel / sub-pixel offset,
   // column -> image / pixel offset), the bias kept beside them as doubles.
   int4* rowtab = reinterpret_cast<int4*>(smem);
   int4* coltab = rowtab + BM;

@@ -238,6 +238,32 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradArgs a) {
 
   // partial tile -> workspace [split][g][k][nn]
   float* dst = a.part + ((size_t)split * a.G + g) * ((size_t)a.Kg * a.Kred);
+  const uint64_t slice_bytes = 4ull * (uint64_t)a.Kg * (uint64_t)a.Kred;
+  if (slice_bytes <= (1ull << 30)) {
+    // Byte offsets per row and per column with out-of-range values for rows and columns past the
+    // matrix edge (2^31 and 2^30: any sum with one of them lies beyond the slice); the range check
+    // of the buffer store drops those elements.
+    const __amdgpu_buffer_rsrc_t out_rsrc = __builtin_amdgcn_make_buffer_rsrc(dst, 0, (int)slice_bytes, 0x00020000);
+    uint32_t co[NB];
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+      const uint32_t nn = n_tile * BN + (wn * NB + j) * 32 + (lane & 31);
+      co[j] = nn < (uint32_t)a.Kred ? 4u * nn : 0x40000000u;
+    }
+#pragma unroll
+    for (int i = 0; i < MB; ++i)
+#pragma unroll
+      for (int r = 0; r < M::NR; ++r) {
+        const uint32_t k = m_tile * BM + (wm * MB + i) * 32 + M::row(r, lane);
+        const uint32_t ro = k < (uint32_t)a.Kg ? 4u * k * (uint32_t)a.Kred : 0x80000000u;
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+          const float v = acc[i][j][r];  // a named float: a bit cast applied to the vector element itself stored zeros
+          __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, v), out_rsrc, ro + co[j], 0, 0);
+        }
+      }
+    return;
+  }
 #pragma unroll
   for (int j = 0; j < NB; ++j) {
     const uint32_t nn = n_tile * BN + (wn * NB + j) * 32 + (lane & 31);

@@ -117,6 +117,29 @@ __device__ __forceinline__ void corr_epilogue(const CorrArgs& a, float* smem, Ac
   int4 ct[NB];
 #pragma unroll
   for (int j = 0; j < NB; ++j) ct[j] = coltab[(wn * NB + j) * MT + lane % MT];
+  if ((uint32_t)a.out_elems < (1u << 29)) {
+    // Output below 2^31 bytes: an element that is not stored gets the offset 2^31 and the range check
+    // of the buffer store drops it -- no branch around the store, 32-bit offsets.
+    const __amdgpu_buffer_rsrc_t out_rsrc =
+        __builtin_amdgcn_make_buffer_rsrc(out, 0, (int)(4u * (uint32_t)a.out_elems), 0x00020000);
+#pragma unroll
+    for (int i = 0; i < MB; ++i)
+#pragma unroll
+      for (int r = 0; r < M::NR; ++r) {
+        const int4 rt = rowtab[(wm * MB + i) * MT + M::row(r, lane)];
+        const float bb = __builtin_bit_cast(float, rt.w);
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+          const int hh = rt.y + ct[j].y, ww = rt.z + ct[j].z;
+          const bool ok = ((uint32_t)hh < (uint32_t)a.OHd) & ((uint32_t)ww < (uint32_t)a.OWd);
+          const uint32_t off = ok ? 4u * (uint32_t)(rt.x + ct[j].x) : 0x80000000u;
+          float v = acc[i][j][r] + bb;
+          if (accumulate) v += __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(out_rsrc, off, 0, 0));
+          __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, v), out_rsrc, off, 0, 0);
+        }
+      }
+    return;
+  }
 #pragma unroll
   for (int i = 0; i < MB; ++i)
 #pragma unroll

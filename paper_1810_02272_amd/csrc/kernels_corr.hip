@@ -90,6 +90,9 @@ __global__ __launch_bounds__(kThreads) void corr_kernel(const CorrArgs a) {
   uint32_t cbase[CPL];
   int cih0[CPL], ciw0[CPL];
   uint32_t cinv[CPL];
+  uint32_t row_bits = 0;  // bit i*TW for every tap row i (MODE 2)
+  if (MODE == 2)
+    for (int i = 0; i < a.THW / a.TW; ++i) row_bits |= 1u << (i * a.TW);
 #pragma unroll
   for (int q = 0; q < CPL; ++q) {
     const uint32_t col = col_tile * BN + q * 64 + lane;
@@ -111,12 +114,27 @@ __global__ __launch_bounds__(kThreads) void corr_kernel(const CorrArgs a) {
     cinv[q] = 0;
     if (MODE == 2) {
       const int TH = a.THW / a.TW;
-      for (int i = 0, tap = 0; i < TH; ++i)
-        for (int j = 0; j < a.TW; ++j, ++tap) {
-          const bool ok = ((uint32_t)(cih0[q] + i * a.dh) < (uint32_t)a.IH) &
-                          ((uint32_t)(ciw0[q] + j * a.dw) < (uint32_t)a.IW);
-          cinv[q] |= ok ? 0u : (1u << tap);
-        }
+      if (a.dh == 1 && a.dw == 1) {
+        // The taps inside the image are i in [lo, hi) x j in [lo, hi): the mask over the tap index
+        // i*TW + j is (bits lo..hi-1 of the column range) times (bit i*TW for every valid i) -- the
+        // shifted copies of the column mask do not overlap, so one multiply builds the outer product.
+        auto bit = [](int n) { return n >= 32 ? 0u : 1u << n; };  // 2^n modulo 2^32
+        int lo = -cih0[q], hi = a.IH - cih0[q];
+        lo = lo < 0 ? 0 : (lo > TH ? TH : lo);
+        hi = hi < lo ? lo : (hi > TH ? TH : hi);
+        const uint32_t rows = row_bits & (bit(hi * a.TW) - bit(lo * a.TW));
+        lo = -ciw0[q], hi = a.IW - ciw0[q];
+        lo = lo < 0 ? 0 : (lo > a.TW ? a.TW : lo);
+        hi = hi < lo ? lo : (hi > a.TW ? a.TW : hi);
+        cinv[q] = ~((bit(hi) - bit(lo)) * rows);
+      } else {
+        for (int i = 0, tap = 0; i < TH; ++i)
+          for (int j = 0; j < a.TW; ++j, ++tap) {
+            const bool ok = ((uint32_t)(cih0[q] + i * a.dh) < (uint32_t)a.IH) &
+                            ((uint32_t)(ciw0[q] + j * a.dw) < (uint32_t)a.IW);
+            cinv[q] |= ok ? 0u : (1u << tap);
+          }
+      }
     }
   }
 

@@ -355,16 +355,19 @@ def test_runs_on_a_side_stream():
     assert nerr(y, oracle.forward(op, x.numpy(), w.numpy(), b.numpy())) <= TOL
 
 
-@pytest.mark.parametrize("group", [1, 2], ids=["gemm", "direct"])
-def test_blobs_between_2_and_4_gib(group):
+@pytest.mark.parametrize("n,group", [(37, 1), (37, 2), (19, 1)], ids=["gemm", "direct", "gemm-1.1GiB"])
+def test_blobs_between_1_and_4_gib(n, group):
     """Maximum sizes: x, y, dx and dy of 2.2 GiB each (5.9e8 elements; the limit is 2^30), where byte
-    offsets no longer fit 31 bits and the GEMM kernels fall back to compare-based bounds checks
-    (one group), and the same sizes on the direct kernels (two groups of two channels).  Sampled
-    outputs the oracle computes one by one, all of dw, the bias gradient in full, finiteness everywhere."""
-    pd = P(37, 4, 2000, 2000, 4, 3, 3, 1, 1, 1, 1, 1, 1, group)
+    offsets no longer fit 31 bits and the GEMM kernels fall back to compare-based bounds checks and
+    64-bit store addresses (one group), the same sizes on the direct kernels (two groups of two
+    channels), and blobs of 1.1 GiB, which take the range-checked stores with one select per element.
+    Sampled outputs the oracle computes one by one, all of dw, the bias gradient in full, finiteness
+    everywhere."""
+    pd = P(n, 4, 2000, 2000, 4, 3, 3, 1, 1, 1, 1, 1, 1, group)
     op = OracleParams(**pd)
     x, w, b, dy = workloads.random_inputs(oracle.x_shape(op), oracle.w_shape(op), oracle.output_shape(op), 5150)
-    assert x.numel() * 4 > (1 << 31) and dy.numel() * 4 > (1 << 31)
+    assert x.numel() * 4 > (1 << 30) and dy.numel() * 4 > (1 << 30)
+    assert (x.numel() * 4 > (1 << 31)) == (n == 37)
     d, ws, _, (y, dx, dw, db) = run_all(pd, x, w, b, dy)
     print("large blobs:", conv.conv_desc_kernel_names(d), flush=True)
     assert ("direct" in conv.conv_desc_kernel_names(d)) == (group == 2)

@@ -12,6 +12,7 @@ import oracle
 import paper_1810_02272_amd as conv
 from oracle import OracleParams
 from paper_1810_02272_amd import workloads
+from parity_metric import gated_error
 from test_parity_gpu import DIRECT_CASES, P, SWEEP
 
 pytestmark = pytest.mark.gpu
@@ -63,10 +64,11 @@ def check_full64(pd, x, w, b, dy):
     d, ws, _, (y, dx, dw, db) = run_all64(pd, x, w, b, dy)
     xn, wn, dyn = x.numpy(), w.numpy(), dy.numpy()
     bn = b.numpy() if b is not None else None
-    errs = {"y": nerr(y, oracle.forward(op, xn, wn, bn)), "dx": nerr(dx, oracle.backward_data(op, wn, dyn)),
-            "dw": nerr(dw, oracle.backward_filter(op, xn, dyn))}
+    refs = {"y": (y, oracle.forward(op, xn, wn, bn)), "dx": (dx, oracle.backward_data(op, wn, dyn)),
+            "dw": (dw, oracle.backward_filter(op, xn, dyn))}
     if b is not None:
-        errs["db"] = nerr(db, oracle.backward_bias(op, dyn))
+        refs["db"] = (db, oracle.backward_bias(op, dyn))
+    errs = {k: gated_error(op, k, g, r, TOL, xn, wn, bn, dyn) for k, (g, r) in refs.items()}
     for k, v in errs.items():
         assert np.isfinite(v) and v <= TOL, (pd, k, v)
     return errs

@@ -2,6 +2,9 @@
 the corners the hand-picked sweep may miss -- stride larger than the kernel, padding beyond the
 kernel extent, dilation with stride, non-square everything, groups) against the CPU oracle, fp32
 and fp64 paths, plus random InnerProduct shapes.  Same gates as the other parity tests."""
+import os
+import time
+
 import numpy as np
 import pytest
 import torch
@@ -84,6 +87,61 @@ def test_random_thin_group_parameters_fp32_and_fp64(block):
                                               bias=bool(pd["bias_term"]))
         check_full64(pd, x.double(), w.double(), b.double() if b is not None else None, dy.double())
     assert direct >= 6, direct  # most of these shapes take the direct kernels
+
+
+def random_multi_tile_params(rng):
+    """Random parameter sets large enough for several tiles per dimension (up to 4e8 FLOPs per pass)."""
+    while True:
+        g = int(rng.choice([1, 1, 2, 4, 8]))
+        c, k = g * int(rng.integers(1, 12)), g * int(rng.integers(1, 40))
+        kh, kw = int(rng.integers(1, 8)), int(rng.integers(1, 8))
+        sh, sw = int(rng.integers(1, 5)), int(rng.integers(1, 5))
+        dh, dw = int(rng.integers(1, 3)), int(rng.integers(1, 3))
+        ph, pw = int(rng.integers(0, 7)), int(rng.integers(0, 7))
+        h, w = int(rng.integers(1, 50)), int(rng.integers(1, 50))
+        n = int(rng.integers(1, 9))
+        pd = dict(n=n, c=c, h=h, w=w, num_output=k, kernel_h=kh, kernel_w=kw, stride_h=sh, stride_w=sw, pad_h=ph,
+                  pad_w=pw, dilation_h=dh, dilation_w=dw, group=g, bias_term=int(rng.integers(0, 2)))
+        oh, ow = oracle.out_size(h, kh, sh, ph, dh), oracle.out_size(w, kw, sw, pw, dw)
+        if oh >= 1 and ow >= 1 and 2.0 * n * k * (c // g) * kh * kw * oh * ow < 4e8:
+            return pd
+
+
+def check_both_types(pd, seed):
+    check_full(pd, seed=seed, bias=bool(pd["bias_term"]))
+    op = OracleParams(**pd)
+    x, w, b, dy = workloads.random_inputs(oracle.x_shape(op), oracle.w_shape(op), oracle.output_shape(op), seed,
+                                          bias=bool(pd["bias_term"]))
+    check_full64(pd, x.double(), w.double(), b.double() if b is not None else None, dy.double())
+
+
+def test_random_multi_tile_parameters_fp32_and_fp64():
+    rng = np.random.default_rng(60600)
+    for i in range(40):
+        pd = random_multi_tile_params(rng)
+        print("random multi-tile case", i, pd, flush=True)
+        check_both_types(pd, 61000 + i)
+
+
+@pytest.mark.skipif("MI355CONV_SOAK_SECONDS" not in os.environ,
+                    reason="extended sweep: set MI355CONV_SOAK_SECONDS (and MI355CONV_SOAK_SEED) to run it")
+def test_extended_random_sweep():
+    """The three generators of this file in turn, fresh parameter sets until the time is up."""
+    budget = float(os.environ["MI355CONV_SOAK_SECONDS"])
+    rng = np.random.default_rng(int(os.environ.get("MI355CONV_SOAK_SEED", "987654")))
+    gens = [random_params, random_thin_group_params, random_multi_tile_params]
+    t0, i = time.time(), 0
+    while time.time() - t0 < budget:
+        pd = gens[i % 3](rng)
+        if i % 1000 == 0:
+            print("extended sweep case", i, pd, flush=True)
+        try:
+            check_both_types(pd, 900000 + i)
+        except Exception:
+            print("failing case", i, pd, flush=True)
+            raise
+        i += 1
+    print("extended sweep:", i, "cases", flush=True)
 
 
 def test_random_inner_product_shapes():

@@ -66,11 +66,28 @@ def run_case(m, k, o, bias, relu, x, w, b, dy, beta=0.0, dw0=None, db0=None):
         zr = ipo.forward(IpOracleParams(m, k, o, int(bias), 0), xn, wn, bn)
         differs = dz_chain.cpu().numpy().astype(np.float64) != dzr
         assert not (differs & (np.abs(zr) > TOL * np.max(np.abs(zr)))).any(), "chained mask differs away from the kink"
-    errs = {"y": nerr(y, yr), "dx": nerr(dx, ipo.backward_data(op, wn, dzr)),
-            "dw": nerr(dw, ipo.backward_filter(op, xn, dzr, None if dw0 is None else dw0.numpy(), beta))}
+    pairs = {"y": (y, yr), "dx": (dx, ipo.backward_data(op, wn, dzr)),
+             "dw": (dw, ipo.backward_filter(op, xn, dzr, None if dw0 is None else dw0.numpy(), beta))}
     if bias:
-        errs["db"] = nerr(db, ipo.backward_bias(op, dzr, None if db0 is None else db0.numpy(), beta))
-    for name, v in errs.items():
+        pairs["db"] = (db, ipo.backward_bias(op, dzr, None if db0 is None else db0.numpy(), beta))
+
+    def term_scale(which):
+        """Largest root-sum-square of the terms of an output (the contraction of the squared operands):
+        the denominator for a tensor of a few elements that cancelled to far below its terms."""
+        sq = lambda a: None if a is None else np.square(np.asarray(a, dtype=np.float64))
+        lin = IpOracleParams(m, k, o, int(bias), 0)
+        r = {"y": lambda: ipo.forward(lin, sq(xn), sq(wn), sq(bn)),
+             "dx": lambda: ipo.backward_data(op, sq(wn), sq(dzr)),
+             "dw": lambda: ipo.backward_filter(op, sq(xn), sq(dzr), None if dw0 is None else sq(dw0.numpy()), beta),
+             "db": lambda: ipo.backward_bias(op, sq(dzr), None if db0 is None else sq(db0.numpy()), beta)}[which]()
+        return float(np.sqrt(np.max(r))) if r.size else 0.0
+
+    errs = {}
+    for name, (got, ref) in pairs.items():
+        v = nerr(got, ref)
+        if np.isfinite(v) and v > TOL and ref.size:
+            v *= float(np.max(np.abs(ref))) / max(float(np.max(np.abs(ref))), term_scale(name))
+        errs[name] = v
         assert np.isfinite(v) and v <= TOL, (pd, name, v, conv.ip_desc_kernel_names(d))
     if relu and m * o:
         assert float(y.min()) >= 0.0

@@ -16,6 +16,7 @@ from paper_1810_02272_amd import workloads
 from test_f64_parity_gpu import check_full64
 from test_ip_parity_gpu import run_case as run_ip_case
 from test_parity_gpu import check_full
+from test_pg_parity_gpu import check_batch as check_pg_batch
 
 pytestmark = pytest.mark.gpu
 
@@ -142,6 +143,56 @@ def test_extended_random_sweep():
             raise
         i += 1
     print("extended sweep:", i, "cases", flush=True)
+
+
+@pytest.mark.skipif("MI355CONV_SOAK_SECONDS" not in os.environ,
+                    reason="extended sweep: set MI355CONV_SOAK_SECONDS (and MI355CONV_SOAK_SEED) to run it")
+def test_extended_random_inner_product_sweep(capsys):
+    budget = float(os.environ["MI355CONV_SOAK_SECONDS"])
+    rng = np.random.default_rng(int(os.environ.get("MI355CONV_SOAK_SEED", "987654")) + 1)
+    t0, i = time.time(), 0
+    while time.time() - t0 < budget:
+        m, k, o = int(rng.integers(1, 300)), int(rng.integers(1, 1500)), int(rng.integers(1, 600))
+        if rng.integers(0, 3) == 0:   # small shapes: single tiles, short reductions
+            m, k, o = int(rng.integers(1, 20)), int(rng.integers(1, 40)), int(rng.integers(1, 20))
+        relu, bias, beta = int(rng.integers(0, 2)), bool(rng.integers(0, 2)), float(rng.integers(0, 2))
+        x, w, b, dy = workloads.ip_random_inputs(m, k, o, seed=910000 + i, bias=bias)
+        try:
+            run_ip_case(m, k, o, bias, relu, x, w, b, dy, beta=beta, dw0=workloads.draw((o, k), "normal", 920000 + i),
+                        db0=workloads.draw((o,), "normal", 930000 + i))
+        except Exception:
+            with capsys.disabled():
+                print("failing inner-product case", i, (m, k, o, relu, bias, beta), flush=True)
+            raise
+        capsys.readouterr()   # drop the per-case lines of the cases that passed
+        i += 1
+    with capsys.disabled():
+        print("extended inner-product sweep:", i, "cases", flush=True)
+
+
+@pytest.mark.skipif("MI355CONV_SOAK_SECONDS" not in os.environ,
+                    reason="extended sweep: set MI355CONV_SOAK_SECONDS (and MI355CONV_SOAK_SEED) to run it")
+def test_extended_random_policy_gradient_sweep(capsys):
+    budget = float(os.environ["MI355CONV_SOAK_SECONDS"])
+    rng = np.random.default_rng(int(os.environ.get("MI355CONV_SOAK_SEED", "987654")) + 2)
+    t0, i = time.time(), 0
+    while time.time() - t0 < budget:
+        while True:
+            episodes, lo, actions = int(rng.integers(1, 300)), int(rng.integers(0, 40)), int(rng.integers(2, 130))
+            hi = lo + int(rng.integers(0, 500))
+            if episodes * (lo + hi) / 2 * actions < 2e6:
+                break
+        gamma = float(rng.choice([0.99, 0.9, 0.5, 1.0, 0.999]))
+        try:
+            check_pg_batch(workloads.pg_batch(episodes, lo, hi, actions, seed=940000 + i), gamma, perturb_seed=950000 + i)
+        except Exception:
+            with capsys.disabled():
+                print("failing policy-gradient case", i, (episodes, lo, hi, actions, gamma), flush=True)
+            raise
+        capsys.readouterr()
+        i += 1
+    with capsys.disabled():
+        print("extended policy-gradient sweep:", i, "cases", flush=True)
 
 
 def test_random_inner_product_shapes():

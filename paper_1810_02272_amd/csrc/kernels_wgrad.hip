@@ -11,6 +11,12 @@
 // lane l takes row l%32 and the four k values 8t + 4(l/32) .. +3, which feed four consecutive
 // 32x32x2 instructions -- the k order inside a group of eight is permuted, identically for both
 // operands, which a sum does not notice.
+//
+// Two staging forms.  Through registers: a thread's loads return into registers and are stored to
+// LDS one chunk later (three chunks in flight).  Straight to LDS (the 128x128 tile): the buffer loads
+// write LDS themselves -- lane l of a wave fills word l of a 64-word segment, i.e. one row pair --
+// with out-of-range lanes writing the zero the range check returns; no staging registers and no LDS
+// store instructions, two chunks in flight, and a wait for the wave's own loads before each barrier.
 #include <hip/hip_runtime.h>
 
 #include "device_utils.h"
@@ -22,26 +28,38 @@ namespace {
 
 constexpr int kThreads = 256;
 
-template <int MB, int NB, int WM, int WN>
+template <int MB, int NB, int WM, int WN, bool DMA = false>
 struct WgCfg {
   static constexpr int MT = 32;
   static constexpr int BK = 32;
   static constexpr int BM = WM * MB * MT;
   static constexpr int BN = WN * NB * MT;
-  static constexpr int LDK = BK + 4;  // 16-byte aligned rows; 8 consecutive rows start on 8 distinct bank quads
+  // Register staging: rows of BK + 4 floats (16-byte aligned; 8 consecutive rows start on 8 distinct
+  // bank quads).  Loads that write LDS themselves put the 64 lanes of a wave -- two rows of 32 k
+  // values -- into 64 consecutive words, so rows come in pairs: a pair takes 2*BK + 4 floats, which
+  // again spreads 16 consecutive rows over the 16 bank quads.
+  static constexpr int LDK = BK + 4;
+  static constexpr int PAIR = 2 * BK + 4;
   static constexpr int A_PER = BM / 8;  // rows per thread: 32 lanes along k, 8 row slots
   static constexpr int B_PER = BN / 8;
-  static constexpr int STAGE = (BM + BN) * LDK;
+  static constexpr int A_FLOATS = DMA ? BM / 2 * PAIR : BM * LDK;
+  static constexpr int STAGE = DMA ? (BM + BN) / 2 * PAIR : (BM + BN) * LDK;
   static constexpr int SMEM_BYTES = 2 * STAGE * 4;
   static_assert(WM * WN == 4, "four waves per workgroup");
+  // float offset of row r inside an operand's tile
+  static constexpr __device__ int row_off(int r) { return DMA ? (r >> 1) * PAIR + (r & 1) * BK : r * LDK; }
 };
+
+typedef __attribute__((address_space(3))) void* LdsPtr;
 
 // MODE: how a gathered x element is bounds-checked, as in the correlation kernel: 0 no padding,
 // 1 row and column compares, 2 per-column tap bitmask (dilation 1, at most 16 taps per dimension and
 // 32 in all, blobs at most 2^29 bytes).
-template <int MB, int NB, int WM, int WN, int MODE>
+// DMA: the loads write LDS themselves (no register staging, no LDS store instructions); the pipeline
+// is then two chunks deep -- chunk ch+1 lands in the other buffer while chunk ch is multiplied.
+template <int MB, int NB, int WM, int WN, int MODE, bool DMA>
 __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradArgs a) {
-  using C = WgCfg<MB, NB, WM, WN>;
+  using C = WgCfg<MB, NB, WM, WN, DMA>;
   using M = Mfma<32>;
   constexpr int BM = C::BM, BN = C::BN, BK = C::BK, LDK = C::LDK, A_PER = C::A_PER, B_PER = C::B_PER;
 
@@ -149,12 +167,18 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradArgs a) {
       inv = colok ? ~(colm * rows) : ~0u;
     }
   };
-  auto load_a = [&](int e) {
+  // DMA: load e of wave wv fills the row pair 4e + wv of the operand's tile in buffer `buf`
+  // (rows 8e + 2wv and 8e + 2wv + 1 = rslot + 8e of the two half waves), lane l the l-th word.
+  auto load_a = [&](int e, int buf = 0) {
     uint32_t off = dybase + aoff[e];
     if (MODE == 1) off = colok ? off : a.dy_bytes;  // blobs of 2^31 bytes and more: explicit select
-    ra[e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(dy_rsrc, off, 0, 0));
+    if (DMA)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(dy_rsrc, (LdsPtr)(smem + buf * C::STAGE + (4 * e + wv) * C::PAIR), 4, off,
+                                               0, 0, 0);
+    else
+      ra[e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(dy_rsrc, off, 0, 0));
   };
-  auto load_b = [&](int e) {
+  auto load_b = [&](int e, int buf = 0) {
     uint32_t off = xbase + boff[e];
     if (MODE == 1) {
       const int ih = ih0 + (int)(bij[e] >> 16), iw = iw0 + (int)(bij[e] & 0xffffu);
@@ -163,7 +187,11 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradArgs a) {
     } else if (MODE == 2) {
       off += __builtin_amdgcn_ubfe(inv, bij[e], 1u) << 31;
     }
-    rb[e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(x_rsrc, off, 0, 0));
+    if (DMA)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(
+          x_rsrc, (LdsPtr)(smem + buf * C::STAGE + C::A_FLOATS + (4 * e + wv) * C::PAIR), 4, off, 0, 0, 0);
+    else
+      rb[e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(x_rsrc, off, 0, 0));
   };
   auto store_a = [&](int buf, int e) { smem[buf * C::STAGE + (rslot + 8 * e) * LDK + kc] = ra[e]; };
   auto store_b = [&](int buf, int e) { smem[buf * C::STAGE + BM * LDK + (rslot + 8 * e) * LDK + kc] = rb[e]; };
@@ -173,23 +201,28 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradArgs a) {
   // reloaded with chunk ch+2, one or two elements per k step, in the shadow of the MFMAs.
   constexpr int NKS = BK / 2;  // MFMA k steps per chunk; four of them share one 16-byte operand read
   constexpr int NSS = BK / 8;
-  const float* opA = smem + (wm * MB * 32 + (lane & 31)) * LDK + (lane >> 5) * 4;
-  const float* opB = smem + BM * LDK + (wn * NB * 32 + (lane & 31)) * LDK + (lane >> 5) * 4;
+  const float* opA = smem + C::row_off(wm * MB * 32 + (lane & 31)) + (lane >> 5) * 4;
+  const float* opB = smem + C::A_FLOATS + C::row_off(wn * NB * 32 + (lane & 31)) + (lane >> 5) * 4;
+  constexpr int BLK = C::row_off(32);  // floats between 32-row blocks
   if (nchunks > 0) {
     col_state(0);
 #pragma unroll
     for (int e = 0; e < A_PER; ++e) load_a(e);
 #pragma unroll
     for (int e = 0; e < B_PER; ++e) load_b(e);
+    if (!DMA) {
 #pragma unroll
-    for (int e = 0; e < A_PER; ++e) store_a(0, e);
+      for (int e = 0; e < A_PER; ++e) store_a(0, e);
 #pragma unroll
-    for (int e = 0; e < B_PER; ++e) store_b(0, e);
-    col_state(nchunks > 1 ? 1 : 0);
+      for (int e = 0; e < B_PER; ++e) store_b(0, e);
+      col_state(nchunks > 1 ? 1 : 0);
 #pragma unroll
-    for (int e = 0; e < A_PER; ++e) load_a(e);
+      for (int e = 0; e < A_PER; ++e) load_a(e);
 #pragma unroll
-    for (int e = 0; e < B_PER; ++e) load_b(e);
+      for (int e = 0; e < B_PER; ++e) load_b(e);
+    } else {
+      __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's words of chunk 0 are in LDS
+    }
   }
   __syncthreads();
   for (int ch = 0; ch < nchunks; ++ch) {
@@ -198,41 +231,55 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradArgs a) {
     const float* sB = opB + cur * C::STAGE;
     f32x4 av[2][MB], bv[2][NB];
 #pragma unroll
-    for (int i = 0; i < MB; ++i) av[0][i] = *reinterpret_cast<const f32x4*>(sA + i * 32 * LDK);
+    for (int i = 0; i < MB; ++i) av[0][i] = *reinterpret_cast<const f32x4*>(sA + i * BLK);
 #pragma unroll
-    for (int j = 0; j < NB; ++j) bv[0][j] = *reinterpret_cast<const f32x4*>(sB + j * 32 * LDK);
+    for (int j = 0; j < NB; ++j) bv[0][j] = *reinterpret_cast<const f32x4*>(sB + j * BLK);
 #pragma unroll
     for (int ks = 0; ks < NKS; ++ks) {
       const int ss = ks / 4, u = ks % 4;
       if (u == 0 && ss + 1 < NSS) {  // operands of the next group of four steps
 #pragma unroll
         for (int i = 0; i < MB; ++i)
-          av[(ss + 1) & 1][i] = *reinterpret_cast<const f32x4*>(sA + i * 32 * LDK + (ss + 1) * 8);
+          av[(ss + 1) & 1][i] = *reinterpret_cast<const f32x4*>(sA + i * BLK + (ss + 1) * 8);
 #pragma unroll
         for (int j = 0; j < NB; ++j)
-          bv[(ss + 1) & 1][j] = *reinterpret_cast<const f32x4*>(sB + j * 32 * LDK + (ss + 1) * 8);
+          bv[(ss + 1) & 1][j] = *reinterpret_cast<const f32x4*>(sB + j * BLK + (ss + 1) * 8);
       }
 #pragma unroll
       for (int i = 0; i < MB; ++i)
 #pragma unroll
         for (int j = 0; j < NB; ++j) M::run(av[ss & 1][i][u], bv[ss & 1][j][u], acc[i][j]);
-      // this step's share of the staging work: registers of chunk ch+1 go to LDS first ...
+      if (DMA) {
+        // this step's share of the loads of chunk ch+1, all issued in the first half of the chunk so
+        // that they have the second half to land (past the last chunk they repeat it: nobody reads them)
+        constexpr int HALF = NKS / 2;
+        if (ks == 0) col_state(ch + 1 < nchunks ? ch + 1 : nchunks - 1);
 #pragma unroll
-      for (int e = 0; e < A_PER; ++e)
-        if (e * NKS / A_PER == ks) store_a(nxt, e);
+        for (int e = 0; e < A_PER; ++e)
+          if (e * HALF / A_PER == ks) load_a(e, nxt);
 #pragma unroll
-      for (int e = 0; e < B_PER; ++e)
-        if (e * NKS / B_PER == ks) store_b(nxt, e);
-      // ... then are reloaded with chunk ch+2 (column state switches once all stores are queued)
-      if (ks == 0) col_state(ch + 2 < nchunks ? ch + 2 : nchunks - 1);
+        for (int e = 0; e < B_PER; ++e)
+          if (e * HALF / B_PER == ks) load_b(e, nxt);
+      } else {
+        // this step's share of the staging work: registers of chunk ch+1 go to LDS first ...
 #pragma unroll
-      for (int e = 0; e < A_PER; ++e)
-        if (e * NKS / A_PER == ks) load_a(e);
+        for (int e = 0; e < A_PER; ++e)
+          if (e * NKS / A_PER == ks) store_a(nxt, e);
 #pragma unroll
-      for (int e = 0; e < B_PER; ++e)
-        if (e * NKS / B_PER == ks) load_b(e);
+        for (int e = 0; e < B_PER; ++e)
+          if (e * NKS / B_PER == ks) store_b(nxt, e);
+        // ... then are reloaded with chunk ch+2 (column state switches once all stores are queued)
+        if (ks == 0) col_state(ch + 2 < nchunks ? ch + 2 : nchunks - 1);
+#pragma unroll
+        for (int e = 0; e < A_PER; ++e)
+          if (e * NKS / A_PER == ks) load_a(e);
+#pragma unroll
+        for (int e = 0; e < B_PER; ++e)
+          if (e * NKS / B_PER == ks) load_b(e);
+      }
       __builtin_amdgcn_sched_barrier(0);
     }
+    if (DMA) __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's words of chunk ch+1 are in LDS
     __syncthreads();
   }
 
@@ -277,26 +324,26 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradArgs a) {
   }
 }
 
-template <int MB, int NB, int WM, int WN, int MODE>
+template <int MB, int NB, int WM, int WN, int MODE, bool DMA>
 int launch_wgrad_m(const WgradArgs& a, hipStream_t s) {
-  using C = WgCfg<MB, NB, WM, WN>;
+  using C = WgCfg<MB, NB, WM, WN, DMA>;
   static bool configured = false;
   if (!configured) {  // more than 64 KB of LDS needs an explicit opt-in, once per process
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&wgrad_kernel<MB, NB, WM, WN, MODE>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&wgrad_kernel<MB, NB, WM, WN, MODE, DMA>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM_BYTES);
     if (e != hipSuccess) return (int)e;
     configured = true;
   }
   const uint32_t blocks = (uint32_t)a.G * a.S * a.m_tiles * a.n_tiles;
-  hipLaunchKernelGGL((wgrad_kernel<MB, NB, WM, WN, MODE>), dim3(blocks), dim3(kThreads), C::SMEM_BYTES, s, a);
+  hipLaunchKernelGGL((wgrad_kernel<MB, NB, WM, WN, MODE, DMA>), dim3(blocks), dim3(kThreads), C::SMEM_BYTES, s, a);
   return (int)hipGetLastError();
 }
 
-template <int MB, int NB, int WM, int WN>
+template <int MB, int NB, int WM, int WN, bool DMA>
 int launch_wgrad_t(const WgradArgs& a, hipStream_t s) {
-  if (a.bounds_mode == 0) return launch_wgrad_m<MB, NB, WM, WN, 0>(a, s);
-  if (a.bounds_mode == 2) return launch_wgrad_m<MB, NB, WM, WN, 2>(a, s);
-  return launch_wgrad_m<MB, NB, WM, WN, 1>(a, s);
+  if (a.bounds_mode == 0) return launch_wgrad_m<MB, NB, WM, WN, 0, DMA>(a, s);
+  if (a.bounds_mode == 2) return launch_wgrad_m<MB, NB, WM, WN, 2, DMA>(a, s);
+  return launch_wgrad_m<MB, NB, WM, WN, 1, DMA>(a, s);
 }
 
 // dst = beta*dst + sum_s part[s] (+ bias, ReLU).  A block owns 64*V consecutive elements (V = 4 with
@@ -380,12 +427,15 @@ const char* wgrad_tile_name(int32_t tile) {
 
 int launch_wgrad(int32_t tile, const WgradArgs& a, void* stream) {
   hipStream_t s = (hipStream_t)stream;
+  // Loads that write LDS themselves pay on the square tile (5.b, 5.c backward filter 1.5 % faster); the
+  // 96-row tile with its short splits and stride-4 gather is 1 % slower with them, the narrow tiles
+  // show no difference.
   switch (tile) {
-    case WGRAD_128x128: return launch_wgrad_t<2, 2, 2, 2>(a, s);
-    case WGRAD_96x128:  return launch_wgrad_t<3, 1, 1, 4>(a, s);
-    case WGRAD_64x128:  return launch_wgrad_t<2, 1, 1, 4>(a, s);
-    case WGRAD_32x128:  return launch_wgrad_t<1, 1, 1, 4>(a, s);
-    case WGRAD_128x64:  return launch_wgrad_t<2, 1, 2, 2>(a, s);
+    case WGRAD_128x128: return launch_wgrad_t<2, 2, 2, 2, true>(a, s);
+    case WGRAD_96x128:  return launch_wgrad_t<3, 1, 1, 4, false>(a, s);
+    case WGRAD_64x128:  return launch_wgrad_t<2, 1, 1, 4, false>(a, s);
+    case WGRAD_32x128:  return launch_wgrad_t<1, 1, 1, 4, false>(a, s);
+    case WGRAD_128x64:  return launch_wgrad_t<2, 1, 2, 2, false>(a, s);
     default: return (int)hipErrorInvalidValue;
   }
 }

@@ -124,6 +124,19 @@ int conv_last_hip_error(void);
 /* Names of the kernel variants the descriptor selected, for logs and profiles ("fwd=...;bwd_data=...;..."). */
 const char* conv_desc_kernel_names(const conv_desc_t* d);
 
+/*
+ * Measurement helper, not part of the layer path (the benchmark uses it to put the published fp32
+ * matrix peak beside what the chip sustains): `workgroups` workgroups of four waves each run
+ * `iters` rounds of four independent 32x32x2 fp32 matrix instructions on registers only, no memory
+ * traffic.  Wave v of workgroup b writes two counts to out[2*(4*b + v)] and out[2*(4*b + v) + 1]:
+ * the core-clock ticks and the ticks of the device's constant-rate timer that its loop took.  `out`
+ * is device memory of 8*workgroups uint64, caller-owned.  `timer_khz` (host pointer, may be NULL)
+ * receives the rate of that timer.  FLOPs of one launch = workgroups * 4 * iters * 4 * 4096.
+ * Enqueued on hip_stream without synchronising.  CONV_EINVAL for a null `out`, workgroups outside
+ * [1, 65536] or iters outside [1, 2^20].
+ */
+int conv_mfma_probe(int32_t workgroups, int32_t iters, uint64_t* out, int32_t* timer_khz, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -112,6 +112,16 @@ def test_null_arguments_and_status_strings():
     assert conv.conv_status_string(0) == "success"
 
 
+def test_mfma_probe_checks_arguments():
+    lib = binding._load()
+    assert lib.conv_mfma_probe(4, 10, None, None, None) == binding.CONV_EINVAL
+    for wg, it in ((0, 10), (65537, 10), (4, 0), (4, (1 << 20) + 1)):
+        assert lib.conv_mfma_probe(wg, it, 16, None, None) == binding.CONV_EINVAL
+    import torch
+    with pytest.raises(conv.ConvError):
+        conv.conv_mfma_probe(4, 10, torch.zeros(32, dtype=torch.int64))
+
+
 def test_binding_refuses_cpu_tensors():
     import torch
     p = conv.ConvParams(1, 1, 4, 4, 1, 3, 3)

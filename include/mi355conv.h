@@ -136,6 +136,8 @@ const char* conv_desc_kernel_names(const conv_desc_t* d);
  * [1, 65536] or iters outside [1, 2^20].
  */
 int conv_mfma_probe(int32_t workgroups, int32_t iters, uint64_t* out, int32_t* timer_khz, void* hip_stream);
+/* The same loop on 16x16x4 fp64 matrix instructions: FLOPs of one launch = workgroups * 4 * iters * 4 * 2048. */
+int conv_mfma_probe_f64(int32_t workgroups, int32_t iters, uint64_t* out, int32_t* timer_khz, void* hip_stream);
 
 #ifdef __cplusplus
 }

@@ -115,6 +115,8 @@ def test_null_arguments_and_status_strings():
 def test_mfma_probe_checks_arguments():
     lib = binding._load()
     assert lib.conv_mfma_probe(4, 10, None, None, None) == binding.CONV_EINVAL
+    assert lib.conv_mfma_probe_f64(4, 10, None, None, None) == binding.CONV_EINVAL
+    assert lib.conv_mfma_probe_f64(0, 10, 16, None, None) == binding.CONV_EINVAL
     for wg, it in ((0, 10), (65537, 10), (4, 0), (4, (1 << 20) + 1)):
         assert lib.conv_mfma_probe(wg, it, 16, None, None) == binding.CONV_EINVAL
     import torch

@@ -659,12 +659,15 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
     a.G = (int32_t)G;
     a.m_tiles = (int32_t)ceil_div(Kg, bm);
     a.n_tiles = (int32_t)ceil_div(kred, bn);
-    // Split the reduction so that the grid has up to four workgroups per compute unit, each split
-    // at least four k tiles long and the partials at most 32 MiB; a grid slightly above a
+    // Split the reduction so that the whole grid is resident at once -- LDS holds two workgroups per
+    // compute unit (three of the 32-row tile), and a grid of 1.4 times that many runs a second,
+    // mostly empty round (5.a: 714 workgroups on 512 places took 255 us, 507 take 234) -- with each
+    // split at least four k tiles long and the partials at most 32 MiB; a grid slightly above a
     // multiple of the 256 compute units is trimmed back to it (its last few workgroups would
-    // otherwise run alone).
+    // otherwise share a compute unit while the others have one to themselves).
     const int64_t tiles = G * a.m_tiles * a.n_tiles;
-    int64_t S = 1024 / tiles;
+    const int64_t places = 256 * (bm == 32 ? 3 : 2);
+    int64_t S = places / tiles;
     const int64_t max_by_len = ceil_div((int64_t)a.ncols, 4 * bk);
     const int64_t max_by_ws = ((int64_t)8 << 20) / (w_elems > 0 ? w_elems : 1);
     if (S > max_by_len) S = max_by_len;

@@ -217,6 +217,12 @@ void configure_ksplit(CorrArgs& a, int64_t out_elems) {
     S = ceil_div(512, units);
     if (S > chunks / 4) S = chunks / 4;
     if (S > 16) S = 16;
+    // a long reduction carries twice as many slices as long as each keeps 32 chunks (the 9216 -> 4096
+    // InnerProduct backward-data pass: 144 tiles, 256 chunks, 4 -> 8 slices, 118 -> 105 us)
+    int64_t S2 = ceil_div(1024, units);
+    if (S2 > chunks / 32) S2 = chunks / 32;
+    if (S2 > 16) S2 = 16;
+    if (S2 > S) S = S2;
   } else if (units < 512 && 2.0 * a.Mrows * a.Kred * (double)a.ncols * a.G >= 5e9) {
     // Mid-sized grids of a large problem (a 14x14 or 7x7 layer with hundreds of channels): one or
     // two workgroups per compute unit with some units idle.  Take the split that brings the load

@@ -124,6 +124,34 @@ def test_random_multi_tile_parameters_fp32_and_fp64():
         check_both_types(pd, 61000 + i)
 
 
+def test_random_many_channel_parameters_reach_the_square_filter_gradient_tile():
+    """Random layers with about 128 or 256 output channels per group and a reduced dimension of 100-500: the 128x128
+    backward-filter tile (loads that write LDS directly) with ragged rows and columns, every bounds mode."""
+    rng = np.random.default_rng(70700)
+    square = 0
+    for i in range(16):
+        while True:
+            g = int(rng.choice([1, 1, 2]))
+            # rows and reduced dimension a little below a multiple of 128: the tile that pads least
+            k = g * (128 * int(rng.integers(1, 3)) - int(rng.integers(0, 20)))
+            kh, kw = int(rng.integers(1, 6)), int(rng.integers(1, 6))
+            c = g * max(1, (128 * int(rng.integers(1, 5)) - int(rng.integers(0, 12))) // (kh * kw))
+            sh, sw = int(rng.integers(1, 3)), int(rng.integers(1, 3))
+            ph, pw = int(rng.integers(0, 3)), int(rng.integers(0, 3))
+            dh = dw = int(rng.choice([1, 1, 2]))
+            h, w = int(rng.integers(4, 16)), int(rng.integers(4, 16))
+            pd = dict(n=int(rng.integers(1, 5)), c=c, h=h, w=w, num_output=k, kernel_h=kh, kernel_w=kw, stride_h=sh,
+                      stride_w=sw, pad_h=ph, pad_w=pw, dilation_h=dh, dilation_w=dw, group=g,
+                      bias_term=int(rng.integers(0, 2)))
+            if oracle.out_size(h, kh, sh, ph, dh) >= 1 and oracle.out_size(w, kw, sw, pw, dw) >= 1:
+                break
+        names = conv.conv_desc_kernel_names(conv.conv_desc_create(conv.ConvParams(**pd)))
+        print("random many-channel case", i, pd, names, flush=True)
+        square += "wgrad_m32_128x128x32" in names
+        check_both_types(pd, 71000 + i)
+    assert square >= 8, square
+
+
 @pytest.mark.skipif("MI355CONV_SOAK_SECONDS" not in os.environ,
                     reason="extended sweep: set MI355CONV_SOAK_SECONDS (and MI355CONV_SOAK_SEED) to run it")
 def test_extended_random_sweep():

@@ -251,6 +251,24 @@ int launch_bias_grad(const BiasGradArgs& a, void* stream);
 int launch_fill_zero(void* dst, size_t bytes, void* stream);  // bytes a multiple of 4
 // pass: 0 forward, 1 backward data (dx overwritten), 2 filter-gradient partials
 int launch_direct(int pass, const DirectArgs& a, bool f64, void* stream);
+// The kernel form launch_direct takes for a pass (decided from the parameters and the alignment of
+// the pointers in `a`; null pointers count as aligned) and its name for conv_desc_kernel_names.
+enum DirectFormKind : int32_t {
+  DF_ELEM = 0,     // one output (or dx) element per thread, any kernel size
+  DF_ELEM_K3,      // the same with the 3x3 taps unrolled
+  DF_ROWS,         // 3x3 / 5x5: a thread owns 8 (unit stride and dilation) or 4 rows of one column
+  DF_ROWS_VEC,     // 3x3 / 5x5 "same" layers: 4 rows x 4 columns per thread, 16-byte accesses
+  DF_S2,           // 3x3 / 5x5 at stride 2: 4 rows x 2 output columns per thread
+  DF_BWD_S2_VEC,   // backward data at stride 2: 2 rows x 4 columns of dx per thread
+  DF_BWD_BLOCKS,   // backward data at stride 2: one 2x2 block of dx per thread
+  DF_WGRAD_TAPS    // filter gradient, any kernel size: lanes = (position slot, tap)
+};
+struct DirectForm {
+  DirectFormKind kind;
+  bool unit;  // unit stride and dilation
+};
+DirectForm direct_form(int pass, const DirectArgs& a, size_t elem_bytes);
+void direct_form_name(int pass, const DirectArgs& a, char* buf, size_t len);
 // double base type: the same argument structs, pointer members addressing doubles
 constexpr int32_t kF64TileCols = 64, kF64TileK = 16;
 int32_t f64_pick_rows(int64_t rows, bool filter_gradient);  // 96, 64, 48, 32 or 16: pads `rows` least

@@ -280,18 +280,11 @@ int launch_patch_t(const CorrArgs& a, hipStream_t s) {
 
 int launch_corr_patch(int32_t tile, const CorrArgs& a, void* stream) {
   hipStream_t s = (hipStream_t)stream;
-  switch (tile) {  //                        MT MB NB WM WN
-    case CORR_128x128: return launch_patch_t<32, 2, 2, 2, 2>(a, s);
-    case CORR_128x64:  return launch_patch_t<32, 2, 1, 2, 2>(a, s);
-    case CORR_96x128:  return launch_patch_t<32, 3, 1, 1, 4>(a, s);
-    case CORR_64x128:  return launch_patch_t<32, 2, 1, 1, 4>(a, s);
-    case CORR_64x64:   return launch_patch_t<32, 1, 1, 2, 2>(a, s);
+  switch (tile) {  // the 256-column tiles of at most 48 rows (see configure_patch)
+    //                                       MT MB NB WM WN
     case CORR_32x256:  return launch_patch_t<32, 1, 2, 1, 4>(a, s);
-    case CORR_32x128:  return launch_patch_t<32, 1, 1, 1, 4>(a, s);
     case CORR_48x256:  return launch_patch_t<16, 3, 4, 1, 4>(a, s);
-    case CORR_48x128:  return launch_patch_t<16, 3, 2, 1, 4>(a, s);
     case CORR_16x256:  return launch_patch_t<16, 1, 4, 1, 4>(a, s);
-    case CORR_16x64:   return launch_patch_t<16, 1, 1, 1, 4>(a, s);
     default: return (int)hipErrorInvalidValue;
   }
 }

@@ -5,6 +5,7 @@
 // (cross-correlation, zero padding, stride, dilation, contiguous channel groups), written out per
 // element; T is the base type of the blobs.
 #include <hip/hip_runtime.h>
+#include <stdio.h>
 
 #include "device_utils.h"
 #include "internal.h"
@@ -521,13 +522,7 @@ __global__ __launch_bounds__(256) void direct_wgrad_rows_s2_kernel(const DirectA
 // Stride-2 launcher for forward (pass 0) and filter gradient (pass 2); false when the shape or the
 // alignment of the blobs does not fit (the caller then takes the one-column kernels).
 template <typename T, int KH, int KW>
-bool launch_s2(int pass, const DirectArgs& src, hipStream_t s, int* status) {
-  const uintptr_t mask = 4 * sizeof(T) - 1;
-  const uintptr_t other = pass == 0 ? (uintptr_t)src.out : (uintptr_t)src.w;  // y or dy: two-element accesses
-  const bool fits = src.sh == 2 && src.sw == 2 && src.dh == 1 && src.dw == 1 && src.W % 4 == 0 &&
-                    src.pw == (KW - 1) / 2 && 2 * src.OW == src.W && ((uintptr_t)src.in & mask) == 0 &&
-                    (other & (2 * sizeof(T) - 1)) == 0;
-  if (!fits) return false;
+int launch_s2(int pass, const DirectArgs& src, hipStream_t s) {
   DirectArgs a = src;
   a.OWQ = src.W / 4;
   a.mOWQ = make_magic((uint32_t)a.OWQ);
@@ -540,8 +535,7 @@ bool launch_s2(int pass, const DirectArgs& src, hipStream_t s, int* status) {
     hipLaunchKernelGGL((direct_wgrad_rows_s2_kernel<T, KH, KW>), dim3((uint32_t)(a.K * a.Cg), (uint32_t)a.S), dim3(256),
                        0, s, a);
   }
-  *status = (int)hipGetLastError();
-  return true;
+  return (int)hipGetLastError();
 }
 
 // Filter gradient, 3x3 and 5x5: lanes are output columns, a thread keeps one running sum per tap
@@ -665,23 +659,19 @@ __global__ __launch_bounds__(256) void direct_bwd_blocks_kernel(const DirectArgs
     }
 }
 
-// False when the block space does not fit 31 bits (padding far larger than the image): the caller
-// then takes the one-element-per-thread kernel, whose index space is dx itself.
+// The block space must fit 31 bits (direct_form checks it; with padding far larger than the image it
+// does not, and the one-element-per-thread kernel, whose index space is dx itself, runs instead).
 template <typename T, int KH, int KW, int S>
-bool launch_bwd_blocks(const DirectArgs& src, hipStream_t s, int* status) {
+int launch_bwd_blocks(const DirectArgs& src, hipStream_t s) {
   DirectArgs a = src;
   a.BH = (a.H + a.ph + S - 1) / S;
   a.BW = (a.W + a.pw + S - 1) / S;
-  const unsigned long long items = (unsigned long long)a.N * (unsigned long long)a.C * (unsigned long long)a.BH *
-                                   (unsigned long long)a.BW;
-  if (items >= (1ull << 31)) return false;
   a.mBH = make_magic((uint32_t)a.BH);
   a.mBW = make_magic((uint32_t)a.BW);
-  a.block_items = (uint32_t)items;
+  a.block_items = (uint32_t)a.N * (uint32_t)a.C * (uint32_t)a.BH * (uint32_t)a.BW;
   const dim3 grid((a.block_items + 255u) / 256u);
   hipLaunchKernelGGL((direct_bwd_blocks_kernel<T, KH, KW, S>), grid, dim3(256), 0, s, a);
-  *status = (int)hipGetLastError();
-  return true;
+  return (int)hipGetLastError();
 }
 
 // Backward data of a stride-2 "same" layer (pad = (k-1)/2 both ways, dilation 1) on rows of a
@@ -752,11 +742,7 @@ __global__ __launch_bounds__(256) void direct_bwd_s2_vec_kernel(const DirectArgs
 }
 
 template <typename T, int KH, int KW>
-bool launch_bwd_s2_vec(const DirectArgs& src, hipStream_t s, int* status) {
-  const bool fits = src.sh == 2 && src.sw == 2 && src.dh == 1 && src.dw == 1 && src.W % 4 == 0 &&
-                    src.ph == (KH - 1) / 2 && src.pw == (KW - 1) / 2 &&
-                    ((uintptr_t)src.out & (4 * sizeof(T) - 1)) == 0;
-  if (!fits) return false;
+int launch_bwd_s2_vec(const DirectArgs& src, hipStream_t s) {
   DirectArgs a = src;
   a.BH = (a.H + 1) / 2;
   a.BW = a.W / 4;
@@ -765,8 +751,7 @@ bool launch_bwd_s2_vec(const DirectArgs& src, hipStream_t s, int* status) {
   a.block_items = (uint32_t)a.N * (uint32_t)a.C * (uint32_t)a.BH * (uint32_t)a.BW;
   const dim3 grid((a.block_items + 255u) / 256u);
   hipLaunchKernelGGL((direct_bwd_s2_vec_kernel<T, KH, KW>), grid, dim3(256), 0, s, a);
-  *status = (int)hipGetLastError();
-  return true;
+  return (int)hipGetLastError();
 }
 
 template <typename T, int KH, int KW>
@@ -782,14 +767,10 @@ int launch_direct_k(int pass, const DirectArgs& a, hipStream_t s) {
 // The rows-per-thread kernels.  Backward data (stride 1 only) runs as the forward pass of the mirrored
 // problem: dy is the input blob with K channels, dx the output with C channels.
 template <typename T, int KH, int KW, bool UNIT>
-int launch_rows(int pass, const DirectArgs& src, hipStream_t s) {
+int launch_rows(int pass, const DirectArgs& src, bool vec, hipStream_t s) {
   constexpr int kRows = rows_per_thread(UNIT);
   DirectArgs a = src;
-  // four columns per thread: "same" padding along the row, rows of a multiple of four elements,
-  // every blob of the pass 16-byte aligned for its base type
-  const uintptr_t align_mask = 4 * sizeof(T) - 1;
-  const bool aligned = (((uintptr_t)src.in | (uintptr_t)src.out | (pass == 2 ? (uintptr_t)src.w : 0)) & align_mask) == 0;
-  const bool vec = UNIT && aligned && src.W % 4 == 0 && src.pw == (KW - 1) / 2 && src.OW == src.W;
+  vec = vec && UNIT;  // the four-columns-per-thread kernels exist at unit stride and dilation only
   if (vec) {
     a.OWQ = src.W / kVecCols;
     a.mOWQ = make_magic((uint32_t)a.OWQ);
@@ -852,33 +833,87 @@ int launch_rows(int pass, const DirectArgs& src, hipStream_t s) {
 
 template <typename T>
 int launch_direct_t(int pass, const DirectArgs& a, hipStream_t s) {
-  if (pass != 1) {
-    int status = 0;
-    if (a.kh == 3 && a.kw == 3 && launch_s2<T, 3, 3>(pass, a, s, &status)) return status;
-    if (a.kh == 5 && a.kw == 5 && launch_s2<T, 5, 5>(pass, a, s, &status)) return status;
+  const DirectForm f = direct_form(pass, a, sizeof(T));
+  const bool k3 = a.kh == 3;
+  switch (f.kind) {
+    case DF_S2: return k3 ? launch_s2<T, 3, 3>(pass, a, s) : launch_s2<T, 5, 5>(pass, a, s);
+    case DF_ROWS:
+    case DF_ROWS_VEC: {
+      const bool vec = f.kind == DF_ROWS_VEC;
+      if (k3) return f.unit ? launch_rows<T, 3, 3, true>(pass, a, vec, s) : launch_rows<T, 3, 3, false>(pass, a, vec, s);
+      return f.unit ? launch_rows<T, 5, 5, true>(pass, a, vec, s) : launch_rows<T, 5, 5, false>(pass, a, vec, s);
+    }
+    case DF_WGRAD_TAPS:
+      hipLaunchKernelGGL(direct_wgrad_kernel<T>, dim3((uint32_t)(a.K * a.Cg), (uint32_t)a.S), dim3(256), 0, s, a);
+      return (int)hipGetLastError();
+    case DF_BWD_S2_VEC: return k3 ? launch_bwd_s2_vec<T, 3, 3>(a, s) : launch_bwd_s2_vec<T, 5, 5>(a, s);
+    case DF_BWD_BLOCKS: return k3 ? launch_bwd_blocks<T, 3, 3, 2>(a, s) : launch_bwd_blocks<T, 5, 5, 2>(a, s);
+    case DF_ELEM_K3: return launch_direct_k<T, 3, 3>(pass, a, s);
+    default: return launch_direct_k<T, 0, 0>(pass, a, s);
   }
-  const bool unit = a.sh == 1 && a.sw == 1 && a.dh == 1 && a.dw == 1;
-  const bool rows_ok = pass != 1 || (a.sh == 1 && a.sw == 1);  // backward data: stride 1 only
-  if (rows_ok && a.kh == 3 && a.kw == 3)
-    return unit ? launch_rows<T, 3, 3, true>(pass, a, s) : launch_rows<T, 3, 3, false>(pass, a, s);
-  if (rows_ok && a.kh == 5 && a.kw == 5)
-    return unit ? launch_rows<T, 5, 5, true>(pass, a, s) : launch_rows<T, 5, 5, false>(pass, a, s);
-  if (pass == 2) {
-    hipLaunchKernelGGL(direct_wgrad_kernel<T>, dim3((uint32_t)(a.K * a.Cg), (uint32_t)a.S), dim3(256), 0, s, a);
-    return (int)hipGetLastError();
-  }
-  if (pass == 1 && a.sh == 2 && a.sw == 2 && a.dh == 1 && a.dw == 1) {
-    int status = 0;
-    if (a.kh == 3 && a.kw == 3 && launch_bwd_s2_vec<T, 3, 3>(a, s, &status)) return status;
-    if (a.kh == 5 && a.kw == 5 && launch_bwd_s2_vec<T, 5, 5>(a, s, &status)) return status;
-    if (a.kh == 3 && a.kw == 3 && launch_bwd_blocks<T, 3, 3, 2>(a, s, &status)) return status;
-    if (a.kh == 5 && a.kw == 5 && launch_bwd_blocks<T, 5, 5, 2>(a, s, &status)) return status;
-  }
-  if (a.kh == 3 && a.kw == 3) return launch_direct_k<T, 3, 3>(pass, a, s);
-  return launch_direct_k<T, 0, 0>(pass, a, s);
 }
 
 }  // namespace
+
+// Which kernel a pass of a thin-group descriptor runs.  The choice depends on the layer parameters and
+// on the alignment of the blobs of the call (the 16-byte forms need aligned rows); null pointers
+// stand for fully aligned blobs, which is what the descriptor's kernel names assume.
+DirectForm direct_form(int pass, const DirectArgs& a, size_t elem) {
+  DirectForm f = {DF_ELEM, false};
+  const bool k3 = a.kh == 3 && a.kw == 3, k5 = a.kh == 5 && a.kw == 5;
+  const int KH = a.kh, KW = a.kw;
+  const uintptr_t in = (uintptr_t)a.in, out = (uintptr_t)a.out, w = (uintptr_t)a.w;
+  const uintptr_t m4 = 4 * elem - 1, m2 = 2 * elem - 1;
+  f.unit = a.sh == 1 && a.sw == 1 && a.dh == 1 && a.dw == 1;
+  const bool s2d1 = a.sh == 2 && a.sw == 2 && a.dh == 1 && a.dw == 1;
+  if (pass != 1 && (k3 || k5)) {
+    // stride 2 with "same" padding along rows of a multiple of four elements: x by 16-byte accesses,
+    // y (forward) or dy (filter gradient) by two-element ones
+    const uintptr_t other = pass == 0 ? out : w;
+    if (s2d1 && a.W % 4 == 0 && a.pw == (KW - 1) / 2 && 2 * a.OW == a.W && (in & m4) == 0 && (other & m2) == 0) {
+      f.kind = DF_S2;
+      return f;
+    }
+  }
+  const bool rows_ok = pass != 1 || (a.sh == 1 && a.sw == 1);  // backward data: stride 1 only
+  if (rows_ok && (k3 || k5)) {
+    // four columns per thread: unit stride and dilation, "same" padding along the row, rows of a
+    // multiple of four elements, every blob of the pass 16-byte aligned for its base type
+    const bool aligned = ((in | out | (pass == 2 ? w : 0)) & m4) == 0;
+    const bool vec = f.unit && aligned && a.W % 4 == 0 && a.pw == (KW - 1) / 2 && a.OW == a.W;
+    f.kind = vec ? DF_ROWS_VEC : DF_ROWS;
+    return f;
+  }
+  if (pass == 2) {
+    f.kind = DF_WGRAD_TAPS;
+    return f;
+  }
+  if (pass == 1 && s2d1 && (k3 || k5)) {
+    if (a.W % 4 == 0 && a.ph == (KH - 1) / 2 && a.pw == (KW - 1) / 2 && (out & m4) == 0) {
+      f.kind = DF_BWD_S2_VEC;
+      return f;
+    }
+    const unsigned long long items = (unsigned long long)a.N * (unsigned long long)a.C *
+                                     (unsigned long long)((a.H + a.ph + 1) / 2) *
+                                     (unsigned long long)((a.W + a.pw + 1) / 2);
+    if (items < (1ull << 31)) {
+      f.kind = DF_BWD_BLOCKS;
+      return f;
+    }
+  }
+  f.kind = k3 ? DF_ELEM_K3 : DF_ELEM;
+  return f;
+}
+
+void direct_form_name(int pass, const DirectArgs& a, char* buf, size_t len) {
+  const DirectForm f = direct_form(pass, a, 4);
+  static const char* kinds[] = {"elem", "elem_k3", "rows", "rows_vec", "s2", "bwd_s2_vec", "bwd_blocks", "wgrad_taps"};
+  const bool sized = f.kind != DF_ELEM && f.kind != DF_ELEM_K3 && f.kind != DF_WGRAD_TAPS;
+  if (sized)
+    snprintf(buf, len, "%s_k%d%s", kinds[f.kind], a.kh, (f.kind == DF_ROWS && f.unit) ? "_unit" : "");
+  else
+    snprintf(buf, len, "%s", kinds[f.kind]);
+}
 
 int launch_direct(int pass, const DirectArgs& a, bool f64, void* stream) {
   hipStream_t s = (hipStream_t)stream;

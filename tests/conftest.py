@@ -25,3 +25,17 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+def pytest_terminal_summary(terminalreporter):
+    """How often the small-tensor rule of parity_metric.py replaced the plain error metric, and where."""
+    try:
+        import parity_metric
+    except Exception:  # pragma: no cover
+        return
+    rec = parity_metric.FALLBACKS
+    terminalreporter.write_line(f"parity metric: term-scale denominator used {len(rec)} time(s) "
+                                f"(tensors of at most {parity_metric.SMALL_TENSOR} elements that miss the plain bar)")
+    for r in rec:
+        terminalreporter.write_line(f"  {r['tensor']} ({r['elements']} elements) plain {r['plain']:.3e} -> "
+                                    f"scaled {r['scaled']:.3e}: {r['case']}")

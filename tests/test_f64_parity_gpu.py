@@ -13,7 +13,7 @@ import paper_1810_02272_amd as conv
 from oracle import OracleParams
 from paper_1810_02272_amd import workloads
 from parity_metric import gated_error
-from test_parity_gpu import DIRECT_CASES, P, SWEEP
+from parity_cases import DIRECT_CASES, SWEEP, VARIANT_CASES, P
 
 pytestmark = pytest.mark.gpu
 TOL = 1e-12
@@ -68,15 +68,18 @@ def check_full64(pd, x, w, b, dy):
             "dw": (dw, oracle.backward_filter(op, xn, dyn))}
     if b is not None:
         refs["db"] = (db, oracle.backward_bias(op, dyn))
-    errs = {k: gated_error(op, k, g, r, TOL, xn, wn, bn, dyn) for k, (g, r) in refs.items()}
+    errs = {k: gated_error(op, k, g, r, TOL, xn, wn, bn, dyn, case=("f64", pd)) for k, (g, r) in refs.items()}
     for k, v in errs.items():
         assert np.isfinite(v) and v <= TOL, (pd, k, v)
     return errs
 
 
-@pytest.mark.parametrize("i", range(len(SWEEP) + len(DIRECT_CASES)))
+F64_SWEEP = SWEEP + DIRECT_CASES + [c[0] for c in VARIANT_CASES]
+
+
+@pytest.mark.parametrize("i", range(len(F64_SWEEP)))
 def test_f64_sweep_full_compare(i):
-    pd = (SWEEP + DIRECT_CASES)[i]
+    pd = F64_SWEEP[i]
     print("f64 case", i, pd, flush=True)
     op = OracleParams(**pd)
     x, w, b, dy = workloads.random_inputs(oracle.x_shape(op), oracle.w_shape(op), oracle.output_shape(op),

@@ -14,6 +14,7 @@ import oracle
 import paper_1810_02272_amd as conv
 from oracle import OracleParams
 from paper_1810_02272_amd import workloads
+from parity_cases import DIRECT_CASES, PATCH_CASES, SWEEP, VARIANT_CASES, P
 from parity_metric import gated_error, nerr
 
 pytestmark = pytest.mark.gpu
@@ -59,98 +60,10 @@ def check_full(pd: dict, seed: int, bias=True):
             "dw": (dw, oracle.backward_filter(op, xn, dyn))}
     if b is not None:
         refs["db"] = (db, oracle.backward_bias(op, dyn))
-    errs = {k: gated_error(op, k, g, r, TOL, xn, wn, bn, dyn) for k, (g, r) in refs.items()}
+    errs = {k: gated_error(op, k, g, r, TOL, xn, wn, bn, dyn, case=pd) for k, (g, r) in refs.items()}
     for k, v in errs.items():
         assert np.isfinite(v) and v <= TOL, (pd, k, v, conv.conv_desc_kernel_names(d))
     return errs
-
-
-def P(n, c, h, w, k, kh, kw, sh=1, sw=1, ph=0, pw=0, dh=1, dw=1, g=1, bias=1):
-    return dict(n=n, c=c, h=h, w=w, num_output=k, kernel_h=kh, kernel_w=kw, stride_h=sh, stride_w=sw, pad_h=ph,
-                pad_w=pw, dilation_h=dh, dilation_w=dw, group=g, bias_term=bias)
-
-
-# Shapes chosen to span several tiles in every dimension with ragged tails, and to hit every
-# parameter: stride (incl. non-divisible), pad (incl. >= kernel extent), dilation, group,
-# non-square everything, 1x1, full-size kernel, single channel, every tile variant.
-SWEEP = [
-    P(3, 5, 17, 19, 7, 3, 3),
-    P(2, 3, 9, 11, 4, 1, 1),
-    P(4, 6, 13, 13, 9, 13, 13),                            # kernel = input: inner product
-    P(3, 4, 23, 17, 10, 3, 5, 2, 3, 1, 2),                  # non-square stride/pad/kernel
-    P(2, 8, 15, 15, 12, 3, 3, 1, 1, 1, 1, 2, 2),            # dilation 2
-    P(2, 4, 21, 18, 6, 3, 2, 2, 1, 2, 0, 3, 2),             # stride + dilation mix
-    P(3, 6, 12, 14, 9, 3, 3, 2, 2, 1, 1, 2, 2, 3),          # groups + stride + dilation (gcd != 1)
-    P(2, 2, 6, 6, 3, 3, 3, 1, 1, 3, 4),                     # pad >= kernel extent
-    P(5, 1, 28, 28, 20, 5, 5),                              # layer 1.a at a small batch
-    P(2, 3, 51, 51, 96, 11, 11, 4, 4),                      # 5.a-like: 96 rows, stride 4
-    P(3, 16, 14, 14, 130, 5, 5, 1, 1, 2, 2, 1, 1, 2),       # 5.b-like: grouped, 65 rows per group
-    P(2, 40, 13, 13, 384, 3, 3, 1, 1, 1, 1),                # 5.c-like: three 128-row tiles
-    P(2, 96, 9, 9, 8, 3, 3, 1, 1, 1, 1, 1, 1, 2),           # 48 backward rows per group (16-wide MFMA tile)
-    P(7, 3, 32, 32, 32, 5, 5, 1, 1, 2, 2),                  # layer 4.a at a small batch
-    P(2, 4, 40, 36, 32, 8, 8, 4, 4),                        # layer 3.a-like
-    P(3, 32, 20, 20, 64, 4, 4, 2, 2),                       # layer 3.b-like
-    P(1, 1, 5, 7, 1, 2, 3, 3, 2, 0, 1),                     # tiny, stride > kernel
-    P(2, 3, 10, 10, 5, 3, 3, 3, 3, 0, 0, 1, 1, 1, 0),       # no bias, stride leaves unread rows
-    P(1, 200, 7, 7, 50, 3, 3, 1, 1, 1, 1),                  # long reduction, 50 rows (split reduction)
-    P(3, 5, 30, 27, 12, 7, 7, 2, 2, 3, 3),                  # 49 taps with padding: compare-based bounds mode
-    P(2, 16, 24, 24, 8, 6, 6, 1, 1, 2, 2),                  # 36 taps at stride 1: backward-data bitmask does not apply
-    # backward-data row space: phases no tap reaches are dropped and dx zero-filled; taps spaced
-    # dilation/stride apart when the stride divides the dilation
-    P(4, 24, 15, 14, 40, 1, 1, 2, 2),                       # 1x1 stride 2: one phase of four
-    P(3, 8, 17, 17, 12, 1, 1, 3, 3, 1, 2),                  # 1x1 stride 3 with padding: one phase of nine
-    P(2, 6, 23, 21, 10, 2, 2, 4, 4, 0, 1),                  # 2x2 stride 4: phases {0, 1} of four (table)
-    P(1, 16, 9, 9, 300, 1, 1, 2, 2),                        # zero fill together with a split reduction
-    P(2, 12, 29, 29, 16, 5, 5, 1, 1, 4, 4, 2, 2),           # 5x5 dilation 2 stride 1: five spaced slots, not nine
-    P(2, 8, 31, 30, 8, 3, 3, 2, 2, 2, 2, 4, 4),             # stride 2 dilation 4: one phase, slots two rows apart
-    P(2, 8, 26, 26, 8, 3, 2, 3, 2, 1, 1, 2, 3, 2),          # neither divides: dense slots, all phases
-    P(3, 12, 12, 14, 18, 3, 3, 2, 2, 1, 1, 2, 2, 3),        # three groups of 4 -> 6 channels on the GEMM tiles
-]
-
-# Thin groups: the direct kernels (one thread per output element; lanes = (position, tap) for the
-# filter gradient).  Depthwise and channel multipliers, every parameter, tap counts that do and do
-# not divide 64, more positions than one chunk, fewer images than splits.
-DIRECT_CASES = [
-    P(5, 24, 19, 17, 24, 3, 3, 1, 1, 1, 1, 1, 1, 24),          # depthwise 3x3
-    P(3, 16, 22, 25, 32, 3, 3, 2, 2, 1, 1, 1, 1, 16),          # channel multiplier 2, stride 2
-    P(2, 12, 15, 15, 12, 5, 5, 1, 1, 2, 2, 1, 1, 12),          # depthwise 5x5
-    P(4, 10, 18, 21, 10, 3, 2, 2, 3, 1, 0, 2, 3, 10, 0),       # stride + dilation + no bias, non-square
-    P(2, 8, 9, 9, 8, 1, 1, 1, 1, 0, 0, 1, 1, 8),               # depthwise 1x1 (a per-channel scale)
-    P(3, 6, 31, 29, 6, 7, 7, 2, 2, 3, 3, 1, 1, 6),             # depthwise 7x7: one position per wave iteration
-    P(1, 300, 6, 6, 300, 3, 3, 1, 1, 1, 1, 1, 1, 300),         # more pairs than a thousand / few images
-    P(70, 4, 8, 8, 4, 3, 3, 1, 1, 1, 1, 1, 1, 4),              # many images per split
-    P(2, 8, 12, 12, 8, 2, 2, 2, 2, 3, 3, 1, 1, 4),             # two channels per group, pad > kernel
-    P(3, 10, 21, 18, 10, 3, 3, 1, 1, 2, 2, 2, 2, 10),          # 3x3 dilation 2 at stride 1
-    P(2, 6, 14, 13, 6, 3, 3, 1, 1, 0, 0, 1, 1, 6),             # 3x3 without padding
-    P(2, 6, 10, 11, 6, 3, 3, 1, 1, 4, 3, 1, 1, 6),             # pad beyond the kernel (mirrored pad negative)
-    P(2, 14, 27, 26, 28, 5, 5, 2, 2, 2, 2, 1, 1, 14),          # 5x5 stride 2, channel multiplier 2
-    P(2, 8, 13, 13, 8, 5, 5, 1, 1, 1, 3, 1, 2, 4),             # 5x5, two channels per group, mixed dilation
-    P(3, 9, 23, 20, 9, 3, 3, 2, 2, 0, 0, 1, 1, 9),             # 3x3 stride 2 without padding (last row unread)
-    P(2, 6, 16, 19, 12, 3, 3, 2, 2, 3, 2, 1, 1, 3),            # 3x3 stride 2, pad beyond the kernel, 2 -> 4 channels
-    P(2, 5, 18, 17, 5, 5, 5, 2, 2, 1, 4, 1, 1, 5),             # 5x5 stride 2, uneven padding
-    # "same" padding along rows of a multiple of four elements: four columns per thread, 16-byte accesses
-    P(3, 7, 18, 12, 7, 3, 3, 1, 1, 1, 1, 1, 1, 7),             # 3x3, OH not a multiple of four
-    P(2, 6, 9, 8, 12, 5, 5, 1, 1, 2, 2, 1, 1, 3),              # 5x5, two channels in and four out per group
-    P(2, 5, 11, 20, 5, 3, 3, 1, 1, 0, 1, 1, 1, 5),             # no padding along the height
-    P(2, 4, 7, 4, 4, 5, 5, 1, 1, 3, 2, 1, 1, 4),               # a single four-column block per row
-    # the same at stride 2: two output columns per thread
-    P(2, 6, 18, 16, 6, 3, 3, 2, 2, 1, 1, 1, 1, 6),             # 3x3 stride 2
-    P(2, 4, 13, 12, 8, 5, 5, 2, 2, 2, 2, 1, 1, 4),             # 5x5 stride 2, channel multiplier 2, odd height
-    P(3, 4, 10, 8, 4, 3, 3, 2, 2, 0, 1, 1, 1, 4),              # no padding along the height
-    P(2, 4, 9, 20, 4, 3, 3, 2, 2, 3, 1, 1, 1, 2),              # two channels per group, tall padding
-    P(1, 3, 3, 3, 3, 3, 3, 2, 2, 40, 37, 1, 1, 3),             # padding far larger than the image
-    P(2, 16, 9, 10, 2, 3, 3, 2, 2, 1, 0, 1, 1, 2),             # eight channels in, one out per group
-]
-
-# Shapes that select the patch-staged kernel (256-column tiles of the 16-row MFMA): 48 or <= 16
-# rows, 8-aligned reduction channels, enough columns for the wide tile to win and for the grid not
-# to want a split reduction.
-PATCH_CASES = [
-    (P(20, 48, 60, 45, 16, 5, 5, 1, 1, 2, 2), "bwd_data"),             # 5x5, one image per many tiles
-    (P(400, 96, 9, 9, 16, 3, 3, 1, 1, 1, 1, 1, 1, 2), "bwd_data"),     # grouped, tiles span 4 images
-    (P(49, 8, 32, 32, 8, 3, 3, 1, 1, 1, 1), "bwd_data"),               # 16-row tile
-    (P(12, 16, 70, 61, 48, 3, 5, 1, 1, 0, 3), "fwd"),                  # forward with 48 rows, ragged pad
-]
 
 
 @pytest.mark.parametrize("i", range(len(SWEEP)))
@@ -199,14 +112,27 @@ def test_thin_groups_blobs_not_16_byte_aligned():
     assert nerr(db, oracle.backward_bias(op, dy.numpy())) <= TOL
 
 
+def selected(pd):
+    d = conv.conv_desc_create(conv.ConvParams(**pd))
+    return dict(kv.split("=", 1) for kv in conv.conv_desc_kernel_names(d).split(";"))
+
+
 @pytest.mark.parametrize("i", range(len(PATCH_CASES)))
 def test_patch_kernel_full_compare(i):
-    pd, which = PATCH_CASES[i]
+    pd, which, variant = PATCH_CASES[i]
     print("patch case", i, pd, flush=True)
-    d = conv.conv_desc_create(conv.ConvParams(**pd))
-    names = dict(kv.split("=", 1) for kv in conv.conv_desc_kernel_names(d).split(";"))
-    assert "_patch" in names[which], names
+    assert selected(pd)[which].startswith(variant), selected(pd)
     check_full(pd, seed=9000 + 10 * i)
+
+
+@pytest.mark.parametrize("i", range(len(VARIANT_CASES)))
+def test_every_tile_and_bounds_mode_full_compare(i):
+    """One shape per (pass, tile, bounds mode) that the other lists do not select (the CPU test
+    test_variant_coverage.py checks that together they select every variant)."""
+    pd, which, variant = VARIANT_CASES[i]
+    print("variant case", i, which, variant, pd, flush=True)
+    assert selected(pd)[which].startswith(variant), selected(pd)
+    check_full(pd, seed=9500 + 10 * i)
 
 
 @pytest.mark.parametrize("name", [l.name for l in workloads.LAYERS if l.config <= 3])

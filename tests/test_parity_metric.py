@@ -65,3 +65,23 @@ def test_floor_never_lowers_the_denominator():
     assert nerr(got, ref) == nerr(got, ref, floor=1.0) == 0.125   # a floor below max|ref| changes nothing
     assert nerr(got, ref, floor=8.0) == 0.0625
     assert nerr(torch.zeros(0), np.zeros(0)) == 0.0
+
+
+def test_only_small_tensors_take_the_term_scale_and_every_use_is_recorded():
+    import parity_metric
+
+    before = len(parity_metric.FALLBACKS)
+    ref = np.full(parity_metric.SMALL_TENSOR + 1, 1e-3)
+    got = torch.from_numpy(ref + 1e-6)                       # 1e-3 of the plain scale: misses 1e-4
+    scale = lambda: 1e3                                      # a term scale that would hide it
+    v = parity_metric.small_tensor_error(nerr(got, ref), ref, 1e-4, scale, "big", "y")
+    assert v > 1e-4 and len(parity_metric.FALLBACKS) == before          # too many elements: plain metric, no record
+    small = ref[:parity_metric.SMALL_TENSOR]
+    v = parity_metric.small_tensor_error(nerr(got[:len(small)], small), small, 1e-4, scale, "small", "y")
+    assert v < 1e-8 and len(parity_metric.FALLBACKS) == before + 1
+    rec = parity_metric.FALLBACKS[-1]
+    assert rec["case"] == "small" and rec["tensor"] == "y" and rec["plain"] > 1e-4 and rec["scaled"] == v
+    # a tensor that meets the plain bar is never re-normalised or recorded
+    ok = torch.from_numpy(small * (1 + 1e-6))
+    assert parity_metric.small_tensor_error(nerr(ok, small), small, 1e-4, scale, "ok", "y") == nerr(ok, small)
+    assert len(parity_metric.FALLBACKS) == before + 1

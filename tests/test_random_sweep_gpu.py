@@ -13,6 +13,8 @@ import oracle
 import paper_1810_02272_amd as conv
 from oracle import OracleParams
 from paper_1810_02272_amd import workloads
+from parity_cases import (IP_RANDOM, MANY_CHANNEL, MULTI_TILE, RANDOM_BLOCKS, THIN_BLOCKS, draw_block, random_ip_case,
+                          random_multi_tile_params, random_params, random_thin_group_params)
 from test_f64_parity_gpu import check_full64
 from test_ip_parity_gpu import run_case as run_ip_case
 from test_parity_gpu import check_full
@@ -21,29 +23,9 @@ from test_pg_parity_gpu import check_batch as check_pg_batch
 pytestmark = pytest.mark.gpu
 
 
-def random_params(rng):
-    """One random, valid parameter set with a small oracle cost."""
-    while True:
-        g = int(rng.choice([1, 1, 1, 2, 3, 4]))
-        c = g * int(rng.integers(1, 9))
-        k = g * int(rng.integers(1, 13))
-        kh, kw = int(rng.integers(1, 6)), int(rng.integers(1, 6))
-        sh, sw = int(rng.integers(1, 4)), int(rng.integers(1, 4))
-        dh, dw = int(rng.integers(1, 4)), int(rng.integers(1, 4))
-        ph, pw = int(rng.integers(0, 5)), int(rng.integers(0, 5))
-        h, w = int(rng.integers(1, 24)), int(rng.integers(1, 24))
-        n = int(rng.integers(1, 6))
-        pd = dict(n=n, c=c, h=h, w=w, num_output=k, kernel_h=kh, kernel_w=kw, stride_h=sh, stride_w=sw, pad_h=ph,
-                  pad_w=pw, dilation_h=dh, dilation_w=dw, group=g, bias_term=int(rng.integers(0, 2)))
-        if (oracle.out_size(h, kh, sh, ph, dh) >= 1 and oracle.out_size(w, kw, sw, pw, dw) >= 1):
-            return pd
-
-
 @pytest.mark.parametrize("block", range(6))
 def test_random_conv_parameters_fp32_and_fp64(block):
-    rng = np.random.default_rng(20260 + block)
-    for i in range(12):
-        pd = random_params(rng)
+    for i, pd in enumerate(draw_block(*RANDOM_BLOCKS[block])):
         print("random case", block, i, pd, flush=True)
         seed = 31000 + 100 * block + i
         check_full(pd, seed=seed, bias=bool(pd["bias_term"]))
@@ -53,32 +35,10 @@ def test_random_conv_parameters_fp32_and_fp64(block):
         check_full64(pd, x.double(), w.double(), b.double() if b is not None else None, dy.double())
 
 
-def random_thin_group_params(rng):
-    """Random depthwise-like parameter sets: many groups of one or two channels, 3x3 and 5x5 kernels
-    (the four-rows kernels) and arbitrary ones (the general direct kernels)."""
-    while True:
-        g = int(rng.integers(2, 13))
-        c, k = g * int(rng.integers(1, 3)), g * int(rng.integers(1, 4))
-        kh, kw = [(3, 3), (5, 5), (int(rng.integers(1, 8)), int(rng.integers(1, 8)))][int(rng.integers(0, 3))]
-        sh, sw = int(rng.integers(1, 4)), int(rng.integers(1, 4))
-        if rng.integers(0, 2):
-            sh = sw = 1
-        dh, dw = int(rng.integers(1, 3)), int(rng.integers(1, 3))
-        ph, pw = int(rng.integers(0, 5)), int(rng.integers(0, 5))
-        h, w = int(rng.integers(1, 30)), int(rng.integers(1, 30))
-        pd = dict(n=int(rng.integers(1, 7)), c=c, h=h, w=w, num_output=k, kernel_h=kh, kernel_w=kw, stride_h=sh,
-                  stride_w=sw, pad_h=ph, pad_w=pw, dilation_h=dh, dilation_w=dw, group=g,
-                  bias_term=int(rng.integers(0, 2)))
-        if (oracle.out_size(h, kh, sh, ph, dh) >= 1 and oracle.out_size(w, kw, sw, pw, dw) >= 1):
-            return pd
-
-
 @pytest.mark.parametrize("block", range(4))
 def test_random_thin_group_parameters_fp32_and_fp64(block):
-    rng = np.random.default_rng(50500 + block)
     direct = 0
-    for i in range(12):
-        pd = random_thin_group_params(rng)
+    for i, pd in enumerate(draw_block(*THIN_BLOCKS[block])):
         print("random thin-group case", block, i, pd, flush=True)
         direct += "direct" in conv.conv_desc_kernel_names(conv.conv_desc_create(conv.ConvParams(**pd)))
         seed = 52000 + 100 * block + i
@@ -90,24 +50,6 @@ def test_random_thin_group_parameters_fp32_and_fp64(block):
     assert direct >= 6, direct  # most of these shapes take the direct kernels
 
 
-def random_multi_tile_params(rng):
-    """Random parameter sets large enough for several tiles per dimension (up to 4e8 FLOPs per pass)."""
-    while True:
-        g = int(rng.choice([1, 1, 2, 4, 8]))
-        c, k = g * int(rng.integers(1, 12)), g * int(rng.integers(1, 40))
-        kh, kw = int(rng.integers(1, 8)), int(rng.integers(1, 8))
-        sh, sw = int(rng.integers(1, 5)), int(rng.integers(1, 5))
-        dh, dw = int(rng.integers(1, 3)), int(rng.integers(1, 3))
-        ph, pw = int(rng.integers(0, 7)), int(rng.integers(0, 7))
-        h, w = int(rng.integers(1, 50)), int(rng.integers(1, 50))
-        n = int(rng.integers(1, 9))
-        pd = dict(n=n, c=c, h=h, w=w, num_output=k, kernel_h=kh, kernel_w=kw, stride_h=sh, stride_w=sw, pad_h=ph,
-                  pad_w=pw, dilation_h=dh, dilation_w=dw, group=g, bias_term=int(rng.integers(0, 2)))
-        oh, ow = oracle.out_size(h, kh, sh, ph, dh), oracle.out_size(w, kw, sw, pw, dw)
-        if oh >= 1 and ow >= 1 and 2.0 * n * k * (c // g) * kh * kw * oh * ow < 4e8:
-            return pd
-
-
 def check_both_types(pd, seed):
     check_full(pd, seed=seed, bias=bool(pd["bias_term"]))
     op = OracleParams(**pd)
@@ -117,9 +59,7 @@ def check_both_types(pd, seed):
 
 
 def test_random_multi_tile_parameters_fp32_and_fp64():
-    rng = np.random.default_rng(60600)
-    for i in range(40):
-        pd = random_multi_tile_params(rng)
+    for i, pd in enumerate(draw_block(*MULTI_TILE)):
         print("random multi-tile case", i, pd, flush=True)
         check_both_types(pd, 61000 + i)
 
@@ -127,24 +67,8 @@ def test_random_multi_tile_parameters_fp32_and_fp64():
 def test_random_many_channel_parameters_reach_the_square_filter_gradient_tile():
     """Random layers with about 128 or 256 output channels per group and a reduced dimension of 100-500: the 128x128
     backward-filter tile (loads that write LDS directly) with ragged rows and columns, every bounds mode."""
-    rng = np.random.default_rng(70700)
     square = 0
-    for i in range(16):
-        while True:
-            g = int(rng.choice([1, 1, 2]))
-            # rows and reduced dimension a little below a multiple of 128: the tile that pads least
-            k = g * (128 * int(rng.integers(1, 3)) - int(rng.integers(0, 20)))
-            kh, kw = int(rng.integers(1, 6)), int(rng.integers(1, 6))
-            c = g * max(1, (128 * int(rng.integers(1, 5)) - int(rng.integers(0, 12))) // (kh * kw))
-            sh, sw = int(rng.integers(1, 3)), int(rng.integers(1, 3))
-            ph, pw = int(rng.integers(0, 3)), int(rng.integers(0, 3))
-            dh = dw = int(rng.choice([1, 1, 2]))
-            h, w = int(rng.integers(4, 16)), int(rng.integers(4, 16))
-            pd = dict(n=int(rng.integers(1, 5)), c=c, h=h, w=w, num_output=k, kernel_h=kh, kernel_w=kw, stride_h=sh,
-                      stride_w=sw, pad_h=ph, pad_w=pw, dilation_h=dh, dilation_w=dw, group=g,
-                      bias_term=int(rng.integers(0, 2)))
-            if oracle.out_size(h, kh, sh, ph, dh) >= 1 and oracle.out_size(w, kw, sw, pw, dw) >= 1:
-                break
+    for i, pd in enumerate(draw_block(*MANY_CHANNEL)):
         names = conv.conv_desc_kernel_names(conv.conv_desc_create(conv.ConvParams(**pd)))
         print("random many-channel case", i, pd, names, flush=True)
         square += "wgrad_m32_128x128x32" in names
@@ -224,10 +148,9 @@ def test_extended_random_policy_gradient_sweep(capsys):
 
 
 def test_random_inner_product_shapes():
-    rng = np.random.default_rng(777)
-    for i in range(16):
-        m, k, o = int(rng.integers(1, 200)), int(rng.integers(1, 700)), int(rng.integers(1, 300))
-        relu, bias = int(rng.integers(0, 2)), bool(rng.integers(0, 2))
+    rng = np.random.default_rng(IP_RANDOM[0])
+    for i in range(IP_RANDOM[1]):
+        m, k, o, relu, bias = random_ip_case(rng)
         x, w, b, dy = workloads.ip_random_inputs(m, k, o, seed=41000 + i, bias=bias)
         run_ip_case(m, k, o, bias, relu, x, w, b, dy, beta=float(rng.integers(0, 2)),
                     dw0=workloads.draw((o, k), "normal", 42000 + i), db0=workloads.draw((o,), "normal", 43000 + i))

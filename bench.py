@@ -68,6 +68,7 @@ def main():
 
     import torch
 
+    import bench_probe
     import paper_1810_02272_amd as conv
     from paper_1810_02272_amd import workloads
 
@@ -208,21 +209,7 @@ def main():
     # What the matrix pipes deliver with nothing else in the way: a register-only loop of matrix
     # instructions on every SIMD (two waves each), with the core clock the chip sustains under it.
     # Context for the published peak that `roofline.peak` uses.
-    wgs, iters = 512, 4096
-    ticks = torch.zeros(8 * wgs, dtype=torch.int64, device=dev)
-    khz = conv.conv_mfma_probe(wgs, iters, ticks, f64=f64)
-    me0, me1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    me0.record(stream)
-    for _ in range(3):
-        conv.conv_mfma_probe(wgs, iters, ticks, f64=f64)
-    me1.record(stream)
-    torch.cuda.synchronize()
-    tk = ticks.cpu().double().reshape(-1, 2)
-    mfma_loop = {"tflops": round(3 * wgs * 4 * iters * 4 * (2048 if f64 else 4096)
-                                 / (me0.elapsed_time(me1) * 1e-3) / 1e12, 1),
-                 "core_clock_ghz": round(float((tk[:, 0] / tk[:, 1]).median()) * khz * 1e-6, 3),
-                 "what": "register-only loop of %s matrix instructions, two waves per SIMD, no memory traffic"
-                         % ("16x16x4 fp64" if f64 else "32x32x2 fp32")}
+    mfma_loop = bench_probe.register_loop_rate(f64=f64)
 
     for _ in range(args.warmup):
         step()

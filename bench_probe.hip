@@ -1,14 +1,21 @@
-// Measurement helper (not on the layer path): a register-only loop of fp32 matrix instructions.
-// No memory traffic inside the loop, so the rate it reaches is what the matrix pipes deliver at
-// the clock the chip sustains under that load -- the practical ceiling the GEMM kernels are
-// compared with beside the published peak.
+// Benchmark helper, built into a small library of its own (libbench_probe.so) that only bench.py
+// loads; the layer library does not contain it.  A register-only loop of matrix instructions: no
+// memory traffic inside the loop, so the rate it reaches is what the matrix pipes deliver at the
+// clock the chip sustains under that load -- the practical ceiling the GEMM kernels are compared
+// with beside the published peak.
+//
+//   int bench_mfma_probe(int f64, int32_t workgroups, int32_t iters, uint64_t* out, int32_t* timer_khz,
+//                        void* hip_stream)
+// `workgroups` workgroups of four waves each run `iters` rounds of four independent matrix
+// instructions (32x32x2 fp32, or 16x16x4 fp64 when f64 != 0) on registers only.  Wave v of workgroup
+// b writes two counts to out[2*(4*b + v)] and out[2*(4*b + v) + 1]: the core-clock ticks and the
+// ticks of the device's constant-rate timer that its loop took.  `out` is device memory of
+// 8*workgroups uint64, caller-owned; `timer_khz` (host pointer, may be NULL) receives the rate of
+// that timer.  FLOPs of one launch = workgroups * 4 * iters * 4 * (4096 fp32 | 2048 fp64).
+// Enqueued on hip_stream without synchronising.  Returns 0, -1 for a null `out`, workgroups outside
+// [1, 65536] or iters outside [1, 2^20], or a positive hipError_t.
 #include <hip/hip_runtime.h>
-
-#include "device_utils.h"
-#include "internal.h"
-#include "mi355conv.h"
-
-namespace mi355conv {
+#include <stdint.h>
 
 namespace {
 
@@ -59,32 +66,21 @@ __global__ __launch_bounds__(256) void mfma_probe64_kernel(int iters, uint64_t* 
   }
 }
 
-int run_probe(bool f64, int32_t workgroups, int32_t iters, uint64_t* out, int32_t* timer_khz, void* hip_stream) {
-  if (!out || workgroups < 1 || workgroups > 65536 || iters < 1 || iters > (1 << 20)) return CONV_EINVAL;
+}  // namespace
+
+extern "C" int bench_mfma_probe(int f64, int32_t workgroups, int32_t iters, uint64_t* out, int32_t* timer_khz,
+                                void* hip_stream) {
+  if (!out || workgroups < 1 || workgroups > 65536 || iters < 1 || iters > (1 << 20)) return -1;
   if (timer_khz) {
     int dev = 0, khz = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e == hipSuccess) e = hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev);
-    if (e != hipSuccess) return record_hip_error((int)e);
+    if (e != hipSuccess) return (int)e;
     *timer_khz = khz;
   }
   if (f64)
     hipLaunchKernelGGL(mfma_probe64_kernel, dim3((unsigned)workgroups), dim3(256), 0, (hipStream_t)hip_stream, iters, out);
   else
     hipLaunchKernelGGL(mfma_probe_kernel, dim3((unsigned)workgroups), dim3(256), 0, (hipStream_t)hip_stream, iters, out);
-  const int e = (int)hipGetLastError();
-  return e ? record_hip_error(e) : CONV_OK;
-}
-
-}  // namespace
-
-}  // namespace mi355conv
-
-extern "C" int conv_mfma_probe(int32_t workgroups, int32_t iters, uint64_t* out, int32_t* timer_khz, void* hip_stream) {
-  return mi355conv::run_probe(false, workgroups, iters, out, timer_khz, hip_stream);
-}
-
-extern "C" int conv_mfma_probe_f64(int32_t workgroups, int32_t iters, uint64_t* out, int32_t* timer_khz,
-                                   void* hip_stream) {
-  return mi355conv::run_probe(true, workgroups, iters, out, timer_khz, hip_stream);
+  return (int)hipGetLastError();
 }

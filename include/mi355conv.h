@@ -34,10 +34,18 @@
  * Execution: every pass is enqueued on the caller's HIP stream (`hip_stream` is a
  * hipStream_t passed as void*; NULL = the default stream) and returns without
  * synchronising.  Passes that use the workspace must not run concurrently on different
- * streams with the same workspace.
+ * streams with the same workspace.  A pass is one to three kernel launches (helper kernels
+ * pack the weights, clear or add partial results around the main kernel).  The first call
+ * of a pass in a process may also perform a one-time, thread-safe kernel attribute set-up
+ * (the opt-in to more than 64 KB of LDS), which is a host-side runtime call and not an
+ * enqueue: make that first call outside HIP stream capture; every later call only enqueues
+ * kernels and can be captured into a HIP graph.
  *
  * Errors: every function returns a conv_status_t (0 = success, negative = error); no
- * exception, abort or printing crosses this boundary.  On error nothing is enqueued.
+ * exception, abort or printing crosses this boundary.  Argument, shape and workspace
+ * errors are detected before anything is enqueued.  CONV_EHIP means the HIP runtime
+ * refused a launch: helper kernels of the same pass launched before it stay enqueued
+ * and the output buffer's contents are then unspecified.
  */
 #ifndef MI355CONV_H
 #define MI355CONV_H
@@ -123,21 +131,6 @@ const char* conv_status_string(int status);
 int conv_last_hip_error(void);
 /* Names of the kernel variants the descriptor selected, for logs and profiles ("fwd=...;bwd_data=...;..."). */
 const char* conv_desc_kernel_names(const conv_desc_t* d);
-
-/*
- * Measurement helper, not part of the layer path (the benchmark uses it to put the published fp32
- * matrix peak beside what the chip sustains): `workgroups` workgroups of four waves each run
- * `iters` rounds of four independent 32x32x2 fp32 matrix instructions on registers only, no memory
- * traffic.  Wave v of workgroup b writes two counts to out[2*(4*b + v)] and out[2*(4*b + v) + 1]:
- * the core-clock ticks and the ticks of the device's constant-rate timer that its loop took.  `out`
- * is device memory of 8*workgroups uint64, caller-owned.  `timer_khz` (host pointer, may be NULL)
- * receives the rate of that timer.  FLOPs of one launch = workgroups * 4 * iters * 4 * 4096.
- * Enqueued on hip_stream without synchronising.  CONV_EINVAL for a null `out`, workgroups outside
- * [1, 65536] or iters outside [1, 2^20].
- */
-int conv_mfma_probe(int32_t workgroups, int32_t iters, uint64_t* out, int32_t* timer_khz, void* hip_stream);
-/* The same loop on 16x16x4 fp64 matrix instructions: FLOPs of one launch = workgroups * 4 * iters * 4 * 2048. */
-int conv_mfma_probe_f64(int32_t workgroups, int32_t iters, uint64_t* out, int32_t* timer_khz, void* hip_stream);
 
 #ifdef __cplusplus
 }

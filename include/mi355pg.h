@@ -33,7 +33,9 @@
  * (void*, NULL = default stream) without synchronising.  Returns a conv_status_t: CONV_EINVAL
  * for null pointers / negative sizes / actions < 1, CONV_ESHAPE when steps (or episodes) exceed
  * 2^31 - 65536 or steps * actions >= 2^31.
- * steps == 0 (or episodes == 0) is a no-op.
+ * steps == 0 (or episodes == 0) is a no-op.  The first pg_softmax_bottom_diff call of a process
+ * with exactly 32 actions performs a one-time, thread-safe kernel attribute set-up (66 KB of LDS)
+ * and must be made outside HIP stream capture; every other call only enqueues kernels.
  */
 #ifndef MI355PG_H
 #define MI355PG_H

@@ -23,7 +23,6 @@ from .binding import (  # noqa: F401
     conv_desc_output_shape,
     conv_desc_workspace_bytes,
     conv_forward,
-    conv_mfma_probe,
     conv_status_string,
     library_path,
 )

@@ -83,10 +83,6 @@ def _load():
     lib.conv_last_hip_error.restype = ctypes.c_int
     lib.conv_desc_kernel_names.restype = ctypes.c_char_p
     lib.conv_desc_kernel_names.argtypes = [vp]
-    lib.conv_mfma_probe.argtypes = [ctypes.c_int32, ctypes.c_int32, vp, i32p, vp]
-    lib.conv_mfma_probe.restype = ctypes.c_int
-    lib.conv_mfma_probe_f64.argtypes = [ctypes.c_int32, ctypes.c_int32, vp, i32p, vp]
-    lib.conv_mfma_probe_f64.restype = ctypes.c_int
     for name in ("conv_desc_create", "conv_desc_destroy", "conv_desc_output_shape", "conv_desc_workspace_bytes",
                  "conv_forward", "conv_backward_data", "conv_backward_filter", "conv_backward_bias",
                  "conv_desc_workspace_bytes_f64", "conv_forward_f64", "conv_backward_data_f64",
@@ -263,16 +259,3 @@ def conv_backward_bias_f64(desc, dy, db, beta=0.0, ws=None, stream=None) -> None
     _check(_load().conv_backward_bias_f64(desc.handle, _ptr(dy, conv_desc_output_shape(desc), "dy", _F64),
                                           _ptr(db, (p.num_output,), "db", _F64), float(beta), wp, wb,
                                           _stream(stream)), "conv_backward_bias_f64")
-
-
-def conv_mfma_probe(workgroups: int, iters: int, out, stream=None, f64: bool = False) -> int:
-    """Enqueue the register-only matrix-instruction loop (fp32, or fp64 with f64=True: conv_mfma_probe_f64);
-    `out` is an int64 device tensor of 8*workgroups elements (per wave: core-clock ticks, constant-timer
-    ticks).  Returns the rate of the constant timer in kHz."""
-    if not (isinstance(out, torch.Tensor) and out.is_cuda and out.dtype == torch.int64 and out.is_contiguous()
-            and out.numel() == 8 * int(workgroups)):
-        raise ConvError(CONV_EINVAL, "conv_mfma_probe: out must be a contiguous int64 device tensor of 8*workgroups")
-    khz = ctypes.c_int32(0)
-    fn = _load().conv_mfma_probe_f64 if f64 else _load().conv_mfma_probe
-    _check(fn(int(workgroups), int(iters), out.data_ptr(), ctypes.byref(khz), _stream(stream)), "conv_mfma_probe")
-    return int(khz.value)

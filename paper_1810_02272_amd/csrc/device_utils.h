@@ -4,6 +4,8 @@
 
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "internal.h"
 
 namespace mi355conv {
@@ -55,6 +57,23 @@ __device__ __forceinline__ uint32_t xcd_contiguous_block_id() {
 // Load with an unsigned 32-bit byte offset from a uniform base (one address register per lane).
 __device__ __forceinline__ float ld_f32(const float* base, uint32_t byte_off) {
   return *reinterpret_cast<const float*>(reinterpret_cast<const char*>(base) + byte_off);
+}
+
+// One-time opt-in of a kernel to more than 64 KB of dynamic LDS.  The first launch of a kernel
+// instance performs it (a host-side attribute call, not an enqueue -- so that first launch must not
+// happen inside a stream capture); std::call_once makes it safe for threads that share a descriptor.
+struct LdsOptIn {
+  std::once_flag once;
+  int err = 0;
+};
+
+template <typename Kernel>
+inline int lds_opt_in(LdsOptIn& state, Kernel kernel, int bytes) {
+  std::call_once(state.once, [&] {
+    state.err = (int)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  });
+  return state.err;
 }
 
 }  // namespace mi355conv

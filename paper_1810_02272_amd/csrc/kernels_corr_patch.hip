@@ -264,13 +264,8 @@ template <int MT, int MB, int NB, int WM, int WN>
 int launch_patch_t(const CorrArgs& a, hipStream_t s) {
   using C = PatchCfg<MT, MB, NB, WM, WN>;
   const size_t lds = (size_t)(2 * C::ASTAGE + 16 * a.PSZ) * 4;
-  static size_t configured = 0;
-  if (lds > configured) {  // more than 64 KB of LDS needs an explicit opt-in
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&corr_patch_kernel<MT, MB, NB, WM, WN>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)(160 * 1024));
-    if (e != hipSuccess) return (int)e;
-    configured = 160 * 1024;
-  }
+  static LdsOptIn opt_in;  // more than 64 KB of LDS needs an explicit opt-in, once per process
+  if (const int e = lds_opt_in(opt_in, &corr_patch_kernel<MT, MB, NB, WM, WN>, 160 * 1024)) return e;
   const uint32_t blocks = (uint32_t)a.G * a.m_tiles * a.col_tiles;
   hipLaunchKernelGGL((corr_patch_kernel<MT, MB, NB, WM, WN>), dim3(blocks), dim3(kThreads), lds, s, a);
   return (int)hipGetLastError();

@@ -414,9 +414,9 @@ int pg_softmax_bottom_diff(const float* logits, const int32_t* action, const flo
   if (!logits || !action || !bottom_diff) return CONV_EINVAL;
   if (actions <= 32) {
     const size_t lds = (size_t)2 * 256 * (actions | 1) * sizeof(float);  // at most 66 KB
+    static LdsOptIn opt_in;  // 32 actions need 66 KB: opt in to the largest size, once per process
     if (lds > 64 * 1024) {
-      const int e = (int)hipFuncSetAttribute(reinterpret_cast<const void*>(pg_softmax_rows_kernel),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      const int e = lds_opt_in(opt_in, pg_softmax_rows_kernel, 2 * 256 * 33 * (int)sizeof(float));
       if (e) return record_hip_error(e);
     }
     const bool vec_ok = (((uintptr_t)logits | (uintptr_t)probs | (uintptr_t)bottom_diff) & 15u) == 0;

@@ -327,13 +327,8 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradArgs a) {
 template <int MB, int NB, int WM, int WN, int MODE, bool DMA>
 int launch_wgrad_m(const WgradArgs& a, hipStream_t s) {
   using C = WgCfg<MB, NB, WM, WN, DMA>;
-  static bool configured = false;
-  if (!configured) {  // more than 64 KB of LDS needs an explicit opt-in, once per process
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&wgrad_kernel<MB, NB, WM, WN, MODE, DMA>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM_BYTES);
-    if (e != hipSuccess) return (int)e;
-    configured = true;
-  }
+  static LdsOptIn opt_in;  // more than 64 KB of LDS needs an explicit opt-in, once per process
+  if (const int e = lds_opt_in(opt_in, &wgrad_kernel<MB, NB, WM, WN, MODE, DMA>, C::SMEM_BYTES)) return e;
   const uint32_t blocks = (uint32_t)a.G * a.S * a.m_tiles * a.n_tiles;
   hipLaunchKernelGGL((wgrad_kernel<MB, NB, WM, WN, MODE, DMA>), dim3(blocks), dim3(kThreads), C::SMEM_BYTES, s, a);
   return (int)hipGetLastError();

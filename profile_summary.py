@@ -1,8 +1,8 @@
 """Turns rocprofv3 CSV output of a ``bench.py`` run into the short text summaries kept under profiles/.
 
-    python -m paper_1810_02272_amd.profile_summary trace  <dir with *_kernel_trace.csv>  > profiles/<name>.txt
-    python -m paper_1810_02272_amd.profile_summary traffic <fetch dir> <write dir> [--workload config4|f64|ip5|dw|pg]
-    python -m paper_1810_02272_amd.profile_summary sq <dir with *_counter_collection.csv of an SQ_* --pmc run>
+    python profile_summary.py trace  <dir with *_kernel_trace.csv>  > profiles/<name>.txt
+    python profile_summary.py traffic <fetch dir> <write dir> [--workload config4|f64|ip5|dw|pg]
+    python profile_summary.py sq <dir with *_counter_collection.csv of an SQ_* --pmc run>
 
 ``trace`` prints calls / average / min / max duration per (kernel, grid).  ``traffic`` reads two
 ``--pmc`` runs (FETCH_SIZE, then WRITE_SIZE, both KiB per dispatch) of

@@ -113,16 +113,19 @@ def test_null_arguments_and_status_strings():
     assert conv.conv_status_string(0) == "success"
 
 
-def test_mfma_probe_checks_arguments():
-    lib = binding._load()
-    assert lib.conv_mfma_probe(4, 10, None, None, None) == binding.CONV_EINVAL
-    assert lib.conv_mfma_probe_f64(4, 10, None, None, None) == binding.CONV_EINVAL
-    assert lib.conv_mfma_probe_f64(0, 10, 16, None, None) == binding.CONV_EINVAL
+def test_bench_probe_library_checks_arguments_and_the_layer_library_has_no_probe():
+    """The register-loop probe is a benchmark helper in a library of its own (bench_probe.hip beside
+    bench.py); the layer library exports no such symbol."""
+    import bench_probe
+    lib = bench_probe.load()
+    assert lib.bench_mfma_probe(0, 4, 10, None, None, None) == -1
     for wg, it in ((0, 10), (65537, 10), (4, 0), (4, (1 << 20) + 1)):
-        assert lib.conv_mfma_probe(wg, it, 16, None, None) == binding.CONV_EINVAL
+        assert lib.bench_mfma_probe(0, wg, it, 16, None, None) == -1
+        assert lib.bench_mfma_probe(1, wg, it, 16, None, None) == -1
     import torch
-    with pytest.raises(conv.ConvError):
-        conv.conv_mfma_probe(4, 10, torch.zeros(32, dtype=torch.int64))
+    with pytest.raises(ValueError):
+        bench_probe.mfma_probe(4, 10, torch.zeros(32, dtype=torch.int64))
+    assert not hasattr(ctypes.CDLL(conv.library_path()), "conv_mfma_probe")
 
 
 def test_binding_refuses_cpu_tensors():

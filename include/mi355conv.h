@@ -103,6 +103,25 @@ int conv_backward_data(const conv_desc_t* d, const float* w, const float* dy, fl
 int conv_backward_filter(const conv_desc_t* d, const float* x, const float* dy, float* dw, float beta,
                          void* ws, size_t ws_bytes, void* hip_stream);
 
+/*
+ * conv_backward_filter for callers that cannot allocate or pass device memory for a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * semantics, layouts and result (bit for bit) as conv_backward_filter, without `ws`: the split
+ * partials go to a fixed 32 MiB device array that belongs to the library (every GPU the library
+ * runs on holds its own copy until the process ends).  The call allocates and frees nothing.
+ * CONV_EWORKSPACE when the layer's filter-gradient workspace exceeds conv_static_workspace_limit()
+ * (conv_desc_create sizes the partials to at most 32 MiB, so only a weight blob larger than that
+ * is refused); use conv_backward_filter with a workspace of your own then.  All calls on one GPU share
+ * that GPU's array: calls that may overlap on one GPU (different streams or threads) race on it and
+ * must be ordered by the caller; calls on one stream are ordered by the stream.  The array keeps the
+ * last call's contents and nothing in it needs clearing between calls.  The first call on a device
+ * looks up the array's address (a host-side runtime call, thread-safe): make it outside stream capture.
+ */
+int conv_backward_filter_static(const conv_desc_t* d, const float* x, const float* dy, float* dw, float beta,
+                                void* hip_stream);
+/* Size in bytes of the fixed array behind conv_backward_filter_static. */
+size_t conv_static_workspace_limit(void);
+
 /* db = beta*db + sum of dy over n, oh, ow; CONV_EINVAL on a bias_term == 0 descriptor. */
 int conv_backward_bias(const conv_desc_t* d, const float* dy, float* db, float beta,
                        void* ws, size_t ws_bytes, void* hip_stream);

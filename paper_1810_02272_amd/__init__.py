@@ -17,6 +17,8 @@ from .binding import (  # noqa: F401
     conv_forward_f64,
     conv_backward_data,
     conv_backward_filter,
+    conv_backward_filter_static,
+    conv_static_workspace_limit,
     conv_desc_create,
     conv_desc_destroy,
     conv_desc_kernel_names,

@@ -70,6 +70,10 @@ def _load():
     lib.conv_backward_data.argtypes = [vp, vp, vp, vp, vp, sz, vp]
     lib.conv_backward_filter.argtypes = [vp, vp, vp, vp, fp, vp, sz, vp]
     lib.conv_backward_bias.argtypes = [vp, vp, vp, fp, vp, sz, vp]
+    lib.conv_backward_filter_static.argtypes = [vp, vp, vp, vp, fp, vp]
+    lib.conv_backward_filter_static.restype = ctypes.c_int
+    lib.conv_static_workspace_limit.argtypes = []
+    lib.conv_static_workspace_limit.restype = sz
     dbl = ctypes.c_double
     lib.conv_desc_workspace_bytes_f64.argtypes = [vp, ctypes.POINTER(sz)]
     lib.conv_forward_f64.argtypes = [vp, vp, vp, vp, vp, vp, sz, vp]
@@ -202,6 +206,20 @@ def conv_backward_filter(desc, x, dy, dw, beta=0.0, ws=None, stream=None) -> Non
     _check(_load().conv_backward_filter(desc.handle, _ptr(x, _x_shape(p), "x"),
                                         _ptr(dy, conv_desc_output_shape(desc), "dy"), _ptr(dw, _w_shape(p), "dw"),
                                         float(beta), wp, wb, _stream(stream)), "conv_backward_filter")
+
+
+def conv_backward_filter_static(desc, x, dy, dw, beta=0.0, stream=None) -> None:
+    """conv_backward_filter without a workspace argument: the library's own fixed device array holds the
+    split partials; nothing is allocated."""
+    p = desc.params
+    _check(_load().conv_backward_filter_static(desc.handle, _ptr(x, _x_shape(p), "x"),
+                                               _ptr(dy, conv_desc_output_shape(desc), "dy"),
+                                               _ptr(dw, _w_shape(p), "dw"), float(beta), _stream(stream)),
+           "conv_backward_filter_static")
+
+
+def conv_static_workspace_limit() -> int:
+    return int(_load().conv_static_workspace_limit())
 
 
 def conv_backward_bias(desc, dy, db, beta=0.0, ws=None, stream=None) -> None:

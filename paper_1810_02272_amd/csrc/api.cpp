@@ -264,6 +264,12 @@ int record_hip_error(int e) {
   return CONV_EHIP;
 }
 
+int conv_desc_backward_filter_workspace_bytes(const conv_desc* d, size_t* bytes) {
+  if (!d || !bytes) return CONV_EINVAL;
+  *bytes = d->wg_ws;
+  return CONV_OK;
+}
+
 int run_forward(const conv_desc* d, const float* x, const float* w, const float* bias, float* y, void* ws,
                 size_t ws_bytes, void* hip_stream) {
   if (!d || !w) return CONV_EINVAL;

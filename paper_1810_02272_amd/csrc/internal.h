@@ -295,6 +295,8 @@ int run_backward_data(const conv_desc* d, const float* w, const float* dy, float
 int run_backward_filter(const conv_desc* d, const float* x, const float* dy, float* dw, float beta, void* ws,
                         size_t ws_bytes, void* stream, const ReduceExtras& extras);
 int record_hip_error(int e);  // remembers e for conv_last_hip_error and returns CONV_EHIP
+// workspace bytes conv_backward_filter needs for this descriptor (at most its conv_desc_workspace_bytes)
+int conv_desc_backward_filter_workspace_bytes(const conv_desc* d, size_t* bytes);
 
 }  // namespace mi355conv
 

@@ -128,6 +128,19 @@ def test_bench_probe_library_checks_arguments_and_the_layer_library_has_no_probe
     assert not hasattr(ctypes.CDLL(conv.library_path()), "conv_mfma_probe")
 
 
+def test_static_workspace_refuses_layers_beyond_its_limit_and_bad_arguments():
+    """conv_backward_filter_static: argument and size errors are found before any runtime call."""
+    lib = binding._load()
+    # a weight blob of 36 MiB: even one slice of partials exceeds the 32 MiB array
+    d = conv.conv_desc_create(conv.ConvParams(**dict(n=1, c=1024, h=8, w=8, num_output=1024, kernel_h=3, kernel_w=3, pad_h=1, pad_w=1)))
+    assert lib.conv_backward_filter_static(d.handle, 16, 16, 16, ctypes.c_float(0.0), None) == binding.CONV_EWORKSPACE
+    ok = conv.conv_desc_create(conv.ConvParams(**dict(n=1, c=2, h=5, w=5, num_output=2, kernel_h=3, kernel_w=3)))
+    assert lib.conv_backward_filter_static(None, 16, 16, 16, ctypes.c_float(0.0), None) == binding.CONV_EINVAL
+    assert lib.conv_backward_filter_static(ok.handle, 16, 16, None, ctypes.c_float(0.0), None) == binding.CONV_EINVAL
+    assert lib.conv_backward_filter_static(ok.handle, 16, 16, 16, ctypes.c_float(0.5), None) == binding.CONV_EINVAL
+    assert lib.conv_backward_filter_static(ok.handle, None, 16, 16, ctypes.c_float(0.0), None) == binding.CONV_EINVAL
+
+
 def test_binding_refuses_cpu_tensors():
     import torch
     p = conv.ConvParams(1, 1, 4, 4, 1, 3, 3)

@@ -35,7 +35,8 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="config4", help="config0..config4, dw (depthwise layers), ip5, ip1, pg, or a comma list of layer names (all conv or all ip)")
+    ap.add_argument("--workload", default="config4", help="config0..config4, small (the eight layers of configs 0-3), dw (depthwise layers), ip5, ip1, pg, or a "
+                                                    "comma list of layer names (all conv or all ip)")
     ap.add_argument("--dtype", default="f32", choices=["f32", "f64"],
                     help="base type of the convolution workloads (f64: the conv_*_f64 entry points)")
     ap.add_argument("--no-cpu-baseline", action="store_true",
@@ -97,6 +98,8 @@ def main():
     if args.workload.startswith("config"):
         cfg = int(args.workload[len("config"):])
         layers = [l for l in workloads.LAYERS if l.config == cfg]
+    elif args.workload == "small":  # the eight layer shapes of configurations 0-3
+        layers = [l for l in workloads.LAYERS if l.config <= 3]
     elif args.workload == "dw":
         layers = list(workloads.DW_LAYERS)
     elif args.workload in ("ip5", "ip1"):
@@ -321,10 +324,18 @@ def main():
         row = {"layer": l.name, "gflop_per_pass": l.flop_per_pass / 1e9,
                "kernels": kernel_names_of(t["desc"])}
         tot = 0.0
+        launches = launches_of(row["kernels"])
         for name in passes:
             ms = sum(acc[(l.name, name)]) / len(acc[(l.name, name)])
             row[name + "_ms"] = round(ms, 5)
             tot += ms
+            if name in launches:
+                # kernel launches of the pass, and what is left of its time after that many empty
+                # dispatches (the floor of a launch-bound pass on this machine)
+                row[name + "_launches"] = launches[name]
+                row[name + "_us_over_launch_floor"] = round(ms * 1e3 - launches[name] * launch_us, 2)
+            if not is_ip and name in flop_passes:  # every blob of the pass moved once, against 8 TB/s
+                row[name + "_alg_GBps"] = round(blob_bytes(l, name) * (2 if f64 else 1) / ms / 1e6, 1)
             if name in flop_passes:
                 row[name + "_tflops"] = round(l.flop_per_pass / ms / 1e9, 2)
             elif name == "bwd_bias":  # one read of dy: the HBM-bound pass
@@ -339,6 +350,11 @@ def main():
                 2 * l.flop_per_pass / (tot - row["bwd_data_ms"]) / 1e9, 2)
         row["fwd_bwd_frac_of_%s_mfma_peak" % ("fp64" if f64 else "fp32")] = round(
             3 * l.flop_per_pass / tot / 1e9 / peak, 4)
+        if not is_ip:
+            alg = sum(blob_bytes(l, name) for name in flop_passes) + dy_bytes(l)
+            row["fwd_bwd_frac_of_hbm_peak"] = round(alg * (2 if f64 else 1) / tot / 1e6 / PEAK_HBM_GBS, 4)
+            row["fwd_bwd_us"] = round(tot * 1e3, 2)
+            row["launches"] = sum(launches.values())
         per_layer.append(row)
 
     # dominant launch: the (layer, pass) with the largest average duration
@@ -368,6 +384,8 @@ def main():
         try:
             tr = json.load(open(traffic_file))
             roofline["traffic"] = tr.get(("f64/" if f64 else "") + f"{dl}:{dp}")
+            # not measured in this run: the figure of the committed rocprofv3 --pmc summary
+            roofline["traffic_from"] = "profiles/hbm_traffic.json"
         except Exception:
             pass
 
@@ -394,6 +412,11 @@ def main():
         "per_layer": per_layer,
     }
 
+    if args.workload == "config4" and not f64 and not args.cold_cache:
+        # The eight layer shapes of configurations 0-3, from steps of their own outside the timed region:
+        # they are launch-latency bound (microseconds of work per pass), so each pass is given with its
+        # launch count and its time over that many empty dispatches, next to both roofline fractions.
+        out["per_layer_small"] = small_layers(torch, conv, workloads, dev, launch_us)
     if not is_ip and not args.no_cpu_baseline:
         # context only (never `value`): the same steps with the filter and bias gradients on a second stream
         two = time_two_streams(args.steps, 3)
@@ -404,6 +427,107 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline_ip(layers) if is_ip else cpu_baseline(layers, args.cpu_sample_images)
     print(json.dumps(out))
+
+
+def launches_of(names):
+    """pass -> kernel launches, from the (S=..,L=..) suffix of a descriptor's kernel names."""
+    import re
+    out = {}
+    for kv in names.split(";"):
+        k, v = kv.split("=", 1)
+        m = re.search(r",L=(\d+)\)$", v)
+        if m:
+            out[k] = int(m.group(1))
+    return out
+
+
+def small_layers(torch, conv, workloads, dev, launch_us, steps=20, warmup=5):
+    """Per-pass times of layers 1.a ... 4.c (fp32): HIP events around every pass over `steps` steps,
+    each layer on its own tensors resident in HBM; per configuration also the time of whole steps
+    enqueued back to back without events."""
+    import math
+    stream = torch.cuda.current_stream()
+    rows, per_config = [], {}
+    for cfg in range(4):
+        layers = [l for l in workloads.LAYERS if l.config == cfg]
+        state = []
+        ws_bytes = 0
+        for l in layers:
+            d = conv.conv_desc_create(conv.ConvParams(**l.params_dict()))
+            ws_bytes = max(ws_bytes, conv.conv_desc_workspace_bytes(d))
+            x, w, b, dy = workloads.layer_inputs(l, bias="zero")
+            state.append(dict(layer=l, desc=d, x=x.to(dev), w=w.to(dev), b=b.to(dev), dy=dy.to(dev),
+                              y=torch.empty(l.y_shape, device=dev), dx=torch.empty(l.x_shape, device=dev),
+                              dw=torch.empty(l.w_shape, device=dev), db=torch.empty(l.k, device=dev)))
+        ws = torch.empty(max(ws_bytes // 4, 1), device=dev)
+        calls = {
+            "fwd": lambda t: conv.conv_forward(t["desc"], t["x"], t["w"], t["b"], t["y"], ws, stream),
+            "bwd_data": lambda t: conv.conv_backward_data(t["desc"], t["w"], t["dy"], t["dx"], ws, stream),
+            "bwd_filter": lambda t: conv.conv_backward_filter(t["desc"], t["x"], t["dy"], t["dw"], 0.0, ws, stream),
+            "bwd_bias": lambda t: conv.conv_backward_bias(t["desc"], t["dy"], t["db"], 0.0, ws, stream),
+        }
+
+        def step(events=None):
+            for t in state:
+                for name, fn in calls.items():
+                    if events is None:
+                        fn(t)
+                    else:
+                        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                        e0.record(stream)
+                        fn(t)
+                        e1.record(stream)
+                        events.append((t["layer"].name, name, e0, e1))
+
+        for _ in range(warmup):
+            step()
+        events = []
+        for _ in range(steps):
+            step(events)
+        torch.cuda.synchronize()
+        acc = {}
+        for lname, pname, e0, e1 in events:
+            acc.setdefault((lname, pname), []).append(e0.elapsed_time(e1))
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            step()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        flop_step = 3 * sum(l.flop_per_pass for l in layers)
+        per_config["config%d" % cfg] = {"us_per_step": round(wall / steps * 1e6, 1),
+                                        "tflops": round(flop_step * steps / wall / 1e12, 3),
+                                        "frac_of_fp32_mfma_peak": round(flop_step * steps / wall / 1e12
+                                                                        / PEAK_FP32_MFMA_TFLOPS, 4)}
+        for t in state:
+            l = t["layer"]
+            names = conv.conv_desc_kernel_names(t["desc"])
+            launches = launches_of(names)
+            row = {"layer": l.name, "gflop_per_pass": round(l.flop_per_pass / 1e9, 4), "kernels": names}
+            tot = 0.0
+            for name in calls:
+                v = sorted(acc[(l.name, name)])
+                us = v[len(v) // 2] * 1e3  # median
+                tot += us
+                p = {"us": round(us, 2), "launches": launches[name],
+                     "us_over_launch_floor": round(us - launches[name] * launch_us, 2)}
+                if name != "bwd_bias":
+                    p["tflops"] = round(l.flop_per_pass / us / 1e6, 2)
+                    p["alg_GBps"] = round(blob_bytes(l, name) / us / 1e3, 1)
+                else:
+                    p["alg_GBps"] = round(dy_bytes(l) / us / 1e3, 1)
+                row[name] = p
+            alg = sum(blob_bytes(l, name) for name in ("fwd", "bwd_data", "bwd_filter")) + dy_bytes(l)
+            row.update({"fwd_bwd_us": round(tot, 2), "launches": sum(launches.values()),
+                        "fwd_bwd_tflops": round(3 * l.flop_per_pass / tot / 1e6, 2),
+                        "frac_of_fp32_mfma_peak": round(3 * l.flop_per_pass / tot / 1e6 / PEAK_FP32_MFMA_TFLOPS, 4),
+                        "frac_of_hbm_peak": round(alg / tot / 1e3 / PEAK_HBM_GBS, 4),
+                        "us_at_mfma_peak": round(3 * l.flop_per_pass / PEAK_FP32_MFMA_TFLOPS / 1e6, 2),
+                        "us_at_hbm_peak": round(alg / PEAK_HBM_GBS / 1e3, 2)})
+            rows.append(row)
+    return {"empty_dispatch_us": round(launch_us, 2), "bound": "launch latency (microseconds of work per pass)",
+            "from": "%d steps per configuration with HIP events around every pass (median); us_per_step from %d "
+                    "steps enqueued back to back without events" % (steps, steps),
+            "per_config": per_config, "layers": rows}
 
 
 def bench_pg(args, torch, lib, workloads, dev):
@@ -515,7 +639,7 @@ def blob_bytes(l, pass_name):
     """fp32 bytes of the blobs one pass of a convolution layer reads and writes, each once."""
     import math
     x, y, w = (math.prod(s) for s in (l.x_shape, l.y_shape, l.w_shape))
-    return 4 * (x + y + (0 if pass_name == "bwd_filter" else w))
+    return 4 * (x + y + w)  # two of them read, the third written, whichever the pass
 
 
 def dy_bytes(l):

@@ -158,15 +158,19 @@ PhaseDim phase_dim(int64_t kernel, int64_t stride, int64_t dilation) {
   return r;
 }
 
-// "tile[m<bounds mode>,e<epilogue form>](S=<splits>)", or "tile_patch[e.](S=1)" for the patch-staged kernel.
+// "tile[m<bounds mode>,e<epilogue form>](S=<splits>,L=<launches>)", or "tile_patch[e.](S=1,L=2)" for the
+// patch-staged kernel.
 // Epilogue forms: s = separable byte offsets, r = range-checked stores with a compare per element,
 // p = plain pointers (output of 2^31 bytes or more).
-void corr_variant_name(char* buf, size_t len, int32_t tile, const CorrArgs& a) {
+// L = kernel launches of the pass: the pack kernel, a zero fill (backward data with unreached
+// phases), the main kernel, the reduce kernel of a split launch.
+void corr_variant_name(char* buf, size_t len, int32_t tile, const CorrArgs& a, int zero_fill) {
   const char e = a.simple_epilogue ? 's' : ((uint32_t)a.out_elems < (1u << 29) ? 'r' : 'p');
+  const int launches = 2 + (a.ksplit > 1) + (zero_fill != 0);
   if (a.use_patch)
-    snprintf(buf, len, "%s_patch[e%c](S=%d)", corr_tile_name(tile), e, a.ksplit);
+    snprintf(buf, len, "%s_patch[e%c](S=%d,L=%d)", corr_tile_name(tile), e, a.ksplit, launches);
   else
-    snprintf(buf, len, "%s[m%d,e%c](S=%d)", corr_tile_name(tile), a.bounds_mode, e, a.ksplit);
+    snprintf(buf, len, "%s[m%d,e%c](S=%d,L=%d)", corr_tile_name(tile), a.bounds_mode, e, a.ksplit, launches);
 }
 
 uint32_t koff_invalid(int32_t mode) { return mode == 0 ? 0x7FFFFFFCu : mode == 2 ? 0x40000000u : 0u; }
@@ -780,9 +784,10 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
     d->bg64_ws = 2 * d->bg_ws;
     auto e64 = [](const CorrArgs& c) { return c.simple_epilogue ? 's' : 'p'; };
     snprintf(d->names64, sizeof(d->names64),
-             "fwd=corr64_%dx64x16[e%c];bwd_data=corr64_%dx64x16[e%c];bwd_filter=wgrad64_%dx64x16(S=%d);"
-             "bwd_bias=bias_grad64(S=%d)",
-             d->fwd64_rows, e64(d->fwd64), d->bwd64_rows, e64(d->bwd64), d->wg64_rows, a.S, d->bg.S);
+             "fwd=corr64_%dx64x16[e%c](S=1,L=2);bwd_data=corr64_%dx64x16[e%c](S=1,L=%d);"
+             "bwd_filter=wgrad64_%dx64x16(S=%d,L=2);bwd_bias=bias_grad64(S=%d,L=2)",
+             d->fwd64_rows, e64(d->fwd64), d->bwd64_rows, e64(d->bwd64), 2 + (d->bwd_zero_fill != 0), d->wg64_rows, a.S,
+             d->bg.S);
     d->ws_bytes64 = d->fwd64_ws;
     if (d->bwd64_ws > d->ws_bytes64) d->ws_bytes64 = d->bwd64_ws;
     if (d->wg64_ws > d->ws_bytes64) d->ws_bytes64 = d->wg64_ws;
@@ -853,8 +858,9 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
       char df[3][32];
       for (int pass = 0; pass < 3; ++pass) direct_form_name(pass, a, df[pass], sizeof(df[pass]));
       snprintf(d->names64, sizeof(d->names64),
-               "fwd=direct64[%s];bwd_data=direct64[%s];bwd_filter=direct64[%s](S=%d);bwd_bias=bias_grad64(S=%d)", df[0],
-               df[1], df[2], a.S, d->bg.S);
+               "fwd=direct64[%s](S=1,L=1);bwd_data=direct64[%s](S=1,L=1);bwd_filter=direct64[%s](S=%d,L=2);"
+               "bwd_bias=bias_grad64(S=%d,L=2)",
+               df[0], df[1], df[2], a.S, d->bg.S);
     }
   }
 
@@ -868,19 +874,19 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
     // checked stores with compares, plain pointers), staging of the filter gradient (lds/reg), one or
     // two launches of the bias gradient
     char f[64], b[64], wg[64];
-    corr_variant_name(f, sizeof(f), d->fwd_tile, d->fwd);
-    corr_variant_name(b, sizeof(b), d->bwd_tile, d->bwd);
-    snprintf(wg, sizeof(wg), "%s[m%d,%s,e%c](S=%d)", wgrad_tile_name(d->wg_tile), d->wg.bounds_mode,
+    corr_variant_name(f, sizeof(f), d->fwd_tile, d->fwd, 0);
+    corr_variant_name(b, sizeof(b), d->bwd_tile, d->bwd, d->bwd_zero_fill);
+    snprintf(wg, sizeof(wg), "%s[m%d,%s,e%c](S=%d,L=2)", wgrad_tile_name(d->wg_tile), d->wg.bounds_mode,
              d->wg_tile == WGRAD_128x128 ? "lds" : "reg", 4 * Kg * kred <= ((int64_t)1 << 30) ? 'r' : 'p', d->wg.S);
     if (d->use_direct) {
       char df[3][32];
       for (int pass = 0; pass < 3; ++pass) direct_form_name(pass, d->dir, df[pass], sizeof(df[pass]));
-      snprintf(f, sizeof(f), "direct[%s]", df[0]);
-      snprintf(b, sizeof(b), "direct[%s]", df[1]);
-      snprintf(wg, sizeof(wg), "direct[%s](S=%d)", df[2], d->dir.S);
+      snprintf(f, sizeof(f), "direct[%s](S=1,L=1)", df[0]);
+      snprintf(b, sizeof(b), "direct[%s](S=1,L=1)", df[1]);
+      snprintf(wg, sizeof(wg), "direct[%s](S=%d,L=2)", df[2], d->dir.S);
     }
-    snprintf(d->names, sizeof(d->names), "fwd=%s;bwd_data=%s;bwd_filter=%s;bwd_bias=bias_grad[%s](S=%d)", f, b, wg,
-             d->bg_direct ? "one" : "two", d->bg.S);
+    snprintf(d->names, sizeof(d->names), "fwd=%s;bwd_data=%s;bwd_filter=%s;bwd_bias=bias_grad[%s](S=%d,L=%d)", f, b, wg,
+             d->bg_direct ? "one" : "two", d->bg.S, d->bg_direct ? 1 : 2);
   }
   *out = d;
   return CONV_OK;

@@ -82,9 +82,9 @@ int ip_desc_create(ip_desc_t** out, const ip_params_t* pp) {
   if (d->cs_ws > d->ws_bytes) d->ws_bytes = d->cs_ws;
   const char* in = d->inner ? conv_desc_kernel_names(d->inner) : "";
   const bool one_launch = M * O * 4 <= ((int64_t)4 << 20);  // see ip_backward_bias
-  snprintf(d->names, sizeof(d->names), "fwd=%s;bwd_data=%s;bwd_filter=%s;bwd_bias=colsum(S=%d)",
+  snprintf(d->names, sizeof(d->names), "fwd=%s;bwd_data=%s;bwd_filter=%s;bwd_bias=colsum(S=%d,L=%d)",
            field(in, "bwd_filter=").c_str(), field(in, "fwd=").c_str(), field(in, "bwd_data=").c_str(),
-           one_launch ? 1 : cs.S);
+           one_launch ? 1 : cs.S, one_launch ? 1 : 2);
   *out = d;
   return CONV_OK;
 }

@@ -333,7 +333,7 @@ struct conv_desc {
   // 2^29 or more elements)
   int32_t f64_ok;
   int32_t fwd64_rows, bwd64_rows, wg64_rows;
-  char names64[192];
+  char names64[256];
   mi355conv::CorrArgs fwd64, bwd64;
   mi355conv::PackArgs fwd64_pack, bwd64_pack;
   size_t fwd64_ws, bwd64_ws;

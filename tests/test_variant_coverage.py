@@ -31,8 +31,8 @@ def fields(names):
 
 
 def split_variant(v):
-    """'tile[m2,es](S=4)' -> ('tile[m2,es]', 4)"""
-    m = re.fullmatch(r"(.*)\(S=(\d+)\)", v)
+    """'tile[m2,es](S=4,L=3)' -> ('tile[m2,es]', 4)"""
+    m = re.fullmatch(r"(.*)\(S=(\d+),L=\d+\)", v)
     return (m.group(1), int(m.group(2))) if m else (v, 1)
 
 

@@ -54,6 +54,9 @@ def parse():
     ap.add_argument("--graph", action="store_true",
                     help="capture one step in a HIP graph and time its replays (no per-pass times): what the "
                          "microsecond-scale layers cost without the per-dispatch launch gaps")
+    ap.add_argument("--separate-bias", action="store_true",
+                    help="fp32 convolution workloads: call conv_backward_filter and conv_backward_bias (two reads of dy) "
+                         "instead of conv_backward_filter_bias (one)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run plain 256 MiB device copies (outside the timed region) so that a rocprofv3 "
                          "--pmc FETCH_SIZE / WRITE_SIZE run of this command holds a kernel of known traffic")
@@ -139,9 +142,11 @@ def main():
     ws = torch.empty(max(ws_bytes // 4, 1), device=dev)
     stream = torch.cuda.current_stream()
 
+    # fp32 convolution: both parameter gradients come from one pass over dy (conv_backward_filter_bias)
+    fused_bias = not is_ip and not f64 and not args.separate_bias
     passes = ("fwd", "relu_bwd", "bwd_data", "bwd_filter", "bwd_bias") if is_ip else (
-        "fwd", "bwd_data", "bwd_filter", "bwd_bias")
-    flop_passes = ("fwd", "bwd_data", "bwd_filter")
+        "fwd", "bwd_data", "bwd_filter_bias") if fused_bias else ("fwd", "bwd_data", "bwd_filter", "bwd_bias")
+    flop_passes = ("fwd", "bwd_data", "bwd_filter", "bwd_filter_bias")
     kernel_names_of = (conv.ip_desc_kernel_names if is_ip else
                        conv.conv_desc_kernel_names_f64 if f64 else conv.conv_desc_kernel_names)
 
@@ -177,6 +182,8 @@ def main():
             conv.conv_backward_data(d, t["w"], t["dy"], t["dx"], wsp, stream)
         elif name == "bwd_filter":
             conv.conv_backward_filter(d, t["x"], t["dy"], t["dw"], 0.0, wsp, stream)
+        elif name == "bwd_filter_bias":
+            conv.conv_backward_filter_bias(d, t["x"], t["dy"], t["dw"], t["db"], 0.0, wsp, stream)
         else:
             conv.conv_backward_bias(d, t["dy"], t["db"], 0.0, wsp, stream)
 
@@ -235,8 +242,11 @@ def main():
             side.wait_event(fork)
             for t in reversed(state):
                 run_pass_on(t, "bwd_data", stream)
-                run_pass_on(t, "bwd_filter", side, ws_side)
-                run_pass_on(t, "bwd_bias", side, ws_side)
+                if fused_bias:
+                    run_pass_on(t, "bwd_filter_bias", side, ws_side)
+                else:
+                    run_pass_on(t, "bwd_filter", side, ws_side)
+                    run_pass_on(t, "bwd_bias", side, ws_side)
             join = torch.cuda.Event()
             join.record(side)
             stream.wait_event(join)
@@ -304,6 +314,20 @@ def main():
     for lname, pname, e0, e1 in events:
         acc.setdefault((lname, pname), []).append(e0.elapsed_time(e1))
     dominant = max(((k, sum(v) / len(v)) for k, v in acc.items()), key=lambda kv: kv[1])[0]
+    separate = {}
+    if fused_bias:  # for reference: the two gradient passes called one by one (not part of the step)
+        ev = []
+        for _ in range(table_steps):
+            for t in state:
+                for name in ("bwd_filter", "bwd_bias"):
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record(stream)
+                    run_pass(t, name)
+                    e1.record(stream)
+                    ev.append((t["layer"].name, name, e0, e1))
+        torch.cuda.synchronize()
+        for lname, pname, e0, e1 in ev:
+            separate.setdefault((lname, pname), []).append(e0.elapsed_time(e1))
 
     # ---- timed region: exactly --steps steps; HIP events around the dominant pass of every step ----
     dom_events = []
@@ -325,6 +349,9 @@ def main():
                "kernels": kernel_names_of(t["desc"])}
         tot = 0.0
         launches = launches_of(row["kernels"])
+        if fused_bias:  # the reduce kernel finishes both gradients: the launches of the filter gradient alone
+            launches["bwd_filter_bias"] = launches.pop("bwd_filter")
+            launches.pop("bwd_bias", None)
         for name in passes:
             ms = sum(acc[(l.name, name)]) / len(acc[(l.name, name)])
             row[name + "_ms"] = round(ms, 5)
@@ -336,6 +363,10 @@ def main():
                 row[name + "_us_over_launch_floor"] = round(ms * 1e3 - launches[name] * launch_us, 2)
             if not is_ip and name in flop_passes:  # every blob of the pass moved once, against 8 TB/s
                 row[name + "_alg_GBps"] = round(blob_bytes(l, name) * (2 if f64 else 1) / ms / 1e6, 1)
+            if name == "bwd_filter_bias":  # the same passes called one by one, outside the step
+                for sep in ("bwd_filter", "bwd_bias"):
+                    row["separate_" + sep + "_ms"] = round(sum(separate[(l.name, sep)]) / len(separate[(l.name, sep)]), 5)
+                row["bias_gradient_extra_ms"] = round(ms - row["separate_bwd_filter_ms"], 5)
             if name in flop_passes:
                 row[name + "_tflops"] = round(l.flop_per_pass / ms / 1e9, 2)
             elif name == "bwd_bias":  # one read of dy: the HBM-bound pass
@@ -343,7 +374,7 @@ def main():
             if name in flop_passes and not is_ip and "direct" in row["kernels"]:
                 row[name + "_GBps"] = round(blob_bytes(l, name) * (2 if f64 else 1) / ms / 1e6, 1)
         row["fwd_bwd_tflops"] = round(3 * l.flop_per_pass / tot / 1e9, 2)
-        if not is_ip and l.name in ("1.a", "3.a", "4.a", "5.a"):
+        if not is_ip and l.name in ("1.a", "3.a", "4.a", "5.a") and "bwd_data_ms" in row:
             # first layer of its network: real training skips its backward-data pass (no gradient
             # flows into the data), so also give the rate over forward + backward filter + backward bias
             row["first_layer_without_bwd_data_tflops"] = round(
@@ -351,7 +382,7 @@ def main():
         row["fwd_bwd_frac_of_%s_mfma_peak" % ("fp64" if f64 else "fp32")] = round(
             3 * l.flop_per_pass / tot / 1e9 / peak, 4)
         if not is_ip:
-            alg = sum(blob_bytes(l, name) for name in flop_passes) + dy_bytes(l)
+            alg = 3 * blob_bytes(l, "fwd") + (0 if fused_bias else dy_bytes(l))
             row["fwd_bwd_frac_of_hbm_peak"] = round(alg * (2 if f64 else 1) / tot / 1e6 / PEAK_HBM_GBS, 4)
             row["fwd_bwd_us"] = round(tot * 1e3, 2)
             row["launches"] = sum(launches.values())
@@ -363,6 +394,8 @@ def main():
     dstate = next(t for t in state if t["layer"].name == dl)
     dlayer = dstate["layer"]
     kernel_names = dict(kv.split("=", 1) for kv in kernel_names_of(dstate["desc"]).split(";"))
+    if "bwd_filter" in kernel_names:  # the pass that also sums dy runs the filter-gradient kernel
+        kernel_names["bwd_filter_bias"] = kernel_names["bwd_filter"]
     direct = not is_ip and "direct" in kernel_names.get(dp, "")
     if dp in ("bwd_bias", "relu_bwd") or direct:
         if direct:  # thin groups: every blob of the pass moved once
@@ -384,6 +417,8 @@ def main():
         try:
             tr = json.load(open(traffic_file))
             roofline["traffic"] = tr.get(("f64/" if f64 else "") + f"{dl}:{dp}")
+            if roofline["traffic"] is None and dp == "bwd_filter_bias":  # the same kernel without the row sums
+                roofline["traffic"] = tr.get(f"{dl}:bwd_filter")
             # not measured in this run: the figure of the committed rocprofv3 --pmc summary
             roofline["traffic_from"] = "profiles/hbm_traffic.json"
         except Exception:
@@ -394,6 +429,8 @@ def main():
                    "backward bias), fp32") if is_ip else
                   "conv fwd+bwd GFLOP/s (forward + backward data + backward filter + backward bias), "
                   + ("fp64" if f64 else "fp32"),
+        "bias_gradient": "from the backward-filter pass's read of dy (conv_backward_filter_bias)" if fused_bias else
+                         "a pass of its own (conv_backward_bias)",
         "value": round(value, 1), "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": args.dtype, "data": "synthetic",
@@ -463,8 +500,8 @@ def small_layers(torch, conv, workloads, dev, launch_us, steps=20, warmup=5):
         calls = {
             "fwd": lambda t: conv.conv_forward(t["desc"], t["x"], t["w"], t["b"], t["y"], ws, stream),
             "bwd_data": lambda t: conv.conv_backward_data(t["desc"], t["w"], t["dy"], t["dx"], ws, stream),
-            "bwd_filter": lambda t: conv.conv_backward_filter(t["desc"], t["x"], t["dy"], t["dw"], 0.0, ws, stream),
-            "bwd_bias": lambda t: conv.conv_backward_bias(t["desc"], t["dy"], t["db"], 0.0, ws, stream),
+            "bwd_filter_bias": lambda t: conv.conv_backward_filter_bias(t["desc"], t["x"], t["dy"], t["dw"], t["db"],
+                                                                        0.0, ws, stream),
         }
 
         def step(events=None):
@@ -508,16 +545,12 @@ def small_layers(torch, conv, workloads, dev, launch_us, steps=20, warmup=5):
                 v = sorted(acc[(l.name, name)])
                 us = v[len(v) // 2] * 1e3  # median
                 tot += us
-                p = {"us": round(us, 2), "launches": launches[name],
-                     "us_over_launch_floor": round(us - launches[name] * launch_us, 2)}
-                if name != "bwd_bias":
-                    p["tflops"] = round(l.flop_per_pass / us / 1e6, 2)
-                    p["alg_GBps"] = round(blob_bytes(l, name) / us / 1e3, 1)
-                else:
-                    p["alg_GBps"] = round(dy_bytes(l) / us / 1e3, 1)
+                nl = launches["bwd_filter" if name == "bwd_filter_bias" else name]
+                p = {"us": round(us, 2), "launches": nl, "us_over_launch_floor": round(us - nl * launch_us, 2),
+                     "tflops": round(l.flop_per_pass / us / 1e6, 2), "alg_GBps": round(blob_bytes(l, name) / us / 1e3, 1)}
                 row[name] = p
-            alg = sum(blob_bytes(l, name) for name in ("fwd", "bwd_data", "bwd_filter")) + dy_bytes(l)
-            row.update({"fwd_bwd_us": round(tot, 2), "launches": sum(launches.values()),
+            alg = 3 * blob_bytes(l, "fwd")
+            row.update({"fwd_bwd_us": round(tot, 2), "launches": sum(row[name]["launches"] for name in calls),
                         "fwd_bwd_tflops": round(3 * l.flop_per_pass / tot / 1e6, 2),
                         "frac_of_fp32_mfma_peak": round(3 * l.flop_per_pass / tot / 1e6 / PEAK_FP32_MFMA_TFLOPS, 4),
                         "frac_of_hbm_peak": round(alg / tot / 1e3 / PEAK_HBM_GBS, 4),

@@ -104,6 +104,19 @@ int conv_backward_filter(const conv_desc_t* d, const float* x, const float* dy, 
                          void* ws, size_t ws_bytes, void* hip_stream);
 
 /*
+ * Backward filter and backward bias of one layer in one pass: dw = beta*dw + filter gradient and
+ * db = beta*db + sum of dy over n, oh, ow (the two parameter gradients a Caffe layer produces in its
+ * backward step, with the same accumulate rule), from a single read of dy -- the filter-gradient kernel
+ * adds up the dy tiles it stages for the matrix unit, so the separate pass over dy that
+ * conv_backward_bias makes (as large as the top blob) is saved.  Results are bit-identical from run
+ * to run; dw is bit-identical to conv_backward_filter's, db may differ from conv_backward_bias's in
+ * the last bits (another summation order).  CONV_EINVAL on a bias_term == 0 descriptor; otherwise the
+ * rules of conv_backward_filter; the workspace is covered by conv_desc_workspace_bytes.
+ */
+int conv_backward_filter_bias(const conv_desc_t* d, const float* x, const float* dy, float* dw, float* db, float beta,
+                              void* ws, size_t ws_bytes, void* hip_stream);
+
+/*
  * conv_backward_filter for callers that cannot allocate or pass device memory for a workspace: code
  * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
  * semantics, layouts and result (bit for bit) as conv_backward_filter, without `ws`: the split

@@ -17,6 +17,7 @@ from .binding import (  # noqa: F401
     conv_forward_f64,
     conv_backward_data,
     conv_backward_filter,
+    conv_backward_filter_bias,
     conv_backward_filter_static,
     conv_static_workspace_limit,
     conv_desc_create,

@@ -70,6 +70,8 @@ def _load():
     lib.conv_backward_data.argtypes = [vp, vp, vp, vp, vp, sz, vp]
     lib.conv_backward_filter.argtypes = [vp, vp, vp, vp, fp, vp, sz, vp]
     lib.conv_backward_bias.argtypes = [vp, vp, vp, fp, vp, sz, vp]
+    lib.conv_backward_filter_bias.argtypes = [vp, vp, vp, vp, vp, fp, vp, sz, vp]
+    lib.conv_backward_filter_bias.restype = ctypes.c_int
     lib.conv_backward_filter_static.argtypes = [vp, vp, vp, vp, fp, vp]
     lib.conv_backward_filter_static.restype = ctypes.c_int
     lib.conv_static_workspace_limit.argtypes = []
@@ -206,6 +208,15 @@ def conv_backward_filter(desc, x, dy, dw, beta=0.0, ws=None, stream=None) -> Non
     _check(_load().conv_backward_filter(desc.handle, _ptr(x, _x_shape(p), "x"),
                                         _ptr(dy, conv_desc_output_shape(desc), "dy"), _ptr(dw, _w_shape(p), "dw"),
                                         float(beta), wp, wb, _stream(stream)), "conv_backward_filter")
+
+
+def conv_backward_filter_bias(desc, x, dy, dw, db, beta=0.0, ws=None, stream=None) -> None:
+    p = desc.params
+    wp, wb = _ws(ws)
+    _check(_load().conv_backward_filter_bias(desc.handle, _ptr(x, _x_shape(p), "x"),
+                                             _ptr(dy, conv_desc_output_shape(desc), "dy"), _ptr(dw, _w_shape(p), "dw"),
+                                             _ptr(db, (p.num_output,), "db"), float(beta), wp, wb, _stream(stream)),
+           "conv_backward_filter_bias")
 
 
 def conv_backward_filter_static(desc, x, dy, dw, beta=0.0, stream=None) -> None:

@@ -374,18 +374,21 @@ int run_backward_data(const conv_desc* d, const float* w, const float* dy, float
 }
 
 int run_backward_filter(const conv_desc* d, const float* x, const float* dy, float* dw, float beta, void* ws,
-                        size_t ws_bytes, void* hip_stream, const ReduceExtras& extras) {
+                        size_t ws_bytes, void* hip_stream, const ReduceExtras& extras, float* db) {
   if (!d || !dw) return CONV_EINVAL;
   if (!(beta == 0.f || beta == 1.f)) return CONV_EINVAL;
   const bool empty = d->p.n == 0;  // the gradient sum is empty: dw = beta*dw
   if (!empty && (!x || !dy)) return CONV_EINVAL;
-  if (!empty && d->wg_ws > 0 && (!ws || ws_bytes < d->wg_ws)) return CONV_EWORKSPACE;
+  const size_t need = db ? d->wgb_ws : d->wg_ws;
+  if (!empty && need > 0 && (!ws || ws_bytes < need)) return CONV_EWORKSPACE;
+  const int32_t w_elems = (int32_t)((int64_t)d->p.num_output * d->wg.Kred);
   WgradArgs a = d->wg;
   a.dy = dy;
   a.x = x;
   a.part = static_cast<float*>(ws);
   int e = 0;
   if (d->use_direct) {
+    // thin groups: the direct filter-gradient kernel, and the stand-alone bias gradient after it
     DirectArgs da = d->dir;
     da.in = x;
     da.w = dy;
@@ -393,13 +396,17 @@ int run_backward_filter(const conv_desc* d, const float* x, const float* dy, flo
     a.S = da.S;
     if (!empty) e = launch_direct(2, da, false, hip_stream);
   } else if (!empty) {
+    if (db) {  // row sums of dy ride along: a slice is the filter partials followed by num_output sums
+      a.part_stride = w_elems + d->p.num_output;
+      a.bias_part = a.part + w_elems;
+    }
     e = launch_wgrad(d->wg_tile, a, hip_stream);
   }
   if (e) return record_hip_error(e);
   ReduceArgs r = {};
   r.part = a.part;
   r.dst = dw;
-  r.count = (int32_t)((int64_t)d->p.num_output * d->wg.Kred);
+  r.count = w_elems;
   r.S = empty ? 0 : a.S;
   r.beta = beta;
   r.bias = extras.bias;
@@ -408,8 +415,15 @@ int run_backward_filter(const conv_desc* d, const float* x, const float* dy, flo
   r.mChanElems = make_magic(r.chan_elems);
   r.mChannels = make_magic(r.channels);
   r.relu = extras.relu;
+  if (db && (empty || !d->use_direct)) {
+    r.stride = w_elems + d->p.num_output;
+    r.dst2 = db;
+    r.count2 = d->p.num_output;
+  }
   e = launch_reduce(r, hip_stream);
-  return e ? record_hip_error(e) : CONV_OK;
+  if (e) return record_hip_error(e);
+  if (db && !empty && d->use_direct) return conv_backward_bias(d, dy, db, beta, ws, ws_bytes, hip_stream);
+  return CONV_OK;
 }
 
 }  // namespace mi355conv
@@ -708,7 +722,14 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
       delete d;
       return CONV_ESHAPE;
     }
+    a.part_stride = (int32_t)w_elems;
+    a.bias_part = nullptr;
     d->wg_ws = (size_t)a.S * (size_t)w_elems * 4;
+    d->wgb_ws = (size_t)a.S * (size_t)(w_elems + K) * 4;
+    if (a.S * (w_elems + K) >= kMaxElems) {
+      delete d;
+      return CONV_ESHAPE;
+    }
   }
 
   // ---- backward bias ----
@@ -852,6 +873,7 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
     if (d->use_direct) {
       d->fwd_ws = d->bwd_ws = 0;
       d->wg_ws = (size_t)a.S * (size_t)w_elems * 4;
+      d->wgb_ws = d->wg_ws > d->bg_ws ? d->wg_ws : d->bg_ws;  // the two passes one after the other
       d->fwd64_ws = d->bwd64_ws = 0;
       d->wg64_ws = 2 * d->wg_ws;
       d->ws_bytes64 = d->wg64_ws > d->bg64_ws ? d->wg64_ws : d->bg64_ws;
@@ -868,6 +890,7 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
   if (d->bwd_ws > d->ws_bytes) d->ws_bytes = d->bwd_ws;
   if (d->wg_ws > d->ws_bytes) d->ws_bytes = d->wg_ws;
   if (d->bg_ws > d->ws_bytes) d->ws_bytes = d->bg_ws;
+  if (p.bias_term && d->wgb_ws > d->ws_bytes) d->ws_bytes = d->wgb_ws;
   {
     // every template parameter and run-time branch that selects different kernel code is spelled out:
     // tile, bounds mode (m0/m1/m2) or patch staging, epilogue form (es/er/ep: separable offsets, range-
@@ -928,6 +951,13 @@ int conv_backward_data(const conv_desc_t* d, const float* w, const float* dy, fl
 int conv_backward_filter(const conv_desc_t* d, const float* x, const float* dy, float* dw, float beta, void* ws,
                          size_t ws_bytes, void* hip_stream) {
   return run_backward_filter(d, x, dy, dw, beta, ws, ws_bytes, hip_stream, ReduceExtras());
+}
+
+int conv_backward_filter_bias(const conv_desc_t* d, const float* x, const float* dy, float* dw, float* db, float beta,
+                              void* ws, size_t ws_bytes, void* hip_stream) {
+  if (!d || !db) return CONV_EINVAL;
+  if (!d->p.bias_term) return CONV_EINVAL;
+  return run_backward_filter(d, x, dy, dw, beta, ws, ws_bytes, hip_stream, ReduceExtras(), db);
 }
 
 int conv_backward_bias(const conv_desc_t* d, const float* dy, float* db, float beta, void* ws, size_t ws_bytes,

@@ -138,12 +138,20 @@ struct WgradArgs {
   int32_t Kred;
   int32_t cols_per_split, S;
   int32_t G, m_tiles, n_tiles;
+  // Elements between the partial slices of two splits (G*Kg*Kred, plus Ktot when the bias gradient
+  // rides along) and, for that case, where the row sums of dy go: bias_part[s*part_stride + g*Kg + k]
+  // = sum of dy[., g*Kg + k, .] over the split's columns (null: not wanted).
+  int32_t part_stride;
+  float* bias_part;
 };
 
 struct ReduceArgs {
-  const float* part;  // [S][count]
+  const float* part;  // [S][stride]: elements [0, count) of a slice go to dst, [count, count + count2) to dst2
   float* dst;         // [count]
   int32_t count, S;
+  int32_t stride;     // elements between slices (0: count)
+  float* dst2;        // [count2] second destination with the same beta (filter + bias gradient in one launch)
+  int32_t count2;
   float beta;
   // optional per-channel bias for blobs laid out [..][channel][chan_elems]: dst += bias[(i / chan_elems) % channels]
   const float* bias;
@@ -292,8 +300,9 @@ int run_forward(const conv_desc* d, const float* x, const float* w, const float*
                 size_t ws_bytes, void* stream);
 int run_backward_data(const conv_desc* d, const float* w, const float* dy, float* dx, float beta, void* ws,
                       size_t ws_bytes, void* stream);
+// db non-null: also db = beta*db + row sums of dy, from the same read of dy
 int run_backward_filter(const conv_desc* d, const float* x, const float* dy, float* dw, float beta, void* ws,
-                        size_t ws_bytes, void* stream, const ReduceExtras& extras);
+                        size_t ws_bytes, void* stream, const ReduceExtras& extras, float* db = nullptr);
 int record_hip_error(int e);  // remembers e for conv_last_hip_error and returns CONV_EHIP
 // workspace bytes conv_backward_filter needs for this descriptor (at most its conv_desc_workspace_bytes)
 int conv_desc_backward_filter_workspace_bytes(const conv_desc* d, size_t* bytes);
@@ -320,6 +329,7 @@ struct conv_desc {
   int32_t wg_tile;
   mi355conv::WgradArgs wg;
   size_t wg_ws;
+  size_t wgb_ws;  // filter and bias gradient together (conv_backward_filter_bias)
   // backward bias
   mi355conv::BiasGradArgs bg;
   size_t bg_ws;

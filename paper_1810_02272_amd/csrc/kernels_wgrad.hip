@@ -204,6 +204,14 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradArgs a) {
   const float* opA = smem + C::row_off(wm * MB * 32 + (lane & 31)) + (lane >> 5) * 4;
   const float* opB = smem + C::A_FLOATS + C::row_off(wn * NB * 32 + (lane & 31)) + (lane >> 5) * 4;
   constexpr int BLK = C::row_off(32);  // floats between 32-row blocks
+  // Bias gradient from the same read of dy: the waves that own the first column block of the first
+  // column tile add up the dy operands they read for the MFMAs -- lanes l and l + 32 of such a wave
+  // together read every element of row l of a chunk, exactly once.  Columns past the split read as
+  // zero; rows past the matrix edge are never stored.
+  const bool row_sums = a.bias_part != nullptr && n_tile == 0 && wn == 0;
+  float bsum[MB];
+#pragma unroll
+  for (int i = 0; i < MB; ++i) bsum[i] = 0.f;
   if (nchunks > 0) {
     col_state(0);
 #pragma unroll
@@ -249,6 +257,11 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradArgs a) {
       for (int i = 0; i < MB; ++i)
 #pragma unroll
         for (int j = 0; j < NB; ++j) M::run(av[ss & 1][i][u], bv[ss & 1][j][u], acc[i][j]);
+      if (u == 3 && row_sums) {
+#pragma unroll
+        for (int i = 0; i < MB; ++i)
+          bsum[i] += (av[ss & 1][i][0] + av[ss & 1][i][1]) + (av[ss & 1][i][2] + av[ss & 1][i][3]);
+      }
       if (DMA) {
         // this step's share of the loads of chunk ch+1, all issued in the first half of the chunk so
         // that they have the second half to land (past the last chunk they repeat it: nobody reads them)
@@ -283,8 +296,17 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradArgs a) {
     __syncthreads();
   }
 
+  if (row_sums) {
+#pragma unroll
+    for (int i = 0; i < MB; ++i) {
+      const float total = bsum[i] + __shfl_xor(bsum[i], 32);
+      const uint32_t k = m_tile * BM + (wm * MB + i) * 32 + (lane & 31);
+      if (lane < 32 && k < (uint32_t)a.Kg) a.bias_part[(size_t)split * a.part_stride + g * a.Kg + k] = total;
+    }
+  }
+
   // partial tile -> workspace [split][g][k][nn]
-  float* dst = a.part + ((size_t)split * a.G + g) * ((size_t)a.Kg * a.Kred);
+  float* dst = a.part + (size_t)split * a.part_stride + (size_t)g * ((size_t)a.Kg * a.Kred);
   const uint64_t slice_bytes = 4ull * (uint64_t)a.Kg * (uint64_t)a.Kred;
   if (slice_bytes <= (1ull << 30)) {
     // Byte offsets per row and per column with out-of-range values for rows and columns past the
@@ -363,20 +385,22 @@ __global__ __launch_bounds__(256) void reduce_kernel(const ReduceArgs a) {
   for (int c = 0; c < 4; ++c)
 #pragma unroll
     for (int e = 0; e < V; ++e) acc[c].v[e] = 0.f;
-  if (i < a.count) {
+  const int total = a.count + a.count2;
+  const size_t stride = a.stride ? (size_t)a.stride : (size_t)a.count;
+  if (i < total) {
     const float* src = a.part + i;
     int k = s0;
     for (; k + 3 < s1; k += 4) {
       Vec x[4];
 #pragma unroll
-      for (int c = 0; c < 4; ++c) x[c] = *reinterpret_cast<const Vec*>(src + (size_t)(k + c) * a.count);
+      for (int c = 0; c < 4; ++c) x[c] = *reinterpret_cast<const Vec*>(src + (size_t)(k + c) * stride);
 #pragma unroll
       for (int c = 0; c < 4; ++c)
 #pragma unroll
         for (int e = 0; e < V; ++e) acc[c].v[e] += x[c].v[e];
     }
     for (; k < s1; ++k) {
-      const Vec x = *reinterpret_cast<const Vec*>(src + (size_t)k * a.count);
+      const Vec x = *reinterpret_cast<const Vec*>(src + (size_t)k * stride);
 #pragma unroll
       for (int e = 0; e < V; ++e) acc[0].v[e] += x.v[e];
     }
@@ -386,21 +410,24 @@ __global__ __launch_bounds__(256) void reduce_kernel(const ReduceArgs a) {
   for (int e = 0; e < V; ++e) sum.v[e] = (acc[0].v[e] + acc[1].v[e]) + (acc[2].v[e] + acc[3].v[e]);
   quarter[q][lane] = sum;
   __syncthreads();
-  if (q == 0 && i < a.count) {
+  if (q == 0 && i < total) {
     Vec out, old;
-    if (a.beta != 0.f) old = *reinterpret_cast<const Vec*>(a.dst + i);
+    // the second destination takes the elements past `count` (both counts are multiples of V)
+    float* const dst = i < a.count ? a.dst + i : a.dst2 + (i - a.count);
+    const bool first = i < a.count;
+    if (a.beta != 0.f) old = *reinterpret_cast<const Vec*>(dst);
 #pragma unroll
     for (int e = 0; e < V; ++e) {
       float s = (quarter[0][lane].v[e] + quarter[1][lane].v[e]) + (quarter[2][lane].v[e] + quarter[3][lane].v[e]);
-      if (a.bias) {
+      if (a.bias && first) {
         const uint32_t c = mdiv((uint32_t)(i + e), a.mChanElems);
         s += a.bias[c - mdiv(c, a.mChannels) * a.channels];
       }
       if (a.beta != 0.f) s += a.beta * old.v[e];
-      if (a.relu) s = s > 0.f ? s : 0.f;
+      if (a.relu && first) s = s > 0.f ? s : 0.f;
       out.v[e] = s;
     }
-    *reinterpret_cast<Vec*>(a.dst + i) = out;
+    *reinterpret_cast<Vec*>(dst) = out;
   }
 }
 
@@ -437,12 +464,14 @@ int launch_wgrad(int32_t tile, const WgradArgs& a, void* stream) {
 
 int launch_reduce(const ReduceArgs& a, void* stream) {
   // the four-element form needs enough elements to keep a thousand workgroups busy
-  const bool vec = a.count >= (1 << 18) && a.count % 4 == 0 &&
-                   ((reinterpret_cast<uintptr_t>(a.part) | reinterpret_cast<uintptr_t>(a.dst)) & 15u) == 0;
+  const int total = a.count + a.count2;
+  const bool vec = a.count >= (1 << 18) && a.count % 4 == 0 && a.count2 % 4 == 0 && a.stride % 4 == 0 &&
+                   ((reinterpret_cast<uintptr_t>(a.part) | reinterpret_cast<uintptr_t>(a.dst) |
+                     reinterpret_cast<uintptr_t>(a.dst2)) & 15u) == 0;
   if (vec)
-    hipLaunchKernelGGL(reduce_kernel<4>, dim3((a.count / 4 + 63) / 64), dim3(256), 0, (hipStream_t)stream, a);
+    hipLaunchKernelGGL(reduce_kernel<4>, dim3((total / 4 + 63) / 64), dim3(256), 0, (hipStream_t)stream, a);
   else
-    hipLaunchKernelGGL(reduce_kernel<1>, dim3((a.count + 63) / 64), dim3(256), 0, (hipStream_t)stream, a);
+    hipLaunchKernelGGL(reduce_kernel<1>, dim3((total + 63) / 64), dim3(256), 0, (hipStream_t)stream, a);
   return (int)hipGetLastError();
 }
 

@@ -28,7 +28,8 @@ MAIN = ("corr_kernel", "corr_patch_kernel", "wgrad_kernel", "bias_grad_kernel")
 PASSES = ("fwd", "bwd_data", "bwd_filter", "bwd_bias")
 # workload -> (main kernels in pass order, pass names, layers, key prefix in hbm_traffic.json)
 WORKLOADS = {
-    "config4": (MAIN, PASSES, ["5.a", "5.b", "5.c"], ""),
+    # the default step takes both parameter gradients from one pass (conv_backward_filter_bias)
+    "config4": (MAIN[:3], ("fwd", "bwd_data", "bwd_filter_bias"), ["5.a", "5.b", "5.c"], ""),
     "f64": (("corr64_kernel", "wgrad64_kernel", "bias_grad64_kernel"), PASSES, ["5.a", "5.b", "5.c"], "f64/"),
     "ip5": (("wgrad_kernel", "relu_bwd_kernel", "corr_kernel", "colsum_kernel", "colsum_direct_kernel"),
             ("fwd", "relu_bwd", "bwd_data", "bwd_filter", "bwd_bias"), ["ip5.6", "ip5.7", "ip5.8"], ""),
@@ -98,7 +99,7 @@ def traffic(fetch_dir: str, write_dir: str, workload: str) -> None:
     for k in fetch:
         total[k] = int(fetch[k] + write[k])
         print(f"{k:16s} {fetch[k] / 1e6:10.1f} {write[k] / 1e6:11.1f} {total[k] / 1e6:10.1f}")
-    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    root = os.path.dirname(os.path.abspath(__file__))
     path = os.path.join(root, "profiles", "hbm_traffic.json")
     merged = json.load(open(path)) if os.path.exists(path) else {}
     merged.update(total)

@@ -104,6 +104,11 @@ def test_null_arguments_and_status_strings():
     assert lib.conv_forward(d.handle, 16, 16, 16, 16, None, 0, None) == binding.CONV_EINVAL
     assert lib.conv_backward_bias(d.handle, 16, 16, 0.0, 16, 1 << 20, None) == binding.CONV_EINVAL
     assert lib.conv_backward_filter(d.handle, 16, 16, 16, 0.5, 16, 1 << 20, None) == binding.CONV_EINVAL
+    assert lib.conv_backward_filter_bias(d.handle, 16, 16, 16, 16, 0.0, 16, 1 << 20, None) == binding.CONV_EINVAL
+    db_ok = conv.conv_desc_create(conv.ConvParams(1, 1, 4, 4, 1, 3, 3, bias_term=1))
+    assert lib.conv_backward_filter_bias(db_ok.handle, 16, 16, 16, None, 0.0, 16, 1 << 20, None) == binding.CONV_EINVAL
+    assert lib.conv_backward_filter_bias(db_ok.handle, 16, 16, 16, 16, 2.0, 16, 1 << 20, None) == binding.CONV_EINVAL
+    assert lib.conv_backward_filter_bias(db_ok.handle, 16, 16, 16, 16, 0.0, None, 0, None) == binding.CONV_EWORKSPACE
     # workspace missing / too small is detected before anything is enqueued
     assert lib.conv_forward(d.handle, 16, 16, None, 16, None, 0, None) == binding.CONV_EWORKSPACE
     assert lib.conv_backward_data(d.handle, 16, 16, 16, 16, 4, None) == binding.CONV_EWORKSPACE

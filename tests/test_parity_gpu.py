@@ -63,7 +63,23 @@ def check_full(pd: dict, seed: int, bias=True):
     errs = {k: gated_error(op, k, g, r, TOL, xn, wn, bn, dyn, case=pd) for k, (g, r) in refs.items()}
     for k, v in errs.items():
         assert np.isfinite(v) and v <= TOL, (pd, k, v, conv.conv_desc_kernel_names(d))
+    if b is not None:
+        check_filter_and_bias_in_one_pass(pd, op, d, ws, dev_in, dw, refs["db"][1], (xn, wn, bn, dyn))
     return errs
+
+
+def check_filter_and_bias_in_one_pass(pd, op, d, ws, dev_in, dw, db_ref, host, beta=0.0, dw0=None, db0=None):
+    """conv_backward_filter_bias: dw bit-identical to conv_backward_filter's, db against the oracle."""
+    xd, _, _, dyd = dev_in
+    dw2 = torch.full_like(dw, float("nan")) if dw0 is None else dw0.clone()
+    db2 = torch.full((pd["num_output"],), float("nan"), device=DEV) if db0 is None else db0.clone()
+    ws.fill_(float("nan"))
+    conv.conv_backward_filter_bias(d, xd, dyd, dw2, db2, beta, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(dw2, dw), (pd, conv.conv_desc_kernel_names(d))
+    v = gated_error(op, "db", db2, db_ref, TOL, *host, case=("filter+bias", pd))
+    assert np.isfinite(v) and v <= TOL, (pd, "db from the filter-gradient pass", v, conv.conv_desc_kernel_names(d))
+    return db2
 
 
 @pytest.mark.parametrize("i", range(len(SWEEP)))
@@ -203,6 +219,8 @@ def test_benchmark_layers_config_4_sampled(name):
     via_dw = float(np.sum(dwc * wn.astype(np.float64).ravel()))
     scale = float(np.sqrt(y.numel())) * float(np.max(np.abs(ref_y))) * l.dy_std
     assert abs(lin - via_dx) <= 1e-3 * scale and abs(lin - via_dw) <= 1e-3 * scale, (lin, via_dx, via_dw, scale)
+    # both parameter gradients from one read of dy, at full size
+    check_filter_and_bias_in_one_pass(pd, op, d, ws, (xd, wd, bd, dyd), dw, ref_db, (xn, wn, bn, dyn))
     # beta = 1 at full size (the wide form of the split reduction): dw + dw and db + db are exact in fp32
     dw0, db0 = dw.clone(), db.clone()
     conv.conv_backward_filter(d, xd, dyd, dw, 1.0, ws)
@@ -224,6 +242,14 @@ def test_beta_accumulates_and_overwrites(pd):
     assert torch.equal(dw, dw0 + dw0) and torch.equal(db, db0 + db0)   # x + x is exact in fp32
     ref = oracle.backward_filter(op, x.numpy(), dy.numpy(), dw=dw0.cpu().numpy(), beta=1.0)
     assert nerr(dw, ref) <= TOL
+    # both gradients in one pass: beta = 0 overwrites NaNs, beta = 1 adds to what is there
+    host = (x.numpy(), w.numpy(), b.numpy(), dy.numpy())
+    db1 = check_filter_and_bias_in_one_pass(pd, op, d, ws, (xd, wd, bd, dyd), dw0, oracle.backward_bias(op, dy.numpy()),
+                                            host)
+    db_ref2 = oracle.backward_bias(op, dy.numpy(), db=db1.cpu().numpy(), beta=1.0)
+    db2 = check_filter_and_bias_in_one_pass(pd, op, d, ws, (xd, wd, bd, dyd), dw, db_ref2, host, beta=1.0, dw0=dw0,
+                                            db0=db1)
+    assert torch.equal(db2, db1 + db1)
 
 
 def test_runs_are_bitwise_repeatable():
@@ -234,6 +260,16 @@ def test_runs_are_bitwise_repeatable():
     _, _, _, second = run_all(pd, x, w, b, dy, poison=False)
     for a, c in zip(first, second):
         assert torch.equal(a, c)
+
+
+def test_filter_and_bias_in_one_pass_on_configs_0_to_3_and_depthwise():
+    for l in [l for l in workloads.LAYERS if l.config <= 3] + [workloads.BY_NAME["dw.e"]]:
+        pd = l.params_dict()
+        op = OracleParams(**pd)
+        x, w, b, dy = workloads.layer_inputs(l, bias="random")
+        d, ws, dev_in, (y, dx, dw, db) = run_all(pd, x, w, b, dy)
+        check_filter_and_bias_in_one_pass(pd, op, d, ws, dev_in, dw, oracle.backward_bias(op, dy.numpy()),
+                                          (x.numpy(), w.numpy(), b.numpy(), dy.numpy()))
 
 
 def test_empty_batch_is_a_noop():
@@ -255,6 +291,14 @@ def test_empty_batch_is_a_noop():
     assert torch.all(dw == 5.0) and torch.all(db == 5.0)
     conv.conv_backward_filter(d, x, y, dw, 0.0, ws)
     conv.conv_backward_bias(d, y, db, 0.0, ws)
+    torch.cuda.synchronize()
+    assert torch.all(dw == 0.0) and torch.all(db == 0.0)
+    dw.fill_(5.0)
+    db.fill_(7.0)
+    conv.conv_backward_filter_bias(d, x, y, dw, db, 1.0, ws)
+    torch.cuda.synchronize()
+    assert torch.all(dw == 5.0) and torch.all(db == 7.0)
+    conv.conv_backward_filter_bias(d, x, y, dw, db, 0.0, ws)
     torch.cuda.synchronize()
     assert torch.all(dw == 0.0) and torch.all(db == 0.0)
 

@@ -137,6 +137,12 @@ VARIANT_CASES = [
     (P(8, 1, 24, 25, 200, 6, 6, 1, 1, 2, 2), "fwd", "corr_m16_16x256x16[m1"),
     (P(33, 1, 9, 10, 200, 3, 3, 1, 1, 2, 2), "fwd", "corr_m16_16x256x16[m2"),
     (P(100, 1, 24, 25, 1, 6, 6), "bwd_data", "corr_m16_16x256x16[m1"),
+    (P(8, 4, 48, 49, 128, 3, 3, 1, 1, 1, 1), "fwd", "corr_m32_128x128x16[m2"),
+    (P(64, 1, 28, 28, 20, 5, 5), "fwd", "corr_m32_32x256x16[m0"),
+    (P(100, 3, 32, 32, 32, 5, 5, 1, 1, 2, 2), "fwd", "corr_m32_32x256x16[m2"),
+    (P(1, 18, 28, 35, 54, 6, 7, 3, 4, 5, 1, 2, 2, 2), "fwd", "corr_m32_32x128x16[m1"),
+    (P(90, 8, 24, 25, 3, 3, 3, 1, 1, 1, 1), "bwd_data", "corr_m16_16x256x16[m2"),
+    (P(2, 3, 7, 6, 60, 3, 3, 2, 2, 1, 1), "fwd", "corr_m32_64x64x16[m2"),
     (P(1, 8, 5, 6, 128, 3, 3), "bwd_filter", "wgrad_m32_128x128x32[m0"),
     (P(1, 3, 5, 6, 128, 6, 6, 2, 2, 3, 3), "bwd_filter", "wgrad_m32_128x128x32[m1"),
     (P(1, 3, 5, 6, 96, 6, 6, 2, 2, 3, 3), "bwd_filter", "wgrad_m32_96x128x32[m1"),

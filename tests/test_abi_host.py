@@ -110,8 +110,10 @@ def test_null_arguments_and_status_strings():
     assert lib.conv_backward_filter_bias(db_ok.handle, 16, 16, 16, 16, 2.0, 16, 1 << 20, None) == binding.CONV_EINVAL
     assert lib.conv_backward_filter_bias(db_ok.handle, 16, 16, 16, 16, 0.0, None, 0, None) == binding.CONV_EWORKSPACE
     # workspace missing / too small is detected before anything is enqueued
-    assert lib.conv_forward(d.handle, 16, 16, None, 16, None, 0, None) == binding.CONV_EWORKSPACE
-    assert lib.conv_backward_data(d.handle, 16, 16, 16, 16, 4, None) == binding.CONV_EWORKSPACE
+    # (a layer large enough to pack its weights into the workspace first; small ones read them directly)
+    big = conv.conv_desc_create(conv.ConvParams(64, 256, 16, 16, 256, 3, 3, bias_term=0))
+    assert lib.conv_forward(big.handle, 16, 16, None, 16, None, 0, None) == binding.CONV_EWORKSPACE
+    assert lib.conv_backward_data(big.handle, 16, 16, 16, 16, 4, None) == binding.CONV_EWORKSPACE
     assert lib.conv_backward_filter(d.handle, 16, 16, 16, 1.0, None, 0, None) == binding.CONV_EWORKSPACE
     for s in (0, -1, -2, -3, -4, -99):
         assert conv.conv_status_string(s)
@@ -206,9 +208,11 @@ def test_ip_null_arguments_and_flags():
     assert lib.ip_forward(d.handle, fake, fake, fake, fake, None, 0, None) == binding.CONV_EWORKSPACE
     assert lib.ip_relu_backward(d.handle, None, fake, fake, None) == binding.CONV_EINVAL               # relu needs y
     assert lib.ip_backward_data(d.handle, fake, None, fake, None, 0, None) == binding.CONV_EINVAL
-    assert lib.ip_backward_data(d.handle, fake, fake, fake, None, 0, None) == binding.CONV_EWORKSPACE
+    # (a layer large enough for its gather passes to pack their weights into the workspace first)
+    big = conv.ip_desc_create(conv.IpParams(128, 4096, 4096, 1, 1))
+    assert lib.ip_backward_data(big.handle, fake, fake, fake, None, 0, None) == binding.CONV_EWORKSPACE
     assert lib.ip_backward_filter(d.handle, fake, fake, fake, 0.5, fake, 1 << 20, None) == binding.CONV_EINVAL
-    assert lib.ip_backward_filter(d.handle, fake, fake, fake, 1.0, None, 0, None) == binding.CONV_EWORKSPACE
+    assert lib.ip_backward_filter(big.handle, fake, fake, fake, 1.0, None, 0, None) == binding.CONV_EWORKSPACE
     assert lib.ip_backward_bias(dn.handle, fake, fake, 0.0, fake, 1 << 20, None) == binding.CONV_EINVAL
     assert lib.ip_backward_bias(d.handle, fake, fake, 0.0, None, 0, None) == binding.CONV_EWORKSPACE
     assert lib.ip_desc_workspace_bytes(None, None) == binding.CONV_EINVAL

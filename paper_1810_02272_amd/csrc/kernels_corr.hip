@@ -200,17 +200,6 @@ __global__ __launch_bounds__(kThreads) void corr_kernel(const CorrArgs a) {
   auto store_b = [&](f32x4(&rb)[CPL], int buf, int q) {
     *reinterpret_cast<f32x4*>(smem + buf * C::STAGE + BM * LDK + (q * 64 + lane) * LDK + (wv ^ bswz) * 4) = rb[q];
   };
-  auto load_all = [&](f32x4(&ra)[C::A_PER], f32x4(&rb)[CPL], int kc) {
-    load_tab(kc);
-    swap_tab();
-#pragma unroll
-    for (int p = 0; p < C::A_PER; ++p) load_a(ra, kc, p);
-#pragma unroll
-    for (int q = 0; q < CPL; ++q)
-#pragma unroll
-      for (int e = 0; e < RPW; ++e) load_b(rb, q, e);
-  };
-
   // Software pipeline, four chunks deep: while the MFMA pipe works on chunk k out of one LDS buffer,
   // the register set holding chunk k+1 (loaded two iterations ago) is written to the other buffer
   // and immediately reloaded with chunk k+3; the other register set holds chunk k+2 meanwhile.
@@ -230,13 +219,30 @@ __global__ __launch_bounds__(kThreads) void corr_kernel(const CorrArgs a) {
   const float* opA = smem + (wm * MB * MT + lane % MT) * LDK + ((lane / MT) ^ oswz) * 4;
   const float* opB = smem + BM * LDK + (wn * NB * MT + lane % MT) * LDK + ((lane / MT) ^ oswz) * 4;
 
-  load_all(raX, rbX, 0);
+  // Prologue: the table entries of the first three chunks are requested together (one scalar-memory
+  // round trip instead of three in a row), then each chunk's operand loads use its own entries.
+  KTabEntry first[3][RPW];
+#pragma unroll
+  for (int c = 0; c < 3; ++c)
+#pragma unroll
+    for (int e = 0; e < RPW; ++e) first[c][e] = a.ktab[(kc_first + (last < c ? last : c)) * BK + wv * RPW + e];
+  auto load_first = [&](f32x4(&ra)[C::A_PER], f32x4(&rb)[CPL], int c) {
+#pragma unroll
+    for (int e = 0; e < RPW; ++e) te[e] = first[c][e];
+#pragma unroll
+    for (int p = 0; p < C::A_PER; ++p) load_a(ra, last < c ? last : c, p);
+#pragma unroll
+    for (int q = 0; q < CPL; ++q)
+#pragma unroll
+      for (int e = 0; e < RPW; ++e) load_b(rb, q, e);
+  };
+  load_first(raX, rbX, 0);
 #pragma unroll
   for (int p = 0; p < C::A_PER; ++p) store_a(raX, 0, p);
 #pragma unroll
   for (int q = 0; q < CPL; ++q) store_b(rbX, 0, q);
-  load_all(raX, rbX, last < 1 ? last : 1);
-  load_all(raY, rbY, last < 2 ? last : 2);
+  load_first(raX, rbX, 1);
+  load_first(raY, rbY, 2);
   load_tab(last < 3 ? last : 3);
   __syncthreads();
 

@@ -385,11 +385,21 @@ __global__ __launch_bounds__(256) void reduce_kernel(const ReduceArgs a) {
   for (int c = 0; c < 4; ++c)
 #pragma unroll
     for (int e = 0; e < V; ++e) acc[c].v[e] = 0.f;
+  constexpr int U = V == 1 ? 16 : 4;  // loads in flight per lane: a long run of slices is latency-bound
   const int total = a.count + a.count2;
   const size_t stride = a.stride ? (size_t)a.stride : (size_t)a.count;
   if (i < total) {
     const float* src = a.part + i;
     int k = s0;
+    for (; k + U - 1 < s1; k += U) {
+      Vec x[U];
+#pragma unroll
+      for (int c = 0; c < U; ++c) x[c] = *reinterpret_cast<const Vec*>(src + (size_t)(k + c) * stride);
+#pragma unroll
+      for (int c = 0; c < U; ++c)
+#pragma unroll
+        for (int e = 0; e < V; ++e) acc[c & 3].v[e] += x[c].v[e];
+    }
     for (; k + 3 < s1; k += 4) {
       Vec x[4];
 #pragma unroll

@@ -83,10 +83,11 @@ def test_extended_random_sweep():
     budget = float(os.environ["MI355CONV_SOAK_SECONDS"])
     rng = np.random.default_rng(int(os.environ.get("MI355CONV_SOAK_SEED", "987654")))
     gens = [random_params, random_thin_group_params, random_multi_tile_params]
-    t0, i = time.time(), 0
+    t0, i, told = time.time(), 0, 0.0
     while time.time() - t0 < budget:
         pd = gens[i % 3](rng)
-        if i % 1000 == 0:
+        if time.time() - told > 20.0:   # a progress line every 20 s (run with -s: a silent run looks hung)
+            told = time.time()
             print("extended sweep case", i, pd, flush=True)
         try:
             check_both_types(pd, 900000 + i)
@@ -102,7 +103,7 @@ def test_extended_random_sweep():
 def test_extended_random_inner_product_sweep(capsys):
     budget = float(os.environ["MI355CONV_SOAK_SECONDS"])
     rng = np.random.default_rng(int(os.environ.get("MI355CONV_SOAK_SEED", "987654")) + 1)
-    t0, i = time.time(), 0
+    t0, i, told = time.time(), 0, time.time()
     while time.time() - t0 < budget:
         m, k, o = int(rng.integers(1, 300)), int(rng.integers(1, 1500)), int(rng.integers(1, 600))
         if rng.integers(0, 3) == 0:   # small shapes: single tiles, short reductions
@@ -118,6 +119,10 @@ def test_extended_random_inner_product_sweep(capsys):
             raise
         capsys.readouterr()   # drop the per-case lines of the cases that passed
         i += 1
+        if time.time() - told > 20.0:
+            told = time.time()
+            with capsys.disabled():
+                print("extended inner-product sweep: case", i, flush=True)
     with capsys.disabled():
         print("extended inner-product sweep:", i, "cases", flush=True)
 
@@ -127,7 +132,7 @@ def test_extended_random_inner_product_sweep(capsys):
 def test_extended_random_policy_gradient_sweep(capsys):
     budget = float(os.environ["MI355CONV_SOAK_SECONDS"])
     rng = np.random.default_rng(int(os.environ.get("MI355CONV_SOAK_SEED", "987654")) + 2)
-    t0, i = time.time(), 0
+    t0, i, told = time.time(), 0, time.time()
     while time.time() - t0 < budget:
         while True:
             episodes, lo, actions = int(rng.integers(1, 300)), int(rng.integers(0, 40)), int(rng.integers(2, 130))
@@ -143,6 +148,10 @@ def test_extended_random_policy_gradient_sweep(capsys):
             raise
         capsys.readouterr()
         i += 1
+        if time.time() - told > 20.0:
+            told = time.time()
+            with capsys.disabled():
+                print("extended policy-gradient sweep: case", i, flush=True)
     with capsys.disabled():
         print("extended policy-gradient sweep:", i, "cases", flush=True)
 

@@ -89,8 +89,11 @@ __global__ __launch_bounds__(kThreads) void corr_patch_kernel(const CorrArgs a) 
     patch_elems = (patch_row_base(n, pa) + TH) * (uint32_t)a.PWID;
   }
 
-  // ---- per-lane B columns: byte address of (column, channel CPG*h + u) inside a patch stage --
-  uint32_t lanebase[NB][CPG];
+  // ---- per-lane B columns: byte address of (column, channels CPG*h .. CPG*h + CPG-1) inside a patch
+  // stage.  A stage is [lane group h][position][CPG channels]: the CPG channels one lane multiplies at a
+  // super step sit side by side, so its B operands are one 8- or 16-byte read, and 16 (or 32)
+  // consecutive columns of a lane group are one contiguous run of LDS.
+  uint32_t lanebase[NB];
 #pragma unroll
   for (int j = 0; j < NB; ++j) {
     uint32_t col = col0 + (wn * NB + j) * MT + lane % MT;
@@ -100,9 +103,7 @@ __global__ __launch_bounds__(kThreads) void corr_patch_kernel(const CorrArgs a) 
     const uint32_t pa = mdiv(pix, a.mPW);
     const uint32_t pb = pix - pa * a.PW;
     const uint32_t cb = patch_row_base(n, pa) * (uint32_t)a.PWID + pb;
-#pragma unroll
-    for (int u = 0; u < CPG; ++u)
-      lanebase[j][u] = patch_bytes0 + 4u * (cb + (uint32_t)(CPG * (lane / MT) + u) * (uint32_t)a.PSZ);
+    lanebase[j] = patch_bytes0 + 4u * (uint32_t)CPG * (cb + (uint32_t)(lane / MT) * (uint32_t)a.PSZ);
   }
 
   // ---- per-thread patch elements: where they come from (relative to channel 0 of the group) --
@@ -143,10 +144,15 @@ __global__ __launch_bounds__(kThreads) void corr_patch_kernel(const CorrArgs a) 
   auto patch_store = [&](int buf) {
     float* dst = smem + 2 * C::ASTAGE + buf * 8 * a.PSZ;
 #pragma unroll
-    for (int c8 = 0; c8 < 8; ++c8)
+    for (int h = 0; h < C::LG; ++h)
 #pragma unroll
       for (int r = 0; r < EPT; ++r)
-        if (t + r * kThreads < (uint32_t)a.PSZ) dst[c8 * a.PSZ + t + r * kThreads] = pr[c8][r];
+        if (t + r * kThreads < (uint32_t)a.PSZ) {
+          vec_a v;
+#pragma unroll
+          for (int u = 0; u < CPG; ++u) v[u] = pr[CPG * h + u][r];
+          *reinterpret_cast<vec_a*>(dst + (h * a.PSZ + t + r * kThreads) * CPG) = v;
+        }
   };
 
   // ---- A tile staging: as in corr_kernel ([row][k], 16 bytes per lane, four chunks deep) -----
@@ -207,13 +213,11 @@ __global__ __launch_bounds__(kThreads) void corr_patch_kernel(const CorrArgs a) 
 #pragma unroll
     for (int ssl = 0; ssl < 2; ++ssl) {
       if (sg < a.NS) {  // the last chunk of an odd number of super steps has only one
-        const uint32_t soff = (uint32_t)(cc & 1) * stage_bytes + 4u * (uint32_t)(ti * a.PWID + tj);
-        float bv[NB][CPG];
+        const uint32_t soff = (uint32_t)(cc & 1) * stage_bytes + 4u * (uint32_t)CPG * (uint32_t)(ti * a.PWID + tj);
+        vec_a bv[NB];
 #pragma unroll
         for (int j = 0; j < NB; ++j)
-#pragma unroll
-          for (int u = 0; u < CPG; ++u)
-            bv[j][u] = *reinterpret_cast<const float*>(reinterpret_cast<const char*>(smem) + (lanebase[j][u] + soff));
+          bv[j] = *reinterpret_cast<const vec_a*>(reinterpret_cast<const char*>(smem) + (lanebase[j] + soff));
 #pragma unroll
         for (int u = 0; u < CPG; ++u) {
 #pragma unroll

@@ -2,6 +2,7 @@
 // workspace sizing and the five entry points.  No device memory is allocated anywhere here, and
 // conv_desc_create touches no device at all (it also runs on machines without a GPU).
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <new>
@@ -175,9 +176,9 @@ void corr_variant_name(char* buf, size_t len, int32_t tile, const CorrArgs& a, i
 
 uint32_t koff_invalid(int32_t mode) { return mode == 0 ? 0x7FFFFFFCu : mode == 2 ? 0x40000000u : 0u; }
 
-// Decides whether the patch-staged kernel can run this correlation and, if so, fills its fields.
-// Used for the 256-column tiles of the 16-row MFMA, where the gather kernel's per-element work is
-// largest (measured: 5x5 grouped backward-data +9 %; equal or slower on 128-column tiles).
+// Decides whether the patch-staged kernel runs this correlation and, if so, fills its fields.
+// Used where the gather kernel's per-element work is largest: the 256-column tiles of at most 48 rows
+// (measured: 5x5 grouped backward-data +9 %), and two 128-column tiles for kernels of 25 taps or more.
 // Needs a stride-1, dilation-1 gather, 8-aligned channels per group, at least 3 taps, a blob of at
 // most 2^30 bytes, and a patch that fits kPatchEPT*256 floats per channel and the LDS.
 void configure_patch(CorrArgs& a, PackArgs& k, int64_t cg_in, int64_t n_img, int32_t bm, int32_t bn) {
@@ -185,7 +186,13 @@ void configure_patch(CorrArgs& a, PackArgs& k, int64_t cg_in, int64_t n_img, int
   k.kperm_T = 0;
   const int64_t T = a.THW, TH = a.THW / a.TW;
   if (a.sh != 1 || a.sw != 1 || a.dh != 1 || a.dw != 1 || cg_in % 8 != 0 || T < 3) return;
-  if (!(bn == 256 && bm <= 48)) return;
+  // 256-column tiles of at most 48 rows; with 25 taps or more also the 128x128 and 32x128 tiles, on grids
+  // that the gather kernel would not split (measured with 5x5 kernels: 128x128 forward 451 -> 443 us,
+  // 32x128 38 -> 34 us; with 3x3 kernels the gather kernel stays ahead, 298 -> 305 us)
+  const bool wide = bn == 256 && bm <= 48;
+  const bool many_taps = T >= 25 && bn == 128 && (bm == 128 || bm == 32) &&
+                         (int64_t)a.G * a.m_tiles * a.col_tiles > 160;
+  if (!wide && !many_taps) return;
   if ((int64_t)a.in_bytes > ((int64_t)1 << 30) || a.ncols < 1) return;
   const int64_t PH = a.P / a.PW, PWID = a.PW + a.TW - 1, RS = PH + TH - 1;
   // largest patch over all column tiles

@@ -1,9 +1,10 @@
 // Patch-staged implicit-GEMM correlation kernel for gfx950: a variant of corr_kernel for
 // stride-1, dilation-1 gathers whose channel count per group is a multiple of 8 (forward of such
 // layers, and every backward-data pass, which is always a stride-1 correlation over dy).  It is
-// selected where the gather kernel spends the most per gathered element -- the 16-row-MFMA tiles
-// of 256 columns (e.g. the 48-row backward-data GEMM of a grouped 5x5 layer); elsewhere the
-// gather kernel measured equal or faster.
+// selected where the gather kernel spends the most per gathered element -- the 256-column tiles of
+// at most 48 rows (e.g. the 48-row backward-data GEMM of a grouped 5x5 layer) -- and, for kernels of
+// 25 taps or more (every patch element is then used 25 times), on the 128x128 and 32x128 tiles;
+// elsewhere the gather kernel measured equal or faster.
 //
 //   D[m][col] = sum_k A[m][k] * in[n, g*Cg + c, a - ph + i, b - pw + j],  k = (c, i, j), col = (n, a, b)
 //
@@ -279,8 +280,10 @@ int launch_patch_t(const CorrArgs& a, hipStream_t s) {
 
 int launch_corr_patch(int32_t tile, const CorrArgs& a, void* stream) {
   hipStream_t s = (hipStream_t)stream;
-  switch (tile) {  // the 256-column tiles of at most 48 rows (see configure_patch)
+  switch (tile) {  // the tiles configure_patch (api.cpp) may select
     //                                       MT MB NB WM WN
+    case CORR_128x128: return launch_patch_t<32, 2, 2, 2, 2>(a, s);
+    case CORR_32x128:  return launch_patch_t<32, 1, 1, 1, 4>(a, s);
     case CORR_32x256:  return launch_patch_t<32, 1, 2, 1, 4>(a, s);
     case CORR_48x256:  return launch_patch_t<16, 3, 4, 1, 4>(a, s);
     case CORR_16x256:  return launch_patch_t<16, 1, 4, 1, 4>(a, s);

@@ -83,9 +83,9 @@ DIRECT_CASES = [
     P(2, 16, 9, 10, 2, 3, 3, 2, 2, 1, 0, 1, 1, 2),             # eight channels in, one out per group
 ]
 
-# Shapes that select the patch-staged kernel (256-column tiles of at most 48 rows): 8-aligned
-# reduction channels, enough columns for the wide tile to win and for the grid not to want a split
-# reduction.  (parameters, pass, the variant that pass must select)
+# Shapes that select the patch-staged kernel (256-column tiles of at most 48 rows; 128x128 and 32x128
+# tiles for kernels of 25 taps or more): 8-aligned reduction channels, enough columns for the tile to win
+# and for the grid not to want a split reduction.  (parameters, pass, the variant that pass must select)
 PATCH_CASES = [
     (P(20, 48, 60, 45, 16, 5, 5, 1, 1, 2, 2), "bwd_data", "corr_m16_48x256x16_patch[es]"),  # 5x5, one image per many tiles
     (P(400, 96, 9, 9, 16, 3, 3, 1, 1, 1, 1, 1, 1, 2), "bwd_data", "corr_m16_48x256x16_patch[es]"),  # grouped, tiles span 4 images
@@ -97,6 +97,13 @@ PATCH_CASES = [
     (P(100, 1, 48, 47, 8, 3, 3, 2, 2, 1, 1), "bwd_data", "corr_m16_16x256x16_patch[er]"),   # 16-row tile, sub-pixel scatter
     (P(64, 12, 48, 49, 8, 3, 3, 2, 2, 1, 1), "bwd_data", "corr_m16_48x256x16_patch[er]"),   # 48 rows = 12 channels x 4 phases
     (P(33, 20, 32, 33, 8, 3, 3, 1, 1, 1, 1), "bwd_data", "corr_m32_32x256x16_patch[es]"),   # 32-row tile at stride 1
+    # kernels of 25 taps or more also take it on the 128x128 and 32x128 tiles (grids of more than 160 tiles)
+    (P(24, 8, 30, 30, 128, 5, 5, 1, 1, 2, 2), "fwd", "corr_m32_128x128x16_patch[es]"),
+    (P(24, 128, 30, 30, 8, 5, 5, 1, 1, 2, 2), "bwd_data", "corr_m32_128x128x16_patch[es]"),
+    (P(48, 32, 41, 41, 8, 9, 9, 2, 2, 4, 4), "bwd_data", "corr_m32_128x128x16_patch[er]"),  # 9x9 at stride 2: 5x5 slots
+    (P(100, 8, 16, 16, 32, 5, 5, 1, 1, 2, 2), "fwd", "corr_m32_32x128x16_patch[es]"),
+    (P(100, 32, 16, 16, 8, 5, 5, 1, 1, 2, 2), "bwd_data", "corr_m32_32x128x16_patch[es]"),
+    (P(48, 8, 41, 41, 8, 9, 9, 2, 2, 4, 4), "bwd_data", "corr_m32_32x128x16_patch[er]"),
 ]
 
 # One cheap shape per (pass, tile, bounds mode) of the gather kernel and per (tile, bounds mode) of the

@@ -15,7 +15,8 @@ import parity_cases as pc
 CORR_TILES = ["corr_m32_128x128x16", "corr_m32_128x64x16", "corr_m32_96x128x16", "corr_m32_64x128x16",
               "corr_m32_64x64x16", "corr_m32_32x256x16", "corr_m32_32x128x16", "corr_m16_48x256x16",
               "corr_m16_48x128x16", "corr_m16_16x256x16", "corr_m16_16x64x16"]
-PATCH_TILES = ["corr_m32_32x256x16", "corr_m16_48x256x16", "corr_m16_16x256x16"]
+PATCH_TILES = ["corr_m32_128x128x16", "corr_m32_32x128x16", "corr_m32_32x256x16", "corr_m16_48x256x16",
+               "corr_m16_16x256x16"]
 WGRAD_TILES = ["wgrad_m32_128x128x32", "wgrad_m32_96x128x32", "wgrad_m32_64x128x32", "wgrad_m32_32x128x32",
                "wgrad_m32_128x64x32"]
 F64_ROWS = [96, 64, 48, 32, 16]
@@ -66,7 +67,7 @@ def test_every_patch_tile_has_a_gpu_parity_case(selected):
     fwd, bwd = selected["fp32"]["fwd"], selected["fp32"]["bwd_data"]
     assert missing(fwd, [f"{t}_patch[es]" for t in PATCH_TILES]) == []      # forward: one phase per channel
     assert missing(bwd, [f"{t}_patch[e{e}]" for t in PATCH_TILES for e in "sr"]) == []
-    # no other tile may take the patch kernel: it is built for these three only
+    # no other tile may take the patch kernel: it is built for these five only
     for v in list(fwd) + list(bwd):
         if "_patch" in v:
             assert v.split("_patch")[0] in PATCH_TILES, v

@@ -403,10 +403,7 @@ int run_backward_filter(const conv_desc* d, const float* x, const float* dy, flo
     a.S = da.S;
     if (!empty) e = launch_direct(2, da, false, hip_stream);
   } else if (!empty) {
-    if (db) {  // row sums of dy ride along: a slice is the filter partials followed by num_output sums
-      a.part_stride = w_elems + d->p.num_output;
-      a.bias_part = a.part + w_elems;
-    }
+    if (db) a.bias_part = a.part + (size_t)a.S * w_elems;  // row sums of dy ride along, behind the filter partials
     e = launch_wgrad(d->wg_tile, a, hip_stream);
   }
   if (e) return record_hip_error(e);
@@ -422,10 +419,11 @@ int run_backward_filter(const conv_desc* d, const float* x, const float* dy, flo
   r.mChanElems = make_magic(r.chan_elems);
   r.mChannels = make_magic(r.channels);
   r.relu = extras.relu;
-  if (db && (empty || !d->use_direct)) {
-    r.stride = w_elems + d->p.num_output;
+  if (db && (empty || !d->use_direct)) {  // the same launch finishes db from the S * n_tiles shares of the row sums
+    r.part2 = empty ? nullptr : a.bias_part;
     r.dst2 = db;
     r.count2 = d->p.num_output;
+    r.S2 = empty ? 0 : a.S * a.n_tiles;
   }
   e = launch_reduce(r, hip_stream);
   if (e) return record_hip_error(e);
@@ -732,8 +730,8 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
     a.part_stride = (int32_t)w_elems;
     a.bias_part = nullptr;
     d->wg_ws = (size_t)a.S * (size_t)w_elems * 4;
-    d->wgb_ws = (size_t)a.S * (size_t)(w_elems + K) * 4;
-    if (a.S * (w_elems + K) >= kMaxElems) {
+    d->wgb_ws = (size_t)a.S * (size_t)(w_elems + a.n_tiles * K) * 4;
+    if (a.S * (w_elems + a.n_tiles * K) >= kMaxElems) {
       delete d;
       return CONV_ESHAPE;
     }

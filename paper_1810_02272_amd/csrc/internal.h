@@ -138,20 +138,25 @@ struct WgradArgs {
   int32_t Kred;
   int32_t cols_per_split, S;
   int32_t G, m_tiles, n_tiles;
-  // Elements between the partial slices of two splits (G*Kg*Kred, plus Ktot when the bias gradient
-  // rides along) and, for that case, where the row sums of dy go: bias_part[s*part_stride + g*Kg + k]
-  // = sum of dy[., g*Kg + k, .] over the split's columns (null: not wanted).
+  // Elements between the partial slices of two splits (G*Kg*Kred).
   int32_t part_stride;
+  // Bias gradient riding along (null: not wanted): the row sums of dy.  Every workgroup adds up the dy
+  // tiles of the chunks ch with ch % n_tiles == its n_tile, so the work is spread over all column
+  // tiles: bias_part[(s*n_tiles + n_tile)*Ktot + g*Kg + k] = that share of the sum of
+  // dy[., g*Kg + k, .] over the split's columns.
   float* bias_part;
 };
 
 struct ReduceArgs {
-  const float* part;  // [S][stride]: elements [0, count) of a slice go to dst, [count, count + count2) to dst2
+  const float* part;  // [S][stride]: elements [0, count) of a slice go to dst
   float* dst;         // [count]
   int32_t count, S;
   int32_t stride;     // elements between slices (0: count)
-  float* dst2;        // [count2] second destination with the same beta (filter + bias gradient in one launch)
-  int32_t count2;
+  // second reduction of the same launch with the same beta (filter + bias gradient together):
+  // dst2[count2] from part2[S2][count2]; the workgroups past the first reduction's take it
+  const float* part2;
+  float* dst2;
+  int32_t count2, S2;
   float beta;
   // optional per-channel bias for blobs laid out [..][channel][chan_elems]: dst += bias[(i / chan_elems) % channels]
   const float* bias;

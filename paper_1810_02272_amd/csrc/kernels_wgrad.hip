@@ -204,11 +204,14 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradArgs a) {
   const float* opA = smem + C::row_off(wm * MB * 32 + (lane & 31)) + (lane >> 5) * 4;
   const float* opB = smem + C::A_FLOATS + C::row_off(wn * NB * 32 + (lane & 31)) + (lane >> 5) * 4;
   constexpr int BLK = C::row_off(32);  // floats between 32-row blocks
-  // Bias gradient from the same read of dy: the waves that own the first column block of the first
-  // column tile add up the dy operands they read for the MFMAs -- lanes l and l + 32 of such a wave
-  // together read every element of row l of a chunk, exactly once.  Columns past the split read as
-  // zero; rows past the matrix edge are never stored.
-  const bool row_sums = a.bias_part != nullptr && n_tile == 0 && wn == 0;
+  // Bias gradient from the same read of dy: the waves that own a workgroup's first column block add up
+  // the dy operands they read for the MFMAs -- lanes l and l + 32 of such a wave together read every
+  // element of row l of a chunk, exactly once.  The column tiles share the work: tile n_tile takes the
+  // chunks ch with ch % n_tiles == n_tile (every column tile of a split stages the same dy rows), and
+  // the reduce kernel adds the n_tiles shares.  Columns past the split read as zero; rows past the
+  // matrix edge are never stored.
+  const bool row_sums = a.bias_part != nullptr && wn == 0;
+  int my_chunk = (int)n_tile;  // the next chunk whose dy tile this workgroup sums
   float bsum[MB];
 #pragma unroll
   for (int i = 0; i < MB; ++i) bsum[i] = 0.f;
@@ -257,10 +260,11 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradArgs a) {
       for (int i = 0; i < MB; ++i)
 #pragma unroll
         for (int j = 0; j < NB; ++j) M::run(av[ss & 1][i][u], bv[ss & 1][j][u], acc[i][j]);
-      if (u == 3 && row_sums) {
+      if (u == 3 && row_sums && ch == my_chunk) {
 #pragma unroll
         for (int i = 0; i < MB; ++i)
           bsum[i] += (av[ss & 1][i][0] + av[ss & 1][i][1]) + (av[ss & 1][i][2] + av[ss & 1][i][3]);
+        if (ss == NSS - 1) my_chunk += a.n_tiles;
       }
       if (DMA) {
         // this step's share of the loads of chunk ch+1, all issued in the first half of the chunk so
@@ -301,7 +305,8 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradArgs a) {
     for (int i = 0; i < MB; ++i) {
       const float total = bsum[i] + __shfl_xor(bsum[i], 32);
       const uint32_t k = m_tile * BM + (wm * MB + i) * 32 + (lane & 31);
-      if (lane < 32 && k < (uint32_t)a.Kg) a.bias_part[(size_t)split * a.part_stride + g * a.Kg + k] = total;
+      if (lane < 32 && k < (uint32_t)a.Kg)
+        a.bias_part[((size_t)split * a.n_tiles + n_tile) * a.Ktot + g * a.Kg + k] = total;
     }
   }
 
@@ -375,21 +380,25 @@ __global__ __launch_bounds__(256) void reduce_kernel(const ReduceArgs a) {
   };
   __shared__ Vec quarter[4][64];
   const int lane = threadIdx.x & 63, q = threadIdx.x >> 6;
-  const int i = (blockIdx.x * 64 + lane) * V;
-  const int per = (a.S + 3) / 4;
+  // workgroups past those of the first reduction take the second one (uniform per workgroup)
+  const int blocks1 = (a.count / V + 63) / 64;
+  const bool second = (int)blockIdx.x >= blocks1;
+  const int i = (((int)blockIdx.x - (second ? blocks1 : 0)) * 64 + lane) * V;
+  const int S = second ? a.S2 : a.S;
+  const int per = (S + 3) / 4;
   const int s0 = q * per;
   int s1 = s0 + per;
-  if (s1 > a.S) s1 = a.S;
+  if (s1 > S) s1 = S;
   Vec acc[4];
 #pragma unroll
   for (int c = 0; c < 4; ++c)
 #pragma unroll
     for (int e = 0; e < V; ++e) acc[c].v[e] = 0.f;
   constexpr int U = V == 1 ? 16 : 4;  // loads in flight per lane: a long run of slices is latency-bound
-  const int total = a.count + a.count2;
-  const size_t stride = a.stride ? (size_t)a.stride : (size_t)a.count;
+  const int total = second ? a.count2 : a.count;
+  const size_t stride = second ? (size_t)a.count2 : a.stride ? (size_t)a.stride : (size_t)a.count;
   if (i < total) {
-    const float* src = a.part + i;
+    const float* src = (second ? a.part2 : a.part) + i;
     int k = s0;
     for (; k + U - 1 < s1; k += U) {
       Vec x[U];
@@ -422,9 +431,8 @@ __global__ __launch_bounds__(256) void reduce_kernel(const ReduceArgs a) {
   __syncthreads();
   if (q == 0 && i < total) {
     Vec out, old;
-    // the second destination takes the elements past `count` (both counts are multiples of V)
-    float* const dst = i < a.count ? a.dst + i : a.dst2 + (i - a.count);
-    const bool first = i < a.count;
+    float* const dst = (second ? a.dst2 : a.dst) + i;
+    const bool first = !second;
     if (a.beta != 0.f) old = *reinterpret_cast<const Vec*>(dst);
 #pragma unroll
     for (int e = 0; e < V; ++e) {
@@ -474,14 +482,15 @@ int launch_wgrad(int32_t tile, const WgradArgs& a, void* stream) {
 
 int launch_reduce(const ReduceArgs& a, void* stream) {
   // the four-element form needs enough elements to keep a thousand workgroups busy
-  const int total = a.count + a.count2;
   const bool vec = a.count >= (1 << 18) && a.count % 4 == 0 && a.count2 % 4 == 0 && a.stride % 4 == 0 &&
                    ((reinterpret_cast<uintptr_t>(a.part) | reinterpret_cast<uintptr_t>(a.dst) |
-                     reinterpret_cast<uintptr_t>(a.dst2)) & 15u) == 0;
+                     reinterpret_cast<uintptr_t>(a.part2) | reinterpret_cast<uintptr_t>(a.dst2)) & 15u) == 0;
   if (vec)
-    hipLaunchKernelGGL(reduce_kernel<4>, dim3((total / 4 + 63) / 64), dim3(256), 0, (hipStream_t)stream, a);
+    hipLaunchKernelGGL(reduce_kernel<4>, dim3((a.count / 4 + 63) / 64 + (a.count2 / 4 + 63) / 64), dim3(256), 0,
+                       (hipStream_t)stream, a);
   else
-    hipLaunchKernelGGL(reduce_kernel<1>, dim3((total + 63) / 64), dim3(256), 0, (hipStream_t)stream, a);
+    hipLaunchKernelGGL(reduce_kernel<1>, dim3((a.count + 63) / 64 + (a.count2 + 63) / 64), dim3(256), 0,
+                       (hipStream_t)stream, a);
   return (int)hipGetLastError();
 }
 

@@ -40,8 +40,8 @@ def parse():
     ap.add_argument("--dtype", default="f32", choices=["f32", "f64"],
                     help="base type of the convolution workloads (f64: the conv_*_f64 entry points)")
     ap.add_argument("--no-cpu-baseline", action="store_true",
-                    help="skip the context legs after the timed steps (the CPU oracle timing and the two-stream "
-                         "schedule): what runs under the profiler")
+                    help="skip the context legs after the timed steps (the small-layer table, the CPU oracle timing "
+                         "and the two-stream schedule): what runs under the profiler")
     ap.add_argument("--cpu-sample-images", type=int, default=128)
     ap.add_argument("--cold-cache", action="store_true",
                     help="rotate every step among enough distinct sets of tensors that one pass over all sets "
@@ -449,7 +449,7 @@ def main():
         "per_layer": per_layer,
     }
 
-    if args.workload == "config4" and not f64 and not args.cold_cache:
+    if args.workload == "config4" and not f64 and not args.cold_cache and not args.no_cpu_baseline:
         # The eight layer shapes of configurations 0-3, from steps of their own outside the timed region:
         # they are launch-latency bound (microseconds of work per pass), so each pass is given with its
         # launch count and its time over that many empty dispatches, next to both roofline fractions.

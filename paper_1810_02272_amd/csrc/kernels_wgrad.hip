@@ -204,14 +204,16 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradArgs a) {
   const float* opA = smem + C::row_off(wm * MB * 32 + (lane & 31)) + (lane >> 5) * 4;
   const float* opB = smem + C::A_FLOATS + C::row_off(wn * NB * 32 + (lane & 31)) + (lane >> 5) * 4;
   constexpr int BLK = C::row_off(32);  // floats between 32-row blocks
-  // Bias gradient from the same read of dy: the waves that own a workgroup's first column block add up
-  // the dy operands they read for the MFMAs -- lanes l and l + 32 of such a wave together read every
-  // element of row l of a chunk, exactly once.  The column tiles share the work: tile n_tile takes the
-  // chunks ch with ch % n_tiles == n_tile (every column tile of a split stages the same dy rows), and
-  // the reduce kernel adds the n_tiles shares.  Columns past the split read as zero; rows past the
-  // matrix edge are never stored.
-  const bool row_sums = a.bias_part != nullptr && wn == 0;
-  int my_chunk = (int)n_tile;  // the next chunk whose dy tile this workgroup sums
+  // Bias gradient from the same read of dy: a wave adds up the dy operands it reads for its MFMAs --
+  // lanes l and l + 32 together read every element of row l of a chunk, exactly once.  The work is
+  // shared out: every column tile of a split stages the same dy rows, and so do the WN waves of a
+  // workgroup that own one row block, so wave wn of column tile n_tile takes the chunks ch with
+  // ch % (n_tiles*WN) == n_tile*WN + wn.  The WN waves are added through LDS at the end (in wave
+  // order) and the reduce kernel adds the n_tiles shares.  Columns past the split read as zero; rows
+  // past the matrix edge are never stored.
+  const bool row_sums = a.bias_part != nullptr;
+  const int chunk_step = a.n_tiles * WN;
+  int my_chunk = (int)n_tile * WN + wn;  // the next chunk whose dy tile this wave sums
   float bsum[MB];
 #pragma unroll
   for (int i = 0; i < MB; ++i) bsum[i] = 0.f;
@@ -264,7 +266,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradArgs a) {
 #pragma unroll
         for (int i = 0; i < MB; ++i)
           bsum[i] += (av[ss & 1][i][0] + av[ss & 1][i][1]) + (av[ss & 1][i][2] + av[ss & 1][i][3]);
-        if (ss == NSS - 1) my_chunk += a.n_tiles;
+        if (ss == NSS - 1) my_chunk += chunk_step;
       }
       if (DMA) {
         // this step's share of the loads of chunk ch+1, all issued in the first half of the chunk so
@@ -300,13 +302,24 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradArgs a) {
     __syncthreads();
   }
 
-  if (row_sums) {
+  if (row_sums) {  // uniform over the grid; the pipeline buffers are free after the loop's last barrier
+    float* red = smem;  // [WN][BM]
 #pragma unroll
     for (int i = 0; i < MB; ++i) {
       const float total = bsum[i] + __shfl_xor(bsum[i], 32);
-      const uint32_t k = m_tile * BM + (wm * MB + i) * 32 + (lane & 31);
-      if (lane < 32 && k < (uint32_t)a.Kg)
-        a.bias_part[((size_t)split * a.n_tiles + n_tile) * a.Ktot + g * a.Kg + k] = total;
+      if (lane < 32) red[wn * BM + (wm * MB + i) * 32 + lane] = total;
+    }
+    __syncthreads();
+    if (wn == 0 && lane < 32) {
+#pragma unroll
+      for (int i = 0; i < MB; ++i) {
+        const int row = (wm * MB + i) * 32 + lane;
+        float total = red[row];
+#pragma unroll
+        for (int v = 1; v < WN; ++v) total += red[v * BM + row];
+        const uint32_t k = m_tile * BM + (uint32_t)row;
+        if (k < (uint32_t)a.Kg) a.bias_part[((size_t)split * a.n_tiles + n_tile) * a.Ktot + g * a.Kg + k] = total;
+      }
     }
   }
 

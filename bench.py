@@ -315,7 +315,9 @@ def main():
         acc.setdefault((lname, pname), []).append(e0.elapsed_time(e1))
     dominant = max(((k, sum(v) / len(v)) for k, v in acc.items()), key=lambda kv: kv[1])[0]
     separate = {}
-    if fused_bias:  # for reference: the two gradient passes called one by one (not part of the step)
+    # for reference: the two gradient passes called one by one (not part of the step; left out of a
+    # counter run, whose summary matches dispatches to passes by their order inside whole steps)
+    if fused_bias and not args.copy_calibration:
         ev = []
         for _ in range(table_steps):
             for t in state:
@@ -363,7 +365,7 @@ def main():
                 row[name + "_us_over_launch_floor"] = round(ms * 1e3 - launches[name] * launch_us, 2)
             if not is_ip and name in flop_passes:  # every blob of the pass moved once, against 8 TB/s
                 row[name + "_alg_GBps"] = round(blob_bytes(l, name) * (2 if f64 else 1) / ms / 1e6, 1)
-            if name == "bwd_filter_bias":  # the same passes called one by one, outside the step
+            if name == "bwd_filter_bias" and separate:  # the same passes called one by one, outside the step
                 for sep in ("bwd_filter", "bwd_bias"):
                     row["separate_" + sep + "_ms"] = round(sum(separate[(l.name, sep)]) / len(separate[(l.name, sep)]), 5)
                 row["bias_gradient_extra_ms"] = round(ms - row["separate_bwd_filter_ms"], 5)

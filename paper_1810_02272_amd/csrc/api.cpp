@@ -755,8 +755,7 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
     d->bg_ws = p.bias_term ? (size_t)a.S * K * 4 : 0;
   }
 
-  // ---- double base type: the same geometry on the one fp64 tile, compare-style bounds checks,
-  // no split of the correlation's reduction ----
+  // ---- double base type: the same geometry on the fp64 tiles, compare-style bounds checks ----
   {
     const int32_t bn64 = kF64TileCols, bk64 = kF64TileK;
     const int64_t max64 = (int64_t)1 << 29;  // 32-bit byte offsets of 8-byte elements
@@ -771,10 +770,9 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
       a.MP = (int32_t)round_up(a.Mrows, bm64);
       a.m_tiles = a.MP / bm64;
       a.col_tiles = (int32_t)ceil_div(a.ncols, bn64);
-      a.ksplit = 1;
-      a.chunks_per_split = a.KP / bk64;
       a.use_patch = 0;
       a.accumulate = 0;
+      configure_ksplit(a, src.out_elems);  // the same rule on this tile's grid (chunks are 16 k rows here too)
       a.simple_epilogue = src.simple_epilogue && 8 * (int64_t)src.out_elems <= ((int64_t)1 << 30);
       k = psrc;
       k.KP = a.KP;
@@ -783,7 +781,8 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
       k.koff_invalid = 0;
       const int64_t pack_elems = (int64_t)a.G * a.KP * a.MP;
       if (pack_elems >= max64 || (int64_t)a.G * a.m_tiles * a.col_tiles >= ((int64_t)1 << 31)) d->f64_ok = 0;
-      ws = (size_t)pack_elems * 8 + (size_t)a.KP * sizeof(KTabEntry);
+      ws = (size_t)pack_elems * 8 + (size_t)a.KP * sizeof(KTabEntry) +
+           (a.ksplit > 1 ? (size_t)a.ksplit * (size_t)src.out_elems * 8 : 0);
     };
     corr64(d->fwd, d->fwd_pack, d->fwd64, d->fwd64_pack, x_elems, d->fwd64_ws, d->fwd64_rows);
     corr64(d->bwd, d->bwd_pack, d->bwd64, d->bwd64_pack, y_elems, d->bwd64_ws, d->bwd64_rows);
@@ -810,9 +809,10 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
     d->bg64_ws = 2 * d->bg_ws;
     auto e64 = [](const CorrArgs& c) { return c.simple_epilogue ? 's' : 'p'; };
     snprintf(d->names64, sizeof(d->names64),
-             "fwd=corr64_%dx64x16[e%c](S=1,L=2);bwd_data=corr64_%dx64x16[e%c](S=1,L=%d);"
+             "fwd=corr64_%dx64x16[e%c](S=%d,L=%d);bwd_data=corr64_%dx64x16[e%c](S=%d,L=%d);"
              "bwd_filter=wgrad64_%dx64x16(S=%d,L=2);bwd_bias=bias_grad64(S=%d,L=2)",
-             d->fwd64_rows, e64(d->fwd64), d->bwd64_rows, e64(d->bwd64), 2 + (d->bwd_zero_fill != 0), d->wg64_rows, a.S,
+             d->fwd64_rows, e64(d->fwd64), d->fwd64.ksplit, 2 + (d->fwd64.ksplit > 1), d->bwd64_rows, e64(d->bwd64),
+             d->bwd64.ksplit, 2 + (d->bwd64.ksplit > 1) + (d->bwd_zero_fill != 0), d->wg64_rows, a.S,
              d->bg.S);
     d->ws_bytes64 = d->fwd64_ws;
     if (d->bwd64_ws > d->ws_bytes64) d->ws_bytes64 = d->bwd64_ws;
@@ -1010,11 +1010,14 @@ static int run_corr64(const conv_desc_t* d, int32_t tile_rows, const CorrArgs& a
                       void* ws, size_t ws_bytes, void* hip_stream) {
   if (!d->f64_ok) return CONV_ESHAPE;
   if (!ws || ws_bytes < need) return CONV_EWORKSPACE;
-  if (zero_out_bytes) {  // backward data with row / column phases no tap reaches
-    const int ez = launch_fill_zero(out, zero_out_bytes, hip_stream);
+  PackArgs k = pack;
+  const size_t pack_bytes = (size_t)k.G * k.KP * k.MP * 8 + (size_t)k.KP * sizeof(KTabEntry);
+  double* const part = reinterpret_cast<double*>(static_cast<char*>(ws) + pack_bytes);
+  if (zero_out_bytes) {  // backward data with row / column phases no tap reaches: clear dx, or the slices' partial sums
+    const int ez = args.ksplit > 1 ? launch_fill_zero(part, (size_t)args.ksplit * zero_out_bytes, hip_stream)
+                                   : launch_fill_zero(out, zero_out_bytes, hip_stream);
     if (ez) return record_hip_error(ez);
   }
-  PackArgs k = pack;
   k.w = reinterpret_cast<const float*>(w);
   k.A = static_cast<float*>(ws);
   k.ktab = reinterpret_cast<KTabEntry*>(static_cast<double*>(ws) + (size_t)k.G * k.KP * k.MP);
@@ -1026,7 +1029,23 @@ static int run_corr64(const conv_desc_t* d, int32_t tile_rows, const CorrArgs& a
   a.in = reinterpret_cast<const float*>(in);
   a.bias = reinterpret_cast<const float*>(bias);
   a.out = reinterpret_cast<float*>(out);
+  a.part = reinterpret_cast<float*>(part);
   e = launch_corr64(tile_rows, a, hip_stream);
+  if (e) return record_hip_error(e);
+  if (a.ksplit > 1) {  // add the slices and the bias
+    ReduceArgs r = {};
+    r.part = a.part;
+    r.dst = a.out;
+    r.count = a.out_elems;
+    r.S = a.ksplit;
+    r.beta = 0.f;
+    r.bias = a.bias;
+    r.chan_elems = d->OH * d->OW;
+    r.channels = d->p.num_output;
+    r.mChanElems = make_magic(r.chan_elems);
+    r.mChannels = make_magic(r.channels);
+    e = launch_reduce64(r, hip_stream);
+  }
   return e ? record_hip_error(e) : CONV_OK;
 }
 

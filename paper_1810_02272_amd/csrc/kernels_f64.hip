@@ -77,7 +77,10 @@ __global__ __launch_bounds__(kThreads) void corr64_kernel(const CorrArgs a) {
   const uint32_t m_tile = lin % (uint32_t)a.m_tiles;
   lin /= (uint32_t)a.m_tiles;
   const uint32_t col_tile = lin % (uint32_t)a.col_tiles;
-  const uint32_t g = lin / (uint32_t)a.col_tiles;
+  lin /= (uint32_t)a.col_tiles;
+  const uint32_t g = lin % (uint32_t)a.G;
+  const uint32_t split = lin / (uint32_t)a.G;  // slice of the reduction (usually the only one)
+  const int kc_first = (int)split * a.chunks_per_split;
 
   // the column this lane gathers
   uint32_t cbase = 0;
@@ -94,7 +97,9 @@ __global__ __launch_bounds__(kThreads) void corr64_kernel(const CorrArgs a) {
       cbase = 8u * (uint32_t)((int)(n * a.in_img_stride + g * a.in_grp_stride) + cih0 * a.IW + ciw0);
     }
   }
-  const double* Ag = reinterpret_cast<const double*>(a.A) + ((size_t)g * a.MP + (size_t)m_tile * BM) * a.KP;
+  const double* Ag =
+      reinterpret_cast<const double*>(a.A) + ((size_t)g * a.MP + (size_t)m_tile * BM) * a.KP + (size_t)kc_first * BK;
+  const KTabEntry* const ktab = a.ktab + kc_first * BK;  // chunk indices below are relative to the slice
   // Piece p = t + 256*i of the A tile: k quad p / BM, row p % BM (consecutive lanes on consecutive
   // rows: the four 8-byte LDS writes of a piece are conflict free).
   const __amdgpu_buffer_rsrc_t in_rsrc =
@@ -114,7 +119,7 @@ __global__ __launch_bounds__(kThreads) void corr64_kernel(const CorrArgs a) {
   KTabEntry te[4], te_next[4];
   auto load_tab = [&](int kc) {
 #pragma unroll
-    for (int e = 0; e < 4; ++e) te_next[e] = a.ktab[kc * BK + wv * 4 + e];
+    for (int e = 0; e < 4; ++e) te_next[e] = ktab[kc * BK + wv * 4 + e];
   };
   auto swap_tab = [&]() {
 #pragma unroll
@@ -159,7 +164,9 @@ __global__ __launch_bounds__(kThreads) void corr64_kernel(const CorrArgs a) {
   // set holding chunk kc+1 (loaded two iterations ago) is written to the other buffer and reloaded
   // with chunk kc+3; the other set holds chunk kc+2.  Chunk indices past the end are clamped: the
   // last iterations re-load and re-store the final chunk into a buffer nobody reads.
-  const int nchunks = a.KP / BK, last = nchunks - 1;
+  int nchunks = a.KP / BK - kc_first;
+  if (nchunks > a.chunks_per_split) nchunks = a.chunks_per_split;
+  const int last = nchunks - 1;
   const double* opA = smem + (lane >> 4) * LDA + wm * MB * 16 + (lane & 15);
   const double* opB = smem + BK * LDA + (lane >> 4) * LDB + wn * NB * 16 + (lane & 15);
   load_tab(0);
@@ -193,11 +200,16 @@ __global__ __launch_bounds__(kThreads) void corr64_kernel(const CorrArgs a) {
   // Epilogue.  One output phase per channel and an output of at most 2^30 bytes (see the fp32
   // epilogue): byte offsets per row and per column with out-of-range values for "not stored", and
   // range-checked buffer stores.
+  // With a split reduction every slice writes its raw partial sums, in the output blob's own layout,
+  // to its part of the workspace; reduce64_kernel adds them and the bias.
+  double* const out = a.ksplit > 1 ? reinterpret_cast<double*>(a.part) + (size_t)split * a.out_elems
+                                   : reinterpret_cast<double*>(a.out);
+  const double* const bias = a.ksplit > 1 ? nullptr : reinterpret_cast<const double*>(a.bias);
   if (a.simple_epilogue) {
     uint32_t* rowoff = reinterpret_cast<uint32_t*>(smem);
     uint32_t* coloff = rowoff + BM;
     double* rbias = reinterpret_cast<double*>(coloff + BN);
-    const double* bias8 = reinterpret_cast<const double*>(a.bias);
+    const double* bias8 = bias;
     if (t < BM) {
       const uint32_t gm = m_tile * BM + t;
       uint32_t off = 0x80000000u;
@@ -226,7 +238,7 @@ __global__ __launch_bounds__(kThreads) void corr64_kernel(const CorrArgs a) {
     }
     __syncthreads();
     const __amdgpu_buffer_rsrc_t out_rsrc =
-        __builtin_amdgcn_make_buffer_rsrc(a.out, 0, (int)(8u * (uint32_t)a.out_elems), 0x00020000);
+        __builtin_amdgcn_make_buffer_rsrc(out, 0, (int)(8u * (uint32_t)a.out_elems), 0x00020000);
     typedef int i32x2 __attribute__((ext_vector_type(2)));
 #pragma unroll
     for (int j = 0; j < NB; ++j) {
@@ -247,8 +259,6 @@ __global__ __launch_bounds__(kThreads) void corr64_kernel(const CorrArgs a) {
   int4* rowtab = reinterpret_cast<int4*>(smem);
   int4* coltab = rowtab + BM;
   double* rowbias = reinterpret_cast<double*>(coltab + BN);
-  const double* bias = reinterpret_cast<const double*>(a.bias);
-  double* const out = reinterpret_cast<double*>(a.out);
   if (t < BM) {
     const uint32_t gm = m_tile * BM + t;
     int off = 0, hh = -(1 << 28), ww = 0;
@@ -440,6 +450,10 @@ __global__ __launch_bounds__(256) void reduce64_kernel(const ReduceArgs a) {
   }
   if (s < a.S) acc0 += src[(size_t)s * a.count];
   double v = acc0 + acc1;
+  if (a.bias) {  // forward: channel of element i of an N x channels x chan_elems blob
+    const uint32_t q = mdiv((uint32_t)i, a.mChanElems);
+    v += reinterpret_cast<const double*>(a.bias)[q - mdiv(q, a.mChannels) * (uint32_t)a.channels];
+  }
   if (a.beta != 0.f) v += (double)a.beta * dst[i];
   dst[i] = v;
 }
@@ -492,7 +506,7 @@ int32_t f64_pick_rows(int64_t rows, bool filter_gradient) {
 }
 
 int launch_corr64(int32_t bm, const CorrArgs& a, void* stream) {
-  const dim3 grid((uint32_t)a.G * a.m_tiles * a.col_tiles), block(kThreads);
+  const dim3 grid((uint32_t)a.G * a.m_tiles * a.col_tiles * (a.ksplit > 1 ? a.ksplit : 1)), block(kThreads);
   hipStream_t s = (hipStream_t)stream;
   switch (bm) {
     case 96: hipLaunchKernelGGL((corr64_kernel<3, 2, 2, 2>), grid, block, 0, s, a); break;

@@ -114,6 +114,10 @@ def test_every_fp64_tile_has_a_gpu_parity_case(selected):
     assert missing(s["fwd"], [f"corr64_{r}x64x16[es]" for r in F64_ROWS]) == []
     assert missing(s["bwd_data"], [f"corr64_{r}x64x16[e{e}]" for r in F64_ROWS for e in "sp"]) == []
     assert missing(s["bwd_filter"], [f"wgrad64_{r}x64x16" for r in F64_ROWS]) == []
+    # split reductions (partial outputs + reduce64_kernel): forward, backward data with both epilogue forms
+    assert any(True in seen for v, seen in s["fwd"].items() if v.startswith("corr64") and "[es]" in v)
+    assert any(True in seen for v, seen in s["bwd_data"].items() if v.startswith("corr64") and "[es]" in v)
+    assert any(True in seen for v, seen in s["bwd_data"].items() if v.startswith("corr64") and "[ep]" in v)
 
 
 def test_no_variant_outside_the_lists_above(selected):

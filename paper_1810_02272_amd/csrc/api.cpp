@@ -227,7 +227,8 @@ void configure_patch(CorrArgs& a, PackArgs& k, int64_t cg_in, int64_t n_img, int
 // workgroup walks its chunks one barrier at a time; S slices run side by side and a reduce kernel
 // adds them.  Worth an extra launch when the grid is well under one workgroup per compute unit,
 // or when a large problem leaves the compute units unevenly loaded.
-void configure_ksplit(CorrArgs& a, int64_t out_elems) {
+// bm x bn: the tile; elem_bytes: 4 or 8 (the double path runs the same rule on its own tiles).
+void configure_ksplit(CorrArgs& a, int64_t out_elems, int32_t bm, int32_t bn, int32_t elem_bytes = 4) {
   a.ksplit = 1;
   a.chunks_per_split = a.KP / 16;
   a.out_elems = (int32_t)out_elems;
@@ -235,7 +236,30 @@ void configure_ksplit(CorrArgs& a, int64_t out_elems) {
   const int64_t units = (int64_t)a.G * a.m_tiles * a.col_tiles, chunks = a.KP / 16;
   if (a.use_patch || chunks < 8 || a.ncols < 1) return;
   int64_t S = 1;
-  if (units <= 160) {
+  const double flops = 2.0 * a.Mrows * a.Kred * (double)a.ncols * a.G;
+  if (units <= 160 && flops < 2e9) {
+    // Small grid of a small problem: the number of slices with the smallest modelled time.  A
+    // workgroup that has its compute unit to itself walks its chunks at the latency of one chunk --
+    // 0.18 us plus 0.30 us per 4096 tile elements (twice that in doubles) -- and S slices cost the
+    // reduce kernel's launch, 1.6 us, plus their partial sums written and read once at 2.4 TB/s
+    // (0.83 us per MB).  Constants fitted to split sweeps of the nine such passes of the benchmark's
+    // small layers (rms error 1 us; the model picks the fastest or second fastest S on each: 2.a
+    // forward, 32 chunks on 64 tiles of 64x64, 0.8 MB out: 4 slices 13.4 us against 14.6 with 8 and
+    // 21.7 unsplit; 3.a forward, 16 chunks on 100 tiles, 1.6 MB out: unsplit 14.4 us against 18.0
+    // with 4).  At most 16 slices of at least two chunks, at most 1024 workgroups.
+    const double t_chunk = 0.18 + 0.30 * (elem_bytes == 8 ? 2.0 : 1.0) * (double)(bm * bn) / 4096.0;
+    const double out_mb = (double)out_elems * elem_bytes / 1e6;
+    double best_t = (double)chunks * t_chunk;
+    for (int64_t c = 2; c <= 16 && c <= chunks / 2 && units * c <= 1024; ++c) {
+      const double t = (double)ceil_div(chunks, c) * t_chunk + 1.6 + 0.83 * (double)c * out_mb;
+      if (t < best_t) {
+        best_t = t;
+        S = c;
+      }
+    }
+  } else if (units <= 160) {
+    // Small grid of a larger problem (the matrix pipes, not latency, set the pace once the slices
+    // fill the chip): two workgroups per compute unit, at least four chunks per slice
     S = ceil_div(512, units);
     if (S > chunks / 4) S = chunks / 4;
     if (S > 16) S = 16;
@@ -245,7 +269,7 @@ void configure_ksplit(CorrArgs& a, int64_t out_elems) {
     if (S2 > chunks / 32) S2 = chunks / 32;
     if (S2 > 16) S2 = 16;
     if (S2 > S) S = S2;
-  } else if (units < 512 && 2.0 * a.Mrows * a.Kred * (double)a.ncols * a.G >= 5e9) {
+  } else if (units < 512 && flops >= 5e9) {
     // Mid-sized grids of a large problem (a 14x14 or 7x7 layer with hundreds of channels): one or
     // two workgroups per compute unit with some units idle.  Take the split that brings the load
     // of the busiest unit, relative to the unsplit grid, down by at least 15 % (20 % when the
@@ -539,7 +563,7 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
     k.tdw = a.dw;
     k.koff_invalid = koff_invalid(a.bounds_mode);
     configure_patch(a, k, Cg, N, bm, bn);
-    configure_ksplit(a, y_elems);
+    configure_ksplit(a, y_elems, bm, bn);
     const int64_t pack_elems = G * (int64_t)a.KP * a.MP;
     if (pack_elems >= kMaxElems || (int64_t)G * a.m_tiles * a.col_tiles >= ((int64_t)1 << 31)) {
       delete d;
@@ -654,7 +678,7 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
     k.tdw = a.dw;
     k.koff_invalid = koff_invalid(a.bounds_mode);
     configure_patch(a, k, Kg, N, bm, bn);
-    configure_ksplit(a, x_elems);
+    configure_ksplit(a, x_elems, bm, bn);
     const int64_t pack_elems = G * (int64_t)a.KP * a.MP;
     if (pack_elems >= kMaxElems || (int64_t)G * a.m_tiles * a.col_tiles >= ((int64_t)1 << 31)) {
       delete d;
@@ -711,16 +735,30 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
     // split at least four k tiles long and the partials at most 32 MiB; a grid slightly above a
     // multiple of the 256 compute units is trimmed back to it (its last few workgroups would
     // otherwise share a compute unit while the others have one to themselves).
-    const int64_t tiles = G * a.m_tiles * a.n_tiles;
-    const int64_t places = 256 * (bm == 32 ? 3 : 2);
-    int64_t S = places / tiles;
     const int64_t max_by_len = ceil_div((int64_t)a.ncols, 4 * bk);
     const int64_t max_by_ws = ((int64_t)8 << 20) / (w_elems > 0 ? w_elems : 1);
-    if (S > max_by_len) S = max_by_len;
-    if (S > max_by_ws) S = max_by_ws;
-    if (S > 256) S = 256;  // beyond one split per compute unit the reduce kernel only gets slower
-    if (S < 1) S = 1;
-    while (S > 1 && tiles * S > 256 && (tiles * S) % 256 != 0 && (tiles * S) % 256 < 64) --S;
+    auto splits_for = [&](int64_t tiles, int64_t places) {
+      int64_t S = places / tiles;
+      if (S > max_by_len) S = max_by_len;
+      if (S > max_by_ws) S = max_by_ws;
+      if (S > 256) S = 256;  // beyond one split per compute unit the reduce kernel only gets slower
+      if (S < 1) S = 1;
+      while (S > 1 && tiles * S > 256 && (tiles * S) % 256 != 0 && (tiles * S) % 256 < 64) --S;
+      return S;
+    };
+    int64_t tiles = G * a.m_tiles * a.n_tiles;
+    int64_t S = splits_for(tiles, 256 * (bm == 32 ? 3 : 2));
+    // A grid that cannot fill the compute units because its splits are as short as they may get takes
+    // the 32-row tile instead of the 64-row one when both pad the rows alike: twice the workgroups,
+    // three resident per compute unit (2.a 12.9 -> 10.8 us, 3.b 13.2 -> 11.0, 3.c 12.3 -> 10.1).
+    if (d->wg_tile == WGRAD_64x128 && tiles * S < 256 && round_up(Kg, 32) == round_up(Kg, 64)) {
+      d->wg_tile = WGRAD_32x128;
+      wgrad_tile_shape(d->wg_tile, &bm, &bn, &bk);
+      a.m_tiles = (int32_t)ceil_div(Kg, bm);
+      a.n_tiles = (int32_t)ceil_div(kred, bn);
+      tiles = G * a.m_tiles * a.n_tiles;
+      S = splits_for(tiles, 256 * 3);
+    }
     a.cols_per_split = (int32_t)round_up(ceil_div((int64_t)a.ncols > 0 ? a.ncols : 1, S), bk);
     a.S = (int32_t)ceil_div((int64_t)a.ncols > 0 ? a.ncols : 1, a.cols_per_split);
     if (a.S * w_elems >= kMaxElems || tiles * a.S >= ((int64_t)1 << 31)) {
@@ -772,7 +810,7 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
       a.col_tiles = (int32_t)ceil_div(a.ncols, bn64);
       a.use_patch = 0;
       a.accumulate = 0;
-      configure_ksplit(a, src.out_elems);  // the same rule on this tile's grid (chunks are 16 k rows here too)
+      configure_ksplit(a, src.out_elems, bm64, bn64, 8);  // the same rule on this tile's grid (chunks are 16 k rows here too)
       a.simple_epilogue = src.simple_epilogue && 8 * (int64_t)src.out_elems <= ((int64_t)1 << 30);
       k = psrc;
       k.KP = a.KP;

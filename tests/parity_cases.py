@@ -155,6 +155,9 @@ VARIANT_CASES = [
     (P(1, 3, 5, 6, 96, 6, 6, 2, 2, 3, 3), "bwd_filter", "wgrad_m32_96x128x32[m1"),
     (P(1, 1, 5, 6, 96, 6, 6, 2, 2, 3, 3), "bwd_filter", "wgrad_m32_128x64x32[m1"),
     (P(1, 1, 5, 6, 96, 3, 3, 2, 2, 1, 1), "bwd_filter", "wgrad_m32_128x64x32[m2"),
+    # the 64-row filter-gradient tile is kept for grids of 256 workgroups or more (48 outputs, 4 column tiles, 86 splits)
+    (P(6, 48, 66, 66, 48, 3, 3), "bwd_filter", "wgrad_m32_64x128x32[m0"),
+    (P(6, 48, 64, 64, 48, 3, 3, 1, 1, 2, 2, 2, 2), "bwd_filter", "wgrad_m32_64x128x32[m1"),
 ]
 
 

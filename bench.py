@@ -559,7 +559,7 @@ def small_layers(torch, conv, workloads, dev, launch_us, steps=20, warmup=5):
                         "us_at_mfma_peak": round(3 * l.flop_per_pass / PEAK_FP32_MFMA_TFLOPS / 1e6, 2),
                         "us_at_hbm_peak": round(alg / PEAK_HBM_GBS / 1e3, 2)})
             rows.append(row)
-    return {"empty_dispatch_us": round(launch_us, 2), "bound": "launch latency (microseconds of work per pass)",
+    return {"empty_dispatch_us": round(launch_us, 2), "bound": "latency: two or three kernels of 3-30 us per pass, back to back (a step takes the sum of their durations)",
             "from": "%d steps per configuration with HIP events around every pass (median); us_per_step from %d "
                     "steps enqueued back to back without events" % (steps, steps),
             "per_config": per_config, "layers": rows}

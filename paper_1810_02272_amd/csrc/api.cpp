@@ -419,12 +419,15 @@ int run_backward_filter(const conv_desc* d, const float* x, const float* dy, flo
   a.part = static_cast<float*>(ws);
   int e = 0;
   if (d->use_direct) {
-    // thin groups: the direct filter-gradient kernel, and the stand-alone bias gradient after it
+    // thin groups: the direct filter-gradient kernel; its workgroups of a group's first input channel
+    // also add up the dy values they read (S x K sums behind the filter partials)
     DirectArgs da = d->dir;
     da.in = x;
     da.w = dy;
     da.part = ws;
     a.S = da.S;
+    a.n_tiles = 1;
+    if (db) da.bias_part = a.bias_part = a.part + (size_t)da.S * w_elems;
     if (!empty) e = launch_direct(2, da, false, hip_stream);
   } else if (!empty) {
     if (db) a.bias_part = a.part + (size_t)a.S * w_elems;  // row sums of dy ride along, behind the filter partials
@@ -443,16 +446,14 @@ int run_backward_filter(const conv_desc* d, const float* x, const float* dy, flo
   r.mChanElems = make_magic(r.chan_elems);
   r.mChannels = make_magic(r.channels);
   r.relu = extras.relu;
-  if (db && (empty || !d->use_direct)) {  // the same launch finishes db from the S * n_tiles shares of the row sums
+  if (db) {  // the same launch finishes db from the S * n_tiles shares of the row sums
     r.part2 = empty ? nullptr : a.bias_part;
     r.dst2 = db;
     r.count2 = d->p.num_output;
     r.S2 = empty ? 0 : a.S * a.n_tiles;
   }
   e = launch_reduce(r, hip_stream);
-  if (e) return record_hip_error(e);
-  if (db && !empty && d->use_direct) return conv_backward_bias(d, dy, db, beta, ws, ws_bytes, hip_stream);
-  return CONV_OK;
+  return e ? record_hip_error(e) : CONV_OK;
 }
 
 }  // namespace mi355conv
@@ -863,6 +864,7 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
     const int64_t taps = (int64_t)p.kernel_h * p.kernel_w;
     d->use_direct = G > 1 && taps <= 64 && direct_is_faster(Cg, Kg, p.kernel_h, p.kernel_w);
     DirectArgs& a = d->dir;
+    a.bias_part = nullptr;
     a.N = p.n;
     a.C = p.c;
     a.H = p.h;
@@ -910,13 +912,13 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
       a.imgs_per_split = (int32_t)ceil_div(N > 0 ? N : 1, S);
       a.S = (int32_t)ceil_div(N > 0 ? N : 1, a.imgs_per_split);
       if ((int64_t)N * a.chunks_per_img >= ((int64_t)1 << 31) || K * Cg >= ((int64_t)1 << 31) ||
-          a.S * w_elems >= kMaxElems)
+          a.S * (w_elems + K) >= kMaxElems)
         d->use_direct = 0;
     }
     if (d->use_direct) {
       d->fwd_ws = d->bwd_ws = 0;
       d->wg_ws = (size_t)a.S * (size_t)w_elems * 4;
-      d->wgb_ws = d->wg_ws > d->bg_ws ? d->wg_ws : d->bg_ws;  // the two passes one after the other
+      d->wgb_ws = (size_t)a.S * (size_t)(w_elems + K) * 4;  // S x K sums of dy behind the filter partials
       d->fwd64_ws = d->bwd64_ws = 0;
       d->wg64_ws = 2 * d->wg_ws;
       d->ws_bytes64 = d->wg64_ws > d->bg64_ws ? d->wg64_ws : d->bg64_ws;

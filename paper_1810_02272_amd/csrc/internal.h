@@ -203,6 +203,8 @@ struct DirectArgs {
   const void* bias;  // forward only (may be null)
   void* out;         // y / dx
   void* part;        // filter gradient: [S][K][Cg][kh][kw] partial sums
+  void* bias_part;   // filter gradient: when not null, [S][K] sums of dy (the workgroups of input channel 0 of a
+                     // group add up the dy values they read: the bias gradient from the same pass)
   int32_t N, C, H, W, K, OH, OW, kh, kw, sh, sw, ph, pw, dh, dw, Cg, Kg;
   uint32_t x_elems, y_elems, w_elems;
   Magic mOW, mOH, mK, mKg;             // forward: output index -> (n, k, oh, ow), k -> group

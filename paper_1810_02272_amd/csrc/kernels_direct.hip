@@ -91,6 +91,14 @@ __global__ __launch_bounds__(256) void direct_bwd_data_kernel(const DirectArgs a
   static_cast<T*>(a.out)[idx] = acc;
 }
 
+// Sum of v over the 64 lanes of a wave, in a fixed order; lane 0 stores it.
+template <typename T>
+__device__ __forceinline__ void wave_sum_to(T v, int lane, T* dst) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) v += __shfl_down(v, off, 64);
+  if (lane == 0) *dst = v;
+}
+
 // part[s][k][c][i][j] = sum over the images of split s and all output positions of
 //   dy[n][k][oh][ow] * x[n][g*Cg + c][oh*sh - ph + i*dh][ow*sw - pw + j*dw]
 // One workgroup per ((k, c) pair, split).  Lane l of a wave stands for tap l % taps of position
@@ -98,6 +106,10 @@ __global__ __launch_bounds__(256) void direct_bwd_data_kernel(const DirectArgs a
 // with every tap (one load of dy, broadcast over the taps, and one load of x per lane); the four
 // waves take the (image, chunk of positions) units in turn, four units in flight per wave.  The
 // per-lane sums are added over slots and waves in a fixed order.
+// With a.bias_part set, the workgroups of a group's first input channel (c == 0) also add up the dy
+// values they read -- each exactly once -- and store bias_part[s][k]: the bias gradient's share of
+// split s, finished by the reduce kernel together with the filter gradient.  The same holds for the
+// 3x3 / 5x5 filter-gradient kernels below.
 template <typename T>
 __global__ __launch_bounds__(256) void direct_wgrad_kernel(const DirectArgs a) {
   __shared__ T red[256];
@@ -117,6 +129,8 @@ __global__ __launch_bounds__(256) void direct_wgrad_kernel(const DirectArgs a) {
   const T* dy = static_cast<const T*>(a.w) + k * P;                                        // + n*K*P + pos
   const T* x = static_cast<const T*>(a.in) + (g * (uint32_t)a.Cg + c) * HW;                // + n*C*HW + ih*W + iw
   T acc = T(0);
+  const bool row_sum = a.bias_part != nullptr && c == 0;  // uniform over the workgroup
+  T bsum = T(0);
   for (uint32_t u0 = (uint32_t)wv; u0 < units; u0 += 4 * kInFlight) {
     T dv[kInFlight], xv[kInFlight];
 #pragma unroll
@@ -126,16 +140,20 @@ __global__ __launch_bounds__(256) void direct_wgrad_kernel(const DirectArgs a) {
       const uint32_t pos = ch * (uint32_t)a.slots + slot;
       const uint32_t oh = mdiv(pos, a.mOW), ow = pos - oh * (uint32_t)a.OW;
       const int ih = (int)oh * a.sh + dih, iw = (int)ow * a.sw + diw;
-      const bool ok = lane_on & (u < units) & (pos < P) & ((uint32_t)ih < (uint32_t)a.H) & ((uint32_t)iw < (uint32_t)a.W);
+      const bool okd = lane_on & (u < units) & (pos < P);  // a real element of dy
+      const bool ok = okd & ((uint32_t)ih < (uint32_t)a.H) & ((uint32_t)iw < (uint32_t)a.W);
       const uint32_t n = n0 + nl;
-      const T d = dy[ok ? n * (uint32_t)a.K * P + pos : 0u];
+      const T d = dy[okd ? n * (uint32_t)a.K * P + pos : 0u];
       dv[q] = ok ? d : T(0);
+      if (row_sum) bsum += (okd && tap == 0) ? d : T(0);  // every element of dy once: the lanes of tap 0
       xv[q] = x[ok ? n * (uint32_t)a.C * HW + (uint32_t)ih * (uint32_t)a.W + (uint32_t)iw : 0u];
     }
 #pragma unroll
     for (int q = 0; q < kInFlight; ++q) acc += dv[q] * xv[q];
   }
   red[t] = acc;
+  __shared__ T bred[4];
+  if (row_sum) wave_sum_to(bsum, lane, &bred[wv]);
   __syncthreads();
   if (t < a.taps) {
     T sum = T(0);
@@ -143,6 +161,8 @@ __global__ __launch_bounds__(256) void direct_wgrad_kernel(const DirectArgs a) {
       for (int sl = 0; sl < a.slots; ++sl) sum += red[w4 * 64 + sl * a.taps + t];
     static_cast<T*>(a.part)[split * a.w_elems + pair * (uint32_t)a.taps + (uint32_t)t] = sum;
   }
+  if (row_sum && t == 0)
+    static_cast<T*>(a.bias_part)[split * (uint32_t)a.K + k] = ((bred[0] + bred[1]) + bred[2]) + bred[3];
 }
 
 // ---- 3x3 and 5x5 kernels: several output rows per thread ----
@@ -335,6 +355,9 @@ __global__ __launch_bounds__(256) void direct_wgrad_rows_vec_kernel(const Direct
   for (int i = 0; i < KH; ++i)
 #pragma unroll
     for (int j = 0; j < KW; ++j) acc[i][j] = T(0);
+  const bool row_sum = a.bias_part != nullptr && c == 0;  // uniform over the workgroup
+  T bsum = T(0);
+  __shared__ T bred[4];
   for (uint32_t item = (uint32_t)t; item < items; item += 256u) {
     const uint32_t q1 = mdiv(item, a.mOWQ), owq = item - q1 * (uint32_t)a.OWQ;
     const uint32_t nl = mdiv(q1, a.mOHB), ohb = q1 - nl * (uint32_t)a.OHB;
@@ -348,6 +371,10 @@ __global__ __launch_bounds__(256) void direct_wgrad_rows_vec_kernel(const Direct
       const Vec4<T> d4 = *reinterpret_cast<const Vec4<T>*>(dn + (ok ? (uint32_t)(oh0 + r) * (uint32_t)a.OW : 0u));
 #pragma unroll
       for (int v = 0; v < kVecCols; ++v) dv[r][v] = ok ? d4.v[v] : T(0);
+    }
+    if (row_sum) {
+#pragma unroll
+      for (int r = 0; r < kVecRows; ++r) bsum += (dv[r][0] + dv[r][1]) + (dv[r][2] + dv[r][3]);
     }
     T xs[kVecRows + KH - 1][kVecCols + KW - 1];
     load_window_vec<T, KH, KW>(a, x + n * (uint32_t)a.C * HW, oh0, ow0, xs);
@@ -369,10 +396,13 @@ __global__ __launch_bounds__(256) void direct_wgrad_rows_vec_kernel(const Direct
       for (int off = 32; off >= 1; off >>= 1) v += __shfl_down(v, off, 64);
       if (lane == 0) red[wv][i * KW + j] = v;
     }
+  if (row_sum) wave_sum_to(bsum, lane, &bred[wv]);
   __syncthreads();
   if (t < KH * KW)
     static_cast<T*>(a.part)[split * a.w_elems + pair * (uint32_t)(KH * KW) + (uint32_t)t] =
         ((red[0][t] + red[1][t]) + red[2][t]) + red[3][t];
+  if (row_sum && t == 0)
+    static_cast<T*>(a.bias_part)[split * (uint32_t)a.K + k] = ((bred[0] + bred[1]) + bred[2]) + bred[3];
 }
 
 // ---- stride 2, "same" padding along rows of a multiple of four elements ----
@@ -479,6 +509,9 @@ __global__ __launch_bounds__(256) void direct_wgrad_rows_s2_kernel(const DirectA
   for (int i = 0; i < KH; ++i)
 #pragma unroll
     for (int j = 0; j < KW; ++j) acc[i][j] = T(0);
+  const bool row_sum = a.bias_part != nullptr && c == 0;  // uniform over the workgroup
+  T bsum = T(0);
+  __shared__ T bred[4];
   for (uint32_t item = (uint32_t)t; item < items; item += 256u) {
     const uint32_t q1 = mdiv(item, a.mOWQ), q = item - q1 * (uint32_t)a.OWQ;
     const uint32_t nl = mdiv(q1, a.mOHB), ohb = q1 - nl * (uint32_t)a.OHB;
@@ -492,6 +525,10 @@ __global__ __launch_bounds__(256) void direct_wgrad_rows_s2_kernel(const DirectA
       const Vec2<T> d2 = *reinterpret_cast<const Vec2<T>*>(dn + (ok ? (uint32_t)(oh0 + r) * (uint32_t)a.OW : 0u));
       dv[r][0] = ok ? d2.v[0] : T(0);
       dv[r][1] = ok ? d2.v[1] : T(0);
+    }
+    if (row_sum) {
+#pragma unroll
+      for (int r = 0; r < kS2Rows; ++r) bsum += dv[r][0] + dv[r][1];
     }
     T xs[2 * (kS2Rows - 1) + KH][KW + 2];
     load_window_s2<T, KH, KW>(a, x + n * (uint32_t)a.C * HW, oh0, (int)q, xs);
@@ -513,10 +550,13 @@ __global__ __launch_bounds__(256) void direct_wgrad_rows_s2_kernel(const DirectA
       for (int off = 32; off >= 1; off >>= 1) v += __shfl_down(v, off, 64);
       if (lane == 0) red[wv][i * KW + j] = v;
     }
+  if (row_sum) wave_sum_to(bsum, lane, &bred[wv]);
   __syncthreads();
   if (t < KH * KW)
     static_cast<T*>(a.part)[split * a.w_elems + pair * (uint32_t)(KH * KW) + (uint32_t)t] =
         ((red[0][t] + red[1][t]) + red[2][t]) + red[3][t];
+  if (row_sum && t == 0)
+    static_cast<T*>(a.bias_part)[split * (uint32_t)a.K + k] = ((bred[0] + bred[1]) + bred[2]) + bred[3];
 }
 
 // Stride-2 launcher for forward (pass 0) and filter gradient (pass 2); false when the shape or the
@@ -560,6 +600,9 @@ __global__ __launch_bounds__(256) void direct_wgrad_rows_kernel(const DirectArgs
   for (int i = 0; i < KH; ++i)
 #pragma unroll
     for (int j = 0; j < KW; ++j) acc[i][j] = T(0);
+  const bool row_sum = a.bias_part != nullptr && c == 0;  // uniform over the workgroup
+  T bsum = T(0);
+  __shared__ T bred[4];
   for (uint32_t item = (uint32_t)t; item < items; item += 256u) {
     const uint32_t q1 = mdiv(item, a.mOW), ow = item - q1 * (uint32_t)a.OW;
     const uint32_t nl = mdiv(q1, a.mOHB), ohb = q1 - nl * (uint32_t)a.OHB;
@@ -573,6 +616,10 @@ __global__ __launch_bounds__(256) void direct_wgrad_rows_kernel(const DirectArgs
       const bool ok = oh0 + r < a.OH;
       const T v = dn[ok ? (uint32_t)(oh0 + r) * (uint32_t)a.OW : 0u];
       dv[r] = ok ? v : T(0);
+    }
+    if (row_sum) {
+#pragma unroll
+      for (int r = 0; r < kRows; ++r) bsum += dv[r];
     }
     if constexpr (UNIT) {
       T xs[kRows + KH - 1][KW];
@@ -602,10 +649,13 @@ __global__ __launch_bounds__(256) void direct_wgrad_rows_kernel(const DirectArgs
       for (int off = 32; off >= 1; off >>= 1) v += __shfl_down(v, off, 64);
       if (lane == 0) red[wv][i * KW + j] = v;
     }
+  if (row_sum) wave_sum_to(bsum, lane, &bred[wv]);
   __syncthreads();
   if (t < KH * KW)
     static_cast<T*>(a.part)[split * a.w_elems + pair * (uint32_t)(KH * KW) + (uint32_t)t] =
         ((red[0][t] + red[1][t]) + red[2][t]) + red[3][t];
+  if (row_sum && t == 0)
+    static_cast<T*>(a.bias_part)[split * (uint32_t)a.K + k] = ((bred[0] + bred[1]) + bred[2]) + bred[3];
 }
 
 // Backward data at stride S (dilation 1), 3x3 and 5x5: a thread owns the S x S block of dx with

@@ -35,7 +35,7 @@ WORKLOADS = {
             ("fwd", "relu_bwd", "bwd_data", "bwd_filter", "bwd_bias"), ["ip5.6", "ip5.7", "ip5.8"], ""),
     "dw": (("direct_rows_kernel", "direct_rows_vec_kernel", "direct_rows_s2_kernel", "direct_bwd_blocks_kernel",
             "direct_bwd_s2_vec_kernel", "direct_wgrad_rows_kernel", "direct_wgrad_rows_vec_kernel",
-            "direct_wgrad_rows_s2_kernel", "bias_grad_kernel"), PASSES,
+            "direct_wgrad_rows_s2_kernel"), ("fwd", "bwd_data", "bwd_filter_bias"),
            ["dw.a", "dw.b", "dw.c", "dw.d", "dw.e"], ""),
     "pg": (("pg_sample_kernel", "pg_discount_kernel", "pg_sigmoid_kernel", "pg_softmax_rows_kernel"),
            ("sample_action", "discount_rewards", "sigmoid_bottom_diff", "softmax_bottom_diff"), ["pg"], ""),
@@ -94,11 +94,11 @@ def traffic(fetch_dir: str, write_dir: str, workload: str) -> None:
     ff, fetch = _per_pass(_counter(fetch_dir), *spec)
     wf, write = _per_pass(_counter(write_dir), *spec)
     print(f"calibration: FETCH_SIZE x {ff:.3f}, WRITE_SIZE x {wf:.3f} (from the 256 MiB device copy)")
-    print(f"{'layer:pass':16s} {'read MB':>10s} {'written MB':>11s} {'total MB':>10s}   (main kernel of the pass)")
+    print(f"{'layer:pass':22s} {'read MB':>10s} {'written MB':>11s} {'total MB':>10s}   (main kernel of the pass)")
     total = {}
     for k in fetch:
         total[k] = int(fetch[k] + write[k])
-        print(f"{k:16s} {fetch[k] / 1e6:10.1f} {write[k] / 1e6:11.1f} {total[k] / 1e6:10.1f}")
+        print(f"{k:22s} {fetch[k] / 1e6:10.1f} {write[k] / 1e6:11.1f} {total[k] / 1e6:10.1f}")
     root = os.path.dirname(os.path.abspath(__file__))
     path = os.path.join(root, "profiles", "hbm_traffic.json")
     merged = json.load(open(path)) if os.path.exists(path) else {}

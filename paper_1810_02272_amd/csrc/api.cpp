@@ -30,8 +30,13 @@ int64_t round_up(int64_t a, int64_t b) { return ceil_div(a, b) * b; }
 // pads at most 3 % more rows (the 32-row MFMA tiles it brings are worth that).  Column tile, among
 // the variants of that height: the one with the smallest estimated makespan on 256 compute
 // units -- rounds of workgroups times tile width -- with a 6 % handicap per halving of the
-// width (narrow tiles re-read the packed weights more often per FLOP).
-int32_t pick_corr_tile(int32_t rows, int64_t groups, int64_t ncols) {
+// width (narrow tiles re-read the packed weights more often per FLOP).  A mid-sized grid of a large
+// problem may split its reduction (configure_ksplit): the estimate then takes the best split of each
+// width, so that a wide tile in three slices can beat a narrow one that leaves the last round a third
+// full (256 -> 384 channels, 3x3 at 13x13, backward data: 128x128 in 3 slices 325-334 us, 128x64
+// unsplit 341).  Kernels of 25 taps or more are left out: their wide tiles take the patch-staged
+// kernel, which does not split.
+int32_t pick_corr_tile(int32_t rows, int64_t groups, int64_t ncols, int64_t kred, int64_t taps) {
   int64_t best_pad = 0, best_bm = 0;
   for (int32_t t = 0; t < CORR_TILE_COUNT; ++t) {
     int32_t bm, bn, bk;
@@ -60,6 +65,12 @@ int32_t pick_corr_tile(int32_t rows, int64_t groups, int64_t ncols) {
     if (bm != best_bm) continue;
     const int64_t units = groups * (best_pad / bm) * ceil_div(ncols > 0 ? ncols : 1, bn);
     double cost = (double)ceil_div(units, 256) * bn;
+    const int64_t chunks = ceil_div(kred, bk);
+    if (units > 160 && units < 512 && taps < 25 && 2.0 * rows * (double)kred * (double)ncols * (double)groups >= 5e9)
+      for (int64_t c = 2; c <= 8 && chunks / c >= 16; ++c) {  // the splits configure_ksplit may take
+        const double split_cost = (double)ceil_div(units * c, 256) * bn / (double)c * (1.0 + 0.01 * (double)c);
+        if (split_cost < cost) cost = split_cost;
+      }
     for (int32_t w = bn; w < 256; w *= 2) cost *= 1.06;
     if (best < 0 || cost < best_cost) {
       best = t;
@@ -501,7 +512,7 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
 
   // ---- forward: rows = output channels of a group, k = (c, i, j), columns = (n, oh, ow) ----
   {
-    d->fwd_tile = pick_corr_tile((int32_t)Kg, G, N * OH * OW);
+    d->fwd_tile = pick_corr_tile((int32_t)Kg, G, N * OH * OW, kred, (int64_t)p.kernel_h * p.kernel_w);
     corr_tile_shape(d->fwd_tile, &bm, &bn, &bk);
     CorrArgs& a = d->fwd;
     a.ncols = (int32_t)(N * OH * OW);
@@ -593,7 +604,7 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
       delete d;
       return CONV_ESHAPE;
     }
-    d->bwd_tile = pick_corr_tile((int32_t)rows, G, N * Ah * Aw);
+    d->bwd_tile = pick_corr_tile((int32_t)rows, G, N * Ah * Aw, kred_b, Qh * Qw);
     corr_tile_shape(d->bwd_tile, &bm, &bn, &bk);
     CorrArgs& a = d->bwd;
     a.ncols = (int32_t)(N * Ah * Aw);

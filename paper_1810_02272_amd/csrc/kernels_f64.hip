@@ -436,23 +436,38 @@ __global__ __launch_bounds__(kThreads) void wgrad64_kernel(const WgradArgs a) {
   }
 }
 
-// dst = beta*dst + sum_s part[s] (+ bias), in a fixed order: one thread per element.
+// dst = beta*dst + sum_s part[s] (+ bias), in a fixed order.  A workgroup owns 64 consecutive elements;
+// its four waves each add a contiguous quarter of the slices (eight loads in flight per lane: a long
+// run of slices is latency-bound otherwise) and the quarter sums are combined in wave order.
 __global__ __launch_bounds__(256) void reduce64_kernel(const ReduceArgs a) {
-  const int i = blockIdx.x * 256 + threadIdx.x;
-  if (i >= a.count) return;
-  const double* src = reinterpret_cast<const double*>(a.part) + i;
-  double* dst = reinterpret_cast<double*>(a.dst);
-  double acc0 = 0., acc1 = 0.;
-  int s = 0;
-  for (; s + 1 < a.S; s += 2) {
-    acc0 += src[(size_t)s * a.count];
-    acc1 += src[(size_t)(s + 1) * a.count];
+  __shared__ double quarter[4][64];
+  const int lane = threadIdx.x & 63, q = threadIdx.x >> 6;
+  const int i = (int)blockIdx.x * 64 + lane;
+  const int per = (a.S + 3) / 4;
+  const int s0 = q * per;
+  int s1 = s0 + per;
+  if (s1 > a.S) s1 = a.S;
+  double acc[4] = {0., 0., 0., 0.};
+  if (i < a.count) {
+    const double* src = reinterpret_cast<const double*>(a.part) + i;
+    int k = s0;
+    for (; k + 7 < s1; k += 8) {
+      double x[8];
+#pragma unroll
+      for (int c = 0; c < 8; ++c) x[c] = src[(size_t)(k + c) * a.count];
+#pragma unroll
+      for (int c = 0; c < 8; ++c) acc[c & 3] += x[c];
+    }
+    for (; k < s1; ++k) acc[0] += src[(size_t)k * a.count];
   }
-  if (s < a.S) acc0 += src[(size_t)s * a.count];
-  double v = acc0 + acc1;
+  quarter[q][lane] = (acc[0] + acc[1]) + (acc[2] + acc[3]);
+  __syncthreads();
+  if (q != 0 || i >= a.count) return;
+  double* dst = reinterpret_cast<double*>(a.dst);
+  double v = ((quarter[0][lane] + quarter[1][lane]) + quarter[2][lane]) + quarter[3][lane];
   if (a.bias) {  // forward: channel of element i of an N x channels x chan_elems blob
-    const uint32_t q = mdiv((uint32_t)i, a.mChanElems);
-    v += reinterpret_cast<const double*>(a.bias)[q - mdiv(q, a.mChannels) * (uint32_t)a.channels];
+    const uint32_t ch = mdiv((uint32_t)i, a.mChanElems);
+    v += reinterpret_cast<const double*>(a.bias)[ch - mdiv(ch, a.mChannels) * (uint32_t)a.channels];
   }
   if (a.beta != 0.f) v += (double)a.beta * dst[i];
   dst[i] = v;
@@ -534,7 +549,7 @@ int launch_wgrad64(int32_t bm, const WgradArgs& a, void* stream) {
 }
 
 int launch_reduce64(const ReduceArgs& a, void* stream) {
-  hipLaunchKernelGGL(reduce64_kernel, dim3((a.count + 255) / 256), dim3(256), 0, (hipStream_t)stream, a);
+  hipLaunchKernelGGL(reduce64_kernel, dim3((a.count + 63) / 64), dim3(256), 0, (hipStream_t)stream, a);
   return (int)hipGetLastError();
 }
 

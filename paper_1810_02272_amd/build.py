@@ -8,7 +8,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_HERE)
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libmi355conv.so")
-SOURCES = ["api.cpp", "api_ip.cpp", "kernels_corr.hip", "kernels_corr_patch.hip", "kernels_wgrad.hip", "kernels_bias.hip",
+SOURCES = ["api.cpp", "api_ip.cpp", "kernels_corr.hip", "kernels_corr_patch.hip", "kernels_corr_thin.hip", "kernels_wgrad.hip", "kernels_bias.hip",
            "kernels_ip.hip", "kernels_pg.hip", "kernels_f64.hip", "kernels_direct.hip", "static_workspace.hip"]
 HEADERS = ["internal.h", "device_utils.h", "corr_epilogue.h"]
 

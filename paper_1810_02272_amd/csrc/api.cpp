@@ -176,10 +176,12 @@ PhaseDim phase_dim(int64_t kernel, int64_t stride, int64_t dilation) {
 // p = plain pointers (output of 2^31 bytes or more).
 // L = kernel launches of the pass: the pack kernel, a zero fill (backward data with unreached
 // phases), the main kernel, the reduce kernel of a split launch.
-void corr_variant_name(char* buf, size_t len, int32_t tile, const CorrArgs& a, int zero_fill) {
+void corr_variant_name(char* buf, size_t len, int32_t tile, const CorrArgs& a, int zero_fill, int thin) {
   const char e = a.simple_epilogue ? 's' : ((uint32_t)a.out_elems < (1u << 29) ? 'r' : 'p');
   const int launches = 2 + (a.ksplit > 1) + (zero_fill != 0);
-  if (a.use_patch)
+  if (thin)
+    snprintf(buf, len, "corr_thin_r%d[m%d,e%c](S=1,L=%d)", a.Mrows, a.bounds_mode, e, launches);
+  else if (a.use_patch)
     snprintf(buf, len, "%s_patch[e%c](S=%d,L=%d)", corr_tile_name(tile), e, a.ksplit, launches);
   else
     snprintf(buf, len, "%s[m%d,e%c](S=%d,L=%d)", corr_tile_name(tile), a.bounds_mode, e, a.ksplit, launches);
@@ -301,6 +303,20 @@ void configure_ksplit(CorrArgs& a, int64_t out_elems, int32_t bm, int32_t bn, in
   a.ksplit = (int32_t)ceil_div(chunks, a.chunks_per_split);
 }
 
+// GEMMs of at most four rows per group (backward data of a layer with one to four input channels
+// per group at stride 1, forward with that few outputs) with the offset-only epilogue take
+// corr_thin_kernel: one lane per column, scalar A operands, no matrix unit -- the 16-row tiles
+// spend three quarters or more of their matrix instructions on padding there.  The packed operand
+// and the k table stay as they are (natural k order); the reduction is not split.
+int32_t configure_thin(CorrArgs& a, PackArgs& k) {
+  if (a.Mrows > 4 || !a.simple_epilogue || a.ncols < 1) return 0;
+  a.use_patch = 0;
+  k.kperm_T = 0;
+  a.ksplit = 1;
+  a.chunks_per_split = a.KP / 16;
+  return 1;
+}
+
 }  // namespace
 
 namespace mi355conv {
@@ -345,7 +361,9 @@ int run_forward(const conv_desc* d, const float* x, const float* w, const float*
   a.bias = bias;
   a.out = y;
   a.part = reinterpret_cast<float*>(static_cast<char*>(ws) + d->fwd_pack_bytes);
-  e = a.use_patch ? launch_corr_patch(d->fwd_tile, a, hip_stream) : launch_corr(d->fwd_tile, a, hip_stream);
+  e = d->fwd_thin    ? launch_corr_thin(a, hip_stream)
+      : a.use_patch ? launch_corr_patch(d->fwd_tile, a, hip_stream)
+                    : launch_corr(d->fwd_tile, a, hip_stream);
   if (e) return record_hip_error(e);
   if (a.ksplit > 1) {  // add the split partials and the bias
     ReduceArgs r = {};
@@ -401,7 +419,9 @@ int run_backward_data(const conv_desc* d, const float* w, const float* dy, float
       e = launch_fill_zero(dx, (size_t)a.out_elems * 4, hip_stream);
     if (e) return record_hip_error(e);
   }
-  e = a.use_patch ? launch_corr_patch(d->bwd_tile, a, hip_stream) : launch_corr(d->bwd_tile, a, hip_stream);
+  e = d->bwd_thin    ? launch_corr_thin(a, hip_stream)
+      : a.use_patch ? launch_corr_patch(d->bwd_tile, a, hip_stream)
+                    : launch_corr(d->bwd_tile, a, hip_stream);
   if (e) return record_hip_error(e);
   if (a.ksplit > 1) {
     ReduceArgs r = {};
@@ -576,6 +596,7 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
     k.koff_invalid = koff_invalid(a.bounds_mode);
     configure_patch(a, k, Cg, N, bm, bn);
     configure_ksplit(a, y_elems, bm, bn);
+    d->fwd_thin = configure_thin(a, k);
     const int64_t pack_elems = G * (int64_t)a.KP * a.MP;
     if (pack_elems >= kMaxElems || (int64_t)G * a.m_tiles * a.col_tiles >= ((int64_t)1 << 31)) {
       delete d;
@@ -691,6 +712,7 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
     k.koff_invalid = koff_invalid(a.bounds_mode);
     configure_patch(a, k, Kg, N, bm, bn);
     configure_ksplit(a, x_elems, bm, bn);
+    d->bwd_thin = configure_thin(a, k);
     const int64_t pack_elems = G * (int64_t)a.KP * a.MP;
     if (pack_elems >= kMaxElems || (int64_t)G * a.m_tiles * a.col_tiles >= ((int64_t)1 << 31)) {
       delete d;
@@ -953,8 +975,8 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
     // checked stores with compares, plain pointers), staging of the filter gradient (lds/reg), one or
     // two launches of the bias gradient
     char f[64], b[64], wg[64];
-    corr_variant_name(f, sizeof(f), d->fwd_tile, d->fwd, 0);
-    corr_variant_name(b, sizeof(b), d->bwd_tile, d->bwd, d->bwd_zero_fill);
+    corr_variant_name(f, sizeof(f), d->fwd_tile, d->fwd, 0, d->fwd_thin);
+    corr_variant_name(b, sizeof(b), d->bwd_tile, d->bwd, d->bwd_zero_fill, d->bwd_thin);
     snprintf(wg, sizeof(wg), "%s[m%d,%s,e%c](S=%d,L=2)", wgrad_tile_name(d->wg_tile), d->wg.bounds_mode,
              d->wg_tile == WGRAD_128x128 ? "lds" : "reg", 4 * Kg * kred <= ((int64_t)1 << 30) ? 'r' : 'p', d->wg.S);
     if (d->use_direct) {

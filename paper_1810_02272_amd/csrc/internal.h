@@ -260,6 +260,7 @@ const char* wgrad_tile_name(int32_t tile);
 int launch_pack(const PackArgs& a, void* stream, bool f64 = false);
 int launch_corr(int32_t tile, const CorrArgs& a, void* stream);
 int launch_corr_patch(int32_t tile, const CorrArgs& a, void* stream);
+int launch_corr_thin(const CorrArgs& a, void* stream);  // Mrows <= 4, offset-only epilogue, no split
 int launch_wgrad(int32_t tile, const WgradArgs& a, void* stream);
 int launch_reduce(const ReduceArgs& a, void* stream);
 int launch_bias_grad(const BiasGradArgs& a, void* stream);
@@ -323,6 +324,7 @@ struct conv_desc {
   int32_t Cg, Kg;
   // forward
   int32_t fwd_tile;
+  int32_t fwd_thin, bwd_thin;  // the pass runs corr_thin_kernel (at most four GEMM rows per group)
   mi355conv::CorrArgs fwd;  // pointers left null
   mi355conv::PackArgs fwd_pack;
   size_t fwd_ws, fwd_pack_bytes;

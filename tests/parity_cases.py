@@ -93,7 +93,7 @@ PATCH_CASES = [
     (P(12, 16, 70, 61, 48, 3, 5, 1, 1, 0, 3), "fwd", "corr_m16_48x256x16_patch[es]"),       # forward with 48 rows, ragged pad
     (P(33, 8, 32, 33, 20, 3, 3, 1, 1, 1, 1), "fwd", "corr_m32_32x256x16_patch[es]"),        # 32-row MFMA tile, forward
     (P(64, 8, 47, 49, 8, 3, 3, 2, 2, 1, 1), "bwd_data", "corr_m32_32x256x16_patch[er]"),    # 32-row tile, four sub-pixel phases
-    (P(90, 8, 24, 25, 3, 3, 3, 1, 1, 1, 1), "fwd", "corr_m16_16x256x16_patch[es]"),         # 16-row tile, forward
+    (P(90, 8, 24, 25, 5, 3, 3, 1, 1, 1, 1), "fwd", "corr_m16_16x256x16_patch[es]"),         # 16-row tile, forward
     (P(100, 1, 48, 47, 8, 3, 3, 2, 2, 1, 1), "bwd_data", "corr_m16_16x256x16_patch[er]"),   # 16-row tile, sub-pixel scatter
     (P(64, 12, 48, 49, 8, 3, 3, 2, 2, 1, 1), "bwd_data", "corr_m16_48x256x16_patch[er]"),   # 48 rows = 12 channels x 4 phases
     (P(33, 20, 32, 33, 8, 3, 3, 1, 1, 1, 1), "bwd_data", "corr_m32_32x256x16_patch[es]"),   # 32-row tile at stride 1
@@ -143,12 +143,12 @@ VARIANT_CASES = [
     (P(2, 1, 48, 49, 200, 1, 1), "fwd", "corr_m16_16x256x16[m0"),
     (P(8, 1, 24, 25, 200, 6, 6, 1, 1, 2, 2), "fwd", "corr_m16_16x256x16[m1"),
     (P(33, 1, 9, 10, 200, 3, 3, 1, 1, 2, 2), "fwd", "corr_m16_16x256x16[m2"),
-    (P(100, 1, 24, 25, 1, 6, 6), "bwd_data", "corr_m16_16x256x16[m1"),
+    (P(33, 6, 40, 41, 1, 6, 6, 1, 1, 0, 0, 2, 2), "bwd_data", "corr_m16_16x256x16[m1"),
     (P(8, 4, 48, 49, 128, 3, 3, 1, 1, 1, 1), "fwd", "corr_m32_128x128x16[m2"),
     (P(64, 1, 28, 28, 20, 5, 5), "fwd", "corr_m32_32x256x16[m0"),
     (P(100, 3, 32, 32, 32, 5, 5, 1, 1, 2, 2), "fwd", "corr_m32_32x256x16[m2"),
     (P(1, 18, 28, 35, 54, 6, 7, 3, 4, 5, 1, 2, 2, 2), "fwd", "corr_m32_32x128x16[m1"),
-    (P(90, 8, 24, 25, 3, 3, 3, 1, 1, 1, 1), "bwd_data", "corr_m16_16x256x16[m2"),
+    (P(90, 8, 24, 25, 5, 3, 3, 1, 1, 1, 1), "bwd_data", "corr_m16_16x256x16[m2"),
     (P(2, 3, 7, 6, 60, 3, 3, 2, 2, 1, 1), "fwd", "corr_m32_64x64x16[m2"),
     (P(1, 8, 5, 6, 128, 3, 3), "bwd_filter", "wgrad_m32_128x128x32[m0"),
     (P(1, 3, 5, 6, 128, 6, 6, 2, 2, 3, 3), "bwd_filter", "wgrad_m32_128x128x32[m1"),
@@ -158,6 +158,16 @@ VARIANT_CASES = [
     # the 64-row filter-gradient tile is kept for grids of 256 workgroups or more (48 outputs, 4 column tiles, 86 splits)
     (P(6, 48, 66, 66, 48, 3, 3), "bwd_filter", "wgrad_m32_64x128x32[m0"),
     (P(6, 48, 64, 64, 48, 3, 3, 1, 1, 2, 2, 2, 2), "bwd_filter", "wgrad_m32_64x128x32[m1"),
+    # at most four GEMM rows per group: corr_thin_kernel, rows x bounds modes (several 64-column workgroups each)
+    (P(8, 1, 13, 14, 2, 1, 1, 2, 2), "fwd", "corr_thin_r2[m0"),
+    (P(3, 1, 24, 25, 2, 6, 6, 2, 2, 1, 1, 2, 2), "fwd", "corr_thin_r2[m1"),
+    (P(8, 1, 13, 14, 3, 1, 1, 2, 2), "fwd", "corr_thin_r3[m0"),
+    (P(3, 1, 24, 25, 4, 6, 6, 2, 2, 1, 1, 2, 2), "fwd", "corr_thin_r4[m1"),
+    (P(3, 2, 13, 14, 1, 6, 6, 1, 1, 0, 0, 2, 2), "bwd_data", "corr_thin_r2[m1"),
+    (P(3, 3, 13, 14, 1, 6, 6, 1, 1, 0, 0, 2, 2), "bwd_data", "corr_thin_r3[m1"),
+    (P(3, 4, 13, 14, 1, 6, 6, 1, 1, 0, 0, 2, 2), "bwd_data", "corr_thin_r4[m1"),
+    (P(5, 4, 21, 19, 7, 3, 3, 1, 1, 1, 1), "bwd_data", "corr_thin_r4[m2"),
+    (P(5, 9, 21, 19, 4, 3, 3), "fwd", "corr_thin_r4[m0"),
 ]
 
 

@@ -63,6 +63,16 @@ def test_every_gather_tile_and_bounds_mode_has_a_gpu_parity_case(selected):
     assert not any("[m0" in v for v in bwd)
 
 
+def test_every_thin_row_count_and_bounds_mode_has_a_gpu_parity_case(selected):
+    """corr_thin_kernel (at most four GEMM rows per group): ROWS x MODE instances, always the offset-only epilogue."""
+    fwd, bwd = selected["fp32"]["fwd"], selected["fp32"]["bwd_data"]
+    assert missing(fwd, [f"corr_thin_r{r}[m{m},es]" for r in (1, 2, 3, 4) for m in (0, 1, 2)]) == []
+    assert missing(bwd, [f"corr_thin_r{r}[m{m},es]" for r in (1, 2, 3, 4) for m in (1, 2)]) == []
+    for v, seen in list(fwd.items()) + list(bwd.items()):
+        if v.startswith("corr_thin"):
+            assert seen == {False}, v   # never split
+
+
 def test_every_patch_tile_has_a_gpu_parity_case(selected):
     fwd, bwd = selected["fp32"]["fwd"], selected["fp32"]["bwd_data"]
     assert missing(fwd, [f"{t}_patch[es]" for t in PATCH_TILES]) == []      # forward: one phase per channel
@@ -123,7 +133,9 @@ def test_every_fp64_tile_has_a_gpu_parity_case(selected):
 def test_no_variant_outside_the_lists_above(selected):
     """A new tile or flag must be added to the lists of this file (and so get a parity case)."""
     for v in list(selected["fp32"]["fwd"]) + list(selected["fp32"]["bwd_data"]):
-        if v.startswith("corr_"):
+        if v.startswith("corr_thin"):
+            assert re.fullmatch(r"corr_thin_r[1234]\[m[012],es\]", v), v
+        elif v.startswith("corr_"):
             assert re.fullmatch(r"(%s)(\[m[012],e[srp]\]|_patch\[e[sr]\])" % "|".join(CORR_TILES), v), v
     for v in selected["fp32"]["bwd_filter"]:
         if v.startswith("wgrad"):

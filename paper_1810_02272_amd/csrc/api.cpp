@@ -34,9 +34,9 @@ int64_t round_up(int64_t a, int64_t b) { return ceil_div(a, b) * b; }
 // problem may split its reduction (configure_ksplit): the estimate then takes the best split of each
 // width, so that a wide tile in three slices can beat a narrow one that leaves the last round a third
 // full (256 -> 384 channels, 3x3 at 13x13, backward data: 128x128 in 3 slices 325-334 us, 128x64
-// unsplit 341).  Kernels of 25 taps or more are left out: their wide tiles take the patch-staged
-// kernel, which does not split.
-int32_t pick_corr_tile(int32_t rows, int64_t groups, int64_t ncols, int64_t kred, int64_t taps) {
+// unsplit 341).  Tiles that the patch-staged kernel may take (may_patch: the gather is one it can
+// stage) are left out: that kernel does not split.
+int32_t pick_corr_tile(int32_t rows, int64_t groups, int64_t ncols, int64_t kred, int64_t taps, bool may_patch) {
   int64_t best_pad = 0, best_bm = 0;
   for (int32_t t = 0; t < CORR_TILE_COUNT; ++t) {
     int32_t bm, bn, bk;
@@ -66,7 +66,8 @@ int32_t pick_corr_tile(int32_t rows, int64_t groups, int64_t ncols, int64_t kred
     const int64_t units = groups * (best_pad / bm) * ceil_div(ncols > 0 ? ncols : 1, bn);
     double cost = (double)ceil_div(units, 256) * bn;
     const int64_t chunks = ceil_div(kred, bk);
-    if (units > 160 && units < 512 && taps < 25 && 2.0 * rows * (double)kred * (double)ncols * (double)groups >= 5e9)
+    const bool patch_tile = may_patch && ((bn == 256 && bm <= 48) || (taps >= 25 && bn == 128 && (bm == 128 || bm == 32)));
+    if (units > 160 && units < 512 && !patch_tile && 2.0 * rows * (double)kred * (double)ncols * (double)groups >= 5e9)
       for (int64_t c = 2; c <= 8 && chunks / c >= 16; ++c) {  // the splits configure_ksplit may take
         const double split_cost = (double)ceil_div(units * c, 256) * bn / (double)c * (1.0 + 0.01 * (double)c);
         if (split_cost < cost) cost = split_cost;
@@ -532,7 +533,8 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
 
   // ---- forward: rows = output channels of a group, k = (c, i, j), columns = (n, oh, ow) ----
   {
-    d->fwd_tile = pick_corr_tile((int32_t)Kg, G, N * OH * OW, kred, (int64_t)p.kernel_h * p.kernel_w);
+    d->fwd_tile = pick_corr_tile((int32_t)Kg, G, N * OH * OW, kred, (int64_t)p.kernel_h * p.kernel_w,
+                                 p.stride_h == 1 && p.stride_w == 1 && p.dilation_h == 1 && p.dilation_w == 1 && Cg % 8 == 0);
     corr_tile_shape(d->fwd_tile, &bm, &bn, &bk);
     CorrArgs& a = d->fwd;
     a.ncols = (int32_t)(N * OH * OW);
@@ -625,7 +627,7 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
       delete d;
       return CONV_ESHAPE;
     }
-    d->bwd_tile = pick_corr_tile((int32_t)rows, G, N * Ah * Aw, kred_b, Qh * Qw);
+    d->bwd_tile = pick_corr_tile((int32_t)rows, G, N * Ah * Aw, kred_b, Qh * Qw, Kg % 8 == 0);
     corr_tile_shape(d->bwd_tile, &bm, &bn, &bk);
     CorrArgs& a = d->bwd;
     a.ncols = (int32_t)(N * Ah * Aw);

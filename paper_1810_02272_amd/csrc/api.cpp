@@ -180,7 +180,9 @@ PhaseDim phase_dim(int64_t kernel, int64_t stride, int64_t dilation) {
 void corr_variant_name(char* buf, size_t len, int32_t tile, const CorrArgs& a, int zero_fill, int thin) {
   const char e = a.simple_epilogue ? 's' : ((uint32_t)a.out_elems < (1u << 29) ? 'r' : 'p');
   const int launches = 2 + (a.ksplit > 1) + (zero_fill != 0);
-  if (thin)
+  if (thin && a.use_patch)  // rows staged in LDS, TW x TW taps unrolled, weights read in place: no pack kernel
+    snprintf(buf, len, "corr_thin_r%d_lds%d[e%c](S=1,L=%d)", a.Mrows, a.TW, e, launches - 1);
+  else if (thin)
     snprintf(buf, len, "corr_thin_r%d[m%d,e%c](S=1,L=%d)", a.Mrows, a.bounds_mode, e, launches);
   else if (a.use_patch)
     snprintf(buf, len, "%s_patch[e%c](S=%d,L=%d)", corr_tile_name(tile), e, a.ksplit, launches);
@@ -309,12 +311,47 @@ void configure_ksplit(CorrArgs& a, int64_t out_elems, int32_t bm, int32_t bn, in
 // corr_thin_kernel: one lane per column, scalar A operands, no matrix unit -- the 16-row tiles
 // spend three quarters or more of their matrix instructions on padding there.  The packed operand
 // and the k table stay as they are (natural k order); the reduction is not split.
-int32_t configure_thin(CorrArgs& a, PackArgs& k) {
+int32_t configure_thin(CorrArgs& a, PackArgs& k, int64_t cg_in, int64_t n_img, bool backward) {
   if (a.Mrows > 4 || !a.simple_epilogue || a.ncols < 1) return 0;
   a.use_patch = 0;
   k.kperm_T = 0;
   a.ksplit = 1;
   a.chunks_per_split = a.KP / 16;
+  // A stride-1, dilation-1 gather with 3x3 or 5x5 taps whose rows fit LDS takes the staged form: 128
+  // columns per workgroup, all channels of the group at once, the patch of the largest tile (geometry
+  // of configure_patch) at most 512 floats per channel and 64 KB in all.  It reads its A operands
+  // from the weight blob (output channel, input channel, tap): forward rows are output channels and
+  // the gathered channels inputs; backward data the other way round with the taps reversed.
+  const int64_t T = a.THW, w_grp = (int64_t)a.Mrows * cg_in * T;
+  if (a.sh == 1 && a.sw == 1 && a.dh == 1 && a.dw == 1 && (a.TW == 3 || a.TW == 5) && T == a.TW * a.TW &&
+      (int64_t)a.in_bytes <= ((int64_t)1 << 30) && w_grp * a.G < ((int64_t)1 << 31)) {
+    const int64_t bn = 128, TH = a.TW;
+    const int64_t PH = a.P / a.PW, PWID = a.PW + a.TW - 1, RS = PH + TH - 1;
+    int64_t max_rows = 0;
+    for (int64_t c0 = 0; c0 < a.ncols; c0 += bn) {
+      const int64_t c1 = (c0 + bn < a.ncols ? c0 + bn : a.ncols) - 1;
+      const int64_t n0 = c0 / a.P, a0 = (c0 % a.P) / a.PW, n1 = c1 / a.P, a1 = (c1 % a.P) / a.PW;
+      const int64_t R0 = PH - a0 + TH - 1;
+      const int64_t rows = (n1 == n0 ? a1 - a0 : R0 + (n1 - n0 - 1) * RS + a1) + TH;
+      if (rows > max_rows) max_rows = rows;
+    }
+    const int64_t psz = max_rows * PWID;
+    if (psz <= 512 && cg_in * psz * 4 <= 64 * 1024) {
+      a.use_patch = 1;
+      a.Cg_in = (int32_t)cg_in;
+      a.NS = 0;
+      a.PH = (int32_t)PH;
+      a.Nimg = (int32_t)n_img;
+      a.PWID = (int32_t)PWID;
+      a.PSZ = (int32_t)psz;
+      a.mPWID = make_magic((uint32_t)PWID);
+      a.mRSEG = make_magic((uint32_t)RS);
+      a.w_grp_stride = (int32_t)w_grp;
+      a.w_row_stride = (int32_t)(backward ? T : cg_in * T);
+      a.w_chan_stride = (int32_t)(backward ? a.Mrows * T : T);
+      a.w_reversed = backward ? 1 : 0;
+    }
+  }
   return 1;
 }
 
@@ -353,10 +390,11 @@ int run_forward(const conv_desc* d, const float* x, const float* w, const float*
   k.w = w;
   k.A = static_cast<float*>(ws);
   k.ktab = reinterpret_cast<KTabEntry*>(k.A + (size_t)k.G * k.KP * k.MP);
-  int e = launch_pack(k, hip_stream);
+  const bool in_place = d->fwd_thin && d->fwd.use_patch;  // that kernel reads the weight blob itself
+  int e = in_place ? 0 : launch_pack(k, hip_stream);
   if (e) return record_hip_error(e);
   CorrArgs a = d->fwd;
-  a.A = k.A;
+  a.A = in_place ? w : k.A;
   a.ktab = k.ktab;
   a.in = x;
   a.bias = bias;
@@ -403,10 +441,11 @@ int run_backward_data(const conv_desc* d, const float* w, const float* dy, float
   k.w = w;
   k.A = static_cast<float*>(ws);
   k.ktab = reinterpret_cast<KTabEntry*>(k.A + (size_t)k.G * k.KP * k.MP);
-  int e = launch_pack(k, hip_stream);
+  const bool in_place = d->bwd_thin && d->bwd.use_patch;  // that kernel reads the weight blob itself
+  int e = in_place ? 0 : launch_pack(k, hip_stream);
   if (e) return record_hip_error(e);
   CorrArgs a = d->bwd;
-  a.A = k.A;
+  a.A = in_place ? w : k.A;
   a.ktab = k.ktab;
   a.in = dy;
   a.bias = nullptr;
@@ -598,7 +637,7 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
     k.koff_invalid = koff_invalid(a.bounds_mode);
     configure_patch(a, k, Cg, N, bm, bn);
     configure_ksplit(a, y_elems, bm, bn);
-    d->fwd_thin = configure_thin(a, k);
+    d->fwd_thin = configure_thin(a, k, Cg, N, false);
     const int64_t pack_elems = G * (int64_t)a.KP * a.MP;
     if (pack_elems >= kMaxElems || (int64_t)G * a.m_tiles * a.col_tiles >= ((int64_t)1 << 31)) {
       delete d;
@@ -714,7 +753,7 @@ int conv_desc_create(conv_desc_t** out, const conv_params_t* pp) {
     k.koff_invalid = koff_invalid(a.bounds_mode);
     configure_patch(a, k, Kg, N, bm, bn);
     configure_ksplit(a, x_elems, bm, bn);
-    d->bwd_thin = configure_thin(a, k);
+    d->bwd_thin = configure_thin(a, k, Kg, N, true);
     const int64_t pack_elems = G * (int64_t)a.KP * a.MP;
     if (pack_elems >= kMaxElems || (int64_t)G * a.m_tiles * a.col_tiles >= ((int64_t)1 << 31)) {
       delete d;

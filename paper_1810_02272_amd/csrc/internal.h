@@ -94,6 +94,9 @@ struct CorrArgs {
   int32_t PWID, PSZ;   // patch row length (PW + TW - 1); floats per channel of an LDS patch stage
   Magic mPWID, mRSEG;  // divisions by PWID and by the patch rows of a full image (PH + TH - 1)
   int32_t simple_epilogue;  // one phase per channel and an output of at most 2^30 bytes: offset-only epilogue
+  // LDS-staged form of corr_thin_kernel: A is the weight blob itself (no pack kernel); element strides of
+  // a GEMM row, a gathered channel and a group in it, and whether the taps run backwards (backward data)
+  int32_t w_row_stride, w_chan_stride, w_grp_stride, w_reversed;
 };
 
 constexpr int kPatchEPT = 3;  // patch elements per thread and channel: PSZ <= 3 * 256

@@ -166,8 +166,27 @@ VARIANT_CASES = [
     (P(3, 2, 13, 14, 1, 6, 6, 1, 1, 0, 0, 2, 2), "bwd_data", "corr_thin_r2[m1"),
     (P(3, 3, 13, 14, 1, 6, 6, 1, 1, 0, 0, 2, 2), "bwd_data", "corr_thin_r3[m1"),
     (P(3, 4, 13, 14, 1, 6, 6, 1, 1, 0, 0, 2, 2), "bwd_data", "corr_thin_r4[m1"),
-    (P(5, 4, 21, 19, 7, 3, 3, 1, 1, 1, 1), "bwd_data", "corr_thin_r4[m2"),
-    (P(5, 9, 21, 19, 4, 3, 3), "fwd", "corr_thin_r4[m0"),
+    (P(5, 4, 21, 19, 7, 4, 4, 1, 1, 1, 1), "bwd_data", "corr_thin_r4[m2"),
+    (P(8, 1, 13, 14, 4, 1, 1, 2, 2), "fwd", "corr_thin_r4[m0"),
+    # the same with the gathered rows staged in LDS (stride 1, dilation 1, 3x3 or 5x5 taps): rows x tap width, both
+    # passes; tiles of 128 columns that span several images, ragged last tile, asymmetric and over-sized padding,
+    # channel counts that are no multiple of the four waves, groups
+    (P(4, 20, 17, 23, 1, 3, 3, 1, 1, 1, 1), "fwd", "corr_thin_r1_lds3"),
+    (P(6, 7, 16, 15, 2, 3, 3, 1, 1, 0, 1), "fwd", "corr_thin_r2_lds3"),
+    (P(6, 6, 16, 15, 3, 3, 3, 1, 1, 2, 2), "fwd", "corr_thin_r3_lds3"),
+    (P(5, 9, 21, 19, 4, 3, 3), "fwd", "corr_thin_r4_lds3"),
+    (P(3, 5, 30, 29, 1, 5, 5, 1, 1, 1, 2), "fwd", "corr_thin_r1_lds5"),
+    (P(7, 3, 12, 11, 2, 5, 5, 1, 1, 2, 2), "fwd", "corr_thin_r2_lds5"),
+    (P(7, 3, 12, 11, 3, 5, 5, 1, 1, 2, 2), "fwd", "corr_thin_r3_lds5"),
+    (P(6, 8, 15, 16, 8, 5, 5, 1, 1, 2, 2, 1, 1, 2), "fwd", "corr_thin_r4_lds5"),
+    (P(9, 1, 10, 9, 17, 3, 3), "bwd_data", "corr_thin_r1_lds3"),
+    (P(4, 2, 25, 27, 5, 3, 3, 1, 1, 0, 2), "bwd_data", "corr_thin_r2_lds3"),
+    (P(4, 3, 25, 27, 5, 3, 3, 1, 1, 1, 1), "bwd_data", "corr_thin_r3_lds3"),
+    (P(5, 4, 21, 19, 7, 3, 3, 1, 1, 1, 1), "bwd_data", "corr_thin_r4_lds3"),
+    (P(3, 1, 33, 31, 6, 5, 5, 1, 1, 2, 2), "bwd_data", "corr_thin_r1_lds5"),
+    (P(7, 2, 12, 11, 6, 5, 5, 1, 1, 2, 2), "bwd_data", "corr_thin_r2_lds5"),
+    (P(3, 3, 20, 31, 9, 5, 5, 1, 1, 4, 4), "bwd_data", "corr_thin_r3_lds5"),
+    (P(6, 8, 15, 16, 8, 5, 5, 1, 1, 2, 2, 1, 1, 2), "bwd_data", "corr_thin_r4_lds5"),
 ]
 
 
@@ -272,6 +291,10 @@ IP_SHAPES = [
     (1, 1, 1), (1, 4, 1), (3, 7, 5), (5, 33, 129), (64, 500, 10), (64, 800, 500), (37, 1000, 130), (130, 257, 70),
     (128, 2048, 96), (16, 4100, 48), (200, 64, 1000), (9, 16, 2050),
 ]
+# beta = 1 (the filter gradient is added to what dw holds).  The last three: at most four outputs -- the sum then
+# happens in the epilogue of the kernel for GEMMs of at most four rows -- and at most four batch rows (that kernel
+# computes dx).
+IP_BETA_SHAPES = [(64, 800, 500), (130, 257, 70), (9, 16, 2050), (37, 300, 3), (20, 1000, 1), (3, 129, 40)]
 IP_RANDOM = (777, 16)
 
 

@@ -15,7 +15,7 @@ import paper_1810_02272_amd as conv
 from oracle import inner_product as ipo
 from oracle.inner_product import IpOracleParams
 from paper_1810_02272_amd import workloads
-from parity_cases import IP_SHAPES
+from parity_cases import IP_BETA_SHAPES, IP_SHAPES
 from parity_metric import small_tensor_error
 
 pytestmark = pytest.mark.gpu
@@ -110,7 +110,7 @@ def test_ip_without_bias():
     run_case(33, 300, 70, False, 1, x, w, None, dy)
 
 
-@pytest.mark.parametrize("shape", [(64, 800, 500), (130, 257, 70), (9, 16, 2050)])
+@pytest.mark.parametrize("shape", IP_BETA_SHAPES, ids=[f"{m}x{k}x{o}" for m, k, o in IP_BETA_SHAPES])
 def test_ip_beta_one_accumulates(shape):
     m, k, o = shape
     x, w, b, dy = workloads.ip_random_inputs(m, k, o, seed=7200 + m)

@@ -68,6 +68,10 @@ def test_every_thin_row_count_and_bounds_mode_has_a_gpu_parity_case(selected):
     fwd, bwd = selected["fp32"]["fwd"], selected["fp32"]["bwd_data"]
     assert missing(fwd, [f"corr_thin_r{r}[m{m},es]" for r in (1, 2, 3, 4) for m in (0, 1, 2)]) == []
     assert missing(bwd, [f"corr_thin_r{r}[m{m},es]" for r in (1, 2, 3, 4) for m in (1, 2)]) == []
+    # the LDS-staged form (stride-1, dilation-1 gathers with 3x3 or 5x5 taps whose rows fit LDS)
+    staged = [f"corr_thin_r{r}_lds{tw}[es]" for r in (1, 2, 3, 4) for tw in (3, 5)]
+    assert missing(fwd, staged) == []
+    assert missing(bwd, staged) == []
     for v, seen in list(fwd.items()) + list(bwd.items()):
         if v.startswith("corr_thin"):
             assert seen == {False}, v   # never split
@@ -134,7 +138,7 @@ def test_no_variant_outside_the_lists_above(selected):
     """A new tile or flag must be added to the lists of this file (and so get a parity case)."""
     for v in list(selected["fp32"]["fwd"]) + list(selected["fp32"]["bwd_data"]):
         if v.startswith("corr_thin"):
-            assert re.fullmatch(r"corr_thin_r[1234]\[m[012],es\]", v), v
+            assert re.fullmatch(r"corr_thin_r[1234](\[m[012],es\]|_lds[35]\[es\])", v), v
         elif v.startswith("corr_"):
             assert re.fullmatch(r"(%s)(\[m[012],e[srp]\]|_patch\[e[sr]\])" % "|".join(CORR_TILES), v), v
     for v in selected["fp32"]["bwd_filter"]:
@@ -162,6 +166,14 @@ def test_inner_product_shapes_cover_the_three_contractions():
                 seen[which].add(split_variant(v)[0])
     assert all(v.startswith("wgrad") for v in seen["fwd"]) and len(seen["fwd"]) >= 3, seen["fwd"]
     assert all(v.startswith("corr") for v in seen["bwd_data"] | seen["bwd_filter"])
+    # beta = 1: the filter gradient is added in the epilogue of the gather kernels and of the kernel for GEMMs of at
+    # most four rows (test_ip_beta_one_accumulates)
+    beta_kernels = set()
+    for m, k, o in pc.IP_BETA_SHAPES:
+        d = conv.ip_desc_create(conv.IpParams(m, k, o, 1, 1))
+        beta_kernels.add(split_variant(fields(conv.ip_desc_kernel_names(d))["bwd_filter"])[0].split("[")[0])
+    assert any(v.startswith("corr_thin_r") for v in beta_kernels), beta_kernels
+    assert any(v.startswith("corr_m") for v in beta_kernels), beta_kernels
     # a forward output of more than 2^30 bytes takes the plain-pointer store of the filter-gradient kernel
     # (test_ip_forward_output_above_1_gib)
     d = conv.ip_desc_create(conv.IpParams(16400, 2, 16400, 1, 0))

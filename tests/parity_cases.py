@@ -274,9 +274,28 @@ def random_many_channel_params(rng):
             return pd
 
 
+def random_thin_row_params(rng):
+    """Random layers with at most four input channels or at most four outputs per group at stride 1, mostly 3x3 and
+    5x5 kernels: GEMMs of at most four rows (the thin-row kernel and its LDS-staged form), with images small enough
+    that a 128-column tile spans several of them and large enough that it does not, padding up to past the kernel."""
+    while True:
+        g = int(rng.choice([1, 1, 1, 2, 3]))
+        few, many = int(rng.integers(1, 5)), int(rng.integers(1, 24))
+        c, k = (g * few, g * many) if rng.integers(0, 2) else (g * many, g * few)
+        kh, kw = [(3, 3), (5, 5), (3, 3), (5, 5), (int(rng.integers(1, 7)), int(rng.integers(1, 7)))][int(rng.integers(0, 5))]
+        ph, pw = int(rng.integers(0, kh + 1)), int(rng.integers(0, kw + 1))
+        h, w = int(rng.integers(1, 45)), int(rng.integers(1, 45))
+        pd = dict(n=int(rng.integers(1, 9)), c=c, h=h, w=w, num_output=k, kernel_h=kh, kernel_w=kw, stride_h=1,
+                  stride_w=1, pad_h=ph, pad_w=pw, dilation_h=1, dilation_w=1, group=g,
+                  bias_term=int(rng.integers(0, 2)))
+        if _valid(pd):
+            return pd
+
+
 # Seeds and counts of the seeded random tests (test_random_sweep_gpu.py draws exactly these).
 RANDOM_BLOCKS = [(20260 + b, 12, random_params) for b in range(6)]
 THIN_BLOCKS = [(50500 + b, 12, random_thin_group_params) for b in range(4)]
+THIN_ROW = (80800, 48, random_thin_row_params)
 MULTI_TILE = (60600, 40, random_multi_tile_params)
 MANY_CHANNEL = (70700, 16, random_many_channel_params)
 
@@ -310,7 +329,7 @@ def fp32_conv_cases():
 
     out = list(SWEEP) + list(DIRECT_CASES) + [c[0] for c in PATCH_CASES] + [c[0] for c in VARIANT_CASES]
     out += [l.params_dict() for l in workloads.LAYERS + workloads.DW_LAYERS]
-    for blk in RANDOM_BLOCKS + THIN_BLOCKS + [MULTI_TILE, MANY_CHANNEL]:
+    for blk in RANDOM_BLOCKS + THIN_BLOCKS + [THIN_ROW, MULTI_TILE, MANY_CHANNEL]:
         out += draw_block(*blk)
     return out
 
@@ -321,6 +340,6 @@ def fp64_conv_cases():
 
     out = list(SWEEP) + list(DIRECT_CASES) + [c[0] for c in VARIANT_CASES]
     out += [l.params_dict() for l in workloads.LAYERS]
-    for blk in RANDOM_BLOCKS + THIN_BLOCKS + [MULTI_TILE, MANY_CHANNEL]:
+    for blk in RANDOM_BLOCKS + THIN_BLOCKS + [THIN_ROW, MULTI_TILE, MANY_CHANNEL]:
         out += draw_block(*blk)
     return out

@@ -3,6 +3,7 @@ the corners the hand-picked sweep may miss -- stride larger than the kernel, pad
 kernel extent, dilation with stride, non-square everything, groups) against the CPU oracle, fp32
 and fp64 paths, plus random InnerProduct shapes.  Same gates as the other parity tests."""
 import os
+import re
 import time
 
 import numpy as np
@@ -13,8 +14,8 @@ import oracle
 import paper_1810_02272_amd as conv
 from oracle import OracleParams
 from paper_1810_02272_amd import workloads
-from parity_cases import (IP_RANDOM, MANY_CHANNEL, MULTI_TILE, RANDOM_BLOCKS, THIN_BLOCKS, draw_block, random_ip_case,
-                          random_multi_tile_params, random_params, random_thin_group_params)
+from parity_cases import (IP_RANDOM, MANY_CHANNEL, MULTI_TILE, RANDOM_BLOCKS, THIN_BLOCKS, THIN_ROW, draw_block,
+                          random_ip_case, random_multi_tile_params, random_params, random_thin_group_params)
 from test_f64_parity_gpu import check_full64
 from test_ip_parity_gpu import run_case as run_ip_case
 from test_parity_gpu import check_full
@@ -56,6 +57,18 @@ def check_both_types(pd, seed):
     x, w, b, dy = workloads.random_inputs(oracle.x_shape(op), oracle.w_shape(op), oracle.output_shape(op), seed,
                                           bias=bool(pd["bias_term"]))
     check_full64(pd, x.double(), w.double(), b.double() if b is not None else None, dy.double())
+
+
+def test_random_thin_row_parameters_reach_the_thin_row_kernel_and_its_staged_form():
+    """Random stride-1 layers with at most four input channels or outputs per group: GEMMs of at most four rows."""
+    plain = staged = 0
+    for i, pd in enumerate(draw_block(*THIN_ROW)):
+        names = conv.conv_desc_kernel_names(conv.conv_desc_create(conv.ConvParams(**pd)))
+        print("random thin-row case", i, pd, names, flush=True)
+        plain += re.search(r"corr_thin_r\d\[", names) is not None
+        staged += re.search(r"corr_thin_r\d_lds", names) is not None
+        check_both_types(pd, 81000 + i)
+    assert plain >= 8 and staged >= 16, (plain, staged)
 
 
 def test_random_multi_tile_parameters_fp32_and_fp64():

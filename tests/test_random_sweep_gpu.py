@@ -15,7 +15,8 @@ import paper_1810_02272_amd as conv
 from oracle import OracleParams
 from paper_1810_02272_amd import workloads
 from parity_cases import (IP_RANDOM, MANY_CHANNEL, MULTI_TILE, RANDOM_BLOCKS, THIN_BLOCKS, THIN_ROW, draw_block,
-                          random_ip_case, random_multi_tile_params, random_params, random_thin_group_params)
+                          random_ip_case, random_multi_tile_params, random_params, random_thin_group_params,
+                          random_thin_row_params)
 from test_f64_parity_gpu import check_full64
 from test_ip_parity_gpu import run_case as run_ip_case
 from test_parity_gpu import check_full
@@ -92,13 +93,13 @@ def test_random_many_channel_parameters_reach_the_square_filter_gradient_tile():
 @pytest.mark.skipif("MI355CONV_SOAK_SECONDS" not in os.environ,
                     reason="extended sweep: set MI355CONV_SOAK_SECONDS (and MI355CONV_SOAK_SEED) to run it")
 def test_extended_random_sweep():
-    """The three generators of this file in turn, fresh parameter sets until the time is up."""
+    """The four generators of this file in turn, fresh parameter sets until the time is up."""
     budget = float(os.environ["MI355CONV_SOAK_SECONDS"])
     rng = np.random.default_rng(int(os.environ.get("MI355CONV_SOAK_SEED", "987654")))
-    gens = [random_params, random_thin_group_params, random_multi_tile_params]
+    gens = [random_params, random_thin_group_params, random_multi_tile_params, random_thin_row_params]
     t0, i, told = time.time(), 0, 0.0
     while time.time() - t0 < budget:
-        pd = gens[i % 3](rng)
+        pd = gens[i % 4](rng)
         if time.time() - told > 20.0:   # a progress line every 20 s (run with -s: a silent run looks hung)
             told = time.time()
             print("extended sweep case", i, pd, flush=True)
